@@ -1,0 +1,12 @@
+"""CPU fp64 oracle for batched draft verification.  TEST INFRASTRUCTURE ONLY:
+imported by tests/, the smoke check and the benchmark's cpu_baseline leg, never
+by the product path."""
+from .seer_oracle import (  # noqa: F401
+    accept,
+    argmax,
+    build,
+    num_threads,
+    verify_accept,
+    verify_attention,
+    verify_attention_rows,
+)
