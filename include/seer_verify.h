@@ -1,0 +1,150 @@
+/*
+ * seer_verify -- batched draft verification for grouped speculative decoding on
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes, no C++ or framework
+ * types.  Pointers marked "device" are HIP device memory owned by the caller;
+ * the library neither frees nor keeps them.  Pointers marked "host" are read
+ * during the call only.
+ *
+ * The method (paper: Section 2.2, draft-then-verify; Section 3.4, adaptive
+ * grouped speculative decoding): every rollout request of a prompt group hands
+ * in gamma draft tokens -- one chain, or several candidate paths sharing a root
+ * (multi-path drafting, Section 3.4.2) -- and the target model scores all of
+ * them in ONE forward pass.  A step emits the accepted draft prefix plus one
+ * bonus token, at most gamma + 1 tokens (Section 3.4.1, expected tokens per
+ * forward (1 - alpha^(gamma+1)) / (1 - alpha)), and must equal what serial
+ * decoding would have produced (Section 3.1, lossless).
+ *
+ * Two calls make up the data-parallel part of that pass:
+ *   seer_verify_attention : attention of the T = gamma + 1 verify positions of
+ *                           every request over its paged KV cache (once per layer)
+ *   seer_accept           : target token per position from the logits, then the
+ *                           longest accepted root path (once per step)
+ *
+ * Common rules
+ *  - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream): no device synchronisation, no allocation, no
+ *    global state.  Scratch memory is sized by the *_workspace() functions
+ *    (host-only, no HIP call) and supplied by the caller; calls that share a
+ *    workspace must be ordered on one stream.
+ *  - Return value: 0 = launched; negative = SEER_E* argument error found on the
+ *    host BEFORE anything is launched (so they can be exercised without a GPU);
+ *    positive = the hipError_t of a failed launch.
+ *  - Content of device arrays cannot be checked on the host.  The kernels keep
+ *    every access in bounds regardless: page ids are clamped into the pool, and
+ *    a request whose ctx_len is below T or beyond max_pages_per_seq*page_size
+ *    gets an all-zero output row block and raises bit 0 of the status word (see
+ *    seer_verify_attention_status_offset).
+ */
+#ifndef SEER_VERIFY_H
+#define SEER_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SEER_OK 0
+#define SEER_EINVAL (-1)       /* null pointer, negative or zero size               */
+#define SEER_ESHAPE (-2)       /* T not in 1..64, Hq not a multiple of Hkv, ...     */
+#define SEER_EUNSUPPORTED (-3) /* head dims / page size no kernel is built for      */
+#define SEER_EWORKSPACE (-4)   /* workspace NULL or smaller than *_workspace()      */
+#define SEER_EALIGN (-5)       /* a tensor pointer is not 16-byte aligned           */
+
+#define SEER_MAX_T 64          /* verify slots per request (width of the mask word) */
+
+/* Shape of one verify-attention call.
+ * Notation: B requests; T = gamma + 1 verify slots per request (slot 0 = the
+ * last accepted token = tree root, slots 1..gamma = draft tokens); Hq query
+ * heads, Hkv KV heads, G = Hq / Hkv heads share one KV head. */
+typedef struct seer_attn_params {
+    int32_t B, T, Hq, Hkv;
+    int32_t Dqk;               /* key / query head dim                                */
+    int32_t Dv;                /* value / output head dim                             */
+    int32_t page_size;         /* tokens per KV page                                  */
+    int32_t num_pages;         /* pages in the pool                                   */
+    int32_t max_pages_per_seq; /* row stride of block_table                           */
+    int32_t max_splits;        /* cap on split-K partitions per request, 1..256; 0 = library default */
+    int32_t kv_shared_latent;  /* 0: separate K and V pools; 1: V = first Dv components of K (MLA, absorbed form) */
+    float scale;               /* softmax scale applied to q.k                        */
+} seer_attn_params;
+
+/* Supported shapes: (Dqk, Dv) in {(64,64), (128,128), (256,256), (192,128),
+ * (576,512)}; any page_size >= 1 that is a multiple of 1 (fast kernels exist
+ * for page_size 16 with D = 128, and for the shared latent 576/512 with
+ * page_size 64; other combinations run a slower general kernel). */
+
+/* Bytes of device scratch seer_verify_attention needs for these params; 0 on
+ * invalid params.  Host-only arithmetic. */
+size_t seer_verify_attention_workspace(const seer_attn_params* p);
+
+/* Byte offset, inside the workspace, of a uint32 status word that the call
+ * zeroes and its kernels OR into: bit 0 = some request had ctx_len < T or
+ * beyond the block table; bit 1 = some page id was outside the pool. */
+size_t seer_verify_attention_status_offset(void);
+
+/*
+ * Multi-token paged-KV attention for the verify pass.
+ *
+ * For request b with n = ctx_len[b] and n0 = n - T: logical KV position j lives
+ * in page block_table[b][j / page_size], slot j % page_size.  The K/V of the T
+ * verify slots are already in the cache as the LAST T logical positions, slot s
+ * at n0 + s.  Query slot t sees every position j < n0 and position n0 + s iff
+ * bit s of tree_mask[b][t] is set; tree_mask == NULL means s <= t (a causal
+ * chain).  out[b,t,h,:] = softmax_j(scale * q[b,t,h,:].K[j,h/G,:]) . V[j,h/G,:]
+ * over the visible j, accumulated in fp32 and rounded to bf16 (nearest even).
+ * A query that sees nothing gets zeros.
+ *
+ *  out         device [B,T,Hq,Dv]  bf16, written
+ *  q           device [B,T,Hq,Dqk] bf16
+ *  k_pages     device [num_pages,Hkv,page_size,Dqk] bf16
+ *  v_pages     device [num_pages,Hkv,page_size,Dv]  bf16; must be NULL iff kv_shared_latent
+ *  block_table device [B,max_pages_per_seq] int32; entries past ceil(n/page_size) are not read
+ *  ctx_len     device [B] int32, INCLUDING the T verify slots
+ *  tree_mask   device [B,T] uint64 ancestor-or-self bits, or NULL
+ *  p           host
+ *  workspace   device, >= seer_verify_attention_workspace(p) bytes, 256-byte aligned
+ */
+int seer_verify_attention(void* out, const void* q, const void* k_pages, const void* v_pages,
+                          const int32_t* block_table, const int32_t* ctx_len,
+                          const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device scratch seer_accept needs; 0 on invalid sizes.  Host-only. */
+size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V);
+
+/*
+ * Acceptance from target logits.
+ *
+ * target_argmax[b,t] = lowest index attaining max_v logits[b,t,v] (fp32
+ * comparison, +0 == -0, inputs NaN-free; -inf allowed).  Node t >= 1 is accepted
+ * iff its parent is accepted and draft_tokens[b,t] == target_argmax[b,parent];
+ * the root is accepted.  The winner is the deepest accepted node (lowest slot
+ * among equally deep ones -- sibling nodes may carry the same token, so this is
+ * a search over paths, not a greedy first-match walk).
+ *
+ *  logits        device [B,T,V] fp32
+ *  draft_tokens  device [B,T] int32; slot 0 (the root's own token) is ignored
+ *  tree_parent   device [B,T] int32 or NULL (= chain, parent[t] = t-1).
+ *                [b,0] is ignored (root); 0 <= parent[t] < t; -2 = padded slot,
+ *                never accepted.  Any other value is treated as padded.
+ *  accepted_len  device [B] int32, written: number of accepted DRAFT tokens, 0..T-1
+ *  accepted_path device [B,T] int32, written: slots root..winner, then -1
+ *  bonus_token   device [B] int32 or NULL, written: target_argmax at the winner
+ *  target_argmax device [B,T] int32, written
+ *  workspace     device, >= seer_accept_workspace(B,T,V) bytes, 16-byte aligned
+ */
+int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+                int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
+                int32_t* bonus_token, int32_t* target_argmax, void* workspace,
+                size_t workspace_bytes, void* hip_stream);
+
+/* Static text for a return code of either call (negative SEER_E*, or a
+ * positive hipError_t). */
+const char* seer_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEER_VERIFY_H */

@@ -1,0 +1,170 @@
+"""Thin Python binding of libseer_verify.so (include/seer_verify.h).
+
+Argument marshalling only: tensors are torch CUDA(HIP) tensors whose device
+pointers are handed to the C ABI; every step of the path runs in the library's
+kernels.  There is no fallback: if the shared object is missing the import of
+the functions fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libseer_verify.so")
+
+SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALIGN = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
+           "seer_accept_workspace", "seer_accept", "seer_strerror")
+
+
+class SeerAttnParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("Dqk", ctypes.c_int32), ("Dv", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("num_pages", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
+                ("max_splits", ctypes.c_int32), ("kv_shared_latent", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class SeerError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("seer_verify: %s (%d)" % (text, code))
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: build it with `python -m paper_2511_14617_amd.build` "
+                              "(hipcc, gfx950); there is no fallback path" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        lib.seer_verify_attention_workspace.argtypes = [ctypes.POINTER(SeerAttnParams)]
+        lib.seer_verify_attention_workspace.restype = sz
+        lib.seer_verify_attention_status_offset.argtypes = []
+        lib.seer_verify_attention_status_offset.restype = sz
+        lib.seer_verify_attention.argtypes = [vp] * 7 + [ctypes.POINTER(SeerAttnParams), vp, sz, vp]
+        lib.seer_verify_attention.restype = ctypes.c_int
+        lib.seer_accept_workspace.argtypes = [i32, i32, i32]
+        lib.seer_accept_workspace.restype = sz
+        lib.seer_accept.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.seer_accept.restype = ctypes.c_int
+        lib.seer_strerror.argtypes = [ctypes.c_int]
+        lib.seer_strerror.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def seer_strerror(code: int) -> str:
+    return load_library().seer_strerror(int(code)).decode()
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise SeerError(code, seer_strerror(code))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _want(t: torch.Tensor, dtype, shape, name: str) -> None:
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError("%s: want contiguous device %s%s, got %s%s on %s" %
+                         (name, dtype, tuple(shape), t.dtype, tuple(t.shape), t.device))
+
+
+def attn_params(q: torch.Tensor, k_pages: torch.Tensor, v_pages: Optional[torch.Tensor],
+                block_table: torch.Tensor, scale: float, Dv: Optional[int] = None,
+                max_splits: int = 0) -> SeerAttnParams:
+    B, T, Hq, Dqk = q.shape
+    num_pages, Hkv, P, _ = k_pages.shape
+    dv = v_pages.shape[3] if v_pages is not None else Dv
+    if dv is None:
+        raise ValueError("Dv is needed when the latent is shared (v_pages is None)")
+    return SeerAttnParams(B, T, Hq, Hkv, Dqk, dv, P, num_pages, block_table.shape[1], max_splits,
+                          1 if v_pages is None else 0, float(scale))
+
+
+def seer_verify_attention_workspace(params: SeerAttnParams) -> int:
+    return int(load_library().seer_verify_attention_workspace(ctypes.byref(params)))
+
+
+def seer_verify_attention(q: torch.Tensor, k_pages: torch.Tensor, v_pages: Optional[torch.Tensor],
+                          block_table: torch.Tensor, ctx_len: torch.Tensor,
+                          tree_mask: Optional[torch.Tensor], scale: float, *, Dv: Optional[int] = None,
+                          max_splits: int = 0, out: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None,
+                          stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """out[B,T,Hq,Dv] bf16.  q [B,T,Hq,Dqk] bf16; k_pages [num_pages,Hkv,P,Dqk] bf16; v_pages
+    [num_pages,Hkv,P,Dv] bf16 or None (shared latent); block_table [B,max_pages] int32; ctx_len [B]
+    int32 (counts the T verify slots); tree_mask [B,T] int64 holding the uint64 ancestor bits, or
+    None for a chain.  `out` and `workspace` (uint8) may be passed to avoid allocation."""
+    lib = load_library()
+    p = attn_params(q, k_pages, v_pages, block_table, scale, Dv, max_splits)
+    _want(q, torch.bfloat16, (p.B, p.T, p.Hq, p.Dqk), "q")
+    _want(k_pages, torch.bfloat16, (p.num_pages, p.Hkv, p.page_size, p.Dqk), "k_pages")
+    if v_pages is not None:
+        _want(v_pages, torch.bfloat16, (p.num_pages, p.Hkv, p.page_size, p.Dv), "v_pages")
+    _want(block_table, torch.int32, (p.B, p.max_pages_per_seq), "block_table")
+    _want(ctx_len, torch.int32, (p.B,), "ctx_len")
+    if tree_mask is not None:
+        _want(tree_mask, torch.int64, (p.B, p.T), "tree_mask")
+    if out is None:
+        out = torch.empty((p.B, p.T, p.Hq, p.Dv), dtype=torch.bfloat16, device=q.device)
+    else:
+        _want(out, torch.bfloat16, (p.B, p.T, p.Hq, p.Dv), "out")
+    need = int(lib.seer_verify_attention_workspace(ctypes.byref(p)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib.seer_verify_attention(_ptr(out), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                     _ptr(ctx_len), _ptr(tree_mask), ctypes.byref(p), _ptr(workspace),
+                                     workspace.numel(), _stream_handle(stream)))
+    return out
+
+
+def seer_verify_attention_status(workspace: torch.Tensor) -> int:
+    """The status word the last call on this workspace left (synchronises)."""
+    off = int(load_library().seer_verify_attention_status_offset())
+    return int(workspace[off:off + 4].view(torch.int32).item()) & 0xFFFFFFFF
+
+
+def seer_accept_workspace(B: int, T: int, V: int) -> int:
+    return int(load_library().seer_accept_workspace(B, T, V))
+
+
+def seer_accept(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: Optional[torch.Tensor], *,
+                workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None
+                ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
+    """(accepted_len[B], accepted_path[B,T], bonus_token[B], target_argmax[B,T]), all int32.
+    logits [B,T,V] fp32; draft_tokens [B,T] int32; tree_parent [B,T] int32 or None (chain)."""
+    lib = load_library()
+    B, T, V = logits.shape
+    _want(logits, torch.float32, (B, T, V), "logits")
+    _want(draft_tokens, torch.int32, (B, T), "draft_tokens")
+    if tree_parent is not None:
+        _want(tree_parent, torch.int32, (B, T), "tree_parent")
+    dev = logits.device
+    alen = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, T), dtype=torch.int32, device=dev)
+    bonus = torch.empty(B, dtype=torch.int32, device=dev)
+    tgt = torch.empty((B, T), dtype=torch.int32, device=dev)
+    need = int(lib.seer_accept_workspace(B, T, V))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    _check(lib.seer_accept(_ptr(logits), _ptr(draft_tokens), _ptr(tree_parent), B, T, V, _ptr(alen), _ptr(path),
+                           _ptr(bonus), _ptr(tgt), _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return alen, path, bonus, tgt

@@ -1,0 +1,209 @@
+// seer_accept: target token per verify slot (vocabulary argmax) and the longest
+// accepted root path over the draft tree.
+//
+// The paper fixes what a verification step emits -- the accepted draft prefix
+// plus one bonus token (Section 3.4.1; Table "Mean acceptance length ...
+// including bonus token") -- and that with several candidate paths the longest
+// accepted one counts (Section 3.4.2).  The scan below is the HBM-bound part:
+// one pass over B*T*V fp32 logits.
+//
+// Kernel 1 (argmax_chunks): the rows are cut into chunks of kChunk floats so
+//   that a launch has rows*chunks workgroups (thousands, against 256 CUs) no
+//   matter how B*T and V split the work.  Each workgroup streams its chunk
+//   with 16-byte loads, keeps (max, lowest index) per lane, reduces across the
+//   wave with shuffles and across the 4 waves through LDS, and writes one
+//   (value, index) pair.
+// Kernel 2 (accept_walk): one wave per request.  Lane t merges the chunk pairs
+//   of slot t in ascending chunk order (strict '>' keeps the lowest index),
+//   publishes the slot's target token, then lane 0 walks the parent pointers in
+//   slot order: ok[t] = ok[parent] && draft[t] == target[parent], depth = depth
+//   of parent + 1, winner = deepest accepted slot, lowest slot on ties.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/seer_verify.h"
+#include "seer_device.h"
+
+namespace seer {
+
+constexpr int kArgmaxThreads = 256;
+constexpr int kChunk = 8192;  // floats per workgroup: 8 x 16-byte loads per lane
+
+__host__ __device__ inline int accept_num_chunks(int V) { return (V + kChunk - 1) / kChunk; }
+
+// (a, ia) beats (b, ib) iff a > b, or a == b and ia < ib.
+__device__ __forceinline__ void take_better(float& v, int& i, float ov, int oi) {
+    const bool better = (ov > v) || (ov == v && oi < i);
+    v = better ? ov : v;
+    i = better ? oi : i;
+}
+
+template <bool kVec4>
+__global__ __launch_bounds__(kArgmaxThreads) void argmax_chunks(const float* __restrict__ logits, int V,
+                                                                int n_chunks, float* __restrict__ part_val,
+                                                                int* __restrict__ part_idx) {
+    const int row = blockIdx.x / n_chunks;
+    const int chunk = blockIdx.x - row * n_chunks;
+    const int begin = chunk * kChunk;
+    const int end = min(V, begin + kChunk);
+    const float* __restrict__ base = logits + static_cast<size_t>(row) * V;
+
+    float best = kNegInf;
+    int best_i = begin;  // a row of -inf (or an all -inf chunk) resolves to its first index
+    if constexpr (kVec4) {
+        // V % 4 == 0 and a 16-byte aligned base: every row starts aligned.
+        constexpr int kIter = kChunk / (kArgmaxThreads * 4);
+        f32x4 x[kIter];
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int i = begin + (it * kArgmaxThreads + threadIdx.x) * 4;
+            x[it] = (i < end) ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(base + i))
+                              : f32x4{kNegInf, kNegInf, kNegInf, kNegInf};
+        }
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int i = begin + (it * kArgmaxThreads + threadIdx.x) * 4;
+            if (i < end) {  // indices ascend within a lane: strict '>' keeps the lowest
+                if (x[it].x > best) { best = x[it].x; best_i = i; }
+                if (x[it].y > best) { best = x[it].y; best_i = i + 1; }
+                if (x[it].z > best) { best = x[it].z; best_i = i + 2; }
+                if (x[it].w > best) { best = x[it].w; best_i = i + 3; }
+            }
+        }
+    } else {
+        for (int i = begin + threadIdx.x; i < end; i += kArgmaxThreads) {
+            const float x = base[i];
+            if (x > best) { best = x; best_i = i; }
+        }
+    }
+    // A lane that met nothing above -inf still reports (-inf, begin); that pair can only
+    // win when the whole chunk is -inf, and then `begin` is the right answer.
+
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const float ov = __shfl_xor(best, o, kWave);
+        const int oi = __shfl_xor(best_i, o, kWave);
+        take_better(best, best_i, ov, oi);
+    }
+    __shared__ float s_val[kArgmaxThreads / kWave];
+    __shared__ int s_idx[kArgmaxThreads / kWave];
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        s_val[wave] = best;
+        s_idx[wave] = best_i;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kArgmaxThreads / kWave; ++w) take_better(best, best_i, s_val[w], s_idx[w]);
+        part_val[blockIdx.x] = best;
+        part_idx[blockIdx.x] = best_i;
+    }
+}
+
+__global__ __launch_bounds__(kWave) void accept_walk(const float* __restrict__ part_val,
+                                                     const int* __restrict__ part_idx, int n_chunks,
+                                                     const int32_t* __restrict__ draft_tokens,
+                                                     const int32_t* __restrict__ tree_parent, int T,
+                                                     int32_t* __restrict__ accepted_len,
+                                                     int32_t* __restrict__ accepted_path,
+                                                     int32_t* __restrict__ bonus_token,
+                                                     int32_t* __restrict__ target_argmax) {
+    __shared__ int s_tgt[SEER_MAX_T];
+    __shared__ int s_draft[SEER_MAX_T];
+    __shared__ int s_par[SEER_MAX_T];
+    __shared__ int s_depth[SEER_MAX_T];
+    __shared__ int s_path[SEER_MAX_T];
+    const int b = blockIdx.x;
+    const int t = threadIdx.x;
+    if (t < T) {
+        const size_t row = static_cast<size_t>(b) * T + t;
+        float best = part_val[row * n_chunks];
+        int best_i = part_idx[row * n_chunks];
+        for (int c = 1; c < n_chunks; ++c) {
+            const float v = part_val[row * n_chunks + c];
+            if (v > best) {  // chunks ascend: strict '>' keeps the lowest index
+                best = v;
+                best_i = part_idx[row * n_chunks + c];
+            }
+        }
+        target_argmax[row] = best_i;
+        s_tgt[t] = best_i;
+        s_draft[t] = draft_tokens[row];
+        int par = tree_parent ? tree_parent[row] : t - 1;
+        if (t == 0) par = -1;
+        if (par < 0 || par >= t) par = (t == 0) ? -1 : -2;  // anything else counts as a padded slot
+        s_par[t] = par;
+        s_path[t] = -1;
+    }
+    __syncthreads();
+    if (t == 0) {
+        uint64_t ok = 1;  // bit t: slot t accepted
+        int win = 0;
+        s_depth[0] = 0;
+        for (int i = 1; i < T; ++i) {
+            const int par = s_par[i];
+            int depth = 0;
+            if (par >= 0 && ((ok >> par) & 1) && s_draft[i] == s_tgt[par]) {
+                ok |= (1ull << i);
+                depth = s_depth[par] + 1;
+                if (depth > s_depth[win]) win = i;
+            }
+            s_depth[i] = depth;
+        }
+        const int len = s_depth[win];
+        accepted_len[b] = len;
+        if (bonus_token) bonus_token[b] = s_tgt[win];
+        int node = win;
+        for (int i = len; i >= 0; --i) {
+            s_path[i] = node;
+            node = s_par[node];
+        }
+    }
+    __syncthreads();
+    if (t < T) accepted_path[static_cast<size_t>(b) * T + t] = s_path[t];
+}
+
+}  // namespace seer
+
+extern "C" size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V) {
+    if (B < 1 || T < 1 || T > SEER_MAX_T || V < 1) return 0;
+    const size_t pairs = static_cast<size_t>(B) * T * seer::accept_num_chunks(V);
+    return pairs * (sizeof(float) + sizeof(int32_t));
+}
+
+extern "C" int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+                           int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
+                           int32_t* bonus_token, int32_t* target_argmax, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    if (B < 0 || V < 1) return SEER_EINVAL;
+    if (T < 1 || T > SEER_MAX_T) return SEER_ESHAPE;
+    if (B == 0) return SEER_OK;
+    if (!logits || !draft_tokens || !accepted_len || !accepted_path || !target_argmax) return SEER_EINVAL;
+    if (static_cast<int64_t>(B) * T * seer::accept_num_chunks(V) > 0x7fffffffLL) return SEER_ESHAPE;
+    const size_t need = seer_accept_workspace(B, T, V);
+    if (!workspace || workspace_bytes < need) return SEER_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return SEER_EALIGN;
+    if (reinterpret_cast<uintptr_t>(logits) % 4 != 0) return SEER_EALIGN;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int n_chunks = seer::accept_num_chunks(V);
+    const size_t pairs = static_cast<size_t>(B) * T * n_chunks;
+    float* part_val = static_cast<float*>(workspace);
+    int* part_idx = reinterpret_cast<int*>(part_val + pairs);
+    const bool vec4 = (V % 4 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0);
+    const dim3 grid(static_cast<unsigned>(pairs));
+    if (vec4) {
+        hipLaunchKernelGGL(seer::argmax_chunks<true>, grid, dim3(seer::kArgmaxThreads), 0, stream, logits, V,
+                           n_chunks, part_val, part_idx);
+    } else {
+        hipLaunchKernelGGL(seer::argmax_chunks<false>, grid, dim3(seer::kArgmaxThreads), 0, stream, logits, V,
+                           n_chunks, part_val, part_idx);
+    }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return static_cast<int>(err);
+    hipLaunchKernelGGL(seer::accept_walk, dim3(B), dim3(seer::kWave), 0, stream, part_val, part_idx, n_chunks,
+                       draft_tokens, tree_parent, T, accepted_len, accepted_path, bonus_token, target_argmax);
+    err = hipGetLastError();
+    return err == hipSuccess ? SEER_OK : static_cast<int>(err);
+}

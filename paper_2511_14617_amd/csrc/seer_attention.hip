@@ -1,0 +1,391 @@
+// seer_verify_attention: entry point, device-side split-K plan, the general
+// (any supported shape) partition kernel, and the split-K combine.
+//
+// What is computed (paper, Section 2.2: the target model verifies all draft
+// tokens of a request in one pass, which beats serial decoding because the
+// context is read from memory once instead of once per token): every one of the
+// T = gamma + 1 verify slots of a request attends to the request's cached
+// prefix and to the draft slots on its own root path (chain or multi-path tree,
+// Section 3.4.2).  One read of a KV page must therefore serve all T slots and
+// all G query heads that share the KV head.
+#include "seer_attention.h"
+
+#include "seer_device.h"
+
+namespace seer {
+
+// ---------------------------------------------------------------------------
+// Plan: one workgroup turns ctx_len[B] into the item table.
+// ---------------------------------------------------------------------------
+constexpr int kPlanThreads = 256;
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ ctx_len, int B, int T,
+                                                            int max_ctx, int target_items, int max_splits,
+                                                            int max_items, PlanHeader* __restrict__ header,
+                                                            int32_t* __restrict__ split_off,
+                                                            WorkItem* __restrict__ items) {
+    __shared__ long long s_sum[kPlanThreads];
+    __shared__ int s_cnt[kPlanThreads];
+    __shared__ int s_bad;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+
+    // total tokens of the valid requests
+    long long local = 0;
+    for (int b = tid; b < B; b += kPlanThreads) {
+        const int n = ctx_len[b];
+        if (n >= T && n <= max_ctx) local += n;
+        else s_bad = 1;
+    }
+    s_sum[tid] = local;
+    __syncthreads();
+    for (int o = kPlanThreads / 2; o > 0; o >>= 1) {
+        if (tid < o) s_sum[tid] += s_sum[tid + o];
+        __syncthreads();
+    }
+    const long long total = s_sum[0];
+    long long want = (total + target_items - 1) / target_items;
+    if (want < kPartAlign) want = kPartAlign;
+    const int part_len = static_cast<int>((want + kPartAlign - 1) / kPartAlign * kPartAlign);
+
+    // partitions per request; thread `tid` owns a contiguous run of requests
+    const int per = (B + kPlanThreads - 1) / kPlanThreads;
+    const int b0 = min(B, tid * per), b1 = min(B, b0 + per);
+    auto splits_of = [&](int n, int& len) -> int {
+        if (n < T || n > max_ctx) { len = 0; return 0; }
+        int ns = (n + part_len - 1) / part_len;
+        if (ns > max_splits) ns = max_splits;
+        len = ((n + ns - 1) / ns + kPartAlign - 1) / kPartAlign * kPartAlign;  // even cut, tile aligned
+        return (n + len - 1) / len;
+    };
+    int cnt = 0;
+    for (int b = b0; b < b1; ++b) {
+        int len;
+        cnt += splits_of(ctx_len[b], len);
+    }
+    s_cnt[tid] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int i = 0; i < kPlanThreads; ++i) {
+            const int c = s_cnt[i];
+            s_cnt[i] = run;
+            run += c;
+        }
+        header->status = s_bad ? 1u : 0u;
+        header->n_items = run < max_items ? run : max_items;
+        header->part_len = part_len;
+        header->reserved = 0;
+        split_off[B] = run;
+    }
+    __syncthreads();
+    int off = s_cnt[tid];
+    for (int b = b0; b < b1; ++b) {
+        const int n = ctx_len[b];
+        int len;
+        const int ns = splits_of(n, len);
+        split_off[b] = off;
+        for (int s = 0; s < ns; ++s) {
+            if (off + s < max_items) {
+                WorkItem it;
+                it.b = b;
+                it.begin = s * len;
+                it.end = min(n, (s + 1) * len);
+                it.split = s;
+                items[off + s] = it;
+            }
+        }
+        off += ns;
+    }
+}
+
+hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t stream) {
+    const long long max_ctx_ll = static_cast<long long>(a.max_pages) * a.P;
+    const int max_ctx = max_ctx_ll > 0x7fffffffLL ? 0x7fffffff : static_cast<int>(max_ctx_ll);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, a.ctx_len, a.B, a.T, max_ctx,
+                       w.target_items, w.max_splits, w.max_items, a.header, const_cast<int32_t*>(a.split_off),
+                       const_cast<WorkItem*>(a.items));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// General partition kernel: one workgroup per (item, query head, slot).
+// Plain vector arithmetic, one KV token per wave iteration: lanes split the
+// head dimension, the dot product is reduced with shuffles, the running
+// (max, sum, acc) is kept per wave and the four waves are merged through LDS.
+// Slow, but it covers every supported head size and page size, and serves as
+// the on-device cross-check of the tiled kernels.
+// ---------------------------------------------------------------------------
+constexpr int kGenThreads = 256;
+constexpr int kGenWaves = kGenThreads / kWave;
+
+template <int DQK, int DV>
+__global__ __launch_bounds__(kGenThreads) void attn_general_kernel(AttnArgs a) {
+    constexpr int NQ = (DQK + 127) / 128;  // bf16 pairs per lane
+    constexpr int NV = (DV + 127) / 128;
+    const int item_idx = blockIdx.x;
+    if (item_idx >= a.header->n_items) return;
+    const WorkItem item = a.items[item_idx];
+    const int hq = blockIdx.y, t = blockIdx.z;
+    const int kvh = hq / a.G;
+    const int b = item.b;
+    const int n = a.ctx_len[b];
+    const int n0 = n - a.T;
+    const uint64_t word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
+                                      : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const uint16_t* __restrict__ kp = static_cast<const uint16_t*>(a.k_pages);
+    const uint16_t* __restrict__ vp = static_cast<const uint16_t*>(a.v_pages);
+    const uint16_t* __restrict__ qrow =
+        static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * DQK;
+
+    float qlo[NQ], qhi[NQ];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        const int d = 2 * lane + 128 * i;
+        const uint32_t pr = (d < DQK) ? *reinterpret_cast<const uint32_t*>(qrow + d) : 0u;
+        qlo[i] = bf16lo_to_f32(pr);
+        qhi[i] = bf16hi_to_f32(pr);
+    }
+    float m = kNegInf, l = 0.f;
+    float alo[NV], ahi[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) alo[i] = ahi[i] = 0.f;
+
+    const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
+    bool bad_page = false;
+    for (int j = item.begin + wave; j < item.end; j += kGenWaves) {
+        const bool visible = (j < n0) || ((word >> (j - n0)) & 1ull);
+        if (!visible) continue;  // uniform across the wave
+        int page = table[j / a.P];
+        if (page < 0 || page >= a.num_pages) {
+            bad_page = true;
+            page = min(max(page, 0), a.num_pages - 1);
+        }
+        const size_t tok = (static_cast<size_t>(page) * a.Hkv + kvh) * a.P + (j % a.P);
+        const uint16_t* __restrict__ krow = kp + tok * DQK;
+        float part = 0.f;
+        uint32_t kpair[NQ];
+#pragma unroll
+        for (int i = 0; i < NQ; ++i) {
+            const int d = 2 * lane + 128 * i;
+            kpair[i] = (d < DQK) ? *reinterpret_cast<const uint32_t*>(krow + d) : 0u;
+            part = fmaf(qlo[i], bf16lo_to_f32(kpair[i]), part);
+            part = fmaf(qhi[i], bf16hi_to_f32(kpair[i]), part);
+        }
+        const float s = wave_sum(part) * a.scale_log2;
+        const float m_new = fmaxf(m, s);
+        const float alpha = fast_exp2(m - m_new);
+        const float p = fast_exp2(s - m_new);
+        l = l * alpha + p;
+        m = m_new;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int d = 2 * lane + 128 * i;
+            uint32_t vpair;
+            if (vp) vpair = (d < DV) ? *reinterpret_cast<const uint32_t*>(vp + tok * DV + d) : 0u;
+            else vpair = (i < NQ) ? kpair[i < NQ ? i : 0] : 0u;  // shared latent: V = K[..., :DV]
+            alo[i] = fmaf(p, bf16lo_to_f32(vpair), alo[i] * alpha);
+            ahi[i] = fmaf(p, bf16hi_to_f32(vpair), ahi[i] * alpha);
+        }
+    }
+    if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
+
+    __shared__ float s_m[kGenWaves], s_l[kGenWaves];
+    __shared__ float s_acc[kGenWaves][DV];
+    if (lane == 0) {
+        s_m[wave] = m;
+        s_l[wave] = l;
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int d = 2 * lane + 128 * i;
+        if (d < DV) {
+            s_acc[wave][d] = alo[i];
+            s_acc[wave][d + 1] = ahi[i];
+        }
+    }
+    __syncthreads();
+    float M = s_m[0];
+#pragma unroll
+    for (int w = 1; w < kGenWaves; ++w) M = fmaxf(M, s_m[w]);
+    float f[kGenWaves];
+    float L = 0.f;
+#pragma unroll
+    for (int w = 0; w < kGenWaves; ++w) {
+        f[w] = (s_m[w] == kNegInf) ? 0.f : fast_exp2(s_m[w] - M);
+        L += s_l[w] * f[w];
+    }
+    const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
+    if (threadIdx.x == 0) {
+        a.part_ml[2 * prow] = M;
+        a.part_ml[2 * prow + 1] = L;
+    }
+    for (int d = threadIdx.x; d < DV; d += kGenThreads) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kGenWaves; ++w) v += s_acc[w][d] * f[w];
+        a.part_acc[prow * DV + d] = v;
+    }
+}
+
+bool general_supports(int Dqk, int Dv) {
+    return (Dqk == 64 && Dv == 64) || (Dqk == 128 && Dv == 128) || (Dqk == 256 && Dv == 256) ||
+           (Dqk == 192 && Dv == 128) || (Dqk == 576 && Dv == 512);
+}
+
+hipError_t launch_general(const AttnArgs& a, hipStream_t stream) {
+    const dim3 grid(a.max_items, a.Hq, a.T), block(kGenThreads);
+#define SEER_GEN_CASE(DQK_, DV_)                                                                   \
+    if (a.Dqk == DQK_ && a.Dv == DV_) {                                                            \
+        hipLaunchKernelGGL((attn_general_kernel<DQK_, DV_>), grid, block, 0, stream, a);           \
+        return hipGetLastError();                                                                  \
+    }
+    SEER_GEN_CASE(64, 64)
+    SEER_GEN_CASE(128, 128)
+    SEER_GEN_CASE(256, 256)
+    SEER_GEN_CASE(192, 128)
+    SEER_GEN_CASE(576, 512)
+#undef SEER_GEN_CASE
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------
+// Combine: out = sum_s acc_s * 2^(m_s - M) / sum_s l_s * 2^(m_s - M), M = max_s m_s.
+// One workgroup per output row (b, t, h).
+// ---------------------------------------------------------------------------
+constexpr int kCombineThreads = 128;
+
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnArgs a) {
+    const size_t row = blockIdx.x;  // (b*T + t)*Hq + h
+    const int per_b = a.T * a.Hq;
+    const int b = static_cast<int>(row / per_b);
+    const int r = static_cast<int>(row - static_cast<size_t>(b) * per_b);
+    const int first = a.split_off[b];
+    int ns = a.split_off[b + 1] - first;
+    if (first + ns > a.max_items) ns = max(0, a.max_items - first);
+    uint16_t* __restrict__ out = static_cast<uint16_t*>(a.out) + row * a.Dv;
+
+    float M = kNegInf;
+    for (int s = 0; s < ns; ++s)
+        M = fmaxf(M, a.part_ml[2 * ((static_cast<size_t>(first) + s) * per_b + r)]);
+    float L = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        const size_t prow = (static_cast<size_t>(first) + s) * per_b + r;
+        const float ms = a.part_ml[2 * prow];
+        if (ms != kNegInf) L += a.part_ml[2 * prow + 1] * fast_exp2(ms - M);
+    }
+    const float inv = (L > 0.f) ? 1.f / L : 0.f;
+    for (int d = threadIdx.x; d < a.Dv; d += kCombineThreads) {
+        float v = 0.f;
+        for (int s = 0; s < ns; ++s) {
+            const size_t prow = (static_cast<size_t>(first) + s) * per_b + r;
+            const float ms = a.part_ml[2 * prow];
+            if (ms != kNegInf) v += a.part_acc[prow * a.Dv + d] * fast_exp2(ms - M);
+        }
+        out[d] = f32_to_bf16(v * inv);
+    }
+}
+
+hipError_t launch_combine(const AttnArgs& a, hipStream_t stream) {
+    const size_t rows = static_cast<size_t>(a.B) * a.T * a.Hq;
+    hipLaunchKernelGGL(combine_kernel, dim3(static_cast<unsigned>(rows)), dim3(kCombineThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace seer
+
+// ---------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------
+namespace {
+
+int validate_params(const seer_attn_params* p) {
+    if (!p) return SEER_EINVAL;
+    if (p->B < 0 || p->num_pages < 1 || p->max_pages_per_seq < 1 || p->page_size < 1) return SEER_EINVAL;
+    if (p->T < 1 || p->T > SEER_MAX_T || p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SEER_ESHAPE;
+    if (p->max_splits < 0 || p->max_splits > 256) return SEER_ESHAPE;
+    if (p->Hq > 65535 || p->T * (int64_t)p->Hq * p->B > 0x7fffffffLL) return SEER_ESHAPE;
+    if (!(p->scale == p->scale)) return SEER_EINVAL;
+    if (!seer::general_supports(p->Dqk, p->Dv)) return SEER_EUNSUPPORTED;
+    if (p->kv_shared_latent && p->Dv > p->Dqk) return SEER_ESHAPE;
+    return SEER_OK;
+}
+
+}  // namespace
+
+extern "C" size_t seer_verify_attention_workspace(const seer_attn_params* p) {
+    if (validate_params(p) != SEER_OK || p->B == 0) return 0;
+    return seer::workspace_layout(*p).total;
+}
+
+extern "C" size_t seer_verify_attention_status_offset(void) { return offsetof(seer::PlanHeader, status); }
+
+extern "C" int seer_verify_attention(void* out, const void* q, const void* k_pages, const void* v_pages,
+                                     const int32_t* block_table, const int32_t* ctx_len,
+                                     const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+    const int rc = validate_params(p);
+    if (rc != SEER_OK) return rc;
+    if (p->B == 0) return SEER_OK;
+    if (!out || !q || !k_pages || !block_table || !ctx_len) return SEER_EINVAL;
+    if (p->kv_shared_latent ? (v_pages != nullptr) : (v_pages == nullptr)) return SEER_EINVAL;
+    const seer::WorkspaceLayout w = seer::workspace_layout(*p);
+    if (!workspace || workspace_bytes < w.total) return SEER_EWORKSPACE;
+    auto misaligned = [](const void* ptr, uintptr_t a) { return reinterpret_cast<uintptr_t>(ptr) % a != 0; };
+    if (misaligned(out, 16) || misaligned(q, 16) || misaligned(k_pages, 16) || misaligned(v_pages, 16) ||
+        misaligned(workspace, 256) || misaligned(block_table, 4) || misaligned(ctx_len, 4) ||
+        misaligned(tree_mask, 8))
+        return SEER_EALIGN;
+
+    char* ws = static_cast<char*>(workspace);
+    seer::AttnArgs a{};
+    a.out = out;
+    a.q = q;
+    a.k_pages = k_pages;
+    a.v_pages = v_pages;
+    a.block_table = block_table;
+    a.ctx_len = ctx_len;
+    a.tree_mask = tree_mask;
+    a.header = reinterpret_cast<seer::PlanHeader*>(ws + w.off_header);
+    a.split_off = reinterpret_cast<const int32_t*>(ws + w.off_split);
+    a.items = reinterpret_cast<const seer::WorkItem*>(ws + w.off_items);
+    a.part_ml = reinterpret_cast<float*>(ws + w.off_ml);
+    a.part_acc = reinterpret_cast<float*>(ws + w.off_acc);
+    a.B = p->B;
+    a.T = p->T;
+    a.Hq = p->Hq;
+    a.Hkv = p->Hkv;
+    a.G = p->Hq / p->Hkv;
+    a.Dqk = p->Dqk;
+    a.Dv = p->Dv;
+    a.P = p->page_size;
+    a.num_pages = p->num_pages;
+    a.max_pages = p->max_pages_per_seq;
+    a.max_items = w.max_items;
+    a.scale_log2 = p->scale * seer::kLog2e;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t err = seer::launch_plan(a, w, stream);
+    if (err != hipSuccess) return static_cast<int>(err);
+    err = seer::launch_general(a, stream);
+    if (err != hipSuccess) return static_cast<int>(err);
+    err = seer::launch_combine(a, stream);
+    return err == hipSuccess ? SEER_OK : static_cast<int>(err);
+}
+
+extern "C" const char* seer_strerror(int code) {
+    switch (code) {
+        case SEER_OK: return "ok";
+        case SEER_EINVAL: return "null pointer or non-positive size";
+        case SEER_ESHAPE: return "shape outside the supported range";
+        case SEER_EUNSUPPORTED: return "no kernel for these head dimensions";
+        case SEER_EWORKSPACE: return "workspace missing or too small";
+        case SEER_EALIGN: return "pointer not aligned as required";
+        default: break;
+    }
+    if (code > 0) return hipGetErrorString(static_cast<hipError_t>(code));
+    return "unknown seer error";
+}

@@ -1,0 +1,122 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the header
+declares, sizes workspaces, and turns bad arguments into SEER_E* codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2511_14617_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library()
+    return binding.load_library()
+
+
+def _params(**kw):
+    from paper_2511_14617_amd.binding import SeerAttnParams
+    base = dict(B=4, T=5, Hq=8, Hkv=2, Dqk=128, Dv=128, page_size=16, num_pages=100, max_pages_per_seq=32,
+                max_splits=0, kv_shared_latent=0, scale=0.088)
+    base.update(kw)
+    return SeerAttnParams(**base)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "seer_verify.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(seer_[a-z_]+)\s*\(", body))
+    from paper_2511_14617_amd import binding
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_params_struct_matches_header():
+    from paper_2511_14617_amd.binding import SeerAttnParams
+    header = open(os.path.join(ROOT, "include", "seer_verify.h")).read()
+    struct = re.search(r"typedef struct seer_attn_params \{(.*?)\} seer_attn_params;", header, flags=re.S).group(1)
+    struct = re.sub(r"/\*.*?\*/", "", struct, flags=re.S)
+    names = []
+    for decl in struct.split(";"):
+        decl = decl.strip()
+        if decl:
+            names += [n.strip() for n in decl.split(None, 1)[1].split(",")]
+    assert names == [f[0] for f in SeerAttnParams._fields_]
+    assert ctypes.sizeof(SeerAttnParams) == 4 * len(names)
+
+
+def test_workspace_sizes(lib):
+    from paper_2511_14617_amd import binding
+    p = _params()
+    n = binding.seer_verify_attention_workspace(p)
+    assert n > 0 and n % 256 == 0
+    assert binding.seer_verify_attention_workspace(_params(T=65)) == 0
+    assert binding.seer_verify_attention_workspace(_params(Dqk=100)) == 0
+    bigger = binding.seer_verify_attention_workspace(_params(B=64, Hq=32, Hkv=8, T=9))
+    assert bigger > n
+    assert binding.seer_accept_workspace(4, 5, 1024) == 4 * 5 * 1 * 8
+    assert binding.seer_accept_workspace(4, 5, 8193) == 4 * 5 * 2 * 8
+    assert binding.seer_accept_workspace(4, 65, 10) == 0
+
+
+def test_attention_argument_errors_before_any_launch(lib):
+    from paper_2511_14617_amd import binding as b
+    call = lib.seer_verify_attention
+    fake = 0x1000   # never dereferenced: all of these fail on the host
+
+    def run(p, out=fake, q=fake, k=fake, v=fake, bt=fake, cl=fake, mask=None, ws=0x10000, ws_bytes=1 << 40):
+        return call(out, q, k, v, bt, cl, mask, ctypes.byref(p) if p is not None else None, ws, ws_bytes, None)
+
+    assert call(fake, fake, fake, fake, fake, fake, None, None, fake, 0, None) == b.SEER_EINVAL
+    assert run(_params(T=0)) == b.SEER_ESHAPE
+    assert run(_params(T=65)) == b.SEER_ESHAPE
+    assert run(_params(Hq=7)) == b.SEER_ESHAPE
+    assert run(_params(max_splits=257)) == b.SEER_ESHAPE
+    assert run(_params(Dqk=100)) == b.SEER_EUNSUPPORTED
+    assert run(_params(Dqk=576, Dv=512, kv_shared_latent=1), v=None, ws_bytes=0) == b.SEER_EWORKSPACE
+    assert run(_params(num_pages=0)) == b.SEER_EINVAL
+    assert run(_params(scale=float("nan"))) == b.SEER_EINVAL
+    assert run(_params(), q=None) == b.SEER_EINVAL
+    assert run(_params(), v=None) == b.SEER_EINVAL                     # separate pools need v_pages
+    assert run(_params(kv_shared_latent=1)) == b.SEER_EINVAL           # shared latent forbids v_pages
+    assert run(_params(), ws=None) == b.SEER_EWORKSPACE
+    assert run(_params(), ws_bytes=1024) == b.SEER_EWORKSPACE
+    assert run(_params(), q=fake + 2) == b.SEER_EALIGN
+    assert run(_params(), ws=0x10010) == b.SEER_EALIGN
+    assert run(_params(B=0)) == b.SEER_OK                              # empty batch: nothing to do
+    for code in (0, -1, -2, -3, -4, -5, 1, -99):
+        assert isinstance(b.seer_strerror(code), str) and b.seer_strerror(code)
+
+
+def test_accept_argument_errors_before_any_launch(lib):
+    from paper_2511_14617_amd import binding as b
+    call = lib.seer_accept
+    fake = 0x1000
+
+    def run(B=4, T=5, V=1000, logits=fake, draft=fake, parent=None, alen=fake, path=fake, bonus=None, tgt=fake,
+            ws=0x10000, ws_bytes=1 << 30):
+        return call(logits, draft, parent, B, T, V, alen, path, bonus, tgt, ws, ws_bytes, None)
+
+    assert run(T=0) == b.SEER_ESHAPE
+    assert run(T=65) == b.SEER_ESHAPE
+    assert run(V=0) == b.SEER_EINVAL
+    assert run(B=-1) == b.SEER_EINVAL
+    assert run(logits=None) == b.SEER_EINVAL
+    assert run(tgt=None) == b.SEER_EINVAL
+    assert run(ws=None) == b.SEER_EWORKSPACE
+    assert run(ws_bytes=8) == b.SEER_EWORKSPACE
+    assert run(ws=0x10004) == b.SEER_EALIGN
+    assert run(logits=fake + 2) == b.SEER_EALIGN
+    assert run(B=0) == b.SEER_OK
+
+
+def test_product_path_fails_loudly_without_the_library(tmp_path, monkeypatch):
+    from paper_2511_14617_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libseer_verify.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()

@@ -1,0 +1,148 @@
+"""GPU parity for seer_verify_attention against the CPU oracle, through the C ABI.
+Sizes here are ones the oracle finishes in seconds; they still span several
+KV tiles, several split-K partitions and ragged last pages."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_14617_amd import workloads as W
+from gpu_util import assert_attention_close, attention_device_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle(inp):
+    return oracle.verify_attention(inp.q, inp.k_pages, inp.v_pages, inp.block_table, inp.ctx_len, inp.tree_mask,
+                                   inp.scale, Dv=inp.cfg.Dv)
+
+
+def _gpu(inp, **kw):
+    from paper_2511_14617_amd import binding
+    d = attention_device_inputs(inp)
+    out = binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
+                                        d["tree_mask"], inp.scale, Dv=inp.cfg.Dv, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+CASES = {
+    "tiny_chain": (W.CONFIGS[1], {}),
+    "chain_T9_multi_split": (W.CONFIGS[2].scaled(B=6, group_size=3, ctx=("uniform", 600, 3000)), {}),
+    "chain_T17": (W.CONFIGS[3].scaled(B=2, ctx=("uniform", 1500, 2600)), {}),
+    "tree_T33": (W.CONFIGS[5].scaled(B=5, group_size=5, ctx=("lognormal", 900, 0.8, 100, 2500)),
+                 {"dedup_fraction": 0.4}),
+    "mla_latent": (W.CONFIGS[4].scaled(B=2, Hq=16, ctx=("uniform", 300, 900)), {}),
+    "T1_decode": (W.CONFIGS[1].scaled(T=1, B=5, ctx=("uniform", 1, 700)), {}),
+    "prefix_shorter_than_draft": (W.CONFIGS[1].scaled(T=9, B=6, ctx=("uniform", 9, 40)), {}),
+    "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
+    "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
+                                           ctx=("uniform", 50, 900)), {}),
+}
+
+
+@pytest.mark.parametrize("values", ["paper", "peaked"])
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_parity_small(name, values):
+    cfg, kw = CASES[name]
+    inp = W.make_attention_inputs(cfg, values=values, **kw)
+    ref = _oracle(inp)
+    out = _gpu(inp)
+    assert_attention_close(out, ref, "%s/%s" % (name, values), hardened=(values == "peaked"))
+
+
+def test_split_invariance_and_split_cap():
+    cfg = W.CONFIGS[2].scaled(B=3, group_size=3, ctx=("uniform", 2000, 5000))
+    inp = W.make_attention_inputs(cfg, values="peaked")
+    ref = _oracle(inp)
+    one = _gpu(inp, max_splits=1)
+    many = _gpu(inp, max_splits=256)
+    two = _gpu(inp, max_splits=2)
+    for o, what in ((one, "S=1"), (many, "S<=256"), (two, "S<=2")):
+        assert_attention_close(o, ref, what, hardened=True)
+
+
+def test_constant_V_and_key_shift():
+    cfg = W.CONFIGS[2].scaled(B=2, group_size=2, ctx=("uniform", 700, 1800))
+    inp = W.make_attention_inputs(cfg, values="peaked")
+    c = W.f32_to_bf16_bits(np.array([0.8125], dtype=np.float32))[0]
+    v_saved = inp.v_pages.copy()
+    inp.v_pages[...] = c
+    out = _gpu(inp).float().cpu().numpy()
+    assert np.abs(out - 0.8125).max() <= 0.8125 * 2.0 ** -8   # bf16 rounding of an fp32 value next to c
+    inp.v_pages = v_saved
+    # scores near +-80 before the max is taken off: keys on a coarse grid plus a large common vector
+    rng = np.random.default_rng(3)
+    kf = rng.integers(-16, 17, size=inp.k_pages.shape).astype(np.float32) / 8.0
+    inp.k_pages = W.f32_to_bf16_bits(kf)
+    base = _oracle(inp)
+    inp.k_pages = W.f32_to_bf16_bits(kf + np.float32(4.0))
+    out = _gpu(inp)
+    assert_attention_close(out, base, "key shift", hardened=True)
+
+
+def test_needles_at_seams_and_masked_needle():
+    cfg = W.CONFIGS[5].scaled(B=3, group_size=3, ctx=("uniform", 700, 1500))
+    inp = W.make_attention_inputs(cfg, values="paper")
+    P = cfg.page_size
+    rng = np.random.default_rng(12)
+    for b in range(cfg.B):
+        n0 = int(inp.ctx_len[b]) - cfg.T
+        for (t, h) in [(0, 0), (5, 9), (17, 31), (32, 16)]:
+            kvh = h // cfg.G
+            qv = W.bf16_bits_to_f32(inp.q[b, t, h])
+            needle = W.f32_to_bf16_bits(qv / np.linalg.norm(qv) * 120.0)
+            anc = [s for s in range(cfg.T) if (int(inp.tree_mask[b, t]) >> s) & 1]
+            non = [s for s in range(cfg.T) if s not in anc]
+            spots = [0, 15, 16, 255, 256, n0 - 1, n0 + anc[-1]]
+            pos = spots[int(rng.integers(0, len(spots)))]
+            pg, sl = inp.block_table[b, pos // P], pos % P
+            inp.k_pages[pg, kvh, sl] = needle
+            inp.v_pages[pg, kvh, sl] = W.f32_to_bf16_bits(rng.standard_normal(cfg.Dv).astype(np.float32) * 3)
+            if non:     # a louder needle on a draft slot this query must not see
+                pos = n0 + non[0]
+                pg, sl = inp.block_table[b, pos // P], pos % P
+                inp.k_pages[pg, kvh, sl] = W.f32_to_bf16_bits(qv / np.linalg.norm(qv) * 200.0)
+                inp.v_pages[pg, kvh, sl] = W.f32_to_bf16_bits(np.full(cfg.Dv, 50.0, dtype=np.float32))
+    ref = _oracle(inp)
+    out = _gpu(inp)
+    assert_attention_close(out, ref, "needles")
+    assert np.abs(ref).max() > 1.0
+
+
+def test_nan_in_slots_past_the_end_is_never_read_into_the_result():
+    cfg = W.CONFIGS[1].scaled(B=4, ctx=("uniform", 100, 400))
+    inp = W.make_attention_inputs(cfg, values="peaked")
+    ref = _oracle(inp)
+    P = cfg.page_size
+    nan = np.uint16(0x7FC0)
+    for b in range(cfg.B):
+        n = int(inp.ctx_len[b])
+        if n % P:
+            pg = inp.block_table[b, (n - 1) // P]
+            inp.k_pages[pg, :, n % P:, :] = nan
+            inp.v_pages[pg, :, n % P:, :] = nan
+    out = _gpu(inp)
+    assert_attention_close(out, ref, "nan tail", hardened=True)
+
+
+def test_bad_ctx_len_is_flagged_not_faulted():
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[1]
+    inp = W.make_attention_inputs(cfg, values="peaked")
+    ref = _oracle(inp)
+    d = attention_device_inputs(inp)
+    bad = inp.ctx_len.copy()
+    bad[1] = cfg.T - 1
+    bad[2] = inp.max_pages_per_seq * cfg.page_size + 1
+    d["ctx_len"] = torch.from_numpy(bad).cuda()
+    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], inp.scale)
+    ws = torch.zeros(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device="cuda")
+    out = binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"], None,
+                                        inp.scale, workspace=ws)
+    torch.cuda.synchronize()
+    assert binding.seer_verify_attention_status(ws) & 1
+    got = out.float().cpu().numpy()
+    assert (got[1] == 0).all() and (got[2] == 0).all()
+    assert_attention_close(out[0:1], ref[0:1], "valid request beside bad ones", hardened=True)
+    assert_attention_close(out[3:4], ref[3:4], "valid request beside bad ones", hardened=True)
