@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the verification hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input that
+is already resident in HBM: seer_verify_attention (plan + partition kernel +
+combine) followed by seer_accept (vocabulary argmax + acceptance walk).
+Workload: the "8B-class grouped rollout" configuration (B=64 requests in 8
+prompt groups, Hq=32, Hkv=8, D=128, 16-token pages, lognormal contexts, k=8
+chain so T=9, V=152064).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+METRIC = "verified tokens/s and verify-attention HBM GB/s (% of peak) on one MI355X"
+
+
+class HipEvents:
+    """hipEvent_t pairs made through the HIP runtime directly: they have to be recorded by the
+    library on the stream it launches on, between its own kernels."""
+
+    def __init__(self, n: int):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a.value, b.value))
+
+    def elapsed_ms(self):
+        out = []
+        for a, b in self.pairs:
+            ms = ctypes.c_float()
+            rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+            assert rc == 0, rc
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def algorithmic_bytes(inp) -> dict:
+    """Bytes the method has to move for one attention call: every KV page some request owns once
+    (that single read serving all T slots and G heads is the point of verification), plus q and out."""
+    cfg = inp.cfg
+    q_bytes = cfg.B * cfg.T * cfg.Hq * cfg.Dqk * 2
+    out_bytes = cfg.B * cfg.T * cfg.Hq * cfg.Dv * 2
+    return {"kv_unique": inp.unique_kv_bytes, "kv_logical": inp.logical_kv_bytes, "q": q_bytes, "out": out_bytes,
+            "total": inp.unique_kv_bytes + q_bytes + out_bytes}
+
+
+def cpu_baseline(att, acc, n_sample_requests: int = 16) -> dict:
+    """The oracle, as it stands, on a bounded sample of the same workload: every k-th request by
+    length rank (so the sample keeps the length mix), all T slots and heads, plus those requests'
+    logits rows.  Reported in the metric's unit (verified tokens/s)."""
+    import oracle
+    cfg = att.cfg
+    order = np.argsort(att.ctx_len, kind="stable")
+    step = max(1, cfg.B // n_sample_requests)
+    pick = np.sort(order[step // 2::step][:n_sample_requests])
+    t0 = time.perf_counter()
+    oracle.verify_attention(att.q[pick], att.k_pages, att.v_pages, att.block_table[pick], att.ctx_len[pick],
+                            None if att.tree_mask is None else att.tree_mask[pick], att.scale, Dv=cfg.Dv)
+    t1 = time.perf_counter()
+    oracle.verify_accept(acc.logits[pick], acc.draft_tokens[pick],
+                         None if acc.tree_parent is None else acc.tree_parent[pick])
+    t2 = time.perf_counter()
+    tokens = len(pick) * cfg.T
+    return {"value": tokens / (t2 - t0), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d of %d requests (every %d-th by length rank; %d KV tokens of %d), all T=%d slots and "
+                      "Hq=%d heads, and their %d logits rows; attention %.2f s + accept %.2f s" % (
+                          len(pick), cfg.B, step, int(att.ctx_len[pick].sum()), int(att.ctx_len.sum()), cfg.T,
+                          cfg.Hq, tokens, t1 - t0, t2 - t1)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (2 = the headline configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attention-only", action="store_true", help="time only seer_verify_attention (profiling aid)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange step; "
+              "no multi-GPU figure is produced). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2511_14617_amd import binding, workloads as W
+    from gpu_util import accept_device_inputs, attention_device_inputs
+
+    binding.load_library()   # fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    cfg = W.CONFIGS[args.config]
+    att = W.make_attention_inputs(cfg)
+    acc = W.make_accept_inputs(cfg, tree_parent=att.tree_parent)
+    d = attention_device_inputs(att)
+    e = accept_device_inputs(acc)
+    dev = d["q"].device
+
+    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], att.scale, Dv=cfg.Dv)
+    ws_att = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device=dev)
+    ws_acc = torch.empty(max(16, binding.seer_accept_workspace(cfg.B, cfg.T, cfg.V)), dtype=torch.uint8, device=dev)
+    out = torch.empty((cfg.B, cfg.T, cfg.Hq, cfg.Dv), dtype=torch.bfloat16, device=dev)
+    acc_out = (torch.empty(cfg.B, dtype=torch.int32, device=dev), torch.empty((cfg.B, cfg.T), dtype=torch.int32, device=dev),
+               torch.empty(cfg.B, dtype=torch.int32, device=dev), torch.empty((cfg.B, cfg.T), dtype=torch.int32, device=dev))
+    events = HipEvents(args.steps)
+
+    def step(ev=None):
+        binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
+                                      d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att, events=ev)
+        if not args.attention_only:
+            binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events.pairs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = events.elapsed_ms()
+    kern_avg_ms = float(np.mean(kern_ms))
+    events.close()
+
+    # split of a step between the two calls (separate, untimed-for-`value` loop)
+    def timed(fn, n=10):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    att_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
+                                                         d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
+                                                         workspace=ws_att))
+    acc_ms = timed(lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc,
+                                               out=acc_out))
+    status = binding.seer_verify_attention_status(ws_att)
+
+    ab = algorithmic_bytes(att)
+    achieved = ab["total"] / (kern_avg_ms * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tfile):
+        with open(tfile) as f:
+            traffic = json.load(f).get("config%d" % cfg.config_id)
+    tokens = cfg.B * cfg.T
+    line = {
+        "metric": METRIC,
+        "value": tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config%d %s: B=%d (%d groups x %d), Hq=%d, Hkv=%d, Dqk=%d, Dv=%d, page=%d, T=%d, "
+                               "V=%d, ctx %s, step = seer_verify_attention + seer_accept" % (
+                                   cfg.config_id, cfg.name, cfg.B, cfg.B // cfg.group_size, cfg.group_size, cfg.Hq,
+                                   cfg.Hkv, cfg.Dqk, cfg.Dv, cfg.page_size, cfg.T, cfg.V, list(cfg.ctx)),
+                   "kv_tokens": int(att.ctx_len.sum()), "seed": cfg.seed,
+                   "attention_only": bool(args.attention_only)},
+        "roofline": {"bound": "hbm", "kernel": "attn_gqa128_kernel (verify-attention partition kernel)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": traffic, "algorithmic_bytes": ab, "kernel_ms_avg": kern_avg_ms,
+                     "kernel_ms_min": float(np.min(kern_ms))},
+        "attention_ms": att_ms, "accept_ms": acc_ms,
+        "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
+        "accept_logits_GBps": acc.logits.nbytes / (acc_ms * 1e-3) / 1e9,
+        "attention_status_word": status,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(att, acc)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -67,13 +67,17 @@ typedef struct seer_attn_params {
     int32_t max_pages_per_seq; /* row stride of block_table                           */
     int32_t max_splits;        /* cap on split-K partitions per request, 1..256; 0 = library default */
     int32_t kv_shared_latent;  /* 0: separate K and V pools; 1: V = first Dv components of K (MLA, absorbed form) */
+    int32_t flags;             /* SEER_ATTN_* bits, normally 0                        */
     float scale;               /* softmax scale applied to q.k                        */
 } seer_attn_params;
 
+/* flags: run the general kernel even where a tiled one exists (for cross-checks). */
+#define SEER_ATTN_GENERAL_KERNEL 1
+
 /* Supported shapes: (Dqk, Dv) in {(64,64), (128,128), (256,256), (192,128),
- * (576,512)}; any page_size >= 1 that is a multiple of 1 (fast kernels exist
- * for page_size 16 with D = 128, and for the shared latent 576/512 with
- * page_size 64; other combinations run a slower general kernel). */
+ * (576,512)} with any page_size >= 1.  Tiled matrix-core kernels exist for
+ * Dqk = Dv = 128 with page_size 16 and G*T <= 256; every other combination
+ * runs a slower general kernel. */
 
 /* Bytes of device scratch seer_verify_attention needs for these params; 0 on
  * invalid params.  Host-only arithmetic. */
@@ -110,6 +114,20 @@ int seer_verify_attention(void* out, const void* q, const void* k_pages, const v
                           const int32_t* block_table, const int32_t* ctx_len,
                           const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Measurement aid: the same call, which also records two caller-created
+ * hipEvent_t (passed as void*) on the stream immediately before and after the
+ * partition kernel -- the kernel that streams the KV pages and dominates the
+ * call -- so that its duration can be read with hipEventElapsedTime without a
+ * profiler.  The plan kernel runs before event_begin, the combine after
+ * event_end.  Results are identical to seer_verify_attention.
+ */
+int seer_verify_attention_timed(void* out, const void* q, const void* k_pages, const void* v_pages,
+                                const int32_t* block_table, const int32_t* ctx_len,
+                                const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
+                                size_t workspace_bytes, void* hip_stream, void* event_begin,
+                                void* event_end);
 
 /* Bytes of device scratch seer_accept needs; 0 on invalid sizes.  Host-only. */
 size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V);

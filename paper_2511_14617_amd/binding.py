@@ -19,14 +19,17 @@ LIB_PATH = os.path.join(_PKG, "libseer_verify.so")
 SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALIGN = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
-           "seer_accept_workspace", "seer_accept", "seer_strerror")
+           "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_strerror")
 
 
 class SeerAttnParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("Dqk", ctypes.c_int32), ("Dv", ctypes.c_int32), ("page_size", ctypes.c_int32),
                 ("num_pages", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
-                ("max_splits", ctypes.c_int32), ("kv_shared_latent", ctypes.c_int32), ("scale", ctypes.c_float)]
+                ("max_splits", ctypes.c_int32), ("kv_shared_latent", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+SEER_ATTN_GENERAL_KERNEL = 1
 
 
 class SeerError(RuntimeError):
@@ -53,6 +56,8 @@ def load_library() -> ctypes.CDLL:
         lib.seer_verify_attention_status_offset.restype = sz
         lib.seer_verify_attention.argtypes = [vp] * 7 + [ctypes.POINTER(SeerAttnParams), vp, sz, vp]
         lib.seer_verify_attention.restype = ctypes.c_int
+        lib.seer_verify_attention_timed.argtypes = lib.seer_verify_attention.argtypes + [vp, vp]
+        lib.seer_verify_attention_timed.restype = ctypes.c_int
         lib.seer_accept_workspace.argtypes = [i32, i32, i32]
         lib.seer_accept_workspace.restype = sz
         lib.seer_accept.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -89,14 +94,14 @@ def _want(t: torch.Tensor, dtype, shape, name: str) -> None:
 
 def attn_params(q: torch.Tensor, k_pages: torch.Tensor, v_pages: Optional[torch.Tensor],
                 block_table: torch.Tensor, scale: float, Dv: Optional[int] = None,
-                max_splits: int = 0) -> SeerAttnParams:
+                max_splits: int = 0, flags: int = 0) -> SeerAttnParams:
     B, T, Hq, Dqk = q.shape
     num_pages, Hkv, P, _ = k_pages.shape
     dv = v_pages.shape[3] if v_pages is not None else Dv
     if dv is None:
         raise ValueError("Dv is needed when the latent is shared (v_pages is None)")
     return SeerAttnParams(B, T, Hq, Hkv, Dqk, dv, P, num_pages, block_table.shape[1], max_splits,
-                          1 if v_pages is None else 0, float(scale))
+                          1 if v_pages is None else 0, flags, float(scale))
 
 
 def seer_verify_attention_workspace(params: SeerAttnParams) -> int:
@@ -106,15 +111,17 @@ def seer_verify_attention_workspace(params: SeerAttnParams) -> int:
 def seer_verify_attention(q: torch.Tensor, k_pages: torch.Tensor, v_pages: Optional[torch.Tensor],
                           block_table: torch.Tensor, ctx_len: torch.Tensor,
                           tree_mask: Optional[torch.Tensor], scale: float, *, Dv: Optional[int] = None,
-                          max_splits: int = 0, out: Optional[torch.Tensor] = None,
+                          max_splits: int = 0, flags: int = 0, out: Optional[torch.Tensor] = None,
                           workspace: Optional[torch.Tensor] = None,
-                          stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                          stream: Optional[torch.cuda.Stream] = None,
+                          events: Optional[Tuple[int, int]] = None) -> torch.Tensor:
     """out[B,T,Hq,Dv] bf16.  q [B,T,Hq,Dqk] bf16; k_pages [num_pages,Hkv,P,Dqk] bf16; v_pages
     [num_pages,Hkv,P,Dv] bf16 or None (shared latent); block_table [B,max_pages] int32; ctx_len [B]
     int32 (counts the T verify slots); tree_mask [B,T] int64 holding the uint64 ancestor bits, or
-    None for a chain.  `out` and `workspace` (uint8) may be passed to avoid allocation."""
+    None for a chain.  `out` and `workspace` (uint8) may be passed to avoid allocation.  `events` = two
+    hipEvent_t handles (ints) to be recorded around the partition kernel (seer_verify_attention_timed)."""
     lib = load_library()
-    p = attn_params(q, k_pages, v_pages, block_table, scale, Dv, max_splits)
+    p = attn_params(q, k_pages, v_pages, block_table, scale, Dv, max_splits, flags)
     _want(q, torch.bfloat16, (p.B, p.T, p.Hq, p.Dqk), "q")
     _want(k_pages, torch.bfloat16, (p.num_pages, p.Hkv, p.page_size, p.Dqk), "k_pages")
     if v_pages is not None:
@@ -130,9 +137,12 @@ def seer_verify_attention(q: torch.Tensor, k_pages: torch.Tensor, v_pages: Optio
     need = int(lib.seer_verify_attention_workspace(ctypes.byref(p)))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    _check(lib.seer_verify_attention(_ptr(out), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
-                                     _ptr(ctx_len), _ptr(tree_mask), ctypes.byref(p), _ptr(workspace),
-                                     workspace.numel(), _stream_handle(stream)))
+    args = (_ptr(out), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _ptr(ctx_len), _ptr(tree_mask),
+            ctypes.byref(p), _ptr(workspace), workspace.numel(), _stream_handle(stream))
+    if events is None:
+        _check(lib.seer_verify_attention(*args))
+    else:
+        _check(lib.seer_verify_attention_timed(*args, events[0], events[1]))
     return out
 
 
@@ -147,7 +157,8 @@ def seer_accept_workspace(B: int, T: int, V: int) -> int:
 
 
 def seer_accept(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: Optional[torch.Tensor], *,
-                workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None
+                workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]] = None
                 ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
     """(accepted_len[B], accepted_path[B,T], bonus_token[B], target_argmax[B,T]), all int32.
     logits [B,T,V] fp32; draft_tokens [B,T] int32; tree_parent [B,T] int32 or None (chain)."""
@@ -158,10 +169,17 @@ def seer_accept(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: O
     if tree_parent is not None:
         _want(tree_parent, torch.int32, (B, T), "tree_parent")
     dev = logits.device
-    alen = torch.empty(B, dtype=torch.int32, device=dev)
-    path = torch.empty((B, T), dtype=torch.int32, device=dev)
-    bonus = torch.empty(B, dtype=torch.int32, device=dev)
-    tgt = torch.empty((B, T), dtype=torch.int32, device=dev)
+    if out is None:
+        alen = torch.empty(B, dtype=torch.int32, device=dev)
+        path = torch.empty((B, T), dtype=torch.int32, device=dev)
+        bonus = torch.empty(B, dtype=torch.int32, device=dev)
+        tgt = torch.empty((B, T), dtype=torch.int32, device=dev)
+    else:
+        alen, path, bonus, tgt = out
+        _want(alen, torch.int32, (B,), "accepted_len")
+        _want(path, torch.int32, (B, T), "accepted_path")
+        _want(bonus, torch.int32, (B,), "bonus_token")
+        _want(tgt, torch.int32, (B, T), "target_argmax")
     need = int(lib.seer_accept_workspace(B, T, V))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)

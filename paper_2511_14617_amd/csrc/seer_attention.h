@@ -85,5 +85,7 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
 hipError_t launch_general(const AttnArgs& a, hipStream_t stream);   // any supported shape
 hipError_t launch_combine(const AttnArgs& a, hipStream_t stream);
 bool general_supports(int Dqk, int Dv);
+bool gqa128_supports(const AttnArgs& a);                            // D = 128, 16-token pages, G*T <= 256
+hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream);
 
 }  // namespace seer

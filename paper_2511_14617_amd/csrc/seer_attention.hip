@@ -307,6 +307,7 @@ int validate_params(const seer_attn_params* p) {
     if (p->B < 0 || p->num_pages < 1 || p->max_pages_per_seq < 1 || p->page_size < 1) return SEER_EINVAL;
     if (p->T < 1 || p->T > SEER_MAX_T || p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SEER_ESHAPE;
     if (p->max_splits < 0 || p->max_splits > 256) return SEER_ESHAPE;
+    if (p->flags & ~SEER_ATTN_GENERAL_KERNEL) return SEER_EINVAL;
     if (p->Hq > 65535 || p->T * (int64_t)p->Hq * p->B > 0x7fffffffLL) return SEER_ESHAPE;
     if (!(p->scale == p->scale)) return SEER_EINVAL;
     if (!seer::general_supports(p->Dqk, p->Dv)) return SEER_EUNSUPPORTED;
@@ -323,10 +324,12 @@ extern "C" size_t seer_verify_attention_workspace(const seer_attn_params* p) {
 
 extern "C" size_t seer_verify_attention_status_offset(void) { return offsetof(seer::PlanHeader, status); }
 
-extern "C" int seer_verify_attention(void* out, const void* q, const void* k_pages, const void* v_pages,
-                                     const int32_t* block_table, const int32_t* ctx_len,
-                                     const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
-                                     size_t workspace_bytes, void* hip_stream) {
+namespace {
+
+int run_verify_attention(void* out, const void* q, const void* k_pages, const void* v_pages,
+                         const int32_t* block_table, const int32_t* ctx_len, const uint64_t* tree_mask,
+                         const seer_attn_params* p, void* workspace, size_t workspace_bytes, void* hip_stream,
+                         hipEvent_t ev_begin, hipEvent_t ev_end) {
     const int rc = validate_params(p);
     if (rc != SEER_OK) return rc;
     if (p->B == 0) return SEER_OK;
@@ -370,10 +373,34 @@ extern "C" int seer_verify_attention(void* out, const void* q, const void* k_pag
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t err = seer::launch_plan(a, w, stream);
     if (err != hipSuccess) return static_cast<int>(err);
-    err = seer::launch_general(a, stream);
+    if (ev_begin && (err = hipEventRecord(ev_begin, stream)) != hipSuccess) return static_cast<int>(err);
+    if (!(p->flags & SEER_ATTN_GENERAL_KERNEL) && seer::gqa128_supports(a)) err = seer::launch_gqa128(a, stream);
+    else err = seer::launch_general(a, stream);
     if (err != hipSuccess) return static_cast<int>(err);
+    if (ev_end && (err = hipEventRecord(ev_end, stream)) != hipSuccess) return static_cast<int>(err);
     err = seer::launch_combine(a, stream);
     return err == hipSuccess ? SEER_OK : static_cast<int>(err);
+}
+
+}  // namespace
+
+extern "C" int seer_verify_attention(void* out, const void* q, const void* k_pages, const void* v_pages,
+                                     const int32_t* block_table, const int32_t* ctx_len,
+                                     const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+    return run_verify_attention(out, q, k_pages, v_pages, block_table, ctx_len, tree_mask, p, workspace,
+                                workspace_bytes, hip_stream, nullptr, nullptr);
+}
+
+extern "C" int seer_verify_attention_timed(void* out, const void* q, const void* k_pages, const void* v_pages,
+                                           const int32_t* block_table, const int32_t* ctx_len,
+                                           const uint64_t* tree_mask, const seer_attn_params* p,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream,
+                                           void* event_begin, void* event_end) {
+    if (!event_begin || !event_end) return SEER_EINVAL;
+    return run_verify_attention(out, q, k_pages, v_pages, block_table, ctx_len, tree_mask, p, workspace,
+                                workspace_bytes, hip_stream, static_cast<hipEvent_t>(event_begin),
+                                static_cast<hipEvent_t>(event_end));
 }
 
 extern "C" const char* seer_strerror(int code) {

@@ -20,7 +20,7 @@ def lib():
 def _params(**kw):
     from paper_2511_14617_amd.binding import SeerAttnParams
     base = dict(B=4, T=5, Hq=8, Hkv=2, Dqk=128, Dv=128, page_size=16, num_pages=100, max_pages_per_seq=32,
-                max_splits=0, kv_shared_latent=0, scale=0.088)
+                max_splits=0, kv_shared_latent=0, flags=0, scale=0.088)
     base.update(kw)
     return SeerAttnParams(**base)
 

@@ -17,6 +17,14 @@ def _oracle(inp):
                                    inp.scale, Dv=inp.cfg.Dv)
 
 
+def _oracle_abs(inp):
+    """sum_j p_j |v_j|: the oracle on the same inputs with the sign bit of every V cleared.  Only
+    meaningful with a separate V pool (with a shared latent, K would change too)."""
+    assert inp.v_pages is not None
+    return oracle.verify_attention(inp.q, inp.k_pages, inp.v_pages & np.uint16(0x7FFF), inp.block_table,
+                                   inp.ctx_len, inp.tree_mask, inp.scale)
+
+
 def _gpu(inp, **kw):
     from paper_2511_14617_amd import binding
     d = attention_device_inputs(inp)
@@ -47,19 +55,32 @@ def test_parity_small(name, values):
     cfg, kw = CASES[name]
     inp = W.make_attention_inputs(cfg, values=values, **kw)
     ref = _oracle(inp)
+    ref_abs = _oracle_abs(inp) if (values == "peaked" and inp.v_pages is not None) else None
     out = _gpu(inp)
-    assert_attention_close(out, ref, "%s/%s" % (name, values), hardened=(values == "peaked"))
+    assert_attention_close(out, ref, "%s/%s" % (name, values), hardened=(values == "peaked"), ref_abs=ref_abs)
+
+
+@pytest.mark.parametrize("name", ["tiny_chain", "chain_T9_multi_split", "tree_T33"])
+def test_parity_small_general_kernel(name):
+    """The general kernel on shapes that normally take the tiled one."""
+    from paper_2511_14617_amd import binding
+    cfg, kw = CASES[name]
+    inp = W.make_attention_inputs(cfg, values="peaked", **kw)
+    ref = _oracle(inp)
+    out = _gpu(inp, flags=binding.SEER_ATTN_GENERAL_KERNEL)
+    assert_attention_close(out, ref, name + "/general", hardened=True)
 
 
 def test_split_invariance_and_split_cap():
     cfg = W.CONFIGS[2].scaled(B=3, group_size=3, ctx=("uniform", 2000, 5000))
     inp = W.make_attention_inputs(cfg, values="peaked")
     ref = _oracle(inp)
+    ref_abs = _oracle_abs(inp)
     one = _gpu(inp, max_splits=1)
     many = _gpu(inp, max_splits=256)
     two = _gpu(inp, max_splits=2)
     for o, what in ((one, "S=1"), (many, "S<=256"), (two, "S<=2")):
-        assert_attention_close(o, ref, what, hardened=True)
+        assert_attention_close(o, ref, what, hardened=True, ref_abs=ref_abs)
 
 
 def test_constant_V_and_key_shift():
@@ -78,7 +99,7 @@ def test_constant_V_and_key_shift():
     base = _oracle(inp)
     inp.k_pages = W.f32_to_bf16_bits(kf + np.float32(4.0))
     out = _gpu(inp)
-    assert_attention_close(out, base, "key shift", hardened=True)
+    assert_attention_close(out, base, "key shift", hardened=True, ref_abs=_oracle_abs(inp))
 
 
 def test_needles_at_seams_and_masked_needle():
@@ -106,7 +127,7 @@ def test_needles_at_seams_and_masked_needle():
                 inp.v_pages[pg, kvh, sl] = W.f32_to_bf16_bits(np.full(cfg.Dv, 50.0, dtype=np.float32))
     ref = _oracle(inp)
     out = _gpu(inp)
-    assert_attention_close(out, ref, "needles")
+    assert_attention_close(out, ref, "needles", ref_abs=_oracle_abs(inp))
     assert np.abs(ref).max() > 1.0
 
 
@@ -122,8 +143,9 @@ def test_nan_in_slots_past_the_end_is_never_read_into_the_result():
             pg = inp.block_table[b, (n - 1) // P]
             inp.k_pages[pg, :, n % P:, :] = nan
             inp.v_pages[pg, :, n % P:, :] = nan
+    ref_abs = _oracle_abs(W.make_attention_inputs(cfg, values="peaked"))
     out = _gpu(inp)
-    assert_attention_close(out, ref, "nan tail", hardened=True)
+    assert_attention_close(out, ref, "nan tail", hardened=True, ref_abs=ref_abs)
 
 
 def test_bad_ctx_len_is_flagged_not_faulted():
@@ -144,5 +166,6 @@ def test_bad_ctx_len_is_flagged_not_faulted():
     assert binding.seer_verify_attention_status(ws) & 1
     got = out.float().cpu().numpy()
     assert (got[1] == 0).all() and (got[2] == 0).all()
-    assert_attention_close(out[0:1], ref[0:1], "valid request beside bad ones", hardened=True)
-    assert_attention_close(out[3:4], ref[3:4], "valid request beside bad ones", hardened=True)
+    ref_abs = _oracle_abs(inp)
+    assert_attention_close(out[0:1], ref[0:1], "valid request beside bad ones", hardened=True, ref_abs=ref_abs[0:1])
+    assert_attention_close(out[3:4], ref[3:4], "valid request beside bad ones", hardened=True, ref_abs=ref_abs[3:4])
