@@ -11,52 +11,75 @@
 namespace seer {
 
 // Split-K work is planned ON THE DEVICE from ctx_len (the host never sees the
-// lengths, so it cannot size partitions without a synchronisation).  The plan
-// kernel cuts every request into partitions of about equal length such that
-// the launch has enough workgroups to fill 256 CUs however the lengths are
-// distributed -- a batch of a few 100k-token stragglers and a batch of several
-// hundred short requests both end up with a few thousand workgroups.
+// lengths, so it cannot size partitions without a synchronisation).
+//
+// Balanced ("stream") partitioning: per KV head, the 32-token tiles of all
+// requests are laid end to end, request after request, and that line is cut
+// into W equal stretches of L tiles, one per workgroup.  W x Hkv is chosen to
+// be what the GPU holds at once, so there is a single round of workgroups and
+// every one of them streams the same number of KV bytes, whatever the mix of
+// lengths -- eight 100k-token stragglers and several hundred short requests
+// both fill all 256 CUs.  A stretch that crosses a request boundary yields one
+// partial result per request it touches; request b therefore owns
+// n_parts(b) = last_wg(b) - first_wg(b) + 1 consecutive partial slots starting at
+// split_off[b], and the combine kernel merges them.
 struct PlanHeader {
     uint32_t status;     // bit 0: bad ctx_len somewhere; bit 1: page id out of range
-    int32_t n_items;     // number of (request, partition) items
-    int32_t part_len;    // nominal partition length in tokens
-    int32_t reserved;
+    int32_t n_items;     // number of (request, stretch) pieces = partial slots in use
+    int32_t tiles_per_wg;  // L; 0 = one workgroup per request (max_splits == 1)
+    int32_t total_tiles;   // tiles per KV head over all requests
 };
 
 struct WorkItem {
     int32_t b;       // request
-    int32_t begin;   // first logical KV position of the partition
+    int32_t begin;   // first logical KV position of the piece
     int32_t end;     // one past the last
-    int32_t split;   // partition index inside the request
+    int32_t split;   // index of the piece inside the request
 };
 
-constexpr int kPartAlign = 256;        // partition lengths are multiples of this many tokens
+constexpr int kPlanTile = 32;          // tokens per scheduling tile
+constexpr int kMinTilesPerWg = 4;      // do not cut finer than 128 tokens
 constexpr int kDefaultMaxSplits = 256;
-constexpr int kTargetWorkgroups = 2048;  // aimed-at (item x kv-head) workgroups per launch
+constexpr int kNumCU = 256;            // MI355X
 
 struct WorkspaceLayout {
     int max_items;
-    int target_items;    // (request, partition) items the plan aims for
+    int wgs_per_head;    // W (balanced mode) or B (one workgroup per request)
     int max_splits;
-    size_t off_header, off_split, off_items, off_ml, off_acc, total;
+    size_t off_header, off_split, off_tiles, off_first, off_items, off_ml, off_acc, total;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workgroups of the partition kernel that one CU holds at once, by kernel shape.
+inline int resident_wgs_per_cu(const seer_attn_params& p) {
+    const bool tiled = p.Dqk == 128 && p.Dv == 128 && p.page_size == 16 && !p.kv_shared_latent &&
+                       !(p.flags & SEER_ATTN_GENERAL_KERNEL);
+    if (!tiled) return 4;
+    const int waves = ((p.Hq / p.Hkv) * p.T + 31) / 32;   // one wave per 32 query rows
+    return waves <= 2 ? 4 : (waves <= 4 ? 2 : 1);
+}
 
 // Host-only arithmetic; the plan kernel is given the same numbers.
 inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
     WorkspaceLayout w{};
     w.max_splits = p.max_splits > 0 ? p.max_splits : kDefaultMaxSplits;
-    w.target_items = kTargetWorkgroups / p.Hkv;
-    if (w.target_items < 1) w.target_items = 1;
-    // sum_b ceil(n_b / L) <= sum_b n_b / L + B <= target_items + B
-    const int64_t bound = static_cast<int64_t>(w.target_items) + p.B;
-    const int64_t cap = static_cast<int64_t>(p.B) * w.max_splits;
-    w.max_items = static_cast<int>(bound < cap ? bound : cap);
+    if (w.max_splits == 1) {
+        w.wgs_per_head = p.B;
+        w.max_items = p.B;
+    } else {
+        w.wgs_per_head = kNumCU * resident_wgs_per_cu(p) / p.Hkv;
+        if (w.wgs_per_head < 1) w.wgs_per_head = 1;
+        // a stretch adds one piece per request boundary it crosses: pieces <= W + B
+        w.max_items = w.wgs_per_head + p.B;
+    }
     const size_t rows = static_cast<size_t>(w.max_items) * p.T * p.Hq;
+    const size_t per_b = sizeof(int32_t) * (static_cast<size_t>(p.B) + 1);
     w.off_header = 0;
     w.off_split = 256;
-    w.off_items = align_up(w.off_split + sizeof(int32_t) * (static_cast<size_t>(p.B) + 1), 256);
+    w.off_tiles = align_up(w.off_split + per_b, 256);
+    w.off_first = align_up(w.off_tiles + per_b, 256);
+    w.off_items = align_up(w.off_first + sizeof(int32_t) * static_cast<size_t>(w.wgs_per_head), 256);
     w.off_ml = align_up(w.off_items + sizeof(WorkItem) * static_cast<size_t>(w.max_items), 256);
     w.off_acc = align_up(w.off_ml + 2 * sizeof(float) * rows, 256);
     w.total = align_up(w.off_acc + sizeof(float) * rows * p.Dv, 256);
@@ -73,11 +96,13 @@ struct AttnArgs {
     const int32_t* ctx_len;
     const uint64_t* tree_mask;
     PlanHeader* header;
-    const int32_t* split_off;   // [B+1]
+    const int32_t* split_off;   // [B+1] first partial slot of each request
+    const int32_t* tile_off;    // [B+1] first tile of each request on the per-head tile line
+    const int32_t* wg_first;    // [wgs_per_head] request in which each workgroup's stretch starts, -1 = idle
     const WorkItem* items;
     float* part_ml;             // [max_items][T][Hq][2]  (running max in log2 units, sum)
     float* part_acc;            // [max_items][T][Hq][Dv] unnormalised
-    int32_t B, T, Hq, Hkv, G, Dqk, Dv, P, num_pages, max_pages, max_items;
+    int32_t B, T, Hq, Hkv, G, Dqk, Dv, P, num_pages, max_pages, max_items, wgs_per_head;
     float scale_log2;           // scale * log2(e): scores are kept in base-2 units
 };
 

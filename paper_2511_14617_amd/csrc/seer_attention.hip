@@ -15,97 +15,152 @@
 namespace seer {
 
 // ---------------------------------------------------------------------------
-// Plan: one workgroup turns ctx_len[B] into the item table.
+// Plan: one workgroup turns ctx_len[B] into the tile line, the stretch of every
+// partition workgroup, and the table of (request, stretch) pieces.
 // ---------------------------------------------------------------------------
 constexpr int kPlanThreads = 256;
 
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ ctx_len, int B, int T,
-                                                            int max_ctx, int target_items, int max_splits,
-                                                            int max_items, PlanHeader* __restrict__ header,
-                                                            int32_t* __restrict__ split_off,
-                                                            WorkItem* __restrict__ items) {
-    __shared__ long long s_sum[kPlanThreads];
-    __shared__ int s_cnt[kPlanThreads];
+struct PlanArgs {
+    const int32_t* ctx_len;
+    int B, T, max_ctx, wgs_per_head, max_splits, max_items;
+    PlanHeader* header;
+    int32_t* split_off;
+    int32_t* tile_off;
+    int32_t* wg_first;
+    WorkItem* items;
+};
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
+    __shared__ int s_scan[kPlanThreads];
+    __shared__ int s_max[kPlanThreads];
     __shared__ int s_bad;
     const int tid = threadIdx.x;
     if (tid == 0) s_bad = 0;
+    for (int w = tid; w < p.wgs_per_head; w += kPlanThreads) p.wg_first[w] = -1;
     __syncthreads();
 
-    // total tokens of the valid requests
-    long long local = 0;
-    for (int b = tid; b < B; b += kPlanThreads) {
-        const int n = ctx_len[b];
-        if (n >= T && n <= max_ctx) local += n;
-        else s_bad = 1;
-    }
-    s_sum[tid] = local;
-    __syncthreads();
-    for (int o = kPlanThreads / 2; o > 0; o >>= 1) {
-        if (tid < o) s_sum[tid] += s_sum[tid + o];
-        __syncthreads();
-    }
-    const long long total = s_sum[0];
-    long long want = (total + target_items - 1) / target_items;
-    if (want < kPartAlign) want = kPartAlign;
-    const int part_len = static_cast<int>((want + kPartAlign - 1) / kPartAlign * kPartAlign);
-
-    // partitions per request; thread `tid` owns a contiguous run of requests
-    const int per = (B + kPlanThreads - 1) / kPlanThreads;
-    const int b0 = min(B, tid * per), b1 = min(B, b0 + per);
-    auto splits_of = [&](int n, int& len) -> int {
-        if (n < T || n > max_ctx) { len = 0; return 0; }
-        int ns = (n + part_len - 1) / part_len;
-        if (ns > max_splits) ns = max_splits;
-        len = ((n + ns - 1) / ns + kPartAlign - 1) / kPartAlign * kPartAlign;  // even cut, tile aligned
-        return (n + len - 1) / len;
+    // thread `tid` owns a contiguous run of requests
+    const int per = (p.B + kPlanThreads - 1) / kPlanThreads;
+    const int b0 = min(p.B, tid * per), b1 = min(p.B, b0 + per);
+    auto tiles_of = [&](int b) -> int {
+        const int n = p.ctx_len[b];
+        if (n < p.T || n > p.max_ctx) return 0;   // flagged, gets a zero output
+        return (n + kPlanTile - 1) / kPlanTile;
     };
-    int cnt = 0;
+
+    // 1. tile line: exclusive prefix of tiles per request, and the longest request
+    int cnt = 0, mx = 0;
     for (int b = b0; b < b1; ++b) {
-        int len;
-        cnt += splits_of(ctx_len[b], len);
+        const int n = p.ctx_len[b];
+        if (n < p.T || n > p.max_ctx) s_bad = 1;
+        const int t = tiles_of(b);
+        cnt += t;
+        mx = max(mx, t);
     }
-    s_cnt[tid] = cnt;
+    s_scan[tid] = cnt;
+    s_max[tid] = mx;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0, m = 0;
+        for (int i = 0; i < kPlanThreads; ++i) {
+            const int c = s_scan[i];
+            s_scan[i] = run;
+            run += c;
+            m = max(m, s_max[i]);
+        }
+        s_max[0] = m;
+        p.tile_off[p.B] = run;
+    }
+    __syncthreads();
+    const int total = p.tile_off[p.B];
+    const int longest = s_max[0];
+    {
+        int off = s_scan[tid];
+        for (int b = b0; b < b1; ++b) {
+            p.tile_off[b] = off;
+            off += tiles_of(b);
+        }
+    }
+    __syncthreads();
+
+    // 2. stretch length L (tiles per workgroup); 0 = one workgroup per request
+    int L = 0;
+    if (p.max_splits > 1) {
+        L = (total + p.wgs_per_head - 1) / p.wgs_per_head;
+        L = max(L, kMinTilesPerWg);
+        // a request of t tiles touches at most ceil(t / L) + 1 stretches
+        L = max(L, (longest + p.max_splits - 2) / (p.max_splits - 1));
+    }
+
+    // 3. pieces per request -> first partial slot of each request
+    auto first_wg = [&](int b) -> int { return L ? p.tile_off[b] / L : b; };
+    auto parts_of = [&](int b) -> int {
+        const int lo = p.tile_off[b], hi = p.tile_off[b + 1];
+        if (hi == lo) return 0;
+        return L ? (hi - 1) / L - lo / L + 1 : 1;
+    };
+    cnt = 0;
+    for (int b = b0; b < b1; ++b) cnt += parts_of(b);
+    __syncthreads();
+    s_scan[tid] = cnt;
     __syncthreads();
     if (tid == 0) {
         int run = 0;
         for (int i = 0; i < kPlanThreads; ++i) {
-            const int c = s_cnt[i];
-            s_cnt[i] = run;
+            const int c = s_scan[i];
+            s_scan[i] = run;
             run += c;
         }
-        header->status = s_bad ? 1u : 0u;
-        header->n_items = run < max_items ? run : max_items;
-        header->part_len = part_len;
-        header->reserved = 0;
-        split_off[B] = run;
+        p.header->status = s_bad ? 1u : 0u;
+        p.header->n_items = min(run, p.max_items);
+        p.header->tiles_per_wg = L;
+        p.header->total_tiles = total;
+        p.split_off[p.B] = run;
     }
     __syncthreads();
-    int off = s_cnt[tid];
+
+    // 4. piece table and the request each stretch starts in
+    int slot = s_scan[tid];
     for (int b = b0; b < b1; ++b) {
-        const int n = ctx_len[b];
-        int len;
-        const int ns = splits_of(n, len);
-        split_off[b] = off;
-        for (int s = 0; s < ns; ++s) {
-            if (off + s < max_items) {
+        p.split_off[b] = slot;
+        const int np = parts_of(b);
+        const int lo = p.tile_off[b], hi = p.tile_off[b + 1];
+        const int n = p.ctx_len[b];
+        const int w0 = first_wg(b);
+        for (int s = 0; s < np; ++s) {
+            const int w = w0 + s;
+            const int t_begin = L ? max(lo, w * L) : lo;
+            const int t_end = L ? min(hi, (w + 1) * L) : hi;
+            if (slot + s < p.max_items) {
                 WorkItem it;
                 it.b = b;
-                it.begin = s * len;
-                it.end = min(n, (s + 1) * len);
+                it.begin = (t_begin - lo) * kPlanTile;
+                it.end = min(n, (t_end - lo) * kPlanTile);
                 it.split = s;
-                items[off + s] = it;
+                p.items[slot + s] = it;
             }
+            if (t_begin == (L ? w * L : lo) && w < p.wgs_per_head) p.wg_first[w] = b;   // stretch w starts here
         }
-        off += ns;
+        slot += np;
     }
 }
 
 hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t stream) {
     const long long max_ctx_ll = static_cast<long long>(a.max_pages) * a.P;
-    const int max_ctx = max_ctx_ll > 0x7fffffffLL ? 0x7fffffff : static_cast<int>(max_ctx_ll);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, a.ctx_len, a.B, a.T, max_ctx,
-                       w.target_items, w.max_splits, w.max_items, a.header, const_cast<int32_t*>(a.split_off),
-                       const_cast<WorkItem*>(a.items));
+    PlanArgs p;
+    p.ctx_len = a.ctx_len;
+    p.B = a.B;
+    p.T = a.T;
+    p.max_ctx = max_ctx_ll > 0x7fffffffLL - kPlanTile ? 0x7fffffff - kPlanTile : static_cast<int>(max_ctx_ll);
+    p.wgs_per_head = w.wgs_per_head;
+    p.max_splits = w.max_splits;
+    p.max_items = w.max_items;
+    p.header = a.header;
+    p.split_off = const_cast<int32_t*>(a.split_off);
+    p.tile_off = const_cast<int32_t*>(a.tile_off);
+    p.wg_first = const_cast<int32_t*>(a.wg_first);
+    p.items = const_cast<WorkItem*>(a.items);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -354,6 +409,8 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.tree_mask = tree_mask;
     a.header = reinterpret_cast<seer::PlanHeader*>(ws + w.off_header);
     a.split_off = reinterpret_cast<const int32_t*>(ws + w.off_split);
+    a.tile_off = reinterpret_cast<const int32_t*>(ws + w.off_tiles);
+    a.wg_first = reinterpret_cast<const int32_t*>(ws + w.off_first);
     a.items = reinterpret_cast<const seer::WorkItem*>(ws + w.off_items);
     a.part_ml = reinterpret_cast<float*>(ws + w.off_ml);
     a.part_acc = reinterpret_cast<float*>(ws + w.off_acc);
@@ -368,6 +425,7 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.num_pages = p->num_pages;
     a.max_pages = p->max_pages_per_seq;
     a.max_items = w.max_items;
+    a.wgs_per_head = w.wgs_per_head;
     a.scale_log2 = p->scale * seer::kLog2e;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);

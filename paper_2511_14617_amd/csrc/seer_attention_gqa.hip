@@ -12,8 +12,9 @@
 // HBM streaming.
 //
 // Work decomposition
-//   grid = (items, Hkv); one workgroup handles one (request, partition, kv head)
-//   and all R = G*T query rows of that head.  Wave w owns rows [32w, 32w+32);
+//   grid = (W, Hkv); workgroup (w, kv head) streams stretch w of the head's tile line
+//   (see the plan in seer_attention.h) and, for each request the stretch touches,
+//   handles all R = G*T query rows of that head.  Wave i owns rows [32i, 32i+32);
 //   NW = ceil(R/32) waves per workgroup.
 //
 // Data flow per 32-token tile (two pages)
@@ -29,6 +30,8 @@
 //   O^T += V^T . P^T M = d (4 tiles of 32), N = rows, 2 steps over the tokens
 //   Q^T (the B operand of the first product) stays in 32 VGPRs for the whole
 //   partition; K/V of tile i+1 are in flight from HBM while tile i is computed.
+#include <type_traits>
+
 #include "seer_attention.h"
 #include "seer_device.h"
 
@@ -42,8 +45,13 @@ constexpr int kPage = 16;        // tokens per page
 constexpr int kTile = 32;        // tokens per tile
 constexpr int kKPitch = 272;     // bytes per K row in LDS (256 + 16)
 constexpr int kKBytes = kTile * kKPitch;         // 8704
-constexpr int kVBytes = (kTile / 4) * kD * 8;    // 8192: [quad][d][4]
+constexpr int kVQuadPitch = kD * 8 + 8 * 16;     // 1152: [d][4 tokens], 16 bytes of padding every 16 d
+constexpr int kVBytes = (kTile / 4) * kVQuadPitch;   // 9216
+// byte offset of (d, token%4 = 0) inside a token quad of V: the padding makes both the 64-byte
+// row-block writes of staging and the 8-byte operand reads hit 32 distinct banks
+__device__ __forceinline__ int v_quad_offset(int d) { return d * 8 + (d >> 4) * 16; }
 constexpr int kBufBytes = kKBytes + kVBytes;
+static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel");
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -66,18 +74,34 @@ void attn_gqa128_kernel(AttnArgs a) {
 
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBufBytes];
 
-    const int item_idx = blockIdx.x;
-    if (item_idx >= a.header->n_items) return;
-    const WorkItem item = a.items[item_idx];
     const int kvh = blockIdx.y;
-    const int b = item.b;
-    const int n = a.ctx_len[b];
-    const int n0 = n - a.T;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const int ln = lane & 31;      // N / M index inside a 32-wide tile
     const int lg = lane >> 5;      // which half of the contraction index this lane feeds
+
+    // ---- this workgroup's stretch of the per-head tile line ---------------------------
+    const int wg = blockIdx.x;
+    const int L = a.header->tiles_per_wg;          // 0: one workgroup per request
+    int b = a.wg_first[wg];
+    if (b < 0) return;                             // idle stretch (uniform for the workgroup)
+    int g = L ? wg * L : a.tile_off[b];
+    const int g_end = L ? min((wg + 1) * L, a.header->total_tiles) : a.tile_off[b + 1];
+    bool bad_page = false;
+
+  for (; g < g_end; ++b) {
+    const int t_lo = a.tile_off[b], t_hi = a.tile_off[b + 1];
+    if (t_hi == t_lo) continue;                    // request without tiles (flagged ctx_len)
+    const int item_idx = a.split_off[b] + (L ? wg - t_lo / L : 0);
+    WorkItem item;
+    item.b = b;
+    item.begin = (g - t_lo) * kTile;
+    const int n = a.ctx_len[b];
+    item.end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
+    g = t_hi;
+    const int n0 = n - a.T;
+    __syncthreads();                               // the previous piece is done with the LDS buffers
 
     // ---- this lane's query row -------------------------------------------------
     const int R = a.G * a.T;
@@ -114,21 +138,34 @@ void attn_gqa128_kernel(AttnArgs a) {
     const size_t page_bytes = static_cast<size_t>(a.Hkv) * kPage * kD * 2;   // one page, all kv heads
     const size_t head_off = static_cast<size_t>(kvh) * kPage * kD * 2;
     const int n_tiles = (item.end - item.begin + kTile - 1) / kTile;
-    bool bad_page = false;
 
+    // Page ids are fetched 64 at a time (lane l holds logical page cache_base + l) and handed
+    // out with v_readlane: one vector load per 32 tiles instead of a dependent table read --
+    // and a full drain of the loads in flight -- in front of every tile.
+    int cache_base = -0x40000000;
+    int pg_cache = 0;
+    const int last_page = (n - 1) / kPage;
     auto page_offset = [&](int logical_page) -> size_t {
-        int pg = table[min(logical_page, a.max_pages - 1)];
-        if (pg < 0 || pg >= a.num_pages) {
-            bad_page = true;
-            pg = min(max(pg, 0), a.num_pages - 1);
+        if (logical_page < cache_base || logical_page >= cache_base + kWave) {   // uniform
+            cache_base = logical_page;
+            const int idx = cache_base + lane;
+            int pg = table[min(idx, a.max_pages - 1)];
+            if (pg < 0 || pg >= a.num_pages) {
+                if (idx <= last_page) bad_page = true;
+                pg = min(max(pg, 0), a.num_pages - 1);
+            }
+            pg_cache = pg;
         }
+        const int pg = __builtin_amdgcn_readlane(pg_cache, __builtin_amdgcn_readfirstlane(logical_page - cache_base));
         return static_cast<size_t>(pg) * page_bytes + head_off;
     };
 
-    u32x4 kst[K_PER];        // K pieces in flight
-    u32x4 vst[V_PER][4];     // V: 4 tokens x 16 bytes per unit
+    // two tiles are in flight from HBM per workgroup (register sets 0 and 1)
+    u32x4 kst[2][K_PER];        // K pieces in flight
+    u32x4 vst[2][V_PER][4];     // V: 4 tokens x 16 bytes per unit
 
-    auto issue_loads = [&](int tile) {
+    auto issue_loads = [&](int tile, auto set_tag) {
+        constexpr int set = decltype(set_tag)::value;
         const int tb = item.begin + tile * kTile;
         const size_t p0 = page_offset(tb / kPage);
         const size_t p1 = page_offset(tb / kPage + 1);
@@ -137,7 +174,7 @@ void attn_gqa128_kernel(AttnArgs a) {
             const int u = tid + j * NT;
             if (K_CHUNKS % NT == 0 || u < K_CHUNKS) {
                 const size_t off = (u < 256 ? p0 : p1) + static_cast<size_t>(u & 255) * 16;
-                kst[j] = *reinterpret_cast<const u32x4*>(kbase + off);
+                kst[set][j] = *reinterpret_cast<const u32x4*>(kbase + off);
             }
         }
 #pragma unroll
@@ -148,35 +185,43 @@ void attn_gqa128_kernel(AttnArgs a) {
                 const size_t off = (quad < 4 ? p0 : p1) + static_cast<size_t>((quad & 3) * 4) * 256 + c * 16;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    u32x4 v = *reinterpret_cast<const u32x4*>(vbase + off + e * 256);
-                    // values of slots past the end of the context are never used: zero them so
-                    // that whatever the page holds there (NaN included) cannot reach 0 * x
-                    if (tb + quad * 4 + e >= n) v = u32x4{0u, 0u, 0u, 0u};
-                    vst[j][e] = v;
+                    vst[set][j][e] = *reinterpret_cast<const u32x4*>(vbase + off + e * 256);
                 }
             }
         }
     };
 
-    auto stage_to_lds = [&](int buf) {
-        unsigned char* kl = lds + buf * kBufBytes;
+    auto stage_to_lds = [&](int tile, auto set_tag) {
+        constexpr int set = decltype(set_tag)::value;
+        const int tb = item.begin + tile * kTile;
+        const bool ragged = tb + kTile > n;     // only the last tile of a request
+        unsigned char* kl = lds + set * kBufBytes;
         unsigned char* vl = kl + kKBytes;
 #pragma unroll
         for (int j = 0; j < K_PER; ++j) {
             const int u = tid + j * NT;
             if (K_CHUNKS % NT == 0 || u < K_CHUNKS)
-                *reinterpret_cast<u32x4*>(kl + (u >> 4) * kKPitch + (u & 15) * 16) = kst[j];
+                *reinterpret_cast<u32x4*>(kl + (u >> 4) * kKPitch + (u & 15) * 16) = kst[set][j];
         }
 #pragma unroll
         for (int j = 0; j < V_PER; ++j) {
             const int u = tid + j * NT;
             if (V_UNITS % NT == 0 || u < V_UNITS) {
                 const int quad = u >> 4, c = u & 15;
-                unsigned char* dst = vl + quad * (kD * 8) + c * 64;
+                unsigned char* dst = vl + quad * kVQuadPitch + v_quad_offset(c * 8);
+                if (ragged) {
+                    // values of slots past the end of the context are never used: zero them so
+                    // that whatever the page holds there (NaN included) cannot reach 0 * x.
+                    // (Done here, where the data is consumed, not where the loads are issued.)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (tb + quad * 4 + e >= n) vst[set][j][e] = u32x4{0u, 0u, 0u, 0u};
+                }
                 // 4 tokens x 8 d  ->  8 d x 4 tokens
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {   // dword e of each token row holds d = 2e, 2e+1
-                    const uint32_t t0 = vst[j][0][e], t1 = vst[j][1][e], t2 = vst[j][2][e], t3 = vst[j][3][e];
+                    const uint32_t t0 = vst[set][j][0][e], t1 = vst[set][j][1][e], t2 = vst[set][j][2][e],
+                                   t3 = vst[set][j][3][e];
                     u32x4 o;
                     o[0] = (t0 & 0xffffu) | (t1 << 16);          // d = 2e   : tokens 0,1
                     o[1] = (t2 & 0xffffu) | (t3 << 16);          //            tokens 2,3
@@ -188,12 +233,11 @@ void attn_gqa128_kernel(AttnArgs a) {
         }
     };
 
-    if (n_tiles > 0) issue_loads(0);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
-        stage_to_lds(buf);
+    auto tile_step = [&](int tile, auto set_tag) {
+        constexpr int buf = decltype(set_tag)::value;
+        stage_to_lds(tile, set_tag);
         __syncthreads();
-        if (tile + 1 < n_tiles) issue_loads(tile + 1);
+        if (tile + 2 < n_tiles) issue_loads(tile + 2, set_tag);
 
         const unsigned char* kl = lds + buf * kBufBytes;
         const unsigned char* vl = kl + kKBytes;
@@ -252,14 +296,22 @@ void attn_gqa128_kernel(AttnArgs a) {
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
                 const int d = dt * 32 + ln;
-                const u32x2 lo = *reinterpret_cast<const u32x2*>(vl + (ks * 4 + lg) * (kD * 8) + d * 8);
-                const u32x2 hi = *reinterpret_cast<const u32x2*>(vl + (ks * 4 + 2 + lg) * (kD * 8) + d * 8);
+                const u32x2 lo = *reinterpret_cast<const u32x2*>(vl + (ks * 4 + lg) * kVQuadPitch + v_quad_offset(d));
+                const u32x2 hi = *reinterpret_cast<const u32x2*>(vl + (ks * 4 + 2 + lg) * kVQuadPitch + v_quad_offset(d));
                 const bf16x8 va = as_bf16x8(u32x4{lo[0], lo[1], hi[0], hi[1]});
                 acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, acc[dt], 0, 0, 0);
             }
         }
+    };   // tile_step
+
+    using Set0 = std::integral_constant<int, 0>;
+    using Set1 = std::integral_constant<int, 1>;
+    if (n_tiles > 0) issue_loads(0, Set0{});
+    if (n_tiles > 1) issue_loads(1, Set1{});
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        tile_step(tile, Set0{});
+        if (tile + 1 < n_tiles) tile_step(tile + 1, Set1{});
     }
-    if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
 
     // ---- partial result: (running max, sum, unnormalised O) per row -------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
@@ -278,6 +330,8 @@ void attn_gqa128_kernel(AttnArgs a) {
                 *reinterpret_cast<f32x4*>(po + dt * 32 + i4 * 8 + lg * 4) = v;
             }
     }
+  }  // pieces of the stretch
+    if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
 }
 
 bool gqa128_supports(const AttnArgs& a) {
@@ -288,7 +342,7 @@ bool gqa128_supports(const AttnArgs& a) {
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int R = a.G * a.T;
     const int nw = (R + 31) / 32;
-    const dim3 grid(a.max_items, a.Hkv);
+    const dim3 grid(a.wgs_per_head, a.Hkv);
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                               \
     case NW_:                                                                                            \
