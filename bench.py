@@ -102,6 +102,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (2 = the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="time only seer_verify_attention (profiling aid)")
+    ap.add_argument("--ctx-scale", type=float, default=1.0,
+                    help="experiment aid: scale every context-length bound of the workload (not the headline run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange step; "
@@ -117,6 +119,10 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     cfg = W.CONFIGS[args.config]
+    if args.ctx_scale != 1.0:
+        c = cfg.ctx
+        scaled = tuple(int(round(x * args.ctx_scale)) if (isinstance(x, (int, float)) and x > 1.5) else x for x in c[1:])
+        cfg = cfg.scaled(ctx=(c[0],) + scaled)
     att = W.make_attention_inputs(cfg)
     acc = W.make_accept_inputs(cfg, tree_parent=att.tree_parent)
     d = attention_device_inputs(att)

@@ -57,7 +57,9 @@ inline int resident_wgs_per_cu(const seer_attn_params& p) {
                        !(p.flags & SEER_ATTN_GENERAL_KERNEL);
     if (!tiled) return 4;
     const int waves = ((p.Hq / p.Hkv) * p.T + 31) / 32;   // one wave per 32 query rows
-    return waves <= 2 ? 4 : (waves <= 4 ? 2 : 1);
+    const int by_waves = 8 / waves;                       // 2 waves per SIMD, 4 SIMDs
+    const int by_lds = 3;                                 // 160 KB / (3 stages x 16 KB)
+    return by_waves < 1 ? 1 : (by_waves < by_lds ? by_waves : by_lds);
 }
 
 // Host-only arithmetic; the plan kernel is given the same numbers.

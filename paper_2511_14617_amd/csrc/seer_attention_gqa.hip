@@ -17,21 +17,23 @@
 //   handles all R = G*T query rows of that head.  Wave i owns rows [32i, 32i+32);
 //   NW = ceil(R/32) waves per workgroup.
 //
-// Data flow per 32-token tile (two pages)
-//   HBM -> VGPR (16-byte lanes, whole 4 KB page-head blocks, coalesced)
-//       -> LDS  K as [token][d] (row pitch 272 B: conflict-free 16-byte reads)
-//               V as [token/4][d][token%4] (4x8 bf16 blocks transposed in registers
-//                 on the way in, so the P.V operand is two 8-byte LDS reads)
-//   S^T = K . Q^T    v_mfma_f32_32x32x16_bf16, M = tokens, N = rows, 8 steps over d
+// Data flow per 32-token tile (two pages, 8 KB of K and 8 KB of V)
+//   HBM -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane, 1 KB per wave
+//          instruction, no staging registers), into a ring of NS stages, so NS-1 tiles
+//          per workgroup are in flight while one is computed.  Rows are 256 B, unpadded;
+//          the 16-byte chunks of a row are stored XOR-swizzled (the lane picks which
+//          global chunk lands in its fixed LDS slot), which makes the operand reads
+//          below free of bank conflicts.  Completion is tracked by hand: s_waitcnt
+//          vmcnt(loads of the younger tiles) then s_barrier.
+//   S^T = K . Q^T    v_mfma_f32_32x32x16_bf16, M = tokens, N = rows, 8 steps over d;
+//                    K operand = one ds_read_b128 per step, Q^T stays in 32 VGPRs
 //   softmax          each lane owns ONE query row (N index = lane % 32) and 16 of the
 //                    tile's 32 tokens, so max/sum are in-lane plus one cross-half
 //                    exchange; the C registers of S^T are, as they stand, the
 //                    B operand of the next product (no shuffle, no LDS round trip)
-//   O^T += V^T . P^T M = d (4 tiles of 32), N = rows, 2 steps over the tokens
-//   Q^T (the B operand of the first product) stays in 32 VGPRs for the whole
-//   partition; K/V of tile i+1 are in flight from HBM while tile i is computed.
-#include <type_traits>
-
+//   O^T += V^T . P^T M = d (4 tiles of 32), N = rows, 2 steps over the tokens; the
+//                    V^T operand (8 tokens at one d) comes from the token-major tile
+//                    through two transposing LDS reads (ds_read_b64_tr_b16)
 #include "seer_attention.h"
 #include "seer_device.h"
 
@@ -40,17 +42,16 @@ namespace seer {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int kD = 128;          // head dim
-constexpr int kPage = 16;        // tokens per page
-constexpr int kTile = 32;        // tokens per tile
-constexpr int kKPitch = 272;     // bytes per K row in LDS (256 + 16)
-constexpr int kKBytes = kTile * kKPitch;         // 8704
-constexpr int kVQuadPitch = kD * 8 + 8 * 16;     // 1152: [d][4 tokens], 16 bytes of padding every 16 d
-constexpr int kVBytes = (kTile / 4) * kVQuadPitch;   // 9216
-// byte offset of (d, token%4 = 0) inside a token quad of V: the padding makes both the 64-byte
-// row-block writes of staging and the 8-byte operand reads hit 32 distinct banks
-__device__ __forceinline__ int v_quad_offset(int d) { return d * 8 + (d >> 4) * 16; }
-constexpr int kBufBytes = kKBytes + kVBytes;
+#define SEER_AS1 __attribute__((address_space(1)))
+#define SEER_AS3 __attribute__((address_space(3)))
+
+constexpr int kD = 128;                  // head dim
+constexpr int kPage = 16;                // tokens per page
+constexpr int kTile = 32;                // tokens per tile
+constexpr int kRowBytes = kD * 2;        // 256
+constexpr int kKBytes = kTile * kRowBytes;   // 8192
+constexpr int kStageBytes = 2 * kKBytes;     // K tile then V tile
+constexpr int kBlocks = 16;              // 1 KB wave-loads per tile: 8 of K, 8 of V
 static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel");
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -63,45 +64,121 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at "do not wait").
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+// Workgroup barrier WITHOUT the memory fences of __syncthreads(): a fence (even one scoped to
+// LDS) makes the compiler drain every outstanding load, including the direct-to-LDS loads of
+// the tiles still in flight, which is exactly what the ring of stages exists to avoid.  The
+// kernel orders its LDS traffic by hand instead: wait_vmcnt for the tile about to be read, then
+// this barrier; LDS reads of a stage are complete (their results consumed by MFMAs) before the
+// wave reaches the barrier after which that stage is overwritten.
+__device__ __forceinline__ void bare_barrier() { __builtin_amdgcn_s_barrier(); }
+// A workgroup-uniform 32-bit value read from global memory, moved to a scalar register.  The
+// hand-placed fences keep the compiler from proving such loads invariant, so it issues them as
+// vector loads; without this the control flow that depends on them would be treated as divergent.
+__device__ __forceinline__ int uniform_load(const int32_t* p) { return __builtin_amdgcn_readfirstlane(*p); }
+
+// Swizzles: a row's 16-byte chunk c is stored at chunk position c ^ f(row).
+//   K: f = row & 7         -> 8 consecutive rows, same chunk: 8 distinct 16-byte bank groups
+//   V: f = (row & 3) << 1  -> 4 consecutive rows, same 32-byte pair: 4 distinct 32-byte groups
+__device__ __forceinline__ int k_swz(int row) { return row & 7; }
+__device__ __forceinline__ int v_swz(int row) { return (row & 3) << 1; }
+
+// This wave's share of one tile, HBM -> LDS stage.  The 16 one-KB blocks of a tile (K rows 4j..4j+3
+// for block j < 8, V rows for block 8 + j) are dealt round-robin to the NW waves.  p0 / p1 are
+// the byte offsets of the tile's two pages (kv head included) in the pools.  (A free function
+// with by-value arguments on purpose: the same code as a by-reference lambda made the compiler
+// keep the captured variables in scratch memory.)
 template <int NW>
+__device__ __forceinline__ void issue_tile_loads(unsigned char* stage, int wave, size_t p0, size_t p1,
+                                                 const unsigned char* kbase, const unsigned char* vbase,
+                                                 int goff_k0, int goff_k1, int goff_v) {
+    constexpr int LPW = (kBlocks + NW - 1) / NW;
+    constexpr int EXTRA = kBlocks % NW;
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int jb = wave + i * NW;
+        if (EXTRA == 0 || i < LPW - 1 || jb < kBlocks) {
+            const int j = jb & 7;
+            const bool is_v = jb >= 8;
+            const size_t pg = (j < 4) ? p0 : p1;
+            const int lane_off = is_v ? goff_v : ((j & 1) ? goff_k1 : goff_k0);
+            const unsigned char* src = (is_v ? vbase : kbase) + pg + (j & 3) * (4 * kRowBytes) + lane_off;
+            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(stage + jb * 1024), 16, 0,
+                                             0);
+        }
+    }
+}
+
+template <int NW, int NS>
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
 void attn_gqa128_kernel(AttnArgs a) {
     constexpr int NT = NW * kWave;
-    constexpr int K_CHUNKS = kTile * kD * 2 / 16;      // 512 16-byte pieces of K per tile
-    constexpr int K_PER = (K_CHUNKS + NT - 1) / NT;
-    constexpr int V_UNITS = (kTile / 4) * (kD / 8);    // 128 (token quad, 8-wide d chunk) units
-    constexpr int V_PER = (V_UNITS + NT - 1) / NT;
+    constexpr int LPW = (kBlocks + NW - 1) / NW;    // wave-loads per tile for the busiest waves
+    constexpr int EXTRA = kBlocks % NW;             // waves below this index issue LPW, the others LPW - 1
+    static_assert(NS >= 2 && NS <= 4, "ring of 2..4 stages");
+    static_assert((NS - 2) * LPW < 64, "vmcnt range");
 
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBufBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NS * kStageBytes];
 
     const int kvh = blockIdx.y;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int ln = lane & 31;      // N / M index inside a 32-wide tile
     const int lg = lane >> 5;      // which half of the contraction index this lane feeds
+    const int l16 = lane >> 4;     // row inside a 4-row load block
+    const int p16 = lane & 15;     // 16-byte slot inside the row
 
     // ---- this workgroup's stretch of the per-head tile line ---------------------------
     const int wg = blockIdx.x;
-    const int L = a.header->tiles_per_wg;          // 0: one workgroup per request
-    int b = a.wg_first[wg];
+    const int L = uniform_load(&a.header->tiles_per_wg);          // 0: one workgroup per request
+    int b = uniform_load(a.wg_first + wg);
     if (b < 0) return;                             // idle stretch (uniform for the workgroup)
-    int g = L ? wg * L : a.tile_off[b];
-    const int g_end = L ? min((wg + 1) * L, a.header->total_tiles) : a.tile_off[b + 1];
+    int g = L ? wg * L : uniform_load(a.tile_off + b);
+    const int g_end = L ? min((wg + 1) * L, uniform_load(&a.header->total_tiles)) : uniform_load(a.tile_off + b + 1);
     bool bad_page = false;
 
+    const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
+    const unsigned char* __restrict__ vbase = static_cast<const unsigned char*>(a.v_pages);
+    const size_t page_bytes = static_cast<size_t>(a.Hkv) * kPage * kRowBytes;   // one page, all kv heads
+    const size_t head_off = static_cast<size_t>(kvh) * kPage * kRowBytes;
+    // per-lane byte offset inside a 4-row block of a page: which global chunk feeds my LDS slot
+    const int goff_k0 = l16 * kRowBytes + ((p16 ^ k_swz(l16)) << 4);       // blocks whose first row is 0 mod 8
+    const int goff_k1 = l16 * kRowBytes + ((p16 ^ k_swz(4 + l16)) << 4);   // ... 4 mod 8
+    const int goff_v = l16 * kRowBytes + ((p16 ^ v_swz(l16)) << 4);
+    // operand read offsets inside a stage
+    int k_rd[8];                   // K: row ln, chunk 2*kk + lg
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) k_rd[kk] = ln * kRowBytes + (((2 * kk + lg) ^ k_swz(ln)) << 4);
+    // V through the transposing read: in each 16-lane group, lane s = 4*k + c4 points at token row k
+    // (of the 4 the group covers) and d columns 4*c4..4*c4+3 of the group's 16; lane i of the group
+    // receives the 4 tokens of column i.
+    const int v_k = p16 >> 2, v_c4 = p16 & 3, v_dhalf = l16 & 1;
+    int v_rd[4];                   // per d-tile: chunk/half part of the address (token part added per read)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        const int chunk = dt * 4 + v_dhalf * 2 + (v_c4 >> 1);
+        v_rd[dt] = ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;   // token rows are 4-aligned + k: same swizzle
+    }
+    const int v_row0 = (lg * 4 + v_k) * kRowBytes;                 // token lg*4 + k (+ 8, + 16*ks)
+
   for (; g < g_end; ++b) {
-    const int t_lo = a.tile_off[b], t_hi = a.tile_off[b + 1];
+    const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
     if (t_hi == t_lo) continue;                    // request without tiles (flagged ctx_len)
-    const int item_idx = a.split_off[b] + (L ? wg - t_lo / L : 0);
-    WorkItem item;
-    item.b = b;
-    item.begin = (g - t_lo) * kTile;
-    const int n = a.ctx_len[b];
-    item.end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
+    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - t_lo / L : 0);
+    const int n = uniform_load(a.ctx_len + b);
+    const int tok_begin = (g - t_lo) * kTile;
+    const int tok_end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
     g = t_hi;
     const int n0 = n - a.T;
-    __syncthreads();                               // the previous piece is done with the LDS buffers
+    const int n_tiles = (tok_end - tok_begin + kTile - 1) / kTile;
+    bare_barrier();                                // every wave is done with the previous piece's stages
 
     // ---- this lane's query row -------------------------------------------------
     const int R = a.G * a.T;
@@ -110,18 +187,32 @@ void attn_gqa128_kernel(AttnArgs a) {
     const int t = row_ok ? r / a.G : 0;
     const int hq = kvh * a.G + (row_ok ? r - t * a.G : 0);
     uint64_t word = 0;
-    if (row_ok) word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
-                                   : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
+    if (row_ok) {
+        word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
+                           : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
+        if (a.T < 64) word &= (1ull << a.T) - 1;   // bits past the last slot would point past the context
+    }
     bf16x8 qreg[8];
     {
         const u32x4* qp = reinterpret_cast<const u32x4*>(
             static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * kD + lg * 8);
+        u32x4 qv[8];
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (row_ok) v = qp[kk * 2];      // d = kk*16 + lg*8 .. +7
-            qreg[kk] = as_bf16x8(v);
+            qv[kk] = u32x4{0u, 0u, 0u, 0u};
+            if (row_ok) qv[kk] = qp[kk * 2];      // d = kk*16 + lg*8 .. +7
         }
+        // Pin the point where these loads must have returned to HERE, before the tile loop: left to
+        // itself the compiler waits for them at their first use inside the loop, with a wait that
+        // also drains the direct-to-LDS loads of the tiles in flight, on every iteration.
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            asm volatile("" : "+v"(qv[kk]));
+            qreg[kk] = as_bf16x8(qv[kk]);
+        }
+        uint32_t w_lo = static_cast<uint32_t>(word), w_hi = static_cast<uint32_t>(word >> 32);
+        asm volatile("" : "+v"(w_lo), "+v"(w_hi));
+        word = (static_cast<uint64_t>(w_hi) << 32) | w_lo;
     }
 
     f32x16 acc[4];
@@ -131,21 +222,13 @@ void attn_gqa128_kernel(AttnArgs a) {
         for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
     float m_run = kNegInf, l_run = 0.f;
 
-    // ---- tile streaming ----------------------------------------------------------
+    // ---- page ids: fetched 64 at a time (lane l holds logical page cache_base + l) and handed
+    // out with v_readlane, so that no table read sits in front of a tile's loads
     const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
-    const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
-    const unsigned char* __restrict__ vbase = static_cast<const unsigned char*>(a.v_pages);
-    const size_t page_bytes = static_cast<size_t>(a.Hkv) * kPage * kD * 2;   // one page, all kv heads
-    const size_t head_off = static_cast<size_t>(kvh) * kPage * kD * 2;
-    const int n_tiles = (item.end - item.begin + kTile - 1) / kTile;
-
-    // Page ids are fetched 64 at a time (lane l holds logical page cache_base + l) and handed
-    // out with v_readlane: one vector load per 32 tiles instead of a dependent table read --
-    // and a full drain of the loads in flight -- in front of every tile.
     int cache_base = -0x40000000;
     int pg_cache = 0;
     const int last_page = (n - 1) / kPage;
-    auto page_offset = [&](int logical_page) -> size_t {
+    auto page_offset = [&](int logical_page) __attribute__((always_inline)) -> size_t {
         if (logical_page < cache_base || logical_page >= cache_base + kWave) {   // uniform
             cache_base = logical_page;
             const int idx = cache_base + lane;
@@ -160,88 +243,45 @@ void attn_gqa128_kernel(AttnArgs a) {
         return static_cast<size_t>(pg) * page_bytes + head_off;
     };
 
-    // two tiles are in flight from HBM per workgroup (register sets 0 and 1)
-    u32x4 kst[2][K_PER];        // K pieces in flight
-    u32x4 vst[2][V_PER][4];     // V: 4 tokens x 16 bytes per unit
-
-    auto issue_loads = [&](int tile, auto set_tag) {
-        constexpr int set = decltype(set_tag)::value;
-        const int tb = item.begin + tile * kTile;
+    // ---- HBM -> LDS, this wave's share of one tile ------------------------------------
+    auto issue_tile = [&](int tile) __attribute__((always_inline)) {
+        const int tb = tok_begin + tile * kTile;
         const size_t p0 = page_offset(tb / kPage);
         const size_t p1 = page_offset(tb / kPage + 1);
-#pragma unroll
-        for (int j = 0; j < K_PER; ++j) {
-            const int u = tid + j * NT;
-            if (K_CHUNKS % NT == 0 || u < K_CHUNKS) {
-                const size_t off = (u < 256 ? p0 : p1) + static_cast<size_t>(u & 255) * 16;
-                kst[set][j] = *reinterpret_cast<const u32x4*>(kbase + off);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < V_PER; ++j) {
-            const int u = tid + j * NT;
-            if (V_UNITS % NT == 0 || u < V_UNITS) {
-                const int quad = u >> 4, c = u & 15;
-                const size_t off = (quad < 4 ? p0 : p1) + static_cast<size_t>((quad & 3) * 4) * 256 + c * 16;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    vst[set][j][e] = *reinterpret_cast<const u32x4*>(vbase + off + e * 256);
-                }
-            }
-        }
+        issue_tile_loads<NW>(lds + (tile % NS) * kStageBytes, wave, p0, p1, kbase, vbase, goff_k0, goff_k1, goff_v);
+    };
+    // wait until at most `younger` of this wave's tiles are still in flight
+    auto wait_tiles = [&](int younger) __attribute__((always_inline)) {
+        const bool full = (EXTRA == 0) || (wave < EXTRA);
+        if (younger <= 0) wait_vmcnt<0>();
+        else if (younger == 1) { if (full) wait_vmcnt<LPW>(); else wait_vmcnt<(LPW > 1 ? LPW - 1 : 0)>(); }
+        else { if (full) wait_vmcnt<(2 * LPW < 64 ? 2 * LPW : 63)>(); else wait_vmcnt<(LPW > 1 ? 2 * (LPW - 1) : 0)>(); }
     };
 
-    auto stage_to_lds = [&](int tile, auto set_tag) {
-        constexpr int set = decltype(set_tag)::value;
-        const int tb = item.begin + tile * kTile;
-        const bool ragged = tb + kTile > n;     // only the last tile of a request
-        unsigned char* kl = lds + set * kBufBytes;
-        unsigned char* vl = kl + kKBytes;
 #pragma unroll
-        for (int j = 0; j < K_PER; ++j) {
-            const int u = tid + j * NT;
-            if (K_CHUNKS % NT == 0 || u < K_CHUNKS)
-                *reinterpret_cast<u32x4*>(kl + (u >> 4) * kKPitch + (u & 15) * 16) = kst[set][j];
-        }
-#pragma unroll
-        for (int j = 0; j < V_PER; ++j) {
-            const int u = tid + j * NT;
-            if (V_UNITS % NT == 0 || u < V_UNITS) {
-                const int quad = u >> 4, c = u & 15;
-                unsigned char* dst = vl + quad * kVQuadPitch + v_quad_offset(c * 8);
-                if (ragged) {
-                    // values of slots past the end of the context are never used: zero them so
-                    // that whatever the page holds there (NaN included) cannot reach 0 * x.
-                    // (Done here, where the data is consumed, not where the loads are issued.)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (tb + quad * 4 + e >= n) vst[set][j][e] = u32x4{0u, 0u, 0u, 0u};
-                }
-                // 4 tokens x 8 d  ->  8 d x 4 tokens
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {   // dword e of each token row holds d = 2e, 2e+1
-                    const uint32_t t0 = vst[set][j][0][e], t1 = vst[set][j][1][e], t2 = vst[set][j][2][e],
-                                   t3 = vst[set][j][3][e];
-                    u32x4 o;
-                    o[0] = (t0 & 0xffffu) | (t1 << 16);          // d = 2e   : tokens 0,1
-                    o[1] = (t2 & 0xffffu) | (t3 << 16);          //            tokens 2,3
-                    o[2] = (t0 >> 16) | (t1 & 0xffff0000u);      // d = 2e+1 : tokens 0,1
-                    o[3] = (t2 >> 16) | (t3 & 0xffff0000u);      //            tokens 2,3
-                    *reinterpret_cast<u32x4*>(dst + e * 16) = o;
-                }
-            }
-        }
-    };
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < n_tiles) issue_tile(s);
 
-    auto tile_step = [&](int tile, auto set_tag) {
-        constexpr int buf = decltype(set_tag)::value;
-        stage_to_lds(tile, set_tag);
-        __syncthreads();
-        if (tile + 2 < n_tiles) issue_loads(tile + 2, set_tag);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        wait_tiles(min(NS - 2, n_tiles - 1 - tile));
+        bare_barrier();                        // every wave's share of this tile has landed,
+                                               // and every wave has finished computing tile - 1
+        if (tile + NS - 1 < n_tiles) issue_tile(tile + NS - 1);   // into the stage tile - 1 used
 
-        const unsigned char* kl = lds + buf * kBufBytes;
+        const unsigned char* kl = lds + (tile % NS) * kStageBytes;
         const unsigned char* vl = kl + kKBytes;
-        const int tb = item.begin + tile * kTile;
+        const int tb = tok_begin + tile * kTile;
+
+        if (tb + kTile > n) {
+            // Ragged last tile of a request: slots past the end hold whatever the page holds (NaN
+            // included), and 0 * NaN must not reach the output: clear those V rows in LDS.
+            const int first_bad = n - tb;
+            for (int c = tid; c < kTile * 16; c += NT)
+                if ((c >> 4) >= first_bad)
+                    *reinterpret_cast<u32x4*>(const_cast<unsigned char*>(vl) + c * 16) = u32x4{0u, 0u, 0u, 0u};
+            __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the clears are done
+            bare_barrier();
+        }
 
         // S^T[token][row] = sum_d K[token][d] * Q[row][d]
         f32x16 s;
@@ -249,23 +289,32 @@ void attn_gqa128_kernel(AttnArgs a) {
         for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            const u32x4 kv = *reinterpret_cast<const u32x4*>(kl + ln * kKPitch + kk * 32 + lg * 16);
+            const u32x4 kv = *reinterpret_cast<const u32x4*>(kl + k_rd[kk]);
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kv), qreg[kk], s, 0, 0, 0);
         }
 
         // register i of s holds token  (i/4)*8 + lg*4 + i%4  of the tile, for this lane's row
-        const bool need_mask = (tb + kTile > n0);
         float mx = kNegInf;
+        if (tb + kTile > n0) {
+            // visibility bits of the tile's 32 tokens for this row: the prefix part is all ones,
+            // the draft part comes from the ancestor word (bit s = slot n0 + s)
+            const int rel = tb - n0;           // uniform; > -32 here, < 64 because tb < n0 + T
+            uint32_t vis = rel >= 0 ? static_cast<uint32_t>(word >> rel)
+                                    : (static_cast<uint32_t>(word << (-rel)) | ((1u << (-rel)) - 1u));
+            vis >>= lg * 4;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float v = s[i] * a.scale_log2;
-            if (need_mask) {
-                const int j = tb + (i >> 2) * 8 + lg * 4 + (i & 3);
-                const bool vis = (j < n0) || (j < n && ((word >> (j - n0)) & 1ull));
-                v = vis ? v : kNegInf;
+            for (int i = 0; i < 16; ++i) {
+                const bool on = (vis >> ((i >> 2) * 8 + (i & 3))) & 1u;
+                const float v = on ? s[i] * a.scale_log2 : kNegInf;
+                s[i] = v;
+                mx = fmaxf(mx, v);
             }
-            s[i] = v;
-            mx = fmaxf(mx, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                s[i] *= a.scale_log2;
+                mx = fmaxf(mx, s[i]);
+            }
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         const float m_new = fmaxf(m_run, mx);
@@ -290,27 +339,49 @@ void attn_gqa128_kernel(AttnArgs a) {
         }
 
         // O^T[d][row] += sum_token V[token][d] * P[row][token]
+        // step ks: this lane's 8 contraction slots are tokens 16ks + 4lg + (0..3) and 16ks + 8 + 4lg + (0..3).
+        // The 16 transposing reads are issued from one asm block that ends in its own
+        // s_waitcnt lgkmcnt(0): through the builtin, the compiler puts a vmcnt(0) in front of
+        // them (it cannot tell them apart from the direct-to-LDS loads still in flight), which
+        // would drain the ring on every tile.
+        u32x2 vr[4][4];    // [dt][ks*2 + (0: tokens +0..3, 1: tokens +8..11)]
+        {
+            const int stage_v = (tile % NS) * kStageBytes + kKBytes + v_row0;
+            const int a0 = stage_v + v_rd[0], a1 = stage_v + v_rd[1], a2 = stage_v + v_rd[2], a3 = stage_v + v_rd[3];
+            asm volatile(
+                "ds_read_b64_tr_b16 %0, %16 offset:0\n"
+                "ds_read_b64_tr_b16 %1, %16 offset:2048\n"
+                "ds_read_b64_tr_b16 %2, %16 offset:4096\n"
+                "ds_read_b64_tr_b16 %3, %16 offset:6144\n"
+                "ds_read_b64_tr_b16 %4, %17 offset:0\n"
+                "ds_read_b64_tr_b16 %5, %17 offset:2048\n"
+                "ds_read_b64_tr_b16 %6, %17 offset:4096\n"
+                "ds_read_b64_tr_b16 %7, %17 offset:6144\n"
+                "ds_read_b64_tr_b16 %8, %18 offset:0\n"
+                "ds_read_b64_tr_b16 %9, %18 offset:2048\n"
+                "ds_read_b64_tr_b16 %10, %18 offset:4096\n"
+                "ds_read_b64_tr_b16 %11, %18 offset:6144\n"
+                "ds_read_b64_tr_b16 %12, %19 offset:0\n"
+                "ds_read_b64_tr_b16 %13, %19 offset:2048\n"
+                "ds_read_b64_tr_b16 %14, %19 offset:4096\n"
+                "ds_read_b64_tr_b16 %15, %19 offset:6144\n"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&v"(vr[0][0]), "=&v"(vr[0][1]), "=&v"(vr[0][2]), "=&v"(vr[0][3]), "=&v"(vr[1][0]),
+                  "=&v"(vr[1][1]), "=&v"(vr[1][2]), "=&v"(vr[1][3]), "=&v"(vr[2][0]), "=&v"(vr[2][1]),
+                  "=&v"(vr[2][2]), "=&v"(vr[2][3]), "=&v"(vr[3][0]), "=&v"(vr[3][1]), "=&v"(vr[3][2]),
+                  "=&v"(vr[3][3])
+                : "v"(a0), "v"(a1), "v"(a2), "v"(a3));
+        }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const bf16x8 pb = as_bf16x8(u32x4{pk[ks * 4], pk[ks * 4 + 1], pk[ks * 4 + 2], pk[ks * 4 + 3]});
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                const int d = dt * 32 + ln;
-                const u32x2 lo = *reinterpret_cast<const u32x2*>(vl + (ks * 4 + lg) * kVQuadPitch + v_quad_offset(d));
-                const u32x2 hi = *reinterpret_cast<const u32x2*>(vl + (ks * 4 + 2 + lg) * kVQuadPitch + v_quad_offset(d));
-                const bf16x8 va = as_bf16x8(u32x4{lo[0], lo[1], hi[0], hi[1]});
+                const u32x2 lo2 = vr[dt][ks * 2], hi2 = vr[dt][ks * 2 + 1];
+                const bf16x8 va = as_bf16x8(u32x4{lo2[0], lo2[1], hi2[0], hi2[1]});
                 acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, acc[dt], 0, 0, 0);
             }
         }
-    };   // tile_step
-
-    using Set0 = std::integral_constant<int, 0>;
-    using Set1 = std::integral_constant<int, 1>;
-    if (n_tiles > 0) issue_loads(0, Set0{});
-    if (n_tiles > 1) issue_loads(1, Set1{});
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-        tile_step(tile, Set0{});
-        if (tile + 1 < n_tiles) tile_step(tile + 1, Set1{});
     }
 
     // ---- partial result: (running max, sum, unnormalised O) per row -------------------
@@ -346,7 +417,7 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                               \
     case NW_:                                                                                            \
-        hipLaunchKernelGGL((attn_gqa128_kernel<NW_>), grid, dim3(NW_ * kWave), 0, stream, a);            \
+        hipLaunchKernelGGL((attn_gqa128_kernel<NW_, 3>), grid, dim3(NW_ * kWave), 0, stream, a);         \
         break;
         SEER_GQA_CASE(1)
         SEER_GQA_CASE(2)
