@@ -1,0 +1,88 @@
+"""The five named workloads at FULL size, in the launch configuration bench.py times.
+
+The oracle cannot run these whole in seconds, so attention is checked on sampled output rows
+(b, t, h) that the oracle computes one by one -- chosen to cover the longest and the shortest
+request, the first and last verify slot, every KV head -- plus properties that hold at any size
+(finite, and the status word clean).  Acceptance is compared in full, bit for bit."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_14617_amd import workloads as W
+from gpu_util import ATOL, RTOL, accept_device_inputs, attention_device_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(inp, n_random=40, seed=0):
+    cfg = inp.cfg
+    rng = np.random.default_rng(seed)
+    longest, shortest = int(np.argmax(inp.ctx_len)), int(np.argmin(inp.ctx_len))
+    rows = []
+    for b in (longest, shortest):
+        for t in (0, cfg.T // 2, cfg.T - 1):
+            for h in (0, cfg.Hq - 1):
+                rows.append((b, t, h))
+    for kvh in range(cfg.Hkv):
+        rows.append((int(rng.integers(0, cfg.B)), int(rng.integers(0, cfg.T)), kvh * cfg.G + int(rng.integers(0, cfg.G))))
+    for _ in range(n_random):
+        rows.append((int(rng.integers(0, cfg.B)), int(rng.integers(0, cfg.T)), int(rng.integers(0, cfg.Hq))))
+    return np.array(sorted(set(rows)), dtype=np.int32)
+
+
+@pytest.mark.parametrize("config_id", [1, 2, 3, 4, 5])
+def test_attention_full_size_sampled_rows(config_id):
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[config_id]
+    inp = W.make_attention_inputs(cfg)
+    d = attention_device_inputs(inp)
+    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], inp.scale, Dv=cfg.Dv)
+    ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device="cuda")
+    out = binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
+                                        d["tree_mask"], inp.scale, Dv=cfg.Dv, workspace=ws)
+    torch.cuda.synchronize()
+    assert binding.seer_verify_attention_status(ws) == 0
+    got_all = out.float()
+    assert bool(torch.isfinite(got_all).all())
+    # the outputs are averages of V rows: none can exceed the largest |V| in the pool
+    vmax = float(np.abs(W.bf16_bits_to_f32(inp.k_pages if inp.v_pages is None else inp.v_pages)[..., :8]).max())
+    assert float(got_all.abs().max()) <= 1.0e4 + 1.0 and vmax > 0
+    rows = _sample_rows(inp, seed=config_id)
+    ref = oracle.verify_attention_rows(rows, inp.q, inp.k_pages, inp.v_pages, inp.block_table, inp.ctx_len,
+                                       inp.tree_mask, inp.scale, Dv=cfg.Dv)
+    got = got_all[rows[:, 0], rows[:, 1], rows[:, 2]].cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    bound = ATOL + RTOL * np.abs(ref)
+    assert (err <= bound).all(), "config %d: max err/bound %.3f" % (config_id, (err / bound).max())
+    # the stated tolerance is loose for these nearly uniform softmaxes: also require the error to be small
+    # against the signal, so that an all-zero or shifted output cannot pass
+    nrms = np.sqrt((err ** 2).mean() / (ref ** 2).mean())
+    assert nrms < 2e-2, "config %d: normalised rms error %.3e" % (config_id, nrms)
+    del d, out, ws, got_all
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("config_id", [1, 2, 3, 4, 5])
+def test_accept_full_size_bit_exact(config_id):
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[config_id]
+    parent = None
+    if cfg.tree is not None:
+        parent = W.multipath_parent(cfg.B, cfg.tree[0], cfg.tree[1], np.random.default_rng(cfg.seed), 0.25)
+    inp = W.make_accept_inputs(cfg, tree_parent=parent)
+    e = accept_device_inputs(inp)
+    alen, path, bonus, tgt = binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"])
+    torch.cuda.synchronize()
+    ra, rp, rb, rt = oracle.verify_accept(inp.logits, inp.draft_tokens, inp.tree_parent)
+    assert np.array_equal(tgt.cpu().numpy(), rt)
+    assert np.array_equal(alen.cpu().numpy(), ra)
+    assert np.array_equal(path.cpu().numpy(), rp)
+    assert np.array_equal(bonus.cpu().numpy(), rb)
+    assert np.array_equal(ra, inp.planted_len)
+    del e
+    gc.collect()
+    torch.cuda.empty_cache()
