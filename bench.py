@@ -26,6 +26,9 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the partition kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled against
+# a 1 GiB copy (profiles/attn_gqa128_config2_hbm_traffic.md); None where no counter run exists.
+MEASURED_TRAFFIC_BYTES = {2: 1.528e9}
 METRIC = "verified tokens/s and verify-attention HBM GB/s (% of peak) on one MI355X"
 
 
@@ -70,13 +73,16 @@ def algorithmic_bytes(inp) -> dict:
             "total": inp.unique_kv_bytes + q_bytes + out_bytes}
 
 
-def cpu_baseline(att, acc, n_sample_requests: int = 16) -> dict:
+def cpu_baseline(att, acc, row_token_budget: float = 4.0e8) -> dict:
     """The oracle, as it stands, on a bounded sample of the same workload: every k-th request by
     length rank (so the sample keeps the length mix), all T slots and heads, plus those requests'
     logits rows.  Reported in the metric's unit (verified tokens/s)."""
     import oracle
     cfg = att.cfg
     order = np.argsort(att.ctx_len, kind="stable")
+    # bound the CPU work: (KV tokens) x (query rows per token) of the sample stays under the budget
+    work_all = float(att.ctx_len.sum()) * cfg.T * cfg.Hq
+    n_sample_requests = int(max(1, min(cfg.B, np.floor(cfg.B * row_token_budget / work_all))))
     step = max(1, cfg.B // n_sample_requests)
     pick = np.sort(order[step // 2::step][:n_sample_requests])
     t0 = time.perf_counter()
@@ -102,6 +108,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (2 = the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="time only seer_verify_attention (profiling aid)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run three 1 GiB device-to-device tensor copies: a plain copy "
+                         "kernel of known size against which rocprofv3 FETCH_SIZE / WRITE_SIZE are scaled")
     ap.add_argument("--ctx-scale", type=float, default=1.0,
                     help="experiment aid: scale every context-length bound of the workload (not the headline run)")
     args = ap.parse_args()
@@ -169,17 +178,20 @@ def main() -> int:
     att_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
                                                          d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
                                                          workspace=ws_att))
-    acc_ms = timed(lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc,
-                                               out=acc_out))
+    acc_ms = 0.0 if args.attention_only else timed(
+        lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out))
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     status = binding.seer_verify_attention_status(ws_att)
 
     ab = algorithmic_bytes(att)
     achieved = ab["total"] / (kern_avg_ms * 1e-3) / 1e9
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tfile):
-        with open(tfile) as f:
-            traffic = json.load(f).get("config%d" % cfg.config_id)
+    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.config_id) if args.ctx_scale == 1.0 else None
     tokens = cfg.B * cfg.T
     line = {
         "metric": METRIC,
@@ -200,13 +212,15 @@ def main() -> int:
                                    cfg.Hkv, cfg.Dqk, cfg.Dv, cfg.page_size, cfg.T, cfg.V, list(cfg.ctx)),
                    "kv_tokens": int(att.ctx_len.sum()), "seed": cfg.seed,
                    "attention_only": bool(args.attention_only)},
-        "roofline": {"bound": "hbm", "kernel": "attn_gqa128_kernel (verify-attention partition kernel)",
+        "roofline": {"bound": "hbm",
+                     "kernel": ("attn_gqa128_kernel" if (cfg.Dqk == 128 and cfg.page_size == 16 and not cfg.shared_latent)
+                                else "attn_general_kernel") + " (verify-attention partition kernel)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "algorithmic_bytes": ab, "kernel_ms_avg": kern_avg_ms,
                      "kernel_ms_min": float(np.min(kern_ms))},
         "attention_ms": att_ms, "accept_ms": acc_ms,
         "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
-        "accept_logits_GBps": acc.logits.nbytes / (acc_ms * 1e-3) / 1e9,
+        "accept_logits_GBps": (acc.logits.nbytes / (acc_ms * 1e-3) / 1e9) if acc_ms > 0 else None,
         "attention_status_word": status,
     }
     if not args.no_cpu_baseline:
