@@ -193,6 +193,20 @@ def main() -> int:
     achieved = ab["total"] / (kern_avg_ms * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(cfg.config_id) if args.ctx_scale == 1.0 else None
     tokens = cfg.B * cfg.T
+    kernel_name = ("attn_gqa128_kernel" if (cfg.Dqk == 128 and cfg.page_size == 16 and not cfg.shared_latent) else
+                   "attn_mla_kernel" if (cfg.shared_latent and cfg.Dqk == 576 and cfg.page_size == 64) else
+                   "attn_general_kernel") + " (verify-attention partition kernel)"
+    if cfg.shared_latent:
+        # the shared-latent shape is bound by the matrix cores: every KV token meets all Hq*T query rows
+        flops = 2.0 * float(att.ctx_len.sum()) * cfg.T * cfg.Hq * (cfg.Dqk + cfg.Dv)
+        tflops = flops / (kern_avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": kernel_name, "achieved": tflops, "peak": 2500.0, "unit": "TFLOP/s",
+                    "frac": tflops / 2500.0, "traffic": traffic, "algorithmic_flops": flops,
+                    "algorithmic_bytes": ab, "kernel_ms_avg": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms))}
+    else:
+        roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "algorithmic_bytes": ab,
+                    "kernel_ms_avg": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms))}
     line = {
         "metric": METRIC,
         "value": tokens / (ms_per_step * 1e-3),
@@ -212,12 +226,7 @@ def main() -> int:
                                    cfg.Hkv, cfg.Dqk, cfg.Dv, cfg.page_size, cfg.T, cfg.V, list(cfg.ctx)),
                    "kv_tokens": int(att.ctx_len.sum()), "seed": cfg.seed,
                    "attention_only": bool(args.attention_only)},
-        "roofline": {"bound": "hbm",
-                     "kernel": ("attn_gqa128_kernel" if (cfg.Dqk == 128 and cfg.page_size == 16 and not cfg.shared_latent)
-                                else "attn_general_kernel") + " (verify-attention partition kernel)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": traffic, "algorithmic_bytes": ab, "kernel_ms_avg": kern_avg_ms,
-                     "kernel_ms_min": float(np.min(kern_ms))},
+        "roofline": roofline,
         "attention_ms": att_ms, "accept_ms": acc_ms,
         "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
         "accept_logits_GBps": (acc.logits.nbytes / (acc_ms * 1e-3) / 1e9) if acc_ms > 0 else None,

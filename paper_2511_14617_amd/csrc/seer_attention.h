@@ -70,7 +70,17 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
         w.wgs_per_head = p.B;
         w.max_items = p.B;
     } else {
-        w.wgs_per_head = kNumCU * resident_wgs_per_cu(p) / p.Hkv;
+        const bool mla_tiled = p.Dqk == 576 && p.Dv == 512 && p.page_size == 64 && p.kv_shared_latent &&
+                               !(p.flags & SEER_ATTN_GENERAL_KERNEL);
+        if (mla_tiled) {
+            // one 4-wave workgroup per CU; a request's rows are cut into blocks of 128, and the
+            // row-block workgroups of one stretch are launched as a group on one XCD (groups of 8 stretches)
+            const int row_blocks = ((p.Hq / p.Hkv) * p.T + 127) / 128;
+            w.wgs_per_head = 8 * (kNumCU / (8 * row_blocks * p.Hkv));
+            if (w.wgs_per_head < 1) w.wgs_per_head = kNumCU / (row_blocks * p.Hkv);
+        } else {
+            w.wgs_per_head = kNumCU * resident_wgs_per_cu(p) / p.Hkv;
+        }
         if (w.wgs_per_head < 1) w.wgs_per_head = 1;
         // a stretch adds one piece per request boundary it crosses: pieces <= W + B
         w.max_items = w.wgs_per_head + p.B;
@@ -114,5 +124,7 @@ hipError_t launch_combine(const AttnArgs& a, hipStream_t stream);
 bool general_supports(int Dqk, int Dv);
 bool gqa128_supports(const AttnArgs& a);                            // D = 128, 16-token pages, G*T <= 256
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream);
+bool mla_supports(const AttnArgs& a);                               // shared latent 576/512, 64-token pages
+hipError_t launch_mla(const AttnArgs& a, hipStream_t stream);
 
 }  // namespace seer

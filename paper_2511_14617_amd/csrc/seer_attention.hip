@@ -432,7 +432,9 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     hipError_t err = seer::launch_plan(a, w, stream);
     if (err != hipSuccess) return static_cast<int>(err);
     if (ev_begin && (err = hipEventRecord(ev_begin, stream)) != hipSuccess) return static_cast<int>(err);
-    if (!(p->flags & SEER_ATTN_GENERAL_KERNEL) && seer::gqa128_supports(a)) err = seer::launch_gqa128(a, stream);
+    const bool tiled_ok = !(p->flags & SEER_ATTN_GENERAL_KERNEL);
+    if (tiled_ok && seer::gqa128_supports(a)) err = seer::launch_gqa128(a, stream);
+    else if (tiled_ok && seer::mla_supports(a)) err = seer::launch_mla(a, stream);
     else err = seer::launch_general(a, stream);
     if (err != hipSuccess) return static_cast<int>(err);
     if (ev_end && (err = hipEventRecord(ev_end, stream)) != hipSuccess) return static_cast<int>(err);

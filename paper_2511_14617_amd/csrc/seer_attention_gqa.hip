@@ -36,14 +36,9 @@
 //                    through two transposing LDS reads (ds_read_b64_tr_b16)
 #include "seer_attention.h"
 #include "seer_device.h"
+#include "seer_tile.h"
 
 namespace seer {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-#define SEER_AS1 __attribute__((address_space(1)))
-#define SEER_AS3 __attribute__((address_space(3)))
 
 constexpr int kD = 128;                  // head dim
 constexpr int kPage = 16;                // tokens per page
@@ -53,35 +48,6 @@ constexpr int kKBytes = kTile * kRowBytes;   // 8192
 constexpr int kStageBytes = 2 * kKBytes;     // K tile then V tile
 constexpr int kBlocks = 16;              // 1 KB wave-loads per tile: 8 of K, 8 of V
 static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel");
-
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-    typedef __attribute__((ext_vector_type(2))) float f32x2;
-    f32x2 v = {lo, hi};
-    bf16x2 r = __builtin_convertvector(v, bf16x2);   // round-to-nearest-even (v_cvt_pk_bf16_f32)
-    return __builtin_bit_cast(uint32_t, r);
-}
-
-// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
-// expcnt 6:4 and lgkmcnt 11:8 left at "do not wait").
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-// Workgroup barrier WITHOUT the memory fences of __syncthreads(): a fence (even one scoped to
-// LDS) makes the compiler drain every outstanding load, including the direct-to-LDS loads of
-// the tiles still in flight, which is exactly what the ring of stages exists to avoid.  The
-// kernel orders its LDS traffic by hand instead: wait_vmcnt for the tile about to be read, then
-// this barrier; LDS reads of a stage are complete (their results consumed by MFMAs) before the
-// wave reaches the barrier after which that stage is overwritten.
-__device__ __forceinline__ void bare_barrier() { __builtin_amdgcn_s_barrier(); }
-// A workgroup-uniform 32-bit value read from global memory, moved to a scalar register.  The
-// hand-placed fences keep the compiler from proving such loads invariant, so it issues them as
-// vector loads; without this the control flow that depends on them would be treated as divergent.
-__device__ __forceinline__ int uniform_load(const int32_t* p) { return __builtin_amdgcn_readfirstlane(*p); }
 
 // Swizzles: a row's 16-byte chunk c is stored at chunk position c ^ f(row).
 //   K: f = row & 7         -> 8 consecutive rows, same chunk: 8 distinct 16-byte bank groups

@@ -18,10 +18,10 @@ def _oracle(inp):
 
 
 def _oracle_abs(inp):
-    """sum_j p_j |v_j|: the oracle on the same inputs with the sign bit of every V cleared.  Only
-    meaningful with a separate V pool (with a shared latent, K would change too)."""
-    assert inp.v_pages is not None
-    return oracle.verify_attention(inp.q, inp.k_pages, inp.v_pages & np.uint16(0x7FFF), inp.block_table,
+    """sum_j p_j |v_j|: the oracle on the same inputs with the sign bit of every V cleared (with a
+    shared latent: an explicit V pool made of the latent's first Dv components, sign cleared)."""
+    v = inp.v_pages if inp.v_pages is not None else np.ascontiguousarray(inp.k_pages[..., : inp.cfg.Dv])
+    return oracle.verify_attention(inp.q, inp.k_pages, v & np.uint16(0x7FFF), inp.block_table,
                                    inp.ctx_len, inp.tree_mask, inp.scale)
 
 
@@ -55,7 +55,7 @@ def test_parity_small(name, values):
     cfg, kw = CASES[name]
     inp = W.make_attention_inputs(cfg, values=values, **kw)
     ref = _oracle(inp)
-    ref_abs = _oracle_abs(inp) if (values == "peaked" and inp.v_pages is not None) else None
+    ref_abs = _oracle_abs(inp) if values == "peaked" else None
     out = _gpu(inp)
     assert_attention_close(out, ref, "%s/%s" % (name, values), hardened=(values == "peaked"), ref_abs=ref_abs)
 
