@@ -309,44 +309,52 @@ hipError_t launch_general(const AttnArgs& a, hipStream_t stream) {
 
 // ---------------------------------------------------------------------------
 // Combine: out = sum_s acc_s * 2^(m_s - M) / sum_s l_s * 2^(m_s - M), M = max_s m_s.
-// One workgroup per output row (b, t, h).
+// A thread owns 4 consecutive output values of one row (16-byte loads of the fp32
+// partials, one 8-byte bf16 store); a 256-thread workgroup covers 1024 / Dv rows,
+// so the launch has a few thousand workgroups instead of one per row.
 // ---------------------------------------------------------------------------
-constexpr int kCombineThreads = 128;
+constexpr int kCombineThreads = 256;
 
-__global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnArgs a) {
-    const size_t row = blockIdx.x;  // (b*T + t)*Hq + h
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnArgs a, long long n_rows) {
+    const int per_row = a.Dv >> 2;                       // threads per output row (Dv is a multiple of 64)
+    const long long gid = static_cast<long long>(blockIdx.x) * kCombineThreads + threadIdx.x;
+    const long long row = gid / per_row;                 // (b*T + t)*Hq + h
+    if (row >= n_rows) return;
+    const int d = static_cast<int>(gid - row * per_row) << 2;
     const int per_b = a.T * a.Hq;
     const int b = static_cast<int>(row / per_b);
-    const int r = static_cast<int>(row - static_cast<size_t>(b) * per_b);
+    const int r = static_cast<int>(row - static_cast<long long>(b) * per_b);
     const int first = a.split_off[b];
     int ns = a.split_off[b + 1] - first;
     if (first + ns > a.max_items) ns = max(0, a.max_items - first);
-    uint16_t* __restrict__ out = static_cast<uint16_t*>(a.out) + row * a.Dv;
 
     float M = kNegInf;
     for (int s = 0; s < ns; ++s)
         M = fmaxf(M, a.part_ml[2 * ((static_cast<size_t>(first) + s) * per_b + r)]);
     float L = 0.f;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < ns; ++s) {
         const size_t prow = (static_cast<size_t>(first) + s) * per_b + r;
         const float ms = a.part_ml[2 * prow];
-        if (ms != kNegInf) L += a.part_ml[2 * prow + 1] * fast_exp2(ms - M);
-    }
-    const float inv = (L > 0.f) ? 1.f / L : 0.f;
-    for (int d = threadIdx.x; d < a.Dv; d += kCombineThreads) {
-        float v = 0.f;
-        for (int s = 0; s < ns; ++s) {
-            const size_t prow = (static_cast<size_t>(first) + s) * per_b + r;
-            const float ms = a.part_ml[2 * prow];
-            if (ms != kNegInf) v += a.part_acc[prow * a.Dv + d] * fast_exp2(ms - M);
+        if (ms != kNegInf) {
+            const float w = fast_exp2(ms - M);
+            L += a.part_ml[2 * prow + 1] * w;
+            const f32x4 p = *reinterpret_cast<const f32x4*>(a.part_acc + prow * a.Dv + d);
+            v += p * w;
         }
-        out[d] = f32_to_bf16(v * inv);
     }
+    const float inv = (L > 0.f) ? 1.f / L : 0.f;         // a row that saw nothing: zeros
+    u32x2 o;
+    o[0] = pack_bf16x2(v[0] * inv, v[1] * inv);
+    o[1] = pack_bf16x2(v[2] * inv, v[3] * inv);
+    *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.out) + row * a.Dv + d) = o;
 }
 
 hipError_t launch_combine(const AttnArgs& a, hipStream_t stream) {
-    const size_t rows = static_cast<size_t>(a.B) * a.T * a.Hq;
-    hipLaunchKernelGGL(combine_kernel, dim3(static_cast<unsigned>(rows)), dim3(kCombineThreads), 0, stream, a);
+    const long long rows = static_cast<long long>(a.B) * a.T * a.Hq;
+    const long long threads = rows * (a.Dv >> 2);
+    const unsigned blocks = static_cast<unsigned>((threads + kCombineThreads - 1) / kCombineThreads);
+    hipLaunchKernelGGL(combine_kernel, dim3(blocks), dim3(kCombineThreads), 0, stream, a, rows);
     return hipGetLastError();
 }
 

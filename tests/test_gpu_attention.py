@@ -43,6 +43,8 @@ CASES = {
     "mla_latent": (W.CONFIGS[4].scaled(B=2, Hq=16, ctx=("uniform", 300, 900)), {}),
     "T1_decode": (W.CONFIGS[1].scaled(T=1, B=5, ctx=("uniform", 1, 700)), {}),
     "prefix_shorter_than_draft": (W.CONFIGS[1].scaled(T=9, B=6, ctx=("uniform", 9, 40)), {}),
+    "many_short_requests": (W.CONFIGS[2].scaled(B=300, group_size=6, T=4, ctx=("uniform", 4, 150), shared_prefix=32), {}),
+    "many_short_mla": (W.CONFIGS[4].scaled(B=40, Hq=32, T=3, ctx=("uniform", 3, 200)), {}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
     "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
                                            ctx=("uniform", 50, 900)), {}),
