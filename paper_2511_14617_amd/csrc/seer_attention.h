@@ -58,7 +58,7 @@ inline int resident_wgs_per_cu(const seer_attn_params& p) {
     if (!tiled) return 4;
     const int waves = ((p.Hq / p.Hkv) * p.T + 31) / 32;   // one wave per 32 query rows
     const int by_waves = 8 / waves;                       // 2 waves per SIMD, 4 SIMDs
-    const int by_lds = 3;                                 // 160 KB / (3 stages x 16 KB)
+    const int by_lds = 4;                                 // 2 stages x 16 KB per workgroup: LDS is not the limit
     return by_waves < 1 ? 1 : (by_waves < by_lds ? by_waves : by_lds);
 }
 

@@ -20,7 +20,8 @@
 // Data flow per 32-token tile (two pages, 8 KB of K and 8 KB of V)
 //   HBM -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane, 1 KB per wave
 //          instruction, no staging registers), into a ring of NS stages, so NS-1 tiles
-//          per workgroup are in flight while one is computed.  Rows are 256 B, unpadded;
+//          per workgroup are in flight while one is computed (NS = 2: measured, four
+//          resident workgroups per CU with one tile in flight each beat three with two).  Rows are 256 B, unpadded;
 //          the 16-byte chunks of a row are stored XOR-swizzled (the lane picks which
 //          global chunk lands in its fixed LDS slot), which makes the operand reads
 //          below free of bank conflicts.  Completion is tracked by hand: s_waitcnt
@@ -383,7 +384,7 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                               \
     case NW_:                                                                                            \
-        hipLaunchKernelGGL((attn_gqa128_kernel<NW_, 3>), grid, dim3(NW_ * kWave), 0, stream, a);         \
+        hipLaunchKernelGGL((attn_gqa128_kernel<NW_, 2>), grid, dim3(NW_ * kWave), 0, stream, a);         \
         break;
         SEER_GQA_CASE(1)
         SEER_GQA_CASE(2)
