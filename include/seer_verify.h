@@ -68,7 +68,7 @@ typedef struct seer_attn_params {
     int32_t max_splits;        /* cap on split-K partitions per request, 1..256; 0 = library default */
     int32_t kv_shared_latent;  /* 0: separate K and V pools; 1: V = first Dv components of K (MLA, absorbed form) */
     int32_t flags;             /* SEER_ATTN_* bits, normally 0                        */
-    float scale;               /* softmax scale applied to q.k                        */
+    float scale;               /* softmax scale applied to q.k: positive and finite   */
 } seer_attn_params;
 
 /* flags: run the general kernel even where a tiled one exists (for cross-checks). */

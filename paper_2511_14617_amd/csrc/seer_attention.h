@@ -2,6 +2,7 @@
 // plan that lives at the head of the caller's workspace, and the launchers of
 // the individual kernels.
 #pragma once
+#include <stdlib.h>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -51,6 +52,13 @@ struct WorkspaceLayout {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// EXPERIMENT: ring depth of the pipelined tiled kernel by waves per workgroup (0: plain kernel).
+inline int gqa_pipe_depth(int waves) {
+    static const int forced = [] { const char* e = getenv("SEER_GQA_D"); return e ? atoi(e) : -1; }();
+    if (forced >= 0) return forced;
+    return waves == 2 ? 1 : (waves == 3 ? 3 : (waves == 5 ? 4 : 0));
+}
+
 // Workgroups of the partition kernel that one CU holds at once, by kernel shape.
 inline int resident_wgs_per_cu(const seer_attn_params& p) {
     const bool tiled = p.Dqk == 128 && p.Dv == 128 && p.page_size == 16 && !p.kv_shared_latent &&
@@ -58,7 +66,8 @@ inline int resident_wgs_per_cu(const seer_attn_params& p) {
     if (!tiled) return 4;
     const int waves = ((p.Hq / p.Hkv) * p.T + 31) / 32;   // one wave per 32 query rows
     const int by_waves = 8 / waves;                       // 2 waves per SIMD, 4 SIMDs
-    const int by_lds = 4;                                 // 2 stages x 16 KB per workgroup: LDS is not the limit
+    const int depth = gqa_pipe_depth(waves);
+    const int by_lds = depth > 0 ? 160 / (16 * (depth + 1)) : 4;   // 160 KB of LDS per CU
     return by_waves < 1 ? 1 : (by_waves < by_lds ? by_waves : by_lds);
 }
 

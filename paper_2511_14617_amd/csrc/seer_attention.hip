@@ -372,7 +372,7 @@ int validate_params(const seer_attn_params* p) {
     if (p->max_splits < 0 || p->max_splits > 256) return SEER_ESHAPE;
     if (p->flags & ~SEER_ATTN_GENERAL_KERNEL) return SEER_EINVAL;
     if (p->Hq > 65535 || p->T * (int64_t)p->Hq * p->B > 0x7fffffffLL) return SEER_ESHAPE;
-    if (!(p->scale == p->scale)) return SEER_EINVAL;
+    if (!(p->scale > 0.f) || p->scale > 3.0e38f) return SEER_EINVAL;   // positive and finite
     if (!seer::general_supports(p->Dqk, p->Dv)) return SEER_EUNSUPPORTED;
     if (p->kv_shared_latent && p->Dv > p->Dqk) return SEER_ESHAPE;
     return SEER_OK;

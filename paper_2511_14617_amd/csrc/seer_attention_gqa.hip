@@ -35,6 +35,8 @@
 //   O^T += V^T . P^T M = d (4 tiles of 32), N = rows, 2 steps over the tokens; the
 //                    V^T operand (8 tokens at one d) comes from the token-major tile
 //                    through two transposing LDS reads (ds_read_b64_tr_b16)
+#include <type_traits>
+
 #include "seer_attention.h"
 #include "seer_device.h"
 #include "seer_tile.h"
@@ -372,6 +374,591 @@ void attn_gqa128_kernel(AttnArgs a) {
     if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
 }
 
+
+// ======================================================================================
+// Software-pipelined variant.
+//
+// The kernel above runs a tile's three phases one after the other in each wave: scores (MFMA),
+// softmax (vector ALU), P.V (MFMA).  A wave that has a SIMD to itself therefore leaves the
+// matrix core idle during its softmax and the vector ALU idle during its MFMAs, and waves that
+// share a SIMD do not fill each other's gaps either, because the per-tile barrier keeps them in
+// the same phase.  Here one loop step works on three consecutive tiles at once, in one basic
+// block with no dependence between the three parts:
+//     step u:   P.V of tile u-2 (MFMA)  |  softmax of tile u-1 (VALU)  |  scores of tile u (MFMA)
+// so the hardware overlaps the VALU work with the MFMAs of the same wave.
+//
+// K is needed two steps before the V of the same tile, so K and V have rings of their own
+// (D+1 slots of 8 KB each) and step u issues the loads of K tile u+D and V tile u+D-2: both are
+// consumed D steps after they were issued, D-1 steps' loads stay in flight behind them.
+// The running-max reference of a row only moves when the new maximum exceeds it by more than
+// 2^8 (the probabilities then stay below 256, exact enough in bf16's 8 bits as before), which
+// makes the rescaling of the 64 output accumulators rare.
+// ======================================================================================
+
+// Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the NW waves.
+template <int NW>
+__device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, size_t p0, size_t p1,
+                                                const unsigned char* base, int goff0, int goff1) {
+#pragma unroll
+    for (int i = 0; i < (8 + NW - 1) / NW; ++i) {
+        const int j = wave + i * NW;
+        if (j < 8) {
+            const size_t pg = (j < 4) ? p0 : p1;
+            const unsigned char* src = base + pg + (j & 3) * (4 * kRowBytes) + ((j & 1) ? goff1 : goff0);
+            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(slot + j * 1024), 16, 0, 0);
+        }
+    }
+}
+
+// 8 transposing reads: for each of the 4 d-tiles, the tokens +0..3 and +8..11 of one 16-token half.
+#define SEER_GQA_TR8(vr_, a0_, a1_, a2_, a3_, OFF0, OFF1)                                                  \
+    asm volatile("ds_read_b64_tr_b16 %0, %8 offset:" #OFF0 "\n"                                            \
+                 "ds_read_b64_tr_b16 %1, %8 offset:" #OFF1 "\n"                                            \
+                 "ds_read_b64_tr_b16 %2, %9 offset:" #OFF0 "\n"                                            \
+                 "ds_read_b64_tr_b16 %3, %9 offset:" #OFF1 "\n"                                            \
+                 "ds_read_b64_tr_b16 %4, %10 offset:" #OFF0 "\n"                                           \
+                 "ds_read_b64_tr_b16 %5, %10 offset:" #OFF1 "\n"                                           \
+                 "ds_read_b64_tr_b16 %6, %11 offset:" #OFF0 "\n"                                           \
+                 "ds_read_b64_tr_b16 %7, %11 offset:" #OFF1 "\n"                                           \
+                 "s_waitcnt lgkmcnt(0)"                                                                    \
+                 : "=&v"(vr_[0][0]), "=&v"(vr_[0][1]), "=&v"(vr_[1][0]), "=&v"(vr_[1][1]), "=&v"(vr_[2][0]), \
+                   "=&v"(vr_[2][1]), "=&v"(vr_[3][0]), "=&v"(vr_[3][1])                                    \
+                 : "v"(a0_), "v"(a1_), "v"(a2_), "v"(a3_))
+
+// max over the two lanes that share a query row (lane and lane ^ 32), without touching LDS:
+// v_permlane32_swap exchanges the upper 32 lanes of its first operand with the lower 32 lanes of
+// its second, so from two copies of x one register ends up with the lower half's values in both
+// halves and the other with the upper half's.  (Issued from an asm block: with the builtin this
+// compiler keeps only the first of the two results.  The s_nop covers the wait states the
+// instruction needs after a vector-ALU write of its operands.)
+__device__ __forceinline__ float max_across_halves(float x) {
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return fmaxf(a, b);
+}
+
+// Softmax bookkeeping of one tile for this lane's row, from the row's raw score maximum mx_raw
+// (masked slots excluded): moves the exponent reference m_run only when the new maximum exceeds
+// it by more than 8 (probabilities then stay below 2^8), returns the reference to subtract (in
+// units of log2 e, scores scaled) and leaves in alpha the factor that brings sums taken under the
+// old reference to the new one.  scale_log2 > 0.
+__device__ __forceinline__ float move_reference(float mx_raw, float scale_log2, float& m_run, float& alpha) {
+    const float mx = max_across_halves(mx_raw) * scale_log2;
+    const float m_new = (mx > m_run + 8.f) ? mx : m_run;      // m_run = -inf: any finite mx moves it
+    const float m_use = (m_new == kNegInf) ? 0.f : m_new;      // nothing visible yet: keep exp2 finite
+    alpha = fast_exp2(m_run - m_use);
+    m_run = m_new;
+    return m_use;
+}
+
+__device__ __forceinline__ void rescale_if_moved(f32x16 (&acc)[4], float alpha) {
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+    }
+}
+
+// One pipeline step at the ends of a piece, where not all three parts exist (the steady state is
+// fused_step below).  k_off / v_off: byte offsets in LDS of the K slot the scores read and of the
+// V slot (row part of the lane's address included) the P.V product reads.  alpha is the
+// rescaling factor the previous step's softmax left for the output accumulators: it is applied
+// before this step's P.V, and replaced by this step's softmax.
+template <bool DO_QK, bool DO_SM, bool DO_PV>
+__device__ __forceinline__ void pipe_step(const unsigned char* lds, int k_off, int v_off, const int (&k_rd)[8],
+                                          const int (&v_rd)[4], const bf16x8 (&qreg)[8], f32x16& s_sm,
+                                          f32x16& s_qk, const uint32_t (&pk_pv)[8], uint32_t (&pk_sm)[8],
+                                          f32x16 (&acc)[4], float& m_run, float& l_run, float& alpha,
+                                          float scale_log2, uint32_t vis) {
+    if constexpr (DO_PV) {
+        rescale_if_moved(acc, alpha);
+        alpha = 1.f;
+        // O^T[d][row] += sum_token V[token][d] * P[row][token], 16 tokens at a time
+        const int a0 = v_off + v_rd[0], a1 = v_off + v_rd[1], a2 = v_off + v_rd[2], a3 = v_off + v_rd[3];
+        u32x2 vr[4][2];
+        SEER_GQA_TR8(vr, a0, a1, a2, a3, 0, 2048);
+        const bf16x8 pb0 = as_bf16x8(u32x4{pk_pv[0], pk_pv[1], pk_pv[2], pk_pv[3]});
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            const bf16x8 va = as_bf16x8(u32x4{vr[dt][0][0], vr[dt][0][1], vr[dt][1][0], vr[dt][1][1]});
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb0, acc[dt], 0, 0, 0);
+        }
+        u32x2 vq[4][2];
+        SEER_GQA_TR8(vq, a0, a1, a2, a3, 4096, 6144);
+        const bf16x8 pb1 = as_bf16x8(u32x4{pk_pv[4], pk_pv[5], pk_pv[6], pk_pv[7]});
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            const bf16x8 va = as_bf16x8(u32x4{vq[dt][0][0], vq[dt][0][1], vq[dt][1][0], vq[dt][1][1]});
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb1, acc[dt], 0, 0, 0);
+        }
+    }
+    if constexpr (DO_QK) {
+        // S^T[token][row] = sum_d K[token][d] * Q[row][d]
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_qk[i] = 0.f;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            u32x4 kv[4];
+            const int b0 = k_off + k_rd[4 * h], b1 = k_off + k_rd[4 * h + 1], b2 = k_off + k_rd[4 * h + 2],
+                      b3 = k_off + k_rd[4 * h + 3];
+            asm volatile("ds_read_b128 %0, %4\n"
+                         "ds_read_b128 %1, %5\n"
+                         "ds_read_b128 %2, %6\n"
+                         "ds_read_b128 %3, %7\n"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(kv[0]), "=&v"(kv[1]), "=&v"(kv[2]), "=&v"(kv[3])
+                         : "v"(b0), "v"(b1), "v"(b2), "v"(b3));
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                s_qk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kv[kk]), qreg[4 * h + kk], s_qk, 0, 0, 0);
+        }
+    }
+    if constexpr (DO_SM) {
+        // register i of s_sm holds token (i/4)*8 + lg*4 + i%4 of the tile (vis is already shifted by lg*4)
+        float mx = kNegInf;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (!((vis >> ((i >> 2) * 8 + (i & 3))) & 1u)) s_sm[i] = kNegInf;
+            mx = fmaxf(mx, s_sm[i]);
+        }
+        const float m_use = move_reference(mx, scale_log2, m_run, alpha);
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float p0 = fast_exp2(fmaf(s_sm[i], scale_log2, -m_use));
+            const float p1 = fast_exp2(fmaf(s_sm[i + 1], scale_log2, -m_use));
+            psum += p0 + p1;
+            pk_sm[i >> 1] = cvt_pk_bf16(p0, p1);
+        }
+        l_run = l_run * alpha + psum;
+    }
+}
+
+// Operand reads whose issue and completion are separated by hand.  The issuing block names the
+// destination registers as outputs although they are only written when the read returns; the
+// matching SEER_LGKM_WAIT block (s_waitcnt lgkmcnt(N), N = reads issued after the group: LDS
+// returns in order) takes them as read-write operands, so every use of the data is ordered after
+// the wait, and nothing between the two blocks has a reason to touch them.
+#define SEER_TR8_ISSUE(vr_, a0_, a1_, a2_, a3_, OFF0, OFF1)                                                \
+    asm volatile("ds_read_b64_tr_b16 %0, %8 offset:" #OFF0 "\n"                                            \
+                 "ds_read_b64_tr_b16 %1, %8 offset:" #OFF1 "\n"                                            \
+                 "ds_read_b64_tr_b16 %2, %9 offset:" #OFF0 "\n"                                            \
+                 "ds_read_b64_tr_b16 %3, %9 offset:" #OFF1 "\n"                                            \
+                 "ds_read_b64_tr_b16 %4, %10 offset:" #OFF0 "\n"                                           \
+                 "ds_read_b64_tr_b16 %5, %10 offset:" #OFF1 "\n"                                           \
+                 "ds_read_b64_tr_b16 %6, %11 offset:" #OFF0 "\n"                                           \
+                 "ds_read_b64_tr_b16 %7, %11 offset:" #OFF1                                                \
+                 : "=&v"(vr_[0][0]), "=&v"(vr_[0][1]), "=&v"(vr_[1][0]), "=&v"(vr_[1][1]), "=&v"(vr_[2][0]), \
+                   "=&v"(vr_[2][1]), "=&v"(vr_[3][0]), "=&v"(vr_[3][1])                                    \
+                 : "v"(a0_), "v"(a1_), "v"(a2_), "v"(a3_))
+#define SEER_TR8_WAIT(N, vr_)                                                                              \
+    asm volatile("s_waitcnt lgkmcnt(" #N ")"                                                               \
+                 : "+v"(vr_[0][0]), "+v"(vr_[0][1]), "+v"(vr_[1][0]), "+v"(vr_[1][1]), "+v"(vr_[2][0]),    \
+                   "+v"(vr_[2][1]), "+v"(vr_[3][0]), "+v"(vr_[3][1]))
+#define SEER_K4_ISSUE(kv_, b0_, b1_, b2_, b3_)                                                             \
+    asm volatile("ds_read_b128 %0, %4\n"                                                                   \
+                 "ds_read_b128 %1, %5\n"                                                                   \
+                 "ds_read_b128 %2, %6\n"                                                                   \
+                 "ds_read_b128 %3, %7"                                                                     \
+                 : "=&v"(kv_[0]), "=&v"(kv_[1]), "=&v"(kv_[2]), "=&v"(kv_[3])                              \
+                 : "v"(b0_), "v"(b1_), "v"(b2_), "v"(b3_))
+#define SEER_K4_WAIT(N, kv_)                                                                               \
+    asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(kv_[0]), "+v"(kv_[1]), "+v"(kv_[2]), "+v"(kv_[3]))
+#define SEER_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Keeps the computation of x in the block (and at the place) where it is written: a value whose
+// only uses are in a later block is otherwise sunk there, out of the shadow of the MFMAs.
+#define SEER_PIN(x) asm volatile("" : "+v"(x))
+
+// The steady-state step: P.V of tile u-2 (8 MFMAs), scores of tile u (8 MFMAs) and the softmax of
+// tile u-1 (about 80 vector-ALU instructions), with the instruction order fixed by hand: one
+// MFMA, then the slice of softmax work that fits in the 32 cycles the matrix core is busy with
+// it.  The compiler's scheduler, left alone, issues the sixteen MFMAs back to back and the
+// softmax after them, which serialises the two units (a wave issues in order).  The operand
+// reads run one group of four MFMAs ahead.
+//
+// issue_k / issue_v issue the step's HBM loads; they are called where their scalar address
+// arithmetic runs in the shadow of LDS reads already issued and of MFMAs already queued.
+template <bool MASKED, typename IssueK, typename IssueV>
+__device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_rd)[8], const int (&v_rd)[4],
+                                           const bf16x8 (&qreg)[8], f32x16& s_sm, f32x16& s_qk,
+                                           const uint32_t (&pk_pv)[8], uint32_t (&pk_sm)[8], f32x16 (&acc)[4],
+                                           float& m_run, float& l_run, float& alpha, float scale_log2,
+                                           uint32_t vis, IssueK&& issue_k, IssueV&& issue_v) {
+    const int a0 = v_off + v_rd[0], a1 = v_off + v_rd[1], a2 = v_off + v_rd[2], a3 = v_off + v_rd[3];
+    u32x2 va[4][2], vb[4][2];
+    u32x4 ka[4], kb[4];
+    SEER_TR8_ISSUE(va, a0, a1, a2, a3, 0, 2048);
+    SEER_TR8_ISSUE(vb, a0, a1, a2, a3, 4096, 6144);
+    issue_k();
+    rescale_if_moved(acc, alpha);
+    if constexpr (MASKED) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (!((vis >> ((i >> 2) * 8 + (i & 3))) & 1u)) s_sm[i] = kNegInf;
+    }
+    SEER_TR8_WAIT(8, va);
+    SEER_SCHED_FENCE();
+    // ---- MFMAs 0..3: P.V on tokens 0..15 | row maximum
+    const bf16x8 pb0 = as_bf16x8(u32x4{pk_pv[0], pk_pv[1], pk_pv[2], pk_pv[3]});
+    float mx = kNegInf;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        const bf16x8 v = as_bf16x8(u32x4{va[dt][0][0], va[dt][0][1], va[dt][1][0], va[dt][1][1]});
+        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, pb0, acc[dt], 0, 0, 0);
+        mx = fmaxf(fmaxf(mx, s_sm[4 * dt]), s_sm[4 * dt + 1]);
+        mx = fmaxf(fmaxf(mx, s_sm[4 * dt + 2]), s_sm[4 * dt + 3]);
+        SEER_PIN(mx);
+        SEER_SCHED_FENCE();
+    }
+    {
+        const int b0 = k_off + k_rd[0], b1 = k_off + k_rd[1], b2 = k_off + k_rd[2], b3 = k_off + k_rd[3];
+        SEER_K4_ISSUE(ka, b0, b1, b2, b3);
+    }
+    issue_v();
+    SEER_TR8_WAIT(4, vb);
+    SEER_SCHED_FENCE();
+    // ---- MFMAs 4..7: P.V on tokens 16..31 | exponent reference, first two pairs of probabilities
+    const bf16x8 pb1 = as_bf16x8(u32x4{pk_pv[4], pk_pv[5], pk_pv[6], pk_pv[7]});
+    float m_use = 0.f, psum = 0.f;
+    auto pair = [&](int i) __attribute__((always_inline)) {
+        const float p0 = fast_exp2(fmaf(s_sm[2 * i], scale_log2, -m_use));
+        const float p1 = fast_exp2(fmaf(s_sm[2 * i + 1], scale_log2, -m_use));
+        psum += p0 + p1;
+        pk_sm[i] = cvt_pk_bf16(p0, p1);
+        SEER_PIN(pk_sm[i]);
+        SEER_PIN(psum);
+    };
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        const bf16x8 v = as_bf16x8(u32x4{vb[dt][0][0], vb[dt][0][1], vb[dt][1][0], vb[dt][1][1]});
+        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, pb1, acc[dt], 0, 0, 0);
+        if (dt == 0) {
+            m_use = move_reference(mx, scale_log2, m_run, alpha);
+            SEER_PIN(m_use);
+            SEER_PIN(alpha);
+            SEER_PIN(m_run);
+        }
+        if (dt == 2) pair(0);
+        if (dt == 3) pair(1);
+        SEER_SCHED_FENCE();
+    }
+    {
+        const int b0 = k_off + k_rd[4], b1 = k_off + k_rd[5], b2 = k_off + k_rd[6], b3 = k_off + k_rd[7];
+        SEER_K4_ISSUE(kb, b0, b1, b2, b3);
+    }
+    SEER_K4_WAIT(4, ka);
+    SEER_SCHED_FENCE();
+    // ---- MFMAs 8..15: scores of the next tile | the other six pairs
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_qk[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        s_qk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[kk]), qreg[kk], s_qk, 0, 0, 0);
+        pair(2 + kk);
+        SEER_SCHED_FENCE();
+    }
+    SEER_K4_WAIT(0, kb);
+    SEER_SCHED_FENCE();
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        s_qk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kb[kk]), qreg[4 + kk], s_qk, 0, 0, 0);
+        if (kk < 2) pair(6 + kk);
+        if (kk == 2) {
+            l_run = l_run * alpha + psum;
+            SEER_PIN(l_run);
+        }
+        SEER_SCHED_FENCE();
+    }
+}
+
+template <int NW, int D>
+__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
+void attn_gqa128_pipe_kernel(AttnArgs a) {
+    constexpr int NT = NW * kWave;
+    constexpr int NSLOT = D + 1;                    // slots in the K ring and in the V ring
+    constexpr int CEIL = (8 + NW - 1) / NW;         // half-tile blocks of the busiest waves
+    constexpr int FLOOR = 8 / NW;
+    constexpr int REM = 8 % NW;                     // waves below this index load CEIL blocks, the others FLOOR
+    static_assert(D >= 1 && (D - 1) * 2 * CEIL < 64, "vmcnt range");
+
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * NSLOT * kKBytes];   // K ring, then V ring
+    constexpr int kVRing = NSLOT * kKBytes;
+
+    const int kvh = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int ln = lane & 31;
+    const int lg = lane >> 5;
+    const int l16 = lane >> 4;
+    const int p16 = lane & 15;
+
+    const int wg = blockIdx.x;
+    const int L = uniform_load(&a.header->tiles_per_wg);
+    int b = uniform_load(a.wg_first + wg);
+    if (b < 0) return;
+    int g = L ? wg * L : uniform_load(a.tile_off + b);
+    const int g_end = L ? min((wg + 1) * L, uniform_load(&a.header->total_tiles)) : uniform_load(a.tile_off + b + 1);
+    bool bad_page = false;
+
+    const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
+    const unsigned char* __restrict__ vbase = static_cast<const unsigned char*>(a.v_pages);
+    const uint32_t page_bytes32 = static_cast<uint32_t>(a.Hkv) * kPage * kRowBytes;   // one page, all kv heads
+    const size_t head_off = static_cast<size_t>(kvh) * kPage * kRowBytes;
+    const int goff_k0 = l16 * kRowBytes + ((p16 ^ k_swz(l16)) << 4);
+    const int goff_k1 = l16 * kRowBytes + ((p16 ^ k_swz(4 + l16)) << 4);
+    const int goff_v = l16 * kRowBytes + ((p16 ^ v_swz(l16)) << 4);
+    int k_rd[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) k_rd[kk] = ln * kRowBytes + (((2 * kk + lg) ^ k_swz(ln)) << 4);
+    const int v_k = p16 >> 2, v_c4 = p16 & 3, v_dhalf = l16 & 1;
+    int v_rd[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        const int chunk = dt * 4 + v_dhalf * 2 + (v_c4 >> 1);
+        v_rd[dt] = ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;
+    }
+    const int v_row0 = (lg * 4 + v_k) * kRowBytes;
+
+  for (; g < g_end; ++b) {
+    const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
+    if (t_hi == t_lo) continue;
+    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - t_lo / L : 0);
+    const int n = uniform_load(a.ctx_len + b);
+    const int tok_begin = (g - t_lo) * kTile;
+    const int tok_end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
+    g = t_hi;
+    const int n0 = n - a.T;
+    const int n_tiles = (tok_end - tok_begin + kTile - 1) / kTile;
+    bare_barrier();                                // every wave is done with the previous piece's slots
+
+    const int R = a.G * a.T;
+    const int r = wave * 32 + ln;
+    const bool row_ok = r < R;
+    const int t = row_ok ? r / a.G : 0;
+    const int hq = kvh * a.G + (row_ok ? r - t * a.G : 0);
+    uint64_t word = 0;
+    if (row_ok) {
+        word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
+                           : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
+        if (a.T < 64) word &= (1ull << a.T) - 1;
+    }
+    bf16x8 qreg[8];
+    {
+        const u32x4* qp = reinterpret_cast<const u32x4*>(
+            static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * kD + lg * 8);
+        u32x4 qv[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            qv[kk] = u32x4{0u, 0u, 0u, 0u};
+            if (row_ok) qv[kk] = qp[kk * 2];
+        }
+        // pin the arrival of these loads to here (see the kernel above)
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            asm volatile("" : "+v"(qv[kk]));
+            qreg[kk] = as_bf16x8(qv[kk]);
+        }
+        uint32_t w_lo = static_cast<uint32_t>(word), w_hi = static_cast<uint32_t>(word >> 32);
+        asm volatile("" : "+v"(w_lo), "+v"(w_hi));
+        word = (static_cast<uint64_t>(w_hi) << 32) | w_lo;
+    }
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
+    float m_run = kNegInf, l_run = 0.f, alpha = 1.f;
+
+    // page ids, 64 at a time (lane l holds logical page cache_base + l), handed out with v_readlane.
+    // A tile is one even-numbered page and its successor, and windows start at even pages, so one
+    // window test covers both.
+    const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
+    int cache_base = -0x40000000;
+    int pg_cache = 0;
+    const int last_page = (n - 1) / kPage;
+    auto page_pair = [&](int lp, size_t& p0, size_t& p1) __attribute__((always_inline)) {
+        if (lp < cache_base || lp >= cache_base + kWave) {   // uniform
+            cache_base = lp;
+            const int idx = cache_base + lane;
+            int pg = table[min(idx, a.max_pages - 1)];
+            if (pg < 0 || pg >= a.num_pages) {
+                if (idx <= last_page) bad_page = true;
+                pg = min(max(pg, 0), a.num_pages - 1);
+            }
+            pg_cache = pg;
+        }
+        const int i0 = __builtin_amdgcn_readfirstlane(lp - cache_base);
+        const uint32_t g0 = __builtin_amdgcn_readlane(pg_cache, i0), g1 = __builtin_amdgcn_readlane(pg_cache, i0 + 1);
+        p0 = static_cast<uint64_t>(g0) * page_bytes32 + head_off;
+        p1 = static_cast<uint64_t>(g1) * page_bytes32 + head_off;
+    };
+
+    // loads of step j: K tile j + D and V tile j + D - 2, where they exist.  The V tile sits in
+    // the same pages of its pool as the K tile issued two steps earlier, whose offsets are kept.
+    size_t pq0 = 0, pq1 = 0, pr0 = 0, pr1 = 0;     // page offsets of the K tiles of steps j - 1 and j - 2
+    size_t pn0 = 0, pn1 = 0;
+    auto issue_k = [&](int j) __attribute__((always_inline)) {
+        const int kt = j + D;
+        if (kt < n_tiles) {
+            page_pair((tok_begin + kt * kTile) / kPage, pn0, pn1);
+            issue_half_tile<NW>(lds + (kt % NSLOT) * kKBytes, wave, pn0, pn1, kbase, goff_k0, goff_k1);
+        }
+    };
+    auto issue_v = [&](int j) __attribute__((always_inline)) {
+        const int vt = j + D - 2;
+        if (vt >= 0 && vt < n_tiles)
+            issue_half_tile<NW>(lds + kVRing + (vt % NSLOT) * kKBytes, wave, pr0, pr1, vbase, goff_v, goff_v);
+        pr0 = pq0, pr1 = pq1, pq0 = pn0, pq1 = pn1;
+    };
+    auto issue_step = [&](int j) __attribute__((always_inline)) {
+        issue_k(j);
+        issue_v(j);
+    };
+    // The loads of step u - D have landed when at most the loads of the D - 1 steps after it are
+    // outstanding.  That count is a compile-time number only while those steps all issued a full
+    // K and V half tile; at the two ends of a piece wait for everything instead.
+    auto wait_step = [&](int u) __attribute__((always_inline)) {
+        const bool full = D > 1 && u >= 1 && u + D - 1 < n_tiles;
+        if (full) {
+            if (REM == 0 || wave < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            else wait_vmcnt<(D - 1) * 2 * FLOOR>();
+        } else {
+            wait_vmcnt<0>();
+        }
+    };
+    // visibility bits of tile j's 32 tokens for this lane's row, shifted to the lane's token half
+    auto vis_of = [&](int j) __attribute__((always_inline)) -> uint32_t {
+        const int rel = tok_begin + j * kTile - n0;          // uniform; in (-32, 64) for a masked tile
+        if (rel <= -kTile) return ~0u;                        // a tile of prefix tokens only
+        const uint32_t vis = rel >= 0 ? static_cast<uint32_t>(word >> rel)
+                                      : (static_cast<uint32_t>(word << (-rel)) | ((1u << (-rel)) - 1u));
+        return vis >> (lg * 4);
+    };
+    auto k_off = [&](int j) __attribute__((always_inline)) -> int { return (j % NSLOT) * kKBytes; };
+    auto v_off = [&](int j) __attribute__((always_inline)) -> int {
+        return kVRing + (j % NSLOT) * kKBytes + v_row0;
+    };
+
+#pragma unroll
+    for (int j = -D; j < 0; ++j) issue_step(j);
+
+    f32x16 s_a, s_b;
+    uint32_t pk_a[8], pk_b[8];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_a[i] = s_b[i] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pk_a[i] = pk_b[i] = 0u;
+
+    // step 0: scores of tile 0 -> s_a
+    wait_step(0);
+    bare_barrier();
+    issue_step(0);
+    pipe_step<true, false, false>(lds, k_off(0), 0, k_rd, v_rd, qreg, s_b, s_a, pk_b, pk_a, acc, m_run, l_run, alpha,
+                                  a.scale_log2, 0u);
+    // step 1: softmax of tile 0 (s_a -> pk_a), scores of tile 1 -> s_b
+    wait_step(1);
+    bare_barrier();
+    issue_step(1);
+    {
+        const uint32_t vis = vis_of(0);
+        if (n_tiles > 1)
+            pipe_step<true, true, false>(lds, k_off(1), 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run,
+                                         alpha, a.scale_log2, vis);
+        else
+            pipe_step<false, true, false>(lds, 0, 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run, alpha,
+                                          a.scale_log2, vis);
+    }
+    // steps 2 .. n_tiles - 1: P.V of tile u-2 (pk_a), softmax of tile u-1 (s_b -> pk_b), scores of tile u -> s_a,
+    // after which the two register sets have swapped roles.  Tiles are masked from some tile on
+    // (the draft slots are the last T positions), so the steps split into an unmasked run, taken
+    // two steps per iteration so that the role swap costs no register moves, and a short masked run.
+    auto full_step = [&](auto masked, int u, f32x16& s_sm, f32x16& s_qk, uint32_t (&pk_pv)[8],
+                         uint32_t (&pk_sm)[8]) __attribute__((always_inline)) {
+        wait_step(u);
+        bare_barrier();                        // all waves: loads of step u - D landed, step u - 1 computed
+        fused_step<decltype(masked)::value>(
+            k_off(u), v_off(u - 2), k_rd, v_rd, qreg, s_sm, s_qk, pk_pv, pk_sm, acc, m_run, l_run, alpha, a.scale_log2,
+            decltype(masked)::value ? vis_of(u - 1) : 0u, [&]() __attribute__((always_inline)) { issue_k(u); },
+            [&]() __attribute__((always_inline)) { issue_v(u); });
+    };
+    auto swap_roles = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { const float x = s_a[i]; s_a[i] = s_b[i]; s_b[i] = x; }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const uint32_t x = pk_a[i]; pk_a[i] = pk_b[i]; pk_b[i] = x; }
+    };
+    {
+        const int first_masked = n0 > tok_begin ? (n0 - tok_begin) / kTile : 0;   // first tile with masked slots
+        const int u_split = min(max(first_masked + 1, 2), n_tiles);
+        int u = 2;
+        for (; u + 1 < u_split; u += 2) {
+            full_step(std::false_type{}, u, s_b, s_a, pk_a, pk_b);
+            full_step(std::false_type{}, u + 1, s_a, s_b, pk_b, pk_a);
+        }
+        if (u < u_split) {
+            full_step(std::false_type{}, u, s_b, s_a, pk_a, pk_b);
+            swap_roles();
+            ++u;
+        }
+        for (; u < n_tiles; ++u) {
+            full_step(std::true_type{}, u, s_b, s_a, pk_a, pk_b);
+            swap_roles();
+        }
+    }
+    // now: s_b = scores of the last tile (if n_tiles > 1), pk_a = probabilities of tile n_tiles - 2
+    if (n_tiles > 1) {
+        const int u = n_tiles;
+        wait_step(u);
+        bare_barrier();
+        issue_step(u);
+        pipe_step<false, true, true>(lds, 0, v_off(u - 2), k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run, l_run,
+                                     alpha, a.scale_log2, vis_of(u - 1));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pk_a[i] = pk_b[i];
+    }
+    {
+        const int u = n_tiles + 1;
+        wait_step(u);
+        bare_barrier();
+        const int tb = tok_begin + (n_tiles - 1) * kTile;
+        if (tb + kTile > n) {
+            // Ragged last tile of a request: slots past the end hold whatever the page holds (NaN
+            // included), and 0 * NaN must not reach the output: clear those V rows in LDS.
+            unsigned char* vl = lds + kVRing + ((n_tiles - 1) % NSLOT) * kKBytes;
+            const int first_bad = n - tb;
+            for (int c = tid; c < kTile * 16; c += NT)
+                if ((c >> 4) >= first_bad) *reinterpret_cast<u32x4*>(vl + c * 16) = u32x4{0u, 0u, 0u, 0u};
+            __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the clears are done
+            bare_barrier();
+        }
+        pipe_step<false, false, true>(lds, 0, v_off(n_tiles - 1), k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run,
+                                      l_run, alpha, a.scale_log2, 0u);
+    }
+
+    // ---- partial result: (reference exponent, sum, unnormalised O) per row ------------
+    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    if (row_ok) {
+        const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
+        if (lg == 0) {
+            a.part_ml[2 * prow] = m_run;
+            a.part_ml[2 * prow + 1] = l_tot;
+        }
+        float* __restrict__ po = a.part_acc + prow * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
+                *reinterpret_cast<f32x4*>(po + dt * 32 + i4 * 8 + lg * 4) = v;
+            }
+    }
+  }  // pieces of the stretch
+    if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
+}
+
 bool gqa128_supports(const AttnArgs& a) {
     return a.Dqk == kD && a.Dv == kD && a.P == kPage && a.v_pages != nullptr && a.G * a.T <= 8 * 32 &&
            a.Hkv <= 65535;
@@ -381,6 +968,27 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int R = a.G * a.T;
     const int nw = (R + 31) / 32;
     const dim3 grid(a.wgs_per_head, a.Hkv);
+    const int depth = gqa_pipe_depth(nw);
+    if (depth > 0) {
+        switch (nw * 8 + depth) {
+#define SEER_GQA_PIPE_CASE(NW_, D_)                                                                      \
+    case NW_ * 8 + D_:                                                                                   \
+        hipLaunchKernelGGL((attn_gqa128_pipe_kernel<NW_, D_>), grid, dim3(NW_ * kWave), 0, stream, a);   \
+        return hipGetLastError();
+            SEER_GQA_PIPE_CASE(2, 1)
+            SEER_GQA_PIPE_CASE(2, 2)
+            SEER_GQA_PIPE_CASE(2, 3)
+            SEER_GQA_PIPE_CASE(3, 1)
+            SEER_GQA_PIPE_CASE(3, 2)
+            SEER_GQA_PIPE_CASE(3, 3)
+            SEER_GQA_PIPE_CASE(3, 4)
+            SEER_GQA_PIPE_CASE(5, 2)
+            SEER_GQA_PIPE_CASE(5, 3)
+            SEER_GQA_PIPE_CASE(5, 4)
+#undef SEER_GQA_PIPE_CASE
+            default: break;
+        }
+    }
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                               \
     case NW_:                                                                                            \

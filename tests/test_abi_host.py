@@ -80,6 +80,9 @@ def test_attention_argument_errors_before_any_launch(lib):
     assert run(_params(Dqk=576, Dv=512, kv_shared_latent=1), v=None, ws_bytes=0) == b.SEER_EWORKSPACE
     assert run(_params(num_pages=0)) == b.SEER_EINVAL
     assert run(_params(scale=float("nan"))) == b.SEER_EINVAL
+    assert run(_params(scale=0.0)) == b.SEER_EINVAL
+    assert run(_params(scale=-0.1)) == b.SEER_EINVAL
+    assert run(_params(scale=float("inf"))) == b.SEER_EINVAL
     assert run(_params(), q=None) == b.SEER_EINVAL
     assert run(_params(), v=None) == b.SEER_EINVAL                     # separate pools need v_pages
     assert run(_params(kv_shared_latent=1)) == b.SEER_EINVAL           # shared latent forbids v_pages
