@@ -56,7 +56,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int gqa_pipe_depth(int waves) {
     static const int forced = [] { const char* e = getenv("SEER_GQA_D"); return e ? atoi(e) : -1; }();
     if (forced >= 0) return forced;
-    return waves == 2 ? 1 : (waves == 3 ? 3 : (waves == 5 ? 4 : 0));
+    return waves == 2 ? 1 : (waves == 3 ? 3 : (waves == 5 ? 3 : 0));
 }
 
 // Workgroups of the partition kernel that one CU holds at once, by kernel shape.

@@ -36,6 +36,7 @@
 //                    V^T operand (8 tokens at one d) comes from the token-major tile
 //                    through two transposing LDS reads (ds_read_b64_tr_b16)
 #include <type_traits>
+#include <utility>
 
 #include "seer_attention.h"
 #include "seer_device.h"
@@ -541,28 +542,28 @@ __device__ __forceinline__ void pipe_step(const unsigned char* lds, int k_off, i
 // returns in order) takes them as read-write operands, so every use of the data is ordered after
 // the wait, and nothing between the two blocks has a reason to touch them.
 #define SEER_TR8_ISSUE(vr_, a0_, a1_, a2_, a3_, OFF0, OFF1)                                                \
-    asm volatile("ds_read_b64_tr_b16 %0, %8 offset:" #OFF0 "\n"                                            \
-                 "ds_read_b64_tr_b16 %1, %8 offset:" #OFF1 "\n"                                            \
-                 "ds_read_b64_tr_b16 %2, %9 offset:" #OFF0 "\n"                                            \
-                 "ds_read_b64_tr_b16 %3, %9 offset:" #OFF1 "\n"                                            \
-                 "ds_read_b64_tr_b16 %4, %10 offset:" #OFF0 "\n"                                           \
-                 "ds_read_b64_tr_b16 %5, %10 offset:" #OFF1 "\n"                                           \
-                 "ds_read_b64_tr_b16 %6, %11 offset:" #OFF0 "\n"                                           \
-                 "ds_read_b64_tr_b16 %7, %11 offset:" #OFF1                                                \
+    asm volatile("ds_read_b64_tr_b16 %0, %8 offset:%12\n"                                                  \
+                 "ds_read_b64_tr_b16 %1, %8 offset:%13\n"                                                  \
+                 "ds_read_b64_tr_b16 %2, %9 offset:%12\n"                                                  \
+                 "ds_read_b64_tr_b16 %3, %9 offset:%13\n"                                                  \
+                 "ds_read_b64_tr_b16 %4, %10 offset:%12\n"                                                 \
+                 "ds_read_b64_tr_b16 %5, %10 offset:%13\n"                                                 \
+                 "ds_read_b64_tr_b16 %6, %11 offset:%12\n"                                                 \
+                 "ds_read_b64_tr_b16 %7, %11 offset:%13"                                                   \
                  : "=&v"(vr_[0][0]), "=&v"(vr_[0][1]), "=&v"(vr_[1][0]), "=&v"(vr_[1][1]), "=&v"(vr_[2][0]), \
                    "=&v"(vr_[2][1]), "=&v"(vr_[3][0]), "=&v"(vr_[3][1])                                    \
-                 : "v"(a0_), "v"(a1_), "v"(a2_), "v"(a3_))
+                 : "v"(a0_), "v"(a1_), "v"(a2_), "v"(a3_), "n"(OFF0), "n"(OFF1))
 #define SEER_TR8_WAIT(N, vr_)                                                                              \
     asm volatile("s_waitcnt lgkmcnt(" #N ")"                                                               \
                  : "+v"(vr_[0][0]), "+v"(vr_[0][1]), "+v"(vr_[1][0]), "+v"(vr_[1][1]), "+v"(vr_[2][0]),    \
                    "+v"(vr_[2][1]), "+v"(vr_[3][0]), "+v"(vr_[3][1]))
-#define SEER_K4_ISSUE(kv_, b0_, b1_, b2_, b3_)                                                             \
-    asm volatile("ds_read_b128 %0, %4\n"                                                                   \
-                 "ds_read_b128 %1, %5\n"                                                                   \
-                 "ds_read_b128 %2, %6\n"                                                                   \
-                 "ds_read_b128 %3, %7"                                                                     \
+#define SEER_K4_ISSUE(kv_, b0_, b1_, b2_, b3_, OFF)                                                        \
+    asm volatile("ds_read_b128 %0, %4 offset:%8\n"                                                         \
+                 "ds_read_b128 %1, %5 offset:%8\n"                                                         \
+                 "ds_read_b128 %2, %6 offset:%8\n"                                                         \
+                 "ds_read_b128 %3, %7 offset:%8"                                                           \
                  : "=&v"(kv_[0]), "=&v"(kv_[1]), "=&v"(kv_[2]), "=&v"(kv_[3])                              \
-                 : "v"(b0_), "v"(b1_), "v"(b2_), "v"(b3_))
+                 : "v"(b0_), "v"(b1_), "v"(b2_), "v"(b3_), "n"(OFF))
 #define SEER_K4_WAIT(N, kv_)                                                                               \
     asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(kv_[0]), "+v"(kv_[1]), "+v"(kv_[2]), "+v"(kv_[3]))
 #define SEER_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -579,7 +580,10 @@ __device__ __forceinline__ void pipe_step(const unsigned char* lds, int k_off, i
 //
 // issue_k / issue_v issue the step's HBM loads; they are called where their scalar address
 // arithmetic runs in the shadow of LDS reads already issued and of MFMAs already queued.
-template <bool MASKED, typename IssueK, typename IssueV>
+//
+// The slots read are at byte offsets K_IMM + k_off (K ring) and V_IMM + v_off (V ring); in the
+// unrolled steady state the runtime parts are zero and the slot is an instruction immediate.
+template <bool MASKED, int K_IMM, int V_IMM, typename IssueK, typename IssueV>
 __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_rd)[8], const int (&v_rd)[4],
                                            const bf16x8 (&qreg)[8], f32x16& s_sm, f32x16& s_qk,
                                            const uint32_t (&pk_pv)[8], uint32_t (&pk_sm)[8], f32x16 (&acc)[4],
@@ -588,8 +592,9 @@ __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_r
     const int a0 = v_off + v_rd[0], a1 = v_off + v_rd[1], a2 = v_off + v_rd[2], a3 = v_off + v_rd[3];
     u32x2 va[4][2], vb[4][2];
     u32x4 ka[4], kb[4];
-    SEER_TR8_ISSUE(va, a0, a1, a2, a3, 0, 2048);
-    SEER_TR8_ISSUE(vb, a0, a1, a2, a3, 4096, 6144);
+    static_assert(K_IMM >= 0 && V_IMM >= 0 && K_IMM < 65536 && V_IMM + 6144 < 65536, "16-bit LDS offsets");
+    SEER_TR8_ISSUE(va, a0, a1, a2, a3, V_IMM, V_IMM + 2048);
+    SEER_TR8_ISSUE(vb, a0, a1, a2, a3, V_IMM + 4096, V_IMM + 6144);
     issue_k();
     rescale_if_moved(acc, alpha);
     if constexpr (MASKED) {
@@ -613,7 +618,7 @@ __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_r
     }
     {
         const int b0 = k_off + k_rd[0], b1 = k_off + k_rd[1], b2 = k_off + k_rd[2], b3 = k_off + k_rd[3];
-        SEER_K4_ISSUE(ka, b0, b1, b2, b3);
+        SEER_K4_ISSUE(ka, b0, b1, b2, b3, K_IMM);
     }
     issue_v();
     SEER_TR8_WAIT(4, vb);
@@ -645,7 +650,7 @@ __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_r
     }
     {
         const int b0 = k_off + k_rd[4], b1 = k_off + k_rd[5], b2 = k_off + k_rd[6], b3 = k_off + k_rd[7];
-        SEER_K4_ISSUE(kb, b0, b1, b2, b3);
+        SEER_K4_ISSUE(kb, b0, b1, b2, b3, K_IMM);
     }
     SEER_K4_WAIT(4, ka);
     SEER_SCHED_FENCE();
@@ -670,6 +675,11 @@ __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_r
         }
         SEER_SCHED_FENCE();
     }
+}
+
+template <typename F, int... I>
+__device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
 }
 
 template <int NW, int D>
@@ -717,9 +727,8 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
         const int chunk = dt * 4 + v_dhalf * 2 + (v_c4 >> 1);
-        v_rd[dt] = ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;
+        v_rd[dt] = (lg * 4 + v_k) * kRowBytes + ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;   // token lg*4 + k
     }
-    const int v_row0 = (lg * 4 + v_k) * kRowBytes;
 
   for (; g < g_end; ++b) {
     const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
@@ -800,18 +809,22 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
     // the same pages of its pool as the K tile issued two steps earlier, whose offsets are kept.
     size_t pq0 = 0, pq1 = 0, pr0 = 0, pr1 = 0;     // page offsets of the K tiles of steps j - 1 and j - 2
     size_t pn0 = 0, pn1 = 0;
+    auto issue_k_at = [&](int kt, int slot_bytes) __attribute__((always_inline)) {
+        page_pair((tok_begin + kt * kTile) / kPage, pn0, pn1);
+        issue_half_tile<NW>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, goff_k1);
+    };
+    auto issue_v_at = [&](int slot_bytes) __attribute__((always_inline)) {
+        issue_half_tile<NW>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, goff_v);
+    };
+    auto shift_pages = [&]() __attribute__((always_inline)) { pr0 = pq0, pr1 = pq1, pq0 = pn0, pq1 = pn1; };
     auto issue_k = [&](int j) __attribute__((always_inline)) {
         const int kt = j + D;
-        if (kt < n_tiles) {
-            page_pair((tok_begin + kt * kTile) / kPage, pn0, pn1);
-            issue_half_tile<NW>(lds + (kt % NSLOT) * kKBytes, wave, pn0, pn1, kbase, goff_k0, goff_k1);
-        }
+        if (kt < n_tiles) issue_k_at(kt, (kt % NSLOT) * kKBytes);
     };
     auto issue_v = [&](int j) __attribute__((always_inline)) {
         const int vt = j + D - 2;
-        if (vt >= 0 && vt < n_tiles)
-            issue_half_tile<NW>(lds + kVRing + (vt % NSLOT) * kKBytes, wave, pr0, pr1, vbase, goff_v, goff_v);
-        pr0 = pq0, pr1 = pq1, pq0 = pn0, pq1 = pn1;
+        if (vt >= 0 && vt < n_tiles) issue_v_at((vt % NSLOT) * kKBytes);
+        shift_pages();
     };
     auto issue_step = [&](int j) __attribute__((always_inline)) {
         issue_k(j);
@@ -839,7 +852,7 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
     };
     auto k_off = [&](int j) __attribute__((always_inline)) -> int { return (j % NSLOT) * kKBytes; };
     auto v_off = [&](int j) __attribute__((always_inline)) -> int {
-        return kVRing + (j % NSLOT) * kKBytes + v_row0;
+        return kVRing + (j % NSLOT) * kKBytes;
     };
 
 #pragma unroll
@@ -879,7 +892,7 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
                          uint32_t (&pk_sm)[8]) __attribute__((always_inline)) {
         wait_step(u);
         bare_barrier();                        // all waves: loads of step u - D landed, step u - 1 computed
-        fused_step<decltype(masked)::value>(
+        fused_step<decltype(masked)::value, 0, 0>(
             k_off(u), v_off(u - 2), k_rd, v_rd, qreg, s_sm, s_qk, pk_pv, pk_sm, acc, m_run, l_run, alpha, a.scale_log2,
             decltype(masked)::value ? vis_of(u - 1) : 0u, [&]() __attribute__((always_inline)) { issue_k(u); },
             [&]() __attribute__((always_inline)) { issue_v(u); });
@@ -894,6 +907,34 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
         const int first_masked = n0 > tok_begin ? (n0 - tok_begin) / kTile : 0;   // first tile with masked slots
         const int u_split = min(max(first_masked + 1, 2), n_tiles);
         int u = 2;
+        // Steady state proper: groups of P steps in which every load exists, every wait count is
+        // the compile-time one, and (u = 2 mod NSLOT at the start of a group) every ring slot is
+        // known at compile time.
+        constexpr int P = NSLOT % 2 == 0 ? NSLOT : 2 * NSLOT;
+        auto steady_step = [&](auto ic) __attribute__((always_inline)) {
+            constexpr int I = decltype(ic)::value;
+            constexpr int kReadSlot = (2 + I) % NSLOT, kVReadSlot = I % NSLOT;
+            constexpr int kIssueSlot = (1 + I) % NSLOT, kVIssueSlot = (I + NSLOT - 1) % NSLOT;
+            if (REM == 0 || wave < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            else wait_vmcnt<(D - 1) * 2 * FLOOR>();
+            bare_barrier();
+            const int uu = u + I;
+            auto ik = [&]() __attribute__((always_inline)) { issue_k_at(uu + D, kIssueSlot * kKBytes); };
+            auto iv = [&]() __attribute__((always_inline)) {
+                issue_v_at(kVIssueSlot * kKBytes);
+                shift_pages();
+            };
+            if constexpr (I % 2 == 0)
+                fused_step<false, kReadSlot * kKBytes, kVRing + kVReadSlot * kKBytes>(
+                    0, 0, k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run, l_run, alpha, a.scale_log2, 0u, ik, iv);
+            else
+                fused_step<false, kReadSlot * kKBytes, kVRing + kVReadSlot * kKBytes>(
+                    0, 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run, alpha, a.scale_log2, 0u, ik, iv);
+        };
+        if constexpr (kVRing + NSLOT * kKBytes <= 65536) {
+            const int u_steady_end = min(u_split, n_tiles - D);
+            for (; u + P <= u_steady_end; u += P) for_each_index(steady_step, std::make_integer_sequence<int, P>{});
+        }
         for (; u + 1 < u_split; u += 2) {
             full_step(std::false_type{}, u, s_b, s_a, pk_a, pk_b);
             full_step(std::false_type{}, u + 1, s_a, s_b, pk_b, pk_a);
@@ -985,6 +1026,9 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
             SEER_GQA_PIPE_CASE(5, 2)
             SEER_GQA_PIPE_CASE(5, 3)
             SEER_GQA_PIPE_CASE(5, 4)
+            SEER_GQA_PIPE_CASE(5, 5)
+            SEER_GQA_PIPE_CASE(5, 6)
+            SEER_GQA_PIPE_CASE(5, 8)
 #undef SEER_GQA_PIPE_CASE
             default: break;
         }
