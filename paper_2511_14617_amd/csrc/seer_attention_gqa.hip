@@ -53,11 +53,17 @@ constexpr int kStageBytes = 2 * kKBytes;     // K tile then V tile
 constexpr int kBlocks = 16;              // 1 KB wave-loads per tile: 8 of K, 8 of V
 static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel");
 
-// Swizzles: a row's 16-byte chunk c is stored at chunk position c ^ f(row).
-//   K: f = row & 7         -> 8 consecutive rows, same chunk: 8 distinct 16-byte bank groups
-//   V: f = (row & 3) << 1  -> 4 consecutive rows, same 32-byte pair: 4 distinct 32-byte groups
-__device__ __forceinline__ int k_swz(int row) { return row & 7; }
-__device__ __forceinline__ int v_swz(int row) { return (row & 3) << 1; }
+// Swizzles: a row's 16-byte chunk c is stored at chunk position c ^ f(row).  LDS has 64 banks of
+// 4 bytes (256 bytes per clock): a row is exactly one pass over the banks, so without a swizzle
+// every row starts at bank 0.
+//   K: f = row & 15        -> 16 consecutive rows, same chunk (one ds_read_b128 quarter-wave):
+//                             16 distinct 16-byte bank groups
+//   V: f = (row & 3) << 2  -> 4 consecutive rows, same 64-byte quarter of the row (half a wave of
+//                             the transposing read): 4 distinct 64-byte groups
+// (measured with several waves reading at once: these reach the rate of a linear access pattern,
+// twice that of swizzles which only spread over 128 bytes)
+__device__ __forceinline__ int k_swz(int row) { return row & 15; }
+__device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
 
 // This wave's share of one tile, HBM -> LDS stage.  The 16 one-KB blocks of a tile (K rows 4j..4j+3
 // for block j < 8, V rows for block 8 + j) are dealt round-robin to the NW waves.  p0 / p1 are
@@ -67,7 +73,7 @@ __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 1; }
 template <int NW>
 __device__ __forceinline__ void issue_tile_loads(unsigned char* stage, int wave, size_t p0, size_t p1,
                                                  const unsigned char* kbase, const unsigned char* vbase,
-                                                 int goff_k0, int goff_k1, int goff_v) {
+                                                 int goff_k0, int goff_v) {
     constexpr int LPW = (kBlocks + NW - 1) / NW;
     constexpr int EXTRA = kBlocks % NW;
 #pragma unroll
@@ -77,7 +83,7 @@ __device__ __forceinline__ void issue_tile_loads(unsigned char* stage, int wave,
             const int j = jb & 7;
             const bool is_v = jb >= 8;
             const size_t pg = (j < 4) ? p0 : p1;
-            const int lane_off = is_v ? goff_v : ((j & 1) ? goff_k1 : goff_k0);
+            const int lane_off = is_v ? goff_v : (goff_k0 ^ ((j & 3) << 6));   // K rows 4j + l16: f = 4(j & 3) + l16
             const unsigned char* src = (is_v ? vbase : kbase) + pg + (j & 3) * (4 * kRowBytes) + lane_off;
             __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(stage + jb * 1024), 16, 0,
                                              0);
@@ -119,8 +125,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     const size_t page_bytes = static_cast<size_t>(a.Hkv) * kPage * kRowBytes;   // one page, all kv heads
     const size_t head_off = static_cast<size_t>(kvh) * kPage * kRowBytes;
     // per-lane byte offset inside a 4-row block of a page: which global chunk feeds my LDS slot
-    const int goff_k0 = l16 * kRowBytes + ((p16 ^ k_swz(l16)) << 4);       // blocks whose first row is 0 mod 8
-    const int goff_k1 = l16 * kRowBytes + ((p16 ^ k_swz(4 + l16)) << 4);   // ... 4 mod 8
+    const int goff_k0 = l16 * kRowBytes + ((p16 ^ k_swz(l16)) << 4);       // for block 0; block j: ^ ((j & 3) << 6)
     const int goff_v = l16 * kRowBytes + ((p16 ^ v_swz(l16)) << 4);
     // operand read offsets inside a stage
     int k_rd[8];                   // K: row ln, chunk 2*kk + lg
@@ -218,7 +223,7 @@ void attn_gqa128_kernel(AttnArgs a) {
         const int tb = tok_begin + tile * kTile;
         const size_t p0 = page_offset(tb / kPage);
         const size_t p1 = page_offset(tb / kPage + 1);
-        issue_tile_loads<NW>(lds + (tile % NS) * kStageBytes, wave, p0, p1, kbase, vbase, goff_k0, goff_k1, goff_v);
+        issue_tile_loads<NW>(lds + (tile % NS) * kStageBytes, wave, p0, p1, kbase, vbase, goff_k0, goff_v);
     };
     // wait until at most `younger` of this wave's tiles are still in flight
     auto wait_tiles = [&](int younger) __attribute__((always_inline)) {
@@ -399,13 +404,14 @@ void attn_gqa128_kernel(AttnArgs a) {
 // Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the NW waves.
 template <int NW>
 __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, size_t p0, size_t p1,
-                                                const unsigned char* base, int goff0, int goff1) {
+                                                const unsigned char* base, int goff, bool is_k) {
 #pragma unroll
     for (int i = 0; i < (8 + NW - 1) / NW; ++i) {
         const int j = wave + i * NW;
         if (j < 8) {
             const size_t pg = (j < 4) ? p0 : p1;
-            const unsigned char* src = base + pg + (j & 3) * (4 * kRowBytes) + ((j & 1) ? goff1 : goff0);
+            const int lane_off = is_k ? goff ^ ((j & 3) << 6) : goff;   // K rows 4j + l16: f = 4(j & 3) + l16
+            const unsigned char* src = base + pg + (j & 3) * (4 * kRowBytes) + lane_off;
             __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(slot + j * 1024), 16, 0, 0);
         }
     }
@@ -717,7 +723,6 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
     const uint32_t page_bytes32 = static_cast<uint32_t>(a.Hkv) * kPage * kRowBytes;   // one page, all kv heads
     const size_t head_off = static_cast<size_t>(kvh) * kPage * kRowBytes;
     const int goff_k0 = l16 * kRowBytes + ((p16 ^ k_swz(l16)) << 4);
-    const int goff_k1 = l16 * kRowBytes + ((p16 ^ k_swz(4 + l16)) << 4);
     const int goff_v = l16 * kRowBytes + ((p16 ^ v_swz(l16)) << 4);
     int k_rd[8];
 #pragma unroll
@@ -811,10 +816,10 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
     size_t pn0 = 0, pn1 = 0;
     auto issue_k_at = [&](int kt, int slot_bytes) __attribute__((always_inline)) {
         page_pair((tok_begin + kt * kTile) / kPage, pn0, pn1);
-        issue_half_tile<NW>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, goff_k1);
+        issue_half_tile<NW>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
     };
     auto issue_v_at = [&](int slot_bytes) __attribute__((always_inline)) {
-        issue_half_tile<NW>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, goff_v);
+        issue_half_tile<NW>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
     };
     auto shift_pages = [&]() __attribute__((always_inline)) { pr0 = pq0, pr1 = pq1, pq0 = pn0, pq1 = pn1; };
     auto issue_k = [&](int j) __attribute__((always_inline)) {
