@@ -19,13 +19,12 @@
 //
 // Data flow per 32-token tile (two pages, 8 KB of K and 8 KB of V)
 //   HBM -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane, 1 KB per wave
-//          instruction, no staging registers), into a ring of NS stages, so NS-1 tiles
-//          per workgroup are in flight while one is computed (NS = 2: measured, four
-//          resident workgroups per CU with one tile in flight each beat three with two).  Rows are 256 B, unpadded;
+//          instruction, no staging registers), into a ring of K slots and a ring of V slots,
+//          D tiles in flight per workgroup while one is computed.  Rows are 256 B, unpadded;
 //          the 16-byte chunks of a row are stored XOR-swizzled (the lane picks which
 //          global chunk lands in its fixed LDS slot), which makes the operand reads
 //          below free of bank conflicts.  Completion is tracked by hand: s_waitcnt
-//          vmcnt(loads of the younger tiles) then s_barrier.
+//          vmcnt(loads of the younger steps) then s_barrier.
 //   S^T = K . Q^T    v_mfma_f32_32x32x16_bf16, M = tokens, N = rows, 8 steps over d;
 //                    K operand = one ds_read_b128 per step, Q^T stays in 32 VGPRs
 //   softmax          each lane owns ONE query row (N index = lane % 32) and 16 of the
@@ -35,6 +34,20 @@
 //   O^T += V^T . P^T M = d (4 tiles of 32), N = rows, 2 steps over the tokens; the
 //                    V^T operand (8 tokens at one d) comes from the token-major tile
 //                    through two transposing LDS reads (ds_read_b64_tr_b16)
+//
+// Software pipeline
+//   A wave that ran a tile's three phases one after the other (scores on the matrix core,
+//   softmax on the vector ALU, P.V on the matrix core) would leave each unit idle while the other
+//   works, and waves sharing a SIMD would not fill each other's gaps either, because the per-tile
+//   barrier keeps them in the same phase.  So one loop step works on three consecutive tiles,
+//   with no dependence between the three parts:
+//       step u:   P.V of tile u-2 (MFMA)  |  softmax of tile u-1 (VALU)  |  scores of tile u (MFMA)
+//   K is needed two steps before the V of the same tile, hence the two rings (D+1 slots of 8 KB
+//   each): step u issues the loads of K tile u+D and V tile u+D-2; both are consumed D steps
+//   after they were issued, with the loads of D-1 steps in flight behind them.
+//   The exponent reference of a row only moves when the new maximum exceeds it by more than 8
+//   (in log2 units: the probabilities then stay below 2^8, as exact in bf16's 8 bits as values
+//   below 1), which makes the rescaling of the 64 output accumulators rare.
 #include <type_traits>
 #include <utility>
 
@@ -49,8 +62,6 @@ constexpr int kPage = 16;                // tokens per page
 constexpr int kTile = 32;                // tokens per tile
 constexpr int kRowBytes = kD * 2;        // 256
 constexpr int kKBytes = kTile * kRowBytes;   // 8192
-constexpr int kStageBytes = 2 * kKBytes;     // K tile then V tile
-constexpr int kBlocks = 16;              // 1 KB wave-loads per tile: 8 of K, 8 of V
 static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel");
 
 // Swizzles: a row's 16-byte chunk c is stored at chunk position c ^ f(row).  LDS has 64 banks of
@@ -64,342 +75,6 @@ static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel"
 // twice that of swizzles which only spread over 128 bytes)
 __device__ __forceinline__ int k_swz(int row) { return row & 15; }
 __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
-
-// This wave's share of one tile, HBM -> LDS stage.  The 16 one-KB blocks of a tile (K rows 4j..4j+3
-// for block j < 8, V rows for block 8 + j) are dealt round-robin to the NW waves.  p0 / p1 are
-// the byte offsets of the tile's two pages (kv head included) in the pools.  (A free function
-// with by-value arguments on purpose: the same code as a by-reference lambda made the compiler
-// keep the captured variables in scratch memory.)
-template <int NW>
-__device__ __forceinline__ void issue_tile_loads(unsigned char* stage, int wave, size_t p0, size_t p1,
-                                                 const unsigned char* kbase, const unsigned char* vbase,
-                                                 int goff_k0, int goff_v) {
-    constexpr int LPW = (kBlocks + NW - 1) / NW;
-    constexpr int EXTRA = kBlocks % NW;
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        const int jb = wave + i * NW;
-        if (EXTRA == 0 || i < LPW - 1 || jb < kBlocks) {
-            const int j = jb & 7;
-            const bool is_v = jb >= 8;
-            const size_t pg = (j < 4) ? p0 : p1;
-            const int lane_off = is_v ? goff_v : (goff_k0 ^ ((j & 3) << 6));   // K rows 4j + l16: f = 4(j & 3) + l16
-            const unsigned char* src = (is_v ? vbase : kbase) + pg + (j & 3) * (4 * kRowBytes) + lane_off;
-            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(stage + jb * 1024), 16, 0,
-                                             0);
-        }
-    }
-}
-
-template <int NW, int NS>
-__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
-void attn_gqa128_kernel(AttnArgs a) {
-    constexpr int NT = NW * kWave;
-    constexpr int LPW = (kBlocks + NW - 1) / NW;    // wave-loads per tile for the busiest waves
-    constexpr int EXTRA = kBlocks % NW;             // waves below this index issue LPW, the others LPW - 1
-    static_assert(NS >= 2 && NS <= 4, "ring of 2..4 stages");
-    static_assert((NS - 2) * LPW < 64, "vmcnt range");
-
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NS * kStageBytes];
-
-    const int kvh = blockIdx.y;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int ln = lane & 31;      // N / M index inside a 32-wide tile
-    const int lg = lane >> 5;      // which half of the contraction index this lane feeds
-    const int l16 = lane >> 4;     // row inside a 4-row load block
-    const int p16 = lane & 15;     // 16-byte slot inside the row
-
-    // ---- this workgroup's stretch of the per-head tile line ---------------------------
-    const int wg = blockIdx.x;
-    const int L = uniform_load(&a.header->tiles_per_wg);          // 0: one workgroup per request
-    int b = uniform_load(a.wg_first + wg);
-    if (b < 0) return;                             // idle stretch (uniform for the workgroup)
-    int g = L ? wg * L : uniform_load(a.tile_off + b);
-    const int g_end = L ? min((wg + 1) * L, uniform_load(&a.header->total_tiles)) : uniform_load(a.tile_off + b + 1);
-    bool bad_page = false;
-
-    const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
-    const unsigned char* __restrict__ vbase = static_cast<const unsigned char*>(a.v_pages);
-    const size_t page_bytes = static_cast<size_t>(a.Hkv) * kPage * kRowBytes;   // one page, all kv heads
-    const size_t head_off = static_cast<size_t>(kvh) * kPage * kRowBytes;
-    // per-lane byte offset inside a 4-row block of a page: which global chunk feeds my LDS slot
-    const int goff_k0 = l16 * kRowBytes + ((p16 ^ k_swz(l16)) << 4);       // for block 0; block j: ^ ((j & 3) << 6)
-    const int goff_v = l16 * kRowBytes + ((p16 ^ v_swz(l16)) << 4);
-    // operand read offsets inside a stage
-    int k_rd[8];                   // K: row ln, chunk 2*kk + lg
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) k_rd[kk] = ln * kRowBytes + (((2 * kk + lg) ^ k_swz(ln)) << 4);
-    // V through the transposing read: in each 16-lane group, lane s = 4*k + c4 points at token row k
-    // (of the 4 the group covers) and d columns 4*c4..4*c4+3 of the group's 16; lane i of the group
-    // receives the 4 tokens of column i.
-    const int v_k = p16 >> 2, v_c4 = p16 & 3, v_dhalf = l16 & 1;
-    int v_rd[4];                   // per d-tile: chunk/half part of the address (token part added per read)
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-        const int chunk = dt * 4 + v_dhalf * 2 + (v_c4 >> 1);
-        v_rd[dt] = ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;   // token rows are 4-aligned + k: same swizzle
-    }
-    const int v_row0 = (lg * 4 + v_k) * kRowBytes;                 // token lg*4 + k (+ 8, + 16*ks)
-
-  for (; g < g_end; ++b) {
-    const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
-    if (t_hi == t_lo) continue;                    // request without tiles (flagged ctx_len)
-    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - t_lo / L : 0);
-    const int n = uniform_load(a.ctx_len + b);
-    const int tok_begin = (g - t_lo) * kTile;
-    const int tok_end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
-    g = t_hi;
-    const int n0 = n - a.T;
-    const int n_tiles = (tok_end - tok_begin + kTile - 1) / kTile;
-    bare_barrier();                                // every wave is done with the previous piece's stages
-
-    // ---- this lane's query row -------------------------------------------------
-    const int R = a.G * a.T;
-    const int r = wave * 32 + ln;
-    const bool row_ok = r < R;
-    const int t = row_ok ? r / a.G : 0;
-    const int hq = kvh * a.G + (row_ok ? r - t * a.G : 0);
-    uint64_t word = 0;
-    if (row_ok) {
-        word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
-                           : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
-        if (a.T < 64) word &= (1ull << a.T) - 1;   // bits past the last slot would point past the context
-    }
-    bf16x8 qreg[8];
-    {
-        const u32x4* qp = reinterpret_cast<const u32x4*>(
-            static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * kD + lg * 8);
-        u32x4 qv[8];
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            qv[kk] = u32x4{0u, 0u, 0u, 0u};
-            if (row_ok) qv[kk] = qp[kk * 2];      // d = kk*16 + lg*8 .. +7
-        }
-        // Pin the point where these loads must have returned to HERE, before the tile loop: left to
-        // itself the compiler waits for them at their first use inside the loop, with a wait that
-        // also drains the direct-to-LDS loads of the tiles in flight, on every iteration.
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            asm volatile("" : "+v"(qv[kk]));
-            qreg[kk] = as_bf16x8(qv[kk]);
-        }
-        uint32_t w_lo = static_cast<uint32_t>(word), w_hi = static_cast<uint32_t>(word >> 32);
-        asm volatile("" : "+v"(w_lo), "+v"(w_hi));
-        word = (static_cast<uint64_t>(w_hi) << 32) | w_lo;
-    }
-
-    f32x16 acc[4];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
-    float m_run = kNegInf, l_run = 0.f;
-
-    // ---- page ids: fetched 64 at a time (lane l holds logical page cache_base + l) and handed
-    // out with v_readlane, so that no table read sits in front of a tile's loads
-    const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
-    int cache_base = -0x40000000;
-    int pg_cache = 0;
-    const int last_page = (n - 1) / kPage;
-    auto page_offset = [&](int logical_page) __attribute__((always_inline)) -> size_t {
-        if (logical_page < cache_base || logical_page >= cache_base + kWave) {   // uniform
-            cache_base = logical_page;
-            const int idx = cache_base + lane;
-            int pg = table[min(idx, a.max_pages - 1)];
-            if (pg < 0 || pg >= a.num_pages) {
-                if (idx <= last_page) bad_page = true;
-                pg = min(max(pg, 0), a.num_pages - 1);
-            }
-            pg_cache = pg;
-        }
-        const int pg = __builtin_amdgcn_readlane(pg_cache, __builtin_amdgcn_readfirstlane(logical_page - cache_base));
-        return static_cast<size_t>(pg) * page_bytes + head_off;
-    };
-
-    // ---- HBM -> LDS, this wave's share of one tile ------------------------------------
-    auto issue_tile = [&](int tile) __attribute__((always_inline)) {
-        const int tb = tok_begin + tile * kTile;
-        const size_t p0 = page_offset(tb / kPage);
-        const size_t p1 = page_offset(tb / kPage + 1);
-        issue_tile_loads<NW>(lds + (tile % NS) * kStageBytes, wave, p0, p1, kbase, vbase, goff_k0, goff_v);
-    };
-    // wait until at most `younger` of this wave's tiles are still in flight
-    auto wait_tiles = [&](int younger) __attribute__((always_inline)) {
-        const bool full = (EXTRA == 0) || (wave < EXTRA);
-        if (younger <= 0) wait_vmcnt<0>();
-        else if (younger == 1) { if (full) wait_vmcnt<LPW>(); else wait_vmcnt<(LPW > 1 ? LPW - 1 : 0)>(); }
-        else { if (full) wait_vmcnt<(2 * LPW < 64 ? 2 * LPW : 63)>(); else wait_vmcnt<(LPW > 1 ? 2 * (LPW - 1) : 0)>(); }
-    };
-
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < n_tiles) issue_tile(s);
-
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        wait_tiles(min(NS - 2, n_tiles - 1 - tile));
-        bare_barrier();                        // every wave's share of this tile has landed,
-                                               // and every wave has finished computing tile - 1
-        if (tile + NS - 1 < n_tiles) issue_tile(tile + NS - 1);   // into the stage tile - 1 used
-
-        const unsigned char* kl = lds + (tile % NS) * kStageBytes;
-        const unsigned char* vl = kl + kKBytes;
-        const int tb = tok_begin + tile * kTile;
-
-        if (tb + kTile > n) {
-            // Ragged last tile of a request: slots past the end hold whatever the page holds (NaN
-            // included), and 0 * NaN must not reach the output: clear those V rows in LDS.
-            const int first_bad = n - tb;
-            for (int c = tid; c < kTile * 16; c += NT)
-                if ((c >> 4) >= first_bad)
-                    *reinterpret_cast<u32x4*>(const_cast<unsigned char*>(vl) + c * 16) = u32x4{0u, 0u, 0u, 0u};
-            __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the clears are done
-            bare_barrier();
-        }
-
-        // S^T[token][row] = sum_d K[token][d] * Q[row][d]
-        f32x16 s;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const u32x4 kv = *reinterpret_cast<const u32x4*>(kl + k_rd[kk]);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kv), qreg[kk], s, 0, 0, 0);
-        }
-
-        // register i of s holds token  (i/4)*8 + lg*4 + i%4  of the tile, for this lane's row
-        float mx = kNegInf;
-        if (tb + kTile > n0) {
-            // visibility bits of the tile's 32 tokens for this row: the prefix part is all ones,
-            // the draft part comes from the ancestor word (bit s = slot n0 + s)
-            const int rel = tb - n0;           // uniform; > -32 here, < 64 because tb < n0 + T
-            uint32_t vis = rel >= 0 ? static_cast<uint32_t>(word >> rel)
-                                    : (static_cast<uint32_t>(word << (-rel)) | ((1u << (-rel)) - 1u));
-            vis >>= lg * 4;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const bool on = (vis >> ((i >> 2) * 8 + (i & 3))) & 1u;
-                const float v = on ? s[i] * a.scale_log2 : kNegInf;
-                s[i] = v;
-                mx = fmaxf(mx, v);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                s[i] *= a.scale_log2;
-                mx = fmaxf(mx, s[i]);
-            }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == kNegInf) ? 0.f : m_new;   // nothing visible yet: keep exp2 finite
-        const float alpha = fast_exp2(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.f;
-        uint32_t pk[8];
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-            const float p0 = fast_exp2(s[i] - m_use);
-            const float p1 = fast_exp2(s[i + 1] - m_use);
-            psum += p0 + p1;
-            pk[i >> 1] = cvt_pk_bf16(p0, p1);
-        }
-        l_run = l_run * alpha + psum;
-        if (__any(alpha != 1.f)) {
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
-        }
-
-        // O^T[d][row] += sum_token V[token][d] * P[row][token]
-        // step ks: this lane's 8 contraction slots are tokens 16ks + 4lg + (0..3) and 16ks + 8 + 4lg + (0..3).
-        // The 16 transposing reads are issued from one asm block that ends in its own
-        // s_waitcnt lgkmcnt(0): through the builtin, the compiler puts a vmcnt(0) in front of
-        // them (it cannot tell them apart from the direct-to-LDS loads still in flight), which
-        // would drain the ring on every tile.
-        u32x2 vr[4][4];    // [dt][ks*2 + (0: tokens +0..3, 1: tokens +8..11)]
-        {
-            const int stage_v = (tile % NS) * kStageBytes + kKBytes + v_row0;
-            const int a0 = stage_v + v_rd[0], a1 = stage_v + v_rd[1], a2 = stage_v + v_rd[2], a3 = stage_v + v_rd[3];
-            asm volatile(
-                "ds_read_b64_tr_b16 %0, %16 offset:0\n"
-                "ds_read_b64_tr_b16 %1, %16 offset:2048\n"
-                "ds_read_b64_tr_b16 %2, %16 offset:4096\n"
-                "ds_read_b64_tr_b16 %3, %16 offset:6144\n"
-                "ds_read_b64_tr_b16 %4, %17 offset:0\n"
-                "ds_read_b64_tr_b16 %5, %17 offset:2048\n"
-                "ds_read_b64_tr_b16 %6, %17 offset:4096\n"
-                "ds_read_b64_tr_b16 %7, %17 offset:6144\n"
-                "ds_read_b64_tr_b16 %8, %18 offset:0\n"
-                "ds_read_b64_tr_b16 %9, %18 offset:2048\n"
-                "ds_read_b64_tr_b16 %10, %18 offset:4096\n"
-                "ds_read_b64_tr_b16 %11, %18 offset:6144\n"
-                "ds_read_b64_tr_b16 %12, %19 offset:0\n"
-                "ds_read_b64_tr_b16 %13, %19 offset:2048\n"
-                "ds_read_b64_tr_b16 %14, %19 offset:4096\n"
-                "ds_read_b64_tr_b16 %15, %19 offset:6144\n"
-                "s_waitcnt lgkmcnt(0)"
-                : "=&v"(vr[0][0]), "=&v"(vr[0][1]), "=&v"(vr[0][2]), "=&v"(vr[0][3]), "=&v"(vr[1][0]),
-                  "=&v"(vr[1][1]), "=&v"(vr[1][2]), "=&v"(vr[1][3]), "=&v"(vr[2][0]), "=&v"(vr[2][1]),
-                  "=&v"(vr[2][2]), "=&v"(vr[2][3]), "=&v"(vr[3][0]), "=&v"(vr[3][1]), "=&v"(vr[3][2]),
-                  "=&v"(vr[3][3])
-                : "v"(a0), "v"(a1), "v"(a2), "v"(a3));
-        }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const bf16x8 pb = as_bf16x8(u32x4{pk[ks * 4], pk[ks * 4 + 1], pk[ks * 4 + 2], pk[ks * 4 + 3]});
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                const u32x2 lo2 = vr[dt][ks * 2], hi2 = vr[dt][ks * 2 + 1];
-                const bf16x8 va = as_bf16x8(u32x4{lo2[0], lo2[1], hi2[0], hi2[1]});
-                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, acc[dt], 0, 0, 0);
-            }
-        }
-    }
-
-    // ---- partial result: (running max, sum, unnormalised O) per row -------------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    if (row_ok) {
-        const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
-        if (lg == 0) {
-            a.part_ml[2 * prow] = m_run;
-            a.part_ml[2 * prow + 1] = l_tot;
-        }
-        float* __restrict__ po = a.part_acc + prow * kD;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
-                *reinterpret_cast<f32x4*>(po + dt * 32 + i4 * 8 + lg * 4) = v;
-            }
-    }
-  }  // pieces of the stretch
-    if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
-}
-
-
-// ======================================================================================
-// Software-pipelined variant.
-//
-// The kernel above runs a tile's three phases one after the other in each wave: scores (MFMA),
-// softmax (vector ALU), P.V (MFMA).  A wave that has a SIMD to itself therefore leaves the
-// matrix core idle during its softmax and the vector ALU idle during its MFMAs, and waves that
-// share a SIMD do not fill each other's gaps either, because the per-tile barrier keeps them in
-// the same phase.  Here one loop step works on three consecutive tiles at once, in one basic
-// block with no dependence between the three parts:
-//     step u:   P.V of tile u-2 (MFMA)  |  softmax of tile u-1 (VALU)  |  scores of tile u (MFMA)
-// so the hardware overlaps the VALU work with the MFMAs of the same wave.
-//
-// K is needed two steps before the V of the same tile, so K and V have rings of their own
-// (D+1 slots of 8 KB each) and step u issues the loads of K tile u+D and V tile u+D-2: both are
-// consumed D steps after they were issued, D-1 steps' loads stay in flight behind them.
-// The running-max reference of a row only moves when the new maximum exceeds it by more than
-// 2^8 (the probabilities then stay below 256, exact enough in bf16's 8 bits as before), which
-// makes the rescaling of the 64 output accumulators rare.
-// ======================================================================================
 
 // Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the NW waves.
 template <int NW>
@@ -418,6 +93,11 @@ __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, s
 }
 
 // 8 transposing reads: for each of the 4 d-tiles, the tokens +0..3 and +8..11 of one 16-token half.
+// Within a 16-lane group, lane s = 4k + c points at token row k (of the 4 the group covers) and d
+// columns 4c..4c+3 of the group's 16; lane i of the group receives the 4 tokens of column i.
+// The reads are issued from an asm block that ends in its own s_waitcnt lgkmcnt(0): through the
+// builtin, the compiler puts a vmcnt(0) in front of them (it cannot tell them apart from the
+// direct-to-LDS loads still in flight), which would drain the ring on every tile.
 #define SEER_GQA_TR8(vr_, a0_, a1_, a2_, a3_, OFF0, OFF1)                                                  \
     asm volatile("ds_read_b64_tr_b16 %0, %8 offset:" #OFF0 "\n"                                            \
                  "ds_read_b64_tr_b16 %1, %8 offset:" #OFF1 "\n"                                            \
@@ -690,7 +370,7 @@ __device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, 
 
 template <int NW, int D>
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
-void attn_gqa128_pipe_kernel(AttnArgs a) {
+void attn_gqa128_kernel(AttnArgs a) {
     constexpr int NT = NW * kWave;
     constexpr int NSLOT = D + 1;                    // slots in the K ring and in the V ring
     constexpr int CEIL = (8 + NW - 1) / NW;         // half-tile blocks of the busiest waves
@@ -768,7 +448,9 @@ void attn_gqa128_pipe_kernel(AttnArgs a) {
             qv[kk] = u32x4{0u, 0u, 0u, 0u};
             if (row_ok) qv[kk] = qp[kk * 2];
         }
-        // pin the arrival of these loads to here (see the kernel above)
+        // Pin the point where these loads must have returned to HERE, before the tile loop: left to
+        // itself the compiler waits for them at their first use inside the loop, with a wait that
+        // also drains the direct-to-LDS loads of the tiles in flight, on every iteration.
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             asm volatile("" : "+v"(qv[kk]));
@@ -1014,34 +696,11 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int R = a.G * a.T;
     const int nw = (R + 31) / 32;
     const dim3 grid(a.wgs_per_head, a.Hkv);
-    const int depth = gqa_pipe_depth(nw);
-    if (depth > 0) {
-        switch (nw * 8 + depth) {
-#define SEER_GQA_PIPE_CASE(NW_, D_)                                                                      \
-    case NW_ * 8 + D_:                                                                                   \
-        hipLaunchKernelGGL((attn_gqa128_pipe_kernel<NW_, D_>), grid, dim3(NW_ * kWave), 0, stream, a);   \
-        return hipGetLastError();
-            SEER_GQA_PIPE_CASE(2, 1)
-            SEER_GQA_PIPE_CASE(2, 2)
-            SEER_GQA_PIPE_CASE(2, 3)
-            SEER_GQA_PIPE_CASE(3, 1)
-            SEER_GQA_PIPE_CASE(3, 2)
-            SEER_GQA_PIPE_CASE(3, 3)
-            SEER_GQA_PIPE_CASE(3, 4)
-            SEER_GQA_PIPE_CASE(5, 2)
-            SEER_GQA_PIPE_CASE(5, 3)
-            SEER_GQA_PIPE_CASE(5, 4)
-            SEER_GQA_PIPE_CASE(5, 5)
-            SEER_GQA_PIPE_CASE(5, 6)
-            SEER_GQA_PIPE_CASE(5, 8)
-#undef SEER_GQA_PIPE_CASE
-            default: break;
-        }
-    }
     switch (nw) {
-#define SEER_GQA_CASE(NW_)                                                                               \
-    case NW_:                                                                                            \
-        hipLaunchKernelGGL((attn_gqa128_kernel<NW_, 2>), grid, dim3(NW_ * kWave), 0, stream, a);         \
+#define SEER_GQA_CASE(NW_)                                                                                     \
+    case NW_:                                                                                                  \
+        hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_)>), grid, dim3(NW_ * kWave), 0,    \
+                           stream, a);                                                                         \
         break;
         SEER_GQA_CASE(1)
         SEER_GQA_CASE(2)

@@ -45,6 +45,11 @@ CASES = {
     "prefix_shorter_than_draft": (W.CONFIGS[1].scaled(T=9, B=6, ctx=("uniform", 9, 40)), {}),
     "many_short_requests": (W.CONFIGS[2].scaled(B=300, group_size=6, T=4, ctx=("uniform", 4, 150), shared_prefix=32), {}),
     "many_short_mla": (W.CONFIGS[4].scaled(B=40, Hq=32, T=3, ctx=("uniform", 3, 200)), {}),
+    # four to eight waves per workgroup of the tiled kernel (32 query rows each)
+    "rows100_T25": (W.CONFIGS[2].scaled(B=3, group_size=3, T=25, ctx=("uniform", 300, 1500)), {}),
+    "rows168_G8_T21": (W.CONFIGS[2].scaled(B=3, group_size=3, Hq=16, Hkv=2, T=21, ctx=("uniform", 300, 1500)), {}),
+    "rows224_G8_T28": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=16, Hkv=2, T=28, ctx=("uniform", 200, 1200)), {}),
+    "rows256_G8_T32": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=8, Hkv=1, T=32, ctx=("uniform", 200, 1200)), {}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
     "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
                                            ctx=("uniform", 50, 900)), {}),
