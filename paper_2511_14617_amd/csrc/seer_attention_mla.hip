@@ -17,8 +17,8 @@
 //   tile from HBM and the others find it in that XCD's L2.
 // Data flow per 32-token tile (36 KB: 32 rows of 1152 B)
 //   HBM/L2 -> LDS directly (global_load_lds_dwordx4), ring of 3 stages; 16-byte chunks of a
-//   row XOR-swizzled by f(row) = ((row & 3) << 1) | ((row >> 2) & 1), which serves both read
-//   patterns below without bank conflicts.
+//   row XOR-swizzled by a 3-bit function of row bits 1..3 (bit 1 of the row moves the chunk by 64
+//   bytes), which spreads both read patterns below over all 64 LDS banks.
 //   S^T = K . Q^T : 36 steps of v_mfma_f32_32x32x16_bf16 (M = tokens, N = rows); K operand =
 //                   ds_read_b128, Q^T (32 rows x 576) lives in 144 VGPRs
 //   softmax       : one query row per lane, as in the D = 128 kernel
@@ -49,27 +49,31 @@ constexpr int kQLdsSteps = kKSteps - kQRegSteps;   // the remaining 12 are re-re
 static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel");
 static_assert(kBlocks % kWaves == 0, "every wave issues the same number of loads");
 
-__device__ __forceinline__ int swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// Row r starts 1152 r bytes into the stage, i.e. at bank group (in 16-byte units) 8 (r & 1) of the 16
+// that make up the 64 banks, so row parity supplies one bit of spread and the swizzle the other three.
+__device__ __forceinline__ int swz(int row) { return (((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1); }
 }  // namespace mla
 
 // 8 transposing reads (an even and an odd d-tile x {step 0 lo, step 0 hi, step 1 lo, step 1 hi}) and the
 // wait for them, as one asm block (see the D = 128 kernel for why these do not go through the builtin).
 // a_even / a_odd: lane address for even / odd d-tiles; OFF: byte offset of the d-tile pair.
-#define SEER_MLA_TR8(vr, a_even, a_odd, OFF)                                                               \
+// The token rows +8 and +24 differ from +0 and +16 in row bit 3, which the swizzle uses: they go
+// through addresses of their own (a_even8 / a_odd8).
+#define SEER_MLA_TR8(vr, a_even, a_even8, a_odd, a_odd8, OFF)                                              \
     asm volatile(                                                                                          \
-        "ds_read_b64_tr_b16 %0, %8 offset:%10\n"                                                           \
-        "ds_read_b64_tr_b16 %1, %8 offset:%11\n"                                                           \
-        "ds_read_b64_tr_b16 %2, %8 offset:%12\n"                                                           \
-        "ds_read_b64_tr_b16 %3, %8 offset:%13\n"                                                           \
-        "ds_read_b64_tr_b16 %4, %9 offset:%10\n"                                                           \
-        "ds_read_b64_tr_b16 %5, %9 offset:%11\n"                                                           \
-        "ds_read_b64_tr_b16 %6, %9 offset:%12\n"                                                           \
-        "ds_read_b64_tr_b16 %7, %9 offset:%13\n"                                                           \
+        "ds_read_b64_tr_b16 %0, %8 offset:%12\n"                                                           \
+        "ds_read_b64_tr_b16 %1, %9 offset:%13\n"                                                           \
+        "ds_read_b64_tr_b16 %2, %8 offset:%14\n"                                                           \
+        "ds_read_b64_tr_b16 %3, %9 offset:%15\n"                                                           \
+        "ds_read_b64_tr_b16 %4, %10 offset:%12\n"                                                          \
+        "ds_read_b64_tr_b16 %5, %11 offset:%13\n"                                                          \
+        "ds_read_b64_tr_b16 %6, %10 offset:%14\n"                                                          \
+        "ds_read_b64_tr_b16 %7, %11 offset:%15\n"                                                          \
         "s_waitcnt lgkmcnt(0)"                                                                             \
         : "=&v"(vr[0][0]), "=&v"(vr[0][1]), "=&v"(vr[0][2]), "=&v"(vr[0][3]), "=&v"(vr[1][0]), "=&v"(vr[1][1]), \
           "=&v"(vr[1][2]), "=&v"(vr[1][3])                                                                 \
-        : "v"(a_even), "v"(a_odd), "n"((OFF)), "n"((OFF) + 8 * mla::kRowBytes), "n"((OFF) + 16 * mla::kRowBytes), \
-          "n"((OFF) + 24 * mla::kRowBytes))
+        : "v"(a_even), "v"(a_even8), "v"(a_odd), "v"(a_odd8), "n"((OFF)), "n"((OFF) + 8 * mla::kRowBytes),  \
+          "n"((OFF) + 16 * mla::kRowBytes), "n"((OFF) + 24 * mla::kRowBytes))
 
 // acc += A . B with the accumulator pinned to the AGPR half of the register file.  Written as asm
 // because the compiler, left to choose, keeps part of the 256 accumulators in VGPRs and then
@@ -127,13 +131,15 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) k_rd[j] = ln * kRowBytes + (((2 * j + lg) ^ swz(ln)) << 4);
     // V operand through the transposing read (lane s = 4k + c4 of a 16-lane group points at token
-    // row k, d columns 4c4..4c4+3 of the group's 16).  Token rows are 4lg + k (+8, +16): swizzle k<<1 | lg.
+    // row k, d columns 4c4..4c4+3 of the group's 16).  Token rows are 4lg + k (+8, +16, +24).
     const int v_k = p16 >> 2, v_c4 = p16 & 3, v_dhalf = l16 & 1;
-    const int v_swz = (v_k << 1) | lg;
+    const int v_swz = swz(lg * 4 + v_k);          // for +0 and +16; +8 and +24 flip the swizzle's bit 0
     const int v_row0 = (lg * 4 + v_k) * kRowBytes;
     // d-tile dt: chunk = 4dt + 2dhalf + (c4 >> 1); even and odd dt differ in bit 2, which the swizzle touches
     const int v_even = v_row0 + (((v_dhalf * 2 + (v_c4 >> 1)) ^ v_swz) << 4) + (v_c4 & 1) * 8;
     const int v_odd = v_row0 + (((4 + v_dhalf * 2 + (v_c4 >> 1)) ^ v_swz) << 4) + (v_c4 & 1) * 8;
+    const int v_even8 = v_row0 + (((v_dhalf * 2 + (v_c4 >> 1)) ^ v_swz ^ 1) << 4) + (v_c4 & 1) * 8;
+    const int v_odd8 = v_row0 + (((4 + v_dhalf * 2 + (v_c4 >> 1)) ^ v_swz ^ 1) << 4) + (v_c4 & 1) * 8;
 
   for (; g < g_end; ++b) {
     const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
@@ -321,10 +327,11 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
         const u32x4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
         const u32x4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
         const int a_even = stage_off + v_even, a_odd = stage_off + v_odd;
+        const int a_even8 = stage_off + v_even8, a_odd8 = stage_off + v_odd8;
 #define SEER_MLA_PV(G2)                                                                                   \
         {                                                                                                 \
             u32x2 vr[2][4];   /* [even | odd d-tile of the pair][step*2 + (tokens +0..3 | +8..11)] */      \
-            SEER_MLA_TR8(vr, a_even, a_odd, (G2) * 128);                                                  \
+            SEER_MLA_TR8(vr, a_even, a_even8, a_odd, a_odd8, (G2) * 128);                                 \
             const u32x4 e0 = {vr[0][0][0], vr[0][0][1], vr[0][1][0], vr[0][1][1]};                        \
             const u32x4 o0 = {vr[1][0][0], vr[1][0][1], vr[1][1][0], vr[1][1][1]};                        \
             const u32x4 e1 = {vr[0][2][0], vr[0][2][1], vr[0][3][0], vr[0][3][1]};                        \
