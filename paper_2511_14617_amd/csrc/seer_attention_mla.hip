@@ -24,6 +24,9 @@
 //   softmax       : one query row per lane, as in the D = 128 kernel
 //   O^T += V^T.P^T: 16 d-tiles x 2 steps; V^T operand from the same LDS tile through the
 //                   transposing read ds_read_b64_tr_b16; O^T (32 rows x 512) = 256 accumulators
+#include <type_traits>
+#include <utility>
+
 #include "seer_attention.h"
 #include "seer_device.h"
 #include "seer_tile.h"
@@ -40,7 +43,7 @@ constexpr int kStageBytes = kTile * kRowBytes;     // 36864
 constexpr int kBlocks = kStageBytes / 1024;        // 36 one-KB wave loads per tile
 constexpr int kWaves = 4;
 constexpr int kRowsPerWg = 32 * kWaves;            // 128
-constexpr int kStages = 3;
+constexpr int kStages = 3;                        // tile u (K operand), tile u-1 (V operand), one in flight
 constexpr int kLoadsPerWave = kBlocks / kWaves;    // 9
 constexpr int kKSteps = kDqk / 16;                 // 36
 constexpr int kDTiles = kDv / 32;                  // 16
@@ -54,26 +57,36 @@ static_assert(kBlocks % kWaves == 0, "every wave issues the same number of loads
 __device__ __forceinline__ int swz(int row) { return (((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1); }
 }  // namespace mla
 
-// 8 transposing reads (an even and an odd d-tile x {step 0 lo, step 0 hi, step 1 lo, step 1 hi}) and the
-// wait for them, as one asm block (see the D = 128 kernel for why these do not go through the builtin).
-// a_even / a_odd: lane address for even / odd d-tiles; OFF: byte offset of the d-tile pair.
-// The token rows +8 and +24 differ from +0 and +16 in row bit 3, which the swizzle uses: they go
-// through addresses of their own (a_even8 / a_odd8).
-#define SEER_MLA_TR8(vr, a_even, a_even8, a_odd, a_odd8, OFF)                                              \
-    asm volatile(                                                                                          \
-        "ds_read_b64_tr_b16 %0, %8 offset:%12\n"                                                           \
-        "ds_read_b64_tr_b16 %1, %9 offset:%13\n"                                                           \
-        "ds_read_b64_tr_b16 %2, %8 offset:%14\n"                                                           \
-        "ds_read_b64_tr_b16 %3, %9 offset:%15\n"                                                           \
-        "ds_read_b64_tr_b16 %4, %10 offset:%12\n"                                                          \
-        "ds_read_b64_tr_b16 %5, %11 offset:%13\n"                                                          \
-        "ds_read_b64_tr_b16 %6, %10 offset:%14\n"                                                          \
-        "ds_read_b64_tr_b16 %7, %11 offset:%15\n"                                                          \
-        "s_waitcnt lgkmcnt(0)"                                                                             \
-        : "=&v"(vr[0][0]), "=&v"(vr[0][1]), "=&v"(vr[0][2]), "=&v"(vr[0][3]), "=&v"(vr[1][0]), "=&v"(vr[1][1]), \
-          "=&v"(vr[1][2]), "=&v"(vr[1][3])                                                                 \
-        : "v"(a_even), "v"(a_even8), "v"(a_odd), "v"(a_odd8), "n"((OFF)), "n"((OFF) + 8 * mla::kRowBytes),  \
-          "n"((OFF) + 16 * mla::kRowBytes), "n"((OFF) + 24 * mla::kRowBytes))
+// LDS byte address of an object in LDS, for the address operands of the asm blocks below.
+template <typename T>
+__device__ __forceinline__ int lds_addr(T* p) {
+    return static_cast<int>(reinterpret_cast<uintptr_t>((SEER_AS3 void*)(p)));
+}
+
+// Operand reads whose issue and completion are separated by hand (LDS returns in order, so
+// "s_waitcnt lgkmcnt(N)" with N = the reads issued after a group means that group has arrived).
+// The issuing block names the destination registers as outputs although they are only written
+// when the read returns; the matching wait block takes them as read-write operands, so every use
+// of the data is ordered after the wait.  They do not go through the builtins: the compiler puts a
+// vmcnt(0) in front of those, because it cannot tell the reads apart from the direct-to-LDS loads
+// still in flight.
+//
+// one read, one wait
+#define SEER_MLA_READ128(dst, addr, OFF) \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF))
+#define SEER_MLA_READ_TR2(dst, addr_lo, addr_hi, OFF_LO, OFF_HI)                                           \
+    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%4\n"                                                   \
+                 "ds_read_b64_tr_b16 %1, %3 offset:%5"                                                     \
+                 : "=&v"(dst[0]), "=&v"(dst[1])                                                            \
+                 : "v"(addr_lo), "v"(addr_hi), "n"(OFF_LO), "n"(OFF_HI))
+template <int N>
+__device__ __forceinline__ void wait_lgkm() {
+    static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+}
+#define SEER_MLA_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Keeps the computation of x at the place where it is written (see the D = 128 kernel).
+#define SEER_MLA_PIN(x) asm volatile("" : "+v"(x))
 
 // acc += A . B with the accumulator pinned to the AGPR half of the register file.  Written as asm
 // because the compiler, left to choose, keeps part of the 256 accumulators in VGPRs and then
@@ -85,10 +98,160 @@ __device__ __forceinline__ void mfma_acc(f32x16& acc, u32x4 a, u32x4 b) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 // The score accumulator, pinned to VGPRs (all AGPRs hold O^T).
-__device__ __forceinline__ void mfma_vgpr(f32x16& acc, u32x4 a, bf16x8 b) {
+__device__ __forceinline__ void mfma_vgpr(f32x16& acc, u32x4 a, u32x4 b) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
+// ... starting from zero
+__device__ __forceinline__ void mfma_vgpr_first(f32x16& acc, u32x4 a, u32x4 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
 __device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
+namespace mla {
+
+template <typename F, int... I>
+__device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+
+// max over the two lanes that share a query row (lane and lane ^ 32): see the D = 128 kernel
+__device__ __forceinline__ float max_across_halves(float x) {
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return fmaxf(a, b);
+}
+
+// A wave issues in order, and an MFMA holds the matrix core for 32 cycles: whatever else a step has
+// to issue (operand reads from LDS, the softmax arithmetic) only runs in the shadow of the MFMAs
+// if it sits BETWEEN them, one MFMA at a time.  Both phases below are written that way: after
+// every MFMA come the one or two LDS reads that feed an MFMA a fixed distance ahead, and a slice
+// of vector-ALU work.
+
+constexpr int kKAhead = 8;    // the K operand of score step kk is read kKAhead MFMAs before it is used
+constexpr int kQAhead = 4;    // ... the parked Q^T operands kQAhead MFMAs before
+constexpr int kVAhead = 6;    // the V^T operand of a P.V MFMA (two transposing reads) kVAhead MFMAs before
+
+// LDS reads outstanding behind the operand(s) of score step kk at the point where that step waits,
+// from the order in which phase_a issues them
+constexpr int qk_wait_count(int kk) {
+    int seq = 0, pos_k[kKSteps] = {}, pos_q[kKSteps] = {}, before[kKSteps] = {};
+    for (int i = 0; i < kKAhead; ++i) pos_k[i] = seq++;
+    for (int m = 0; m < kKSteps; ++m) {
+        before[m] = seq;
+        if (m + kKAhead < kKSteps) pos_k[m + kKAhead] = seq++;
+        if (m + kQAhead >= kQRegSteps && m + kQAhead < kKSteps) pos_q[m + kQAhead] = seq++;
+    }
+    int need = pos_k[kk];
+    if (kk >= kQRegSteps && pos_q[kk] > need) need = pos_q[kk];
+    return before[kk] - 1 - need;
+}
+static_assert(kQRegSteps >= kQAhead && qk_wait_count(0) == kKAhead - 1 && qk_wait_count(kKSteps - 1) == 0, "");
+
+// Phase A of a pipeline step: the scores of tile u (36 MFMAs into s_new) with, in their shadow, the
+// softmax of tile u-1 (s_old -> pk, m_run, l_run, alpha).  ka: LDS addresses of this lane's K
+// operand chunks for contraction steps 0..3 of the tile (steps 4g + j are 128 g bytes further);
+// qt: LDS address of this lane's parked Q^T operands.  s_old must already carry -inf in masked slots.
+template <bool DO_QK, bool DO_SM>
+__device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 (&qreg)[kQRegSteps], f32x16& s_new,
+                                        f32x16& s_old, uint32_t (&pk)[8], float& m_run, float& l_run, float& alpha,
+                                        float scale_log2) {
+    u32x4 kr[kKAhead], qr[kQAhead];
+    if constexpr (DO_QK) {
+        for_each_index([&](auto ic) __attribute__((always_inline)) {
+            constexpr int I = decltype(ic)::value;
+            (void)&kr, (void)&ka;   // (asm operands alone do not capture)
+            SEER_MLA_READ128(kr[I], ka[I & 3], (I >> 2) * 128);
+        }, std::make_integer_sequence<int, kKAhead>{});
+    }
+    float m_use = 0.f, psum = 0.f, p_even = 0.f;
+    if constexpr (DO_SM) {
+        // register i of s_old holds token (i/4)*8 + lg*4 + i%4 of the tile, for this lane's row
+        float mx = kNegInf;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(mx, s_old[i]), s_old[i + 1]);
+        // Lazy reference: m_run is the exponent reference of (l, acc), not necessarily the true
+        // maximum; it moves only when the tile maximum exceeds it by more than 8 (log2 units), so p
+        // stays below 2^8 (bf16 and fp32 have the range) and the 256-register rescale is rare.
+        mx = max_across_halves(mx) * scale_log2;
+        const float m_new = (mx > m_run + 8.f) ? mx : m_run;
+        m_use = (m_new == kNegInf) ? 0.f : m_new;
+        alpha = fast_exp2(m_run - m_use);
+        m_run = m_new;
+        SEER_MLA_PIN(m_use);
+        SEER_MLA_PIN(alpha);
+        SEER_MLA_PIN(m_run);
+    }
+    // probability of slot i; two of them make one packed register
+    auto element = [&](auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (DO_SM) {
+            const float p = fast_exp2(fmaf(s_old[i], scale_log2, -m_use));
+            psum += p;
+            if constexpr (i % 2 == 0) {
+                p_even = p;
+                SEER_MLA_PIN(p_even);
+            } else {
+                pk[i >> 1] = cvt_pk_bf16(p_even, p);
+                SEER_MLA_PIN(pk[i >> 1]);
+            }
+            SEER_MLA_PIN(psum);
+        }
+    };
+    SEER_MLA_FENCE();
+    if constexpr (DO_QK) {
+        for_each_index([&](auto ic) __attribute__((always_inline)) {
+            constexpr int kk = decltype(ic)::value;
+            (void)&kr, (void)&qr, (void)&ka, (void)&qt;   // (asm operands alone do not capture)
+            wait_lgkm<qk_wait_count(kk)>();
+            const u32x4 qv = kk < kQRegSteps ? qreg[kk < kQRegSteps ? kk : 0] : qr[kk % kQAhead];
+            if constexpr (kk == 0) mfma_vgpr_first(s_new, kr[0], qv); else mfma_vgpr(s_new, kr[kk % kKAhead], qv);
+            if constexpr (kk + kKAhead < kKSteps)
+                SEER_MLA_READ128(kr[kk % kKAhead], ka[(kk + kKAhead) & 3], ((kk + kKAhead) >> 2) * 128);
+            if constexpr (kk + kQAhead >= kQRegSteps && kk + kQAhead < kKSteps)
+                SEER_MLA_READ128(qr[kk % kQAhead], qt, (kk + kQAhead - kQRegSteps) * 1024);
+            // one probability in the shadow of every second MFMA
+            if constexpr (kk >= 2 && kk % 2 == 0 && (kk - 2) / 2 < 16) element(std::integral_constant<int, (kk - 2) / 2>{});
+            SEER_MLA_FENCE();
+        }, std::make_integer_sequence<int, kKSteps>{});
+    } else {
+        for_each_index(element, std::make_integer_sequence<int, 16>{});
+    }
+    if constexpr (DO_SM) {
+        l_run = l_run * alpha + psum;
+        SEER_MLA_PIN(l_run);
+    }
+}
+
+// Phase B: O^T[d][row] += sum_token V[token][d] * P[row][token] for one tile (32 MFMAs), V = first 512
+// dims of the latent through the transposing read.  MFMA m = 4 G2 + w works on the pair of d-tiles G2:
+// w = 0, 1: even, odd d-tile, tokens 0..15;  w = 2, 3: even, odd d-tile, tokens 16..31.
+// a_even / a_odd: lane address for even / odd d-tiles; the token rows +8 and +24 differ from +0 and
+// +16 in row bit 3, which the swizzle uses: they go through addresses of their own (a_even8 / a_odd8).
+__device__ __forceinline__ void phase_b(int a_even, int a_even8, int a_odd, int a_odd8, const uint32_t (&pk)[8],
+                                        f32x16 (&acc)[kDTiles]) {
+    const u32x4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
+    const u32x4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
+    u32x2 vr[kVAhead][2];   // [ring slot][tokens +0..3 | +8..11 of the MFMA's 16]
+    auto read_for = [&](auto ic) __attribute__((always_inline)) {
+        constexpr int m = decltype(ic)::value;
+        constexpr int G2 = m >> 2, w = m & 3;
+        constexpr int off_lo = G2 * 128 + (w >= 2 ? 16 : 0) * kRowBytes, off_hi = off_lo + 8 * kRowBytes;
+        (void)&vr, (void)&a_even, (void)&a_even8, (void)&a_odd, (void)&a_odd8;   // (asm operands alone do not capture)
+        if constexpr (w & 1) SEER_MLA_READ_TR2(vr[m % kVAhead], a_odd, a_odd8, off_lo, off_hi);
+        else SEER_MLA_READ_TR2(vr[m % kVAhead], a_even, a_even8, off_lo, off_hi);
+    };
+    for_each_index(read_for, std::make_integer_sequence<int, kVAhead>{});
+    for_each_index([&](auto ic) __attribute__((always_inline)) {
+        constexpr int m = decltype(ic)::value;
+        constexpr int left = kDTiles * 2 - 1 - m;                       // MFMAs after this one
+        wait_lgkm<2 * (left < kVAhead - 1 ? left : kVAhead - 1)>();
+        const u32x4 v = {vr[m % kVAhead][0][0], vr[m % kVAhead][0][1], vr[m % kVAhead][1][0], vr[m % kVAhead][1][1]};
+        mfma_acc(acc[(m >> 2) * 2 + (m & 1)], v, (m & 2) ? pb1 : pb0);
+        if constexpr (m + kVAhead < kDTiles * 2) read_for(std::integral_constant<int, m + kVAhead>{});
+    }, std::make_integer_sequence<int, kDTiles * 2>{});
+}
+
+}  // namespace mla
 
 __global__ __launch_bounds__(mla::kWaves* kWave) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_mla_kernel(AttnArgs a, int row_blocks) {
@@ -165,7 +328,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
                            : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
         if (a.T < 64) word &= (1ull << a.T) - 1;
     }
-    bf16x8 qreg[kQRegSteps];
+    u32x4 qreg[kQRegSteps];
     {
         const u32x4* qp = reinterpret_cast<const u32x4*>(
             static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * kDqk + lg * 8);
@@ -184,7 +347,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
 #pragma unroll
         for (int kk = 0; kk < kQRegSteps; ++kk) {   // pin the arrival of these loads before the tile loop
             asm volatile("" : "+v"(qv[kk]));
-            qreg[kk] = as_bf16x8(qv[kk]);
+            qreg[kk] = qv[kk];
         }
         uint32_t w_lo = static_cast<uint32_t>(word), w_hi = static_cast<uint32_t>(word >> 32);
         asm volatile("" : "+v"(w_lo), "+v"(w_hi));
@@ -196,7 +359,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
-    float m_run = kNegInf, l_run = 0.f;
+    float m_run = kNegInf, l_run = 0.f, alpha = 1.f;
 
     // ---- page ids, 64 at a time, handed out by v_readlane ------------------------------------
     const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
@@ -233,81 +396,44 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
         }
     };
 
-#pragma unroll
-    for (int s = 0; s < kStages - 1; ++s)
-        if (s < n_tiles) issue_tile(s);
-
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        if (tile + 1 < n_tiles) wait_vmcnt<kLoadsPerWave>(); else wait_vmcnt<0>();
+    // ---- the pipeline: step u = scores of tile u | softmax of tile u-1, then P.V of tile u-1 ------
+    // Tile u + kStages - 2 is requested at step u, into the stage that tile u-2 left at the end of step u-1.
+    const int lds_base = lds_addr(lds);
+    const int qt = lds_addr(&q_tail[wave][0][lane]);
+    f32x16 s_a, s_b;
+    uint32_t pk[8];
+    // top of step u: tile u has landed for every wave, every wave is done with step u-1
+    auto step_top = [&](int u) __attribute__((always_inline)) {
+        if (kStages > 3 && u + 1 < n_tiles) wait_vmcnt<(kStages > 3 ? kLoadsPerWave : 0)>(); else wait_vmcnt<0>();
         bare_barrier();
-        if (tile + kStages - 1 < n_tiles) issue_tile(tile + kStages - 1);
-
-        const int stage_off = (tile % kStages) * kStageBytes;
-        const unsigned char* kl = lds + stage_off;
-        const int tb = tok_begin + tile * kTile;
-
-        if (tb + kTile > n) {
+        if (u + kStages - 2 < n_tiles) issue_tile(u + kStages - 2);
+        if (u == n_tiles - 1 && tok_begin + (u + 1) * kTile > n) {
             // ragged last tile: clear the rows past the end (0 * NaN must not reach the output)
-            const int first_bad = n - tb;
+            unsigned char* kl = lds + (u % kStages) * kStageBytes;
+            const int first_bad = n - (tok_begin + u * kTile);
             for (int c = tid; c < kTile * kChunksPerRow; c += NT)
-                if (c / kChunksPerRow >= first_bad)
-                    *reinterpret_cast<u32x4*>(const_cast<unsigned char*>(kl) + c * 16) = u32x4{0u, 0u, 0u, 0u};
+                if (c / kChunksPerRow >= first_bad) *reinterpret_cast<u32x4*>(kl + c * 16) = u32x4{0u, 0u, 0u, 0u};
             __builtin_amdgcn_s_waitcnt(0xc07f);
             bare_barrier();
         }
-
-        // S^T[token][row] = sum_d K[token][d] * Q[row][d]
-        f32x16 s;
+    };
+    // -inf into the slots of tile j that this lane's row does not see
+    auto apply_mask = [&](int j, f32x16& sc) __attribute__((always_inline)) {
+        const int rel = tok_begin + j * kTile - n0;        // uniform; a tile with masked slots has rel > -32
+        if (rel <= -kTile) return;
+        uint32_t vis = rel >= 0 ? static_cast<uint32_t>(word >> rel)
+                                : (static_cast<uint32_t>(word << (-rel)) | ((1u << (-rel)) - 1u));
+        vis >>= lg * 4;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.f;
+        for (int i = 0; i < 16; ++i)
+            if (!((vis >> ((i >> 2) * 8 + (i & 3))) & 1u)) sc[i] = kNegInf;
+    };
+    auto k_addrs = [&](int u, int (&ka)[4]) __attribute__((always_inline)) {
+        const int st = lds_base + (u % kStages) * kStageBytes;
 #pragma unroll
-        for (int kk = 0; kk < kKSteps; ++kk) {
-            const u32x4 kv = *reinterpret_cast<const u32x4*>(kl + k_rd[kk & 3] + (kk >> 2) * 128);
-            const bf16x8 qb = kk < kQRegSteps ? qreg[kk < kQRegSteps ? kk : 0]
-                                              : as_bf16x8(q_tail[wave][kk < kQRegSteps ? 0 : kk - kQRegSteps][lane]);
-            mfma_vgpr(s, kv, qb);
-        }
-        mfma_drain();   // the vector ALU reads s next, and the compiler does not know an MFMA wrote it
-
-        float mx = kNegInf;
-        if (tb + kTile > n0) {
-            const int rel = tb - n0;
-            uint32_t vis = rel >= 0 ? static_cast<uint32_t>(word >> rel)
-                                    : (static_cast<uint32_t>(word << (-rel)) | ((1u << (-rel)) - 1u));
-            vis >>= lg * 4;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const bool on = (vis >> ((i >> 2) * 8 + (i & 3))) & 1u;
-                const float v = on ? s[i] * a.scale_log2 : kNegInf;
-                s[i] = v;
-                mx = fmaxf(mx, v);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                s[i] *= a.scale_log2;
-                mx = fmaxf(mx, s[i]);
-            }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        // Lazy reference: m_run is the exponent reference of (l, acc), not necessarily the true
-        // maximum; it moves only when the tile maximum exceeds it by more than 2^8, so p stays
-        // below 256 (bf16 and fp32 have the range) and the 256-register rescale is rare.
-        const bool move_ref = mx > m_run + 8.f;
-        const float m_new = move_ref ? mx : m_run;
-        const float m_use = (m_new == kNegInf) ? 0.f : m_new;
-        const float alpha = move_ref ? fast_exp2(m_run - m_use) : 1.f;
-        m_run = m_new;
-        float psum = 0.f;
-        uint32_t pk[8];
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-            const float p0 = fast_exp2(s[i] - m_use);
-            const float p1 = fast_exp2(s[i + 1] - m_use);
-            psum += p0 + p1;
-            pk[i >> 1] = cvt_pk_bf16(p0, p1);
-        }
-        l_run = l_run * alpha + psum;
+        for (int j = 0; j < 4; ++j) ka[j] = st + k_rd[j];
+    };
+    auto pv = [&](int j) __attribute__((always_inline)) {
         if (__any(alpha != 1.f)) {
             mfma_drain();
             // one d-tile at a time through VGPRs (the empty asm statements keep the compiler from
@@ -321,36 +447,48 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
                 acc[dt] = tmp;
                 asm volatile("" : "+a"(acc[dt]));
             }
+            asm volatile("s_nop 7");
         }
+        const int st = lds_base + (j % kStages) * kStageBytes;
+        phase_b(st + v_even, st + v_even8, st + v_odd, st + v_odd8, pk, acc);
+    };
 
-        // O^T[d][row] += sum_token V[token][d] * P[row][token], V = first 512 dims of the latent
-        const u32x4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
-        const u32x4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
-        const int a_even = stage_off + v_even, a_odd = stage_off + v_odd;
-        const int a_even8 = stage_off + v_even8, a_odd8 = stage_off + v_odd8;
-#define SEER_MLA_PV(G2)                                                                                   \
-        {                                                                                                 \
-            u32x2 vr[2][4];   /* [even | odd d-tile of the pair][step*2 + (tokens +0..3 | +8..11)] */      \
-            SEER_MLA_TR8(vr, a_even, a_even8, a_odd, a_odd8, (G2) * 128);                                 \
-            const u32x4 e0 = {vr[0][0][0], vr[0][0][1], vr[0][1][0], vr[0][1][1]};                        \
-            const u32x4 o0 = {vr[1][0][0], vr[1][0][1], vr[1][1][0], vr[1][1][1]};                        \
-            const u32x4 e1 = {vr[0][2][0], vr[0][2][1], vr[0][3][0], vr[0][3][1]};                        \
-            const u32x4 o1 = {vr[1][2][0], vr[1][2][1], vr[1][3][0], vr[1][3][1]};                        \
-            mfma_acc(acc[(G2) * 2], e0, pb0);                                                             \
-            mfma_acc(acc[(G2) * 2 + 1], o0, pb0);                                                         \
-            mfma_acc(acc[(G2) * 2], e1, pb1);                                                             \
-            mfma_acc(acc[(G2) * 2 + 1], o1, pb1);                                                         \
-        }
-        SEER_MLA_PV(0)
-        SEER_MLA_PV(1)
-        SEER_MLA_PV(2)
-        SEER_MLA_PV(3)
-        SEER_MLA_PV(4)
-        SEER_MLA_PV(5)
-        SEER_MLA_PV(6)
-        SEER_MLA_PV(7)
-#undef SEER_MLA_PV
+#pragma unroll
+    for (int t2 = 0; t2 < kStages - 2; ++t2)
+        if (t2 < n_tiles) issue_tile(t2);
+
+    int ka[4];
+    step_top(0);
+    k_addrs(0, ka);
+    phase_a<true, false>(ka, qt, qreg, s_a, s_b, pk, m_run, l_run, alpha, a.scale_log2);
+    // steps 1 .. n_tiles - 1, two per iteration so that s_a and s_b swap roles without register moves
+    int u = 1;
+    for (; u + 1 < n_tiles; u += 2) {
+        step_top(u);
+        k_addrs(u, ka);
+        apply_mask(u - 1, s_a);
+        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_run, l_run, alpha, a.scale_log2);
+        pv(u - 1);
+        step_top(u + 1);
+        k_addrs(u + 1, ka);
+        apply_mask(u, s_b);
+        phase_a<true, true>(ka, qt, qreg, s_a, s_b, pk, m_run, l_run, alpha, a.scale_log2);
+        pv(u);
     }
+    if (u < n_tiles) {
+        step_top(u);
+        k_addrs(u, ka);
+        apply_mask(u - 1, s_a);
+        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_run, l_run, alpha, a.scale_log2);
+        pv(u - 1);
+        asm volatile("" : "+v"(s_b));       // the copy below reads s_b after the P.V MFMAs, not right behind the score MFMAs
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_a[i] = s_b[i];
+    }
+    // the last tile's scores are in s_a
+    apply_mask(n_tiles - 1, s_a);
+    phase_a<false, true>(ka, qt, qreg, s_b, s_a, pk, m_run, l_run, alpha, a.scale_log2);
+    pv(n_tiles - 1);
 
     // ---- partial result ------------------------------------------------------------------------
     mfma_drain();
