@@ -4,8 +4,14 @@ by the product path."""
 from .seer_oracle import (  # noqa: F401
     accept,
     argmax,
+    argmax_sampled,
     build,
+    emitted_tokens,
+    gumbel,
+    kv_commit,
+    log2_det,
     num_threads,
+    philox4x32_10,
     verify_accept,
     verify_attention,
     verify_attention_rows,

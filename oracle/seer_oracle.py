@@ -15,6 +15,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "seer_oracle.c")
+_SRC_NEXT = os.path.join(_HERE, "seer_oracle_next.c")      # commit of the accepted path, sampled verification
 _LIB = os.path.join(_HERE, "libseer_oracle.so")
 _lib = None
 
@@ -24,10 +25,21 @@ _ERR = {-1: "bad shape or null pointer", -2: "ctx_len < T or more pages than the
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP, no fast-math)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_NEXT))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-                               "-o", tmp, _SRC, "-lm"])
+        common = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-Wall", "-Wextra"]
+        objs = []
+        # the second file decides an argmax in fp32: no contraction of a*b+c beyond the fmaf calls it writes
+        for src, extra in ((_SRC, []), (_SRC_NEXT, ["-ffp-contract=off"])):
+            obj = "%s.%d.o" % (os.path.splitext(src)[0], os.getpid())
+            subprocess.check_call(common + extra + ["-c", "-o", obj, src])
+            objs.append(obj)
+        try:
+            subprocess.check_call(common + ["-shared", "-o", tmp] + objs + ["-lm"])
+        finally:
+            for obj in objs:
+                os.remove(obj)
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -43,6 +55,16 @@ def _load():
                                                       + [ctypes.c_void_p] * 6 + [ctypes.c_int] * 9
                                                       + [ctypes.c_double])
         _lib.oracle_accept.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 2 + [ctypes.c_void_p] * 3
+        _lib.oracle_kv_commit.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 8 + [ctypes.c_void_p]
+        _lib.oracle_emitted_tokens.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 2 + [ctypes.c_void_p] * 2
+        _lib.oracle_philox4x32_10.argtypes = [ctypes.c_void_p] * 3
+        _lib.oracle_philox4x32_10.restype = None
+        _lib.oracle_log2_det.argtypes = [ctypes.c_float]
+        _lib.oracle_log2_det.restype = ctypes.c_float
+        _lib.oracle_gumbel.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32]
+        _lib.oracle_gumbel.restype = ctypes.c_float
+        _lib.oracle_argmax_sampled.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float,
+                                               ctypes.c_uint64, ctypes.c_void_p]
     return _lib
 
 
@@ -141,3 +163,56 @@ def verify_accept(logits, draft_tokens, tree_parent):
     tgt = argmax(logits)
     alen, path, bonus = accept(tgt, draft_tokens, tree_parent)
     return alen, path, bonus, tgt
+
+
+def kv_commit(k_pages, v_pages, block_table, ctx_len, accepted_len, accepted_path):
+    """Compacts the accepted path's key/value rows behind the root (oracle_kv_commit).
+
+    Returns (k_pages, v_pages, ctx_len) after the step; the inputs are not modified.  Pools are uint16
+    bit patterns [num_pages, Hkv, P, D]; v_pages None = shared latent.
+    """
+    k = np.array(k_pages, dtype=np.uint16, order="C", copy=True)
+    v = None if v_pages is None else np.array(v_pages, dtype=np.uint16, order="C", copy=True)
+    bt, cl = _c(block_table, np.int32), _c(ctx_len, np.int32)
+    al, ap = _c(accepted_len, np.int32), _c(accepted_path, np.int32)
+    num_pages, Hkv, P, Dqk = k.shape
+    B, T = ap.shape
+    Dv = v.shape[3] if v is not None else 0
+    out_len = np.empty(B, np.int32)
+    _check(_load().oracle_kv_commit(_p(k), _p(v), _p(bt), _p(cl), _p(al), _p(ap), B, T, Hkv, Dqk, Dv, P, num_pages,
+                                    bt.shape[1], _p(out_len)))
+    return k, v, out_len
+
+
+def emitted_tokens(draft_tokens, accepted_len, accepted_path, bonus_token):
+    """(emitted [B,T] padded with -1, n_emitted [B]): accepted draft tokens in path order, then the bonus."""
+    d, al, ap, bo = (_c(x, np.int32) for x in (draft_tokens, accepted_len, accepted_path, bonus_token))
+    B, T = d.shape
+    em, n = np.empty((B, T), np.int32), np.empty(B, np.int32)
+    _check(_load().oracle_emitted_tokens(_p(d), _p(al), _p(ap), _p(bo), B, T, _p(em), _p(n)))
+    return em, n
+
+
+def philox4x32_10(counter, key) -> np.ndarray:
+    c, k = np.asarray(counter, np.uint32).copy(), np.asarray(key, np.uint32).copy()
+    out = np.empty(4, np.uint32)
+    _load().oracle_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def log2_det(x: float) -> float:
+    return float(_load().oracle_log2_det(float(x)))
+
+
+def gumbel(seed: int, row: int, v: int) -> float:
+    return float(_load().oracle_gumbel(seed, row, v))
+
+
+def argmax_sampled(logits, temperature: float, seed: int) -> np.ndarray:
+    """Token drawn from softmax(logits / temperature) per row, by the reproducible Gumbel-max rule."""
+    lg = _c(logits, np.float32)
+    V = lg.shape[-1]
+    rows = lg.size // V
+    out = np.empty(rows, np.int32)
+    _check(_load().oracle_argmax_sampled(_p(lg), rows, V, temperature, seed, _p(out)))
+    return out.reshape(lg.shape[:-1])
