@@ -180,6 +180,19 @@ def main() -> int:
                                                          workspace=ws_att))
     acc_ms = 0.0 if args.attention_only else timed(
         lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out))
+    # the calls around the step (not part of `value`): acceptance under sampling, and the commit of the
+    # accepted path (on a copy of the lengths, so that every repetition moves the same rows)
+    sampled_ms = commit_ms = None
+    if not args.attention_only:
+        sampled_ms = timed(lambda: binding.seer_accept_sampled(e["logits"], e["draft_tokens"], e["tree_parent"], 0.8,
+                                                               20251114, workspace=ws_acc, out=acc_out))
+        binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out)
+        n_copy = d["ctx_len"].clone()
+
+        def commit():
+            n_copy.copy_(d["ctx_len"])
+            binding.seer_kv_commit(d["k_pages"], d["v_pages"], d["block_table"], n_copy, acc_out[0], acc_out[1])
+        commit_ms = timed(commit)
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -231,6 +244,7 @@ def main() -> int:
         "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
         "accept_logits_GBps": (acc.logits.nbytes / (acc_ms * 1e-3) / 1e9) if acc_ms > 0 else None,
         "attention_status_word": status,
+        "accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(att, acc)

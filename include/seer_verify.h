@@ -158,6 +158,61 @@ int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t*
                 int32_t* bonus_token, int32_t* target_argmax, void* workspace,
                 size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Acceptance under sampling (Section 4.1 of the paper: its workloads sample at
+ * temperature 1.0 and 0.8; Section 3.4: its drafts are token sequences, not
+ * distributions).  As seer_accept, except that the target token of a slot is a
+ * DRAW from softmax(logits[b,t,:] / temperature) instead of the argmax, by the
+ * Gumbel-max rule: token = lowest index attaining max_v fma(logits[v],
+ * 1/temperature, G(seed, b*T+t, v)) in fp32.  G is a pure function of its
+ * arguments (Philox4x32-10 with counter (v/4, row, 0, 0) and key = seed;
+ * u = ((word >> 9) + 0.5) * 2^-23; G = -ln(-ln u) through a fixed fp32
+ * polynomial log2), so a call is reproducible bit for bit, and accepting a
+ * draft token iff it equals the draw at its parent is lossless.
+ *
+ *  temperature  > 0, finite            seed  any 64-bit value; use a new one per step
+ *  target_token device [B,T] int32, written: the drawn token of each slot
+ * Everything else, the workspace size included, as for seer_accept.
+ */
+int seer_accept_sampled(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+                        int32_t B, int32_t T, int32_t V, float temperature, uint64_t seed,
+                        int32_t* accepted_len, int32_t* accepted_path, int32_t* bonus_token,
+                        int32_t* target_token, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Commit of the accepted path: the step right after verification (Section 3.4:
+ * of several candidate paths one root path is accepted; Section 3.1: the
+ * sequence continues exactly as serial decoding would have).  For every request
+ * the key/value rows of accepted_path[b][1..a], a = accepted_len[b], which sit
+ * at logical positions n0 + path[i] (n0 = ctx_len[b] - T), are moved to
+ * positions n0+1 .. n0+a, and ctx_len[b] becomes n0 + 1 + a (root + accepted
+ * draft tokens; the bonus token has no key/value yet, it is the next step's
+ * root).  Rows past the new length keep stale contents.  For a chain nothing
+ * moves.  Optionally the tokens the step emits are written: the a accepted
+ * draft tokens in path order, then the bonus token.
+ *
+ *  p              shapes as for seer_verify_attention (B, T, Hkv, Dqk, Dv, page_size,
+ *                 num_pages, max_pages_per_seq, kv_shared_latent are used); Dqk and Dv
+ *                 multiples of 8; (T-1) * (Dqk + Dv) / 8 <= 4608
+ *  k_pages, v_pages  device, modified in place; v_pages NULL iff kv_shared_latent
+ *  block_table    device [B,max_pages_per_seq] int32
+ *  ctx_len        device [B] int32, read and overwritten
+ *  accepted_len, accepted_path  device, as written by seer_accept
+ *  draft_tokens, bonus_token    device; needed only if emitted_tokens is given
+ *  emitted_tokens device [B,T] int32 or NULL, written: a + 1 tokens, then -1
+ *  n_emitted      device [B] int32 (NULL iff emitted_tokens is NULL), written: a + 1
+ *  status         device [1] int32 or NULL; bits are OR-ed in: 1 = a ctx_len out of
+ *                 range, 2 = a page id outside the pool, 4 = accepted_len / accepted_path
+ *                 malformed (path[0] != 0, not ascending, >= T).  Such requests are
+ *                 left untouched.  The caller clears it.
+ * Returns SEER_OK or a negative SEER_E* / positive hipError_t; asynchronous on
+ * hip_stream.  Requests must not share the pages that hold their T verify slots.
+ */
+int seer_kv_commit(const seer_attn_params* p, void* k_pages, void* v_pages, const int32_t* block_table,
+                   int32_t* ctx_len, const int32_t* accepted_len, const int32_t* accepted_path,
+                   const int32_t* draft_tokens, const int32_t* bonus_token, int32_t* emitted_tokens,
+                   int32_t* n_emitted, int32_t* status, void* hip_stream);
+
 /* Static text for a return code of either call (negative SEER_E*, or a
  * positive hipError_t). */
 const char* seer_strerror(int code);

@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_PKG, "libseer_verify.so")
 SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALIGN = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
-           "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_strerror")
+           "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
+           "seer_kv_commit", "seer_strerror")
 
 
 class SeerAttnParams(ctypes.Structure):
@@ -62,6 +63,11 @@ def load_library() -> ctypes.CDLL:
         lib.seer_accept_workspace.restype = sz
         lib.seer_accept.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.seer_accept.restype = ctypes.c_int
+        lib.seer_accept_sampled.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_float, ctypes.c_uint64,
+                                            vp, vp, vp, vp, vp, sz, vp]
+        lib.seer_accept_sampled.restype = ctypes.c_int
+        lib.seer_kv_commit.argtypes = [ctypes.POINTER(SeerAttnParams)] + [vp] * 12
+        lib.seer_kv_commit.restype = ctypes.c_int
         lib.seer_strerror.argtypes = [ctypes.c_int]
         lib.seer_strerror.restype = ctypes.c_char_p
         _lib = lib
@@ -158,7 +164,8 @@ def seer_accept_workspace(B: int, T: int, V: int) -> int:
 
 def seer_accept(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: Optional[torch.Tensor], *,
                 workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
-                out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]] = None
+                out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+                temperature: Optional[float] = None, seed: int = 0
                 ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
     """(accepted_len[B], accepted_path[B,T], bonus_token[B], target_argmax[B,T]), all int32.
     logits [B,T,V] fp32; draft_tokens [B,T] int32; tree_parent [B,T] int32 or None (chain)."""
@@ -183,6 +190,54 @@ def seer_accept(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: O
     need = int(lib.seer_accept_workspace(B, T, V))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
-    _check(lib.seer_accept(_ptr(logits), _ptr(draft_tokens), _ptr(tree_parent), B, T, V, _ptr(alen), _ptr(path),
-                           _ptr(bonus), _ptr(tgt), _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    if temperature is None:
+        _check(lib.seer_accept(_ptr(logits), _ptr(draft_tokens), _ptr(tree_parent), B, T, V, _ptr(alen), _ptr(path),
+                               _ptr(bonus), _ptr(tgt), _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    else:
+        _check(lib.seer_accept_sampled(_ptr(logits), _ptr(draft_tokens), _ptr(tree_parent), B, T, V,
+                                       float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(alen), _ptr(path),
+                                       _ptr(bonus), _ptr(tgt), _ptr(workspace), workspace.numel(),
+                                       _stream_handle(stream)))
     return alen, path, bonus, tgt
+
+
+def seer_accept_sampled(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: Optional[torch.Tensor],
+                        temperature: float, seed: int, **kw):
+    """As seer_accept, with the target token of each slot drawn from softmax(logits / temperature)
+    (reproducible Gumbel-max draw keyed by seed); the fourth result holds the drawn tokens."""
+    return seer_accept(logits, draft_tokens, tree_parent, temperature=temperature, seed=seed, **kw)
+
+
+def seer_kv_commit(k_pages: torch.Tensor, v_pages: Optional[torch.Tensor], block_table: torch.Tensor,
+                   ctx_len: torch.Tensor, accepted_len: torch.Tensor, accepted_path: torch.Tensor, *,
+                   draft_tokens: Optional[torch.Tensor] = None, bonus_token: Optional[torch.Tensor] = None,
+                   status: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """Moves the accepted path's K/V rows behind the root, in place, and advances ctx_len in place.
+    With draft_tokens and bonus_token also returns (emitted_tokens[B,T], n_emitted[B]), else None."""
+    lib = load_library()
+    num_pages, Hkv, P, Dqk = k_pages.shape
+    B, T = accepted_path.shape
+    Dv = v_pages.shape[3] if v_pages is not None else 0
+    _want(block_table, torch.int32, (B, block_table.shape[1]), "block_table")
+    _want(ctx_len, torch.int32, (B,), "ctx_len")
+    _want(accepted_len, torch.int32, (B,), "accepted_len")
+    _want(accepted_path, torch.int32, (B, T), "accepted_path")
+    if not (k_pages.is_contiguous() and k_pages.is_cuda and k_pages.element_size() == 2):
+        raise ValueError("k_pages: want a contiguous 16-bit device tensor")
+    if v_pages is not None and not (v_pages.is_contiguous() and v_pages.element_size() == 2
+                                    and tuple(v_pages.shape[:3]) == (num_pages, Hkv, P)):
+        raise ValueError("v_pages: want a contiguous 16-bit device tensor [num_pages, Hkv, P, Dv]")
+    params = SeerAttnParams(B, T, Hkv, Hkv, Dqk, Dv, P, num_pages, block_table.shape[1], 0,
+                            1 if v_pages is None else 0, 0, 1.0)
+    emitted = n_emitted = None
+    if draft_tokens is not None:
+        _want(draft_tokens, torch.int32, (B, T), "draft_tokens")
+        _want(bonus_token, torch.int32, (B,), "bonus_token")
+        emitted = torch.empty((B, T), dtype=torch.int32, device=k_pages.device)
+        n_emitted = torch.empty(B, dtype=torch.int32, device=k_pages.device)
+    if status is not None:
+        _want(status, torch.int32, (1,), "status")
+    _check(lib.seer_kv_commit(ctypes.byref(params), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _ptr(ctx_len),
+                              _ptr(accepted_len), _ptr(accepted_path), _ptr(draft_tokens), _ptr(bonus_token),
+                              _ptr(emitted), _ptr(n_emitted), _ptr(status), _stream_handle(stream)))
+    return None if emitted is None else (emitted, n_emitted)

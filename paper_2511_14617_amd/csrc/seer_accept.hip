@@ -23,6 +23,7 @@
 
 #include "../../include/seer_verify.h"
 #include "seer_device.h"
+#include "seer_sampling.h"
 
 namespace seer {
 
@@ -38,10 +39,17 @@ __device__ __forceinline__ void take_better(float& v, int& i, float ov, int oi) 
     i = better ? oi : i;
 }
 
-template <bool kVec4>
+// kSampled: the maximum is taken over logits[v] / tau + G(seed, row, v) (seer_sampling.h) instead of
+// the logits themselves; one generator call serves the four elements of a 16-byte load.
+struct SampleArgs {
+    float inv_tau;
+    uint32_t seed_lo, seed_hi;
+};
+
+template <bool kVec4, bool kSampled>
 __global__ __launch_bounds__(kArgmaxThreads) void argmax_chunks(const float* __restrict__ logits, int V,
                                                                 int n_chunks, float* __restrict__ part_val,
-                                                                int* __restrict__ part_idx) {
+                                                                int* __restrict__ part_idx, SampleArgs sa) {
     const int row = blockIdx.x / n_chunks;
     const int chunk = blockIdx.x - row * n_chunks;
     const int begin = chunk * kChunk;
@@ -64,6 +72,14 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_chunks(const float* __r
         for (int it = 0; it < kIter; ++it) {
             const int i = begin + (it * kArgmaxThreads + threadIdx.x) * 4;
             if (i < end) {  // indices ascend within a lane: strict '>' keeps the lowest
+                if constexpr (kSampled) {
+                    const Philox4 r = philox4x32_10(static_cast<uint32_t>(i) >> 2, static_cast<uint32_t>(row), 0u, 0u,
+                                                    sa.seed_lo, sa.seed_hi);
+                    x[it].x = perturb(x[it].x, sa.inv_tau, r.w[0]);
+                    x[it].y = perturb(x[it].y, sa.inv_tau, r.w[1]);
+                    x[it].z = perturb(x[it].z, sa.inv_tau, r.w[2]);
+                    x[it].w = perturb(x[it].w, sa.inv_tau, r.w[3]);
+                }
                 if (x[it].x > best) { best = x[it].x; best_i = i; }
                 if (x[it].y > best) { best = x[it].y; best_i = i + 1; }
                 if (x[it].z > best) { best = x[it].z; best_i = i + 2; }
@@ -72,7 +88,12 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_chunks(const float* __r
         }
     } else {
         for (int i = begin + threadIdx.x; i < end; i += kArgmaxThreads) {
-            const float x = base[i];
+            float x = base[i];
+            if constexpr (kSampled) {
+                const Philox4 r = philox4x32_10(static_cast<uint32_t>(i) >> 2, static_cast<uint32_t>(row), 0u, 0u,
+                                                sa.seed_lo, sa.seed_hi);
+                x = perturb(x, sa.inv_tau, r.w[i & 3]);
+            }
             if (x > best) { best = x; best_i = i; }
         }
     }
@@ -172,38 +193,60 @@ extern "C" size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V) {
     return pairs * (sizeof(float) + sizeof(int32_t));
 }
 
-extern "C" int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
-                           int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
-                           int32_t* bonus_token, int32_t* target_argmax, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
+namespace seer {
+
+static int run_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent, int32_t B,
+                      int32_t T, int32_t V, bool sampled, SampleArgs sa, int32_t* accepted_len,
+                      int32_t* accepted_path, int32_t* bonus_token, int32_t* target_token, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
     if (B < 0 || V < 1) return SEER_EINVAL;
     if (T < 1 || T > SEER_MAX_T) return SEER_ESHAPE;
     if (B == 0) return SEER_OK;
-    if (!logits || !draft_tokens || !accepted_len || !accepted_path || !target_argmax) return SEER_EINVAL;
-    if (static_cast<int64_t>(B) * T * seer::accept_num_chunks(V) > 0x7fffffffLL) return SEER_ESHAPE;
+    if (!logits || !draft_tokens || !accepted_len || !accepted_path || !target_token) return SEER_EINVAL;
+    if (static_cast<int64_t>(B) * T * accept_num_chunks(V) > 0x7fffffffLL) return SEER_ESHAPE;
     const size_t need = seer_accept_workspace(B, T, V);
     if (!workspace || workspace_bytes < need) return SEER_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return SEER_EALIGN;
     if (reinterpret_cast<uintptr_t>(logits) % 4 != 0) return SEER_EALIGN;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int n_chunks = seer::accept_num_chunks(V);
+    const int n_chunks = accept_num_chunks(V);
     const size_t pairs = static_cast<size_t>(B) * T * n_chunks;
     float* part_val = static_cast<float*>(workspace);
     int* part_idx = reinterpret_cast<int*>(part_val + pairs);
     const bool vec4 = (V % 4 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0);
     const dim3 grid(static_cast<unsigned>(pairs));
-    if (vec4) {
-        hipLaunchKernelGGL(seer::argmax_chunks<true>, grid, dim3(seer::kArgmaxThreads), 0, stream, logits, V,
-                           n_chunks, part_val, part_idx);
-    } else {
-        hipLaunchKernelGGL(seer::argmax_chunks<false>, grid, dim3(seer::kArgmaxThreads), 0, stream, logits, V,
-                           n_chunks, part_val, part_idx);
-    }
+    const dim3 block(kArgmaxThreads);
+    if (vec4 && sampled) hipLaunchKernelGGL((argmax_chunks<true, true>), grid, block, 0, stream, logits, V, n_chunks, part_val, part_idx, sa);
+    else if (vec4) hipLaunchKernelGGL((argmax_chunks<true, false>), grid, block, 0, stream, logits, V, n_chunks, part_val, part_idx, sa);
+    else if (sampled) hipLaunchKernelGGL((argmax_chunks<false, true>), grid, block, 0, stream, logits, V, n_chunks, part_val, part_idx, sa);
+    else hipLaunchKernelGGL((argmax_chunks<false, false>), grid, block, 0, stream, logits, V, n_chunks, part_val, part_idx, sa);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return static_cast<int>(err);
-    hipLaunchKernelGGL(seer::accept_walk, dim3(B), dim3(seer::kWave), 0, stream, part_val, part_idx, n_chunks,
-                       draft_tokens, tree_parent, T, accepted_len, accepted_path, bonus_token, target_argmax);
+    hipLaunchKernelGGL(accept_walk, dim3(B), dim3(kWave), 0, stream, part_val, part_idx, n_chunks, draft_tokens,
+                       tree_parent, T, accepted_len, accepted_path, bonus_token, target_token);
     err = hipGetLastError();
     return err == hipSuccess ? SEER_OK : static_cast<int>(err);
+}
+
+}  // namespace seer
+
+extern "C" int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+                           int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
+                           int32_t* bonus_token, int32_t* target_argmax, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    return seer::run_accept(logits, draft_tokens, tree_parent, B, T, V, false, seer::SampleArgs{1.f, 0u, 0u},
+                            accepted_len, accepted_path, bonus_token, target_argmax, workspace, workspace_bytes,
+                            hip_stream);
+}
+
+extern "C" int seer_accept_sampled(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+                                   int32_t B, int32_t T, int32_t V, float temperature, uint64_t seed,
+                                   int32_t* accepted_len, int32_t* accepted_path, int32_t* bonus_token,
+                                   int32_t* target_token, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream) {
+    if (!(temperature > 0.f) || temperature > 3.0e38f) return SEER_EINVAL;   // positive and finite
+    const seer::SampleArgs sa{1.0f / temperature, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+    return seer::run_accept(logits, draft_tokens, tree_parent, B, T, V, true, sa, accepted_len, accepted_path,
+                            bonus_token, target_token, workspace, workspace_bytes, hip_stream);
 }

@@ -117,6 +117,40 @@ def test_accept_argument_errors_before_any_launch(lib):
     assert run(B=0) == b.SEER_OK
 
 
+def test_sampled_accept_and_commit_argument_errors_before_any_launch(lib):
+    from paper_2511_14617_amd import binding as b
+    fake = 0x1000
+
+    def sampled(tau=1.0, **kw):
+        a = dict(B=4, T=5, V=1000, ws=0x10000, ws_bytes=1 << 30)
+        a.update(kw)
+        return lib.seer_accept_sampled(fake, fake, None, a["B"], a["T"], a["V"], tau, 7, fake, fake, None, fake,
+                                       a["ws"], a["ws_bytes"], None)
+
+    assert sampled(tau=0.0) == b.SEER_EINVAL
+    assert sampled(tau=-1.0) == b.SEER_EINVAL
+    assert sampled(tau=float("nan")) == b.SEER_EINVAL
+    assert sampled(tau=float("inf")) == b.SEER_EINVAL
+    assert sampled(T=65) == b.SEER_ESHAPE
+    assert sampled(ws=None) == b.SEER_EWORKSPACE
+    assert sampled(B=0) == b.SEER_OK
+
+    def commit(p, k=fake, v=fake, table=fake, n=fake, alen=fake, path=fake, draft=None, bonus=None, em=None,
+               nem=None):
+        return lib.seer_kv_commit(ctypes.byref(p), k, v, table, n, alen, path, draft, bonus, em, nem, None, None)
+
+    assert lib.seer_kv_commit(None, fake, fake, fake, fake, fake, fake, None, None, None, None, None, None) == b.SEER_EINVAL
+    assert commit(_params(T=65)) == b.SEER_ESHAPE
+    assert commit(_params(Dqk=100)) == b.SEER_ESHAPE                    # rows move in 16-byte chunks
+    assert commit(_params(num_pages=0)) == b.SEER_EINVAL
+    assert commit(_params(), v=None) == b.SEER_EINVAL
+    assert commit(_params(), path=None) == b.SEER_EINVAL
+    assert commit(_params(), em=fake) == b.SEER_EINVAL                   # emitted tokens need drafts, bonus and a count
+    assert commit(_params(), k=fake + 2) == b.SEER_EALIGN
+    assert commit(_params(T=64, Dqk=576, Dv=512)) == b.SEER_EUNSUPPORTED  # more than a workgroup holds in registers
+    assert commit(_params(B=0)) == b.SEER_OK
+
+
 def test_product_path_fails_loudly_without_the_library(tmp_path, monkeypatch):
     from paper_2511_14617_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
