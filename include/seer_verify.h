@@ -73,6 +73,12 @@ typedef struct seer_attn_params {
 
 /* flags: run the general kernel even where a tiled one exists (for cross-checks). */
 #define SEER_ATTN_GENERAL_KERNEL 1
+/* flags: cut the KV stream into equal stretches.  By default the library sizes each workgroup's
+ * stretch by that workgroup slot's measured speed in earlier calls ON THE SAME WORKSPACE (a few
+ * hundred bytes of history kept in it; any contents are valid, unusable ones mean equal stretches).
+ * The result is the same up to the rounding order of the partial sums; with this flag the cut, and
+ * therefore the result, does not depend on earlier calls. */
+#define SEER_ATTN_FIXED_SPLIT 2
 
 /* Supported shapes: (Dqk, Dv) in {(64,64), (128,128), (256,256), (192,128),
  * (576,512)} with any page_size >= 1.  Tiled matrix-core kernels exist for

@@ -15,20 +15,37 @@ namespace seer {
 //
 // Balanced ("stream") partitioning: per KV head, the 32-token tiles of all
 // requests are laid end to end, request after request, and that line is cut
-// into W equal stretches of L tiles, one per workgroup.  W x Hkv is chosen to
-// be what the GPU holds at once, so there is a single round of workgroups and
-// every one of them streams the same number of KV bytes, whatever the mix of
-// lengths -- eight 100k-token stragglers and several hundred short requests
-// both fill all 256 CUs.  A stretch that crosses a request boundary yields one
-// partial result per request it touches; request b therefore owns
+// into W stretches, one per workgroup.  W x Hkv is chosen to be what the GPU
+// holds at once, so there is a single round of workgroups and every one of
+// them streams about the same number of KV bytes, whatever the mix of lengths
+// -- eight 100k-token stragglers and several hundred short requests both fill
+// all 256 CUs.  A stretch that crosses a request boundary yields one partial
+// result per request it touches; request b therefore owns
 // n_parts(b) = last_wg(b) - first_wg(b) + 1 consecutive partial slots starting at
 // split_off[b], and the combine kernel merges them.
+//
+// Stretch lengths follow the measured speed of each workgroup slot.  Workgroups
+// that stream the same number of bytes do not finish together: on this part the
+// eight XCDs differ by about 12 % in sustained gather bandwidth, and of two
+// workgroups resident on one CU the one dispatched first is served first.  Both
+// are properties of the workgroup's index (the grid is laid out so that the
+// workgroups with the same stretch index w, one per KV head, share XCD and
+// dispatch round), and stable from call to call.  So every partition workgroup
+// adds its tiles and its duration (constant 100 MHz clock) to two counters of
+// its stretch index in the workspace, and the next call's plan cuts the line in
+// proportion to the smoothed tiles-per-time of each index (clamped to
+// [3/4, 4/3] of the mean).  A workspace that holds no valid history (first use,
+// other W) gives equal stretches; SEER_ATTN_FIXED_SPLIT always does.
 struct PlanHeader {
     uint32_t status;     // bit 0: bad ctx_len somewhere; bit 1: page id out of range
     int32_t n_items;     // number of (request, stretch) pieces = partial slots in use
     int32_t tiles_per_wg;  // L; 0 = one workgroup per request (max_splits == 1)
     int32_t total_tiles;   // tiles per KV head over all requests
+    uint32_t fb_magic;     // kFeedbackMagic once the speed history below the header is meaningful
+    int32_t fb_w;          // W it was recorded for
 };
+constexpr uint32_t kFeedbackMagic = 0x5ee2fb01u;
+constexpr int kMaxWgsPerHead = 1024;   // 256 CUs x 4 resident workgroups, one KV head
 
 struct WorkItem {
     int32_t b;       // request
@@ -46,7 +63,7 @@ struct WorkspaceLayout {
     int max_items;
     int wgs_per_head;    // W (balanced mode) or B (one workgroup per request)
     int max_splits;
-    size_t off_header, off_split, off_tiles, off_first, off_items, off_ml, off_acc, total;
+    size_t off_header, off_split, off_tiles, off_first, off_start, off_reqfirst, off_fb, off_items, off_ml, off_acc, total;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -98,7 +115,11 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
     w.off_split = 256;
     w.off_tiles = align_up(w.off_split + per_b, 256);
     w.off_first = align_up(w.off_tiles + per_b, 256);
-    w.off_items = align_up(w.off_first + sizeof(int32_t) * static_cast<size_t>(w.wgs_per_head), 256);
+    const size_t per_w = sizeof(int32_t) * (static_cast<size_t>(w.wgs_per_head) + 1);
+    w.off_start = align_up(w.off_first + per_w, 256);
+    w.off_reqfirst = align_up(w.off_start + per_w, 256);
+    w.off_fb = align_up(w.off_reqfirst + per_b, 256);             // time[W], tiles[W], smoothed speed[W]
+    w.off_items = align_up(w.off_fb + 3 * per_w, 256);
     w.off_ml = align_up(w.off_items + sizeof(WorkItem) * static_cast<size_t>(w.max_items), 256);
     w.off_acc = align_up(w.off_ml + 2 * sizeof(float) * rows, 256);
     w.total = align_up(w.off_acc + sizeof(float) * rows * p.Dv, 256);
@@ -118,6 +139,12 @@ struct AttnArgs {
     const int32_t* split_off;   // [B+1] first partial slot of each request
     const int32_t* tile_off;    // [B+1] first tile of each request on the per-head tile line
     const int32_t* wg_first;    // [wgs_per_head] request in which each workgroup's stretch starts, -1 = idle
+    const int32_t* wg_start;    // [wgs_per_head + 1] first tile of each stretch on the tile line (balanced mode)
+    const int32_t* req_first;   // [B] first stretch that touches each request (balanced mode)
+    uint32_t* fb_time;          // [wgs_per_head] sum over KV heads of the workgroup's duration, 10 ns ticks
+    uint32_t* fb_tiles;         // [wgs_per_head] sum over KV heads of the tiles it streamed
+    float* fb_speed;            // [wgs_per_head] smoothed tiles per tick (owned by the plan kernel)
+    int32_t fixed_split;        // 1: equal stretches, no history read or written
     const WorkItem* items;
     float* part_ml;             // [max_items][T][Hq][2]  (running max in log2 units, sum)
     float* part_acc;            // [max_items][T][Hq][Dv] unnormalised

@@ -22,22 +22,73 @@ constexpr int kPlanThreads = 256;
 
 struct PlanArgs {
     const int32_t* ctx_len;
-    int B, T, max_ctx, wgs_per_head, max_splits, max_items;
+    int B, T, max_ctx, wgs_per_head, max_splits, max_items, fixed_split;
     PlanHeader* header;
     int32_t* split_off;
     int32_t* tile_off;
     int32_t* wg_first;
+    int32_t* wg_start;
+    int32_t* req_first;
+    uint32_t* fb_time;
+    uint32_t* fb_tiles;
+    float* fb_speed;
     WorkItem* items;
 };
 
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
-    __shared__ int s_scan[kPlanThreads];
-    __shared__ int s_max[kPlanThreads];
-    __shared__ int s_bad;
-    const int tid = threadIdx.x;
-    if (tid == 0) s_bad = 0;
-    for (int w = tid; w < p.wgs_per_head; w += kPlanThreads) p.wg_first[w] = -1;
+// Block-wide primitives for the 256 threads of the plan kernel (4 waves): wave shuffles, then one
+// value per wave through LDS.  s_tmp: at least 2 * (kPlanThreads / kWave) words, reused call after call.
+__device__ __forceinline__ int plan_excl_scan(int v, int* s_tmp, int& total) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
+    }
+    __syncthreads();                     // s_tmp may still be read by the previous call
+    if (lane == kWave - 1) s_tmp[wave] = incl;
     __syncthreads();
+    int base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanThreads / kWave; ++w) {
+        const int x = s_tmp[w];
+        if (w < wave) base += x;
+        sum += x;
+    }
+    total = sum;
+    return base + incl - v;
+}
+__device__ __forceinline__ float plan_sum(float v, float* s_tmp) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, kWave);
+    __syncthreads();
+    if (lane == 0) s_tmp[wave] = v;
+    __syncthreads();
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < kPlanThreads / kWave; ++w) sum += s_tmp[w];
+    return sum;
+}
+__device__ __forceinline__ int plan_max(int v, int* s_tmp) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o, kWave));
+    __syncthreads();
+    if (lane == 0) s_tmp[wave] = v;
+    __syncthreads();
+    int m = s_tmp[0];
+#pragma unroll
+    for (int w = 1; w < kPlanThreads / kWave; ++w) m = max(m, s_tmp[w]);
+    return m;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
+    __shared__ int s_tmp[2 * kPlanThreads / kWave];
+    __shared__ int s_start[kMaxWgsPerHead + 1];
+    const int tid = threadIdx.x;
+    const int W = p.wgs_per_head;
+    for (int w = tid; w < W; w += kPlanThreads) p.wg_first[w] = -1;
 
     // thread `tid` owns a contiguous run of requests
     const int per = (p.B + kPlanThreads - 1) / kPlanThreads;
@@ -49,88 +100,147 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
     };
 
     // 1. tile line: exclusive prefix of tiles per request, and the longest request
-    int cnt = 0, mx = 0;
+    int cnt = 0, mx = 0, bad = 0;
     for (int b = b0; b < b1; ++b) {
         const int n = p.ctx_len[b];
-        if (n < p.T || n > p.max_ctx) s_bad = 1;
+        if (n < p.T || n > p.max_ctx) bad = 1;
         const int t = tiles_of(b);
         cnt += t;
         mx = max(mx, t);
     }
-    s_scan[tid] = cnt;
-    s_max[tid] = mx;
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0, m = 0;
-        for (int i = 0; i < kPlanThreads; ++i) {
-            const int c = s_scan[i];
-            s_scan[i] = run;
-            run += c;
-            m = max(m, s_max[i]);
-        }
-        s_max[0] = m;
-        p.tile_off[p.B] = run;
-    }
-    __syncthreads();
-    const int total = p.tile_off[p.B];
-    const int longest = s_max[0];
+    int total = 0;
+    const int my_tile_off = plan_excl_scan(cnt, s_tmp, total);
+    const int longest = plan_max(mx, s_tmp);
+    bad = plan_max(bad, s_tmp);
     {
-        int off = s_scan[tid];
+        int off = my_tile_off;
         for (int b = b0; b < b1; ++b) {
             p.tile_off[b] = off;
             off += tiles_of(b);
         }
+        if (tid == 0) p.tile_off[p.B] = total;
     }
-    __syncthreads();
 
-    // 2. stretch length L (tiles per workgroup); 0 = one workgroup per request
+    // 2. the stretches (balanced mode; L = 0 means one workgroup per request)
     int L = 0;
     if (p.max_splits > 1) {
-        L = (total + p.wgs_per_head - 1) / p.wgs_per_head;
-        L = max(L, kMinTilesPerWg);
-        // a request of t tiles touches at most ceil(t / L) + 1 stretches
-        L = max(L, (longest + p.max_splits - 2) / (p.max_splits - 1));
+        L = max((total + W - 1) / W, 1);
+        // a request of t tiles touches at most ceil(t / Lmin) + 1 stretches, which must fit max_splits
+        const int Lmin = max(kMinTilesPerWg, (longest + p.max_splits - 2) / (p.max_splits - 1));
+        // relative speed of each stretch index from the history in the workspace; thread t owns the
+        // stretch indices [t * per_w, t * per_w + per_w)
+        constexpr int kPerW = kMaxWgsPerHead / kPlanThreads;
+        const int per_w = (W + kPlanThreads - 1) / kPlanThreads;
+        const int w0 = min(W, tid * per_w);
+        const bool have = !p.fixed_split && p.header->fb_magic == kFeedbackMagic && p.header->fb_w == W;
+        float speed[kPerW];
+        float sum = 0.f, known = 0.f;
+#pragma unroll
+        for (int i = 0; i < kPerW; ++i) {
+            const int w = w0 + i;
+            speed[i] = 0.f;
+            if (i < per_w && w < W) {
+                float est = have ? p.fb_speed[w] : 0.f;
+                const uint32_t ticks = have ? p.fb_time[w] : 0u, tiles = have ? p.fb_tiles[w] : 0u;
+                if (ticks > 0u && tiles > 0u) {
+                    const float meas = static_cast<float>(tiles) / static_cast<float>(ticks);
+                    est = est > 0.f ? 0.5f * est + 0.5f * meas : meas;
+                }
+                if (!(est > 0.f) || !(est < 1e30f)) est = 0.f;     // unknown (also whatever a stale workspace held)
+                if (!p.fixed_split) {
+                    p.fb_speed[w] = est;
+                    p.fb_time[w] = 0u;
+                    p.fb_tiles[w] = 0u;
+                }
+                speed[i] = est;
+                if (est > 0.f) {
+                    sum += est;
+                    known += 1.f;
+                }
+            }
+        }
+        sum = plan_sum(sum, reinterpret_cast<float*>(s_tmp));
+        known = plan_sum(known, reinterpret_cast<float*>(s_tmp));
+        const float mean = known > 0.f ? sum / known : 1.f;
+        float rsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < kPerW; ++i) {
+            if (i < per_w && w0 + i < W) {
+                const float r = speed[i] > 0.f ? speed[i] / mean : 1.f;
+                speed[i] = fminf(fmaxf(r, 0.75f), 4.f / 3.f);
+                rsum += speed[i];
+            }
+        }
+        const float R = plan_sum(rsum, reinterpret_cast<float*>(s_tmp));
+        int want[kPerW], mine = 0;
+#pragma unroll
+        for (int i = 0; i < kPerW; ++i) {
+            want[i] = 0;
+            if (i < per_w && w0 + i < W)
+                want[i] = max(Lmin, static_cast<int>(ceilf(static_cast<float>(total) * speed[i] / R)));
+            mine += want[i];
+        }
+        int all = 0;
+        int start = plan_excl_scan(mine, s_tmp, all);      // (the ceilings make the stretches reach the end)
+#pragma unroll
+        for (int i = 0; i < kPerW; ++i) {
+            if (i < per_w && w0 + i < W) {
+                s_start[w0 + i] = min(total, start);
+                start += want[i];
+            }
+        }
+        if (tid == 0) s_start[W] = total;
+        __syncthreads();
+        for (int w = tid; w <= W; w += kPlanThreads) p.wg_start[w] = s_start[w];
     }
+    // stretch that holds tile x (x < total): the last one that starts at or before it
+    auto stretch_of = [&](int x) -> int {
+        int lo = 0, hi = W - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_start[mid] <= x) lo = mid; else hi = mid - 1;
+        }
+        return lo;
+    };
 
     // 3. pieces per request -> first partial slot of each request
-    auto first_wg = [&](int b) -> int { return L ? p.tile_off[b] / L : b; };
-    auto parts_of = [&](int b) -> int {
-        const int lo = p.tile_off[b], hi = p.tile_off[b + 1];
-        if (hi == lo) return 0;
-        return L ? (hi - 1) / L - lo / L + 1 : 1;
-    };
     cnt = 0;
-    for (int b = b0; b < b1; ++b) cnt += parts_of(b);
-    __syncthreads();
-    s_scan[tid] = cnt;
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int i = 0; i < kPlanThreads; ++i) {
-            const int c = s_scan[i];
-            s_scan[i] = run;
-            run += c;
+    {
+        int lo = my_tile_off;
+        for (int b = b0; b < b1; ++b) {
+            const int hi = lo + tiles_of(b);
+            if (hi > lo) cnt += L ? stretch_of(hi - 1) - stretch_of(lo) + 1 : 1;
+            lo = hi;
         }
-        p.header->status = s_bad ? 1u : 0u;
-        p.header->n_items = min(run, p.max_items);
+    }
+    int n_pieces = 0;
+    int slot = plan_excl_scan(cnt, s_tmp, n_pieces);
+    if (tid == 0) {
+        p.header->status = bad ? 1u : 0u;
+        p.header->n_items = min(n_pieces, p.max_items);
         p.header->tiles_per_wg = L;
         p.header->total_tiles = total;
-        p.split_off[p.B] = run;
+        if (!p.fixed_split) {
+            p.header->fb_magic = kFeedbackMagic;
+            p.header->fb_w = W;
+        }
+        p.split_off[p.B] = n_pieces;
     }
-    __syncthreads();
 
     // 4. piece table and the request each stretch starts in
-    int slot = s_scan[tid];
+    int lo = my_tile_off;
     for (int b = b0; b < b1; ++b) {
+        const int hi = lo + tiles_of(b);
         p.split_off[b] = slot;
-        const int np = parts_of(b);
-        const int lo = p.tile_off[b], hi = p.tile_off[b + 1];
         const int n = p.ctx_len[b];
-        const int w0 = first_wg(b);
+        const int w_first = hi > lo ? (L ? stretch_of(lo) : b) : 0;
+        const int np = hi > lo ? (L ? stretch_of(hi - 1) - w_first + 1 : 1) : 0;
+        p.req_first[b] = w_first;
         for (int s = 0; s < np; ++s) {
-            const int w = w0 + s;
-            const int t_begin = L ? max(lo, w * L) : lo;
-            const int t_end = L ? min(hi, (w + 1) * L) : hi;
+            const int w = w_first + s;
+            const int w_begin = L ? s_start[w] : lo, w_end = L ? s_start[w + 1] : hi;
+            const int t_begin = max(lo, w_begin);
+            const int t_end = min(hi, w_end);
             if (slot + s < p.max_items) {
                 WorkItem it;
                 it.b = b;
@@ -139,9 +249,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
                 it.split = s;
                 p.items[slot + s] = it;
             }
-            if (t_begin == (L ? w * L : lo) && w < p.wgs_per_head) p.wg_first[w] = b;   // stretch w starts here
+            if (t_begin == w_begin && w < W) p.wg_first[w] = b;   // stretch w starts here
         }
         slot += np;
+        lo = hi;
     }
 }
 
@@ -159,6 +270,12 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
     p.split_off = const_cast<int32_t*>(a.split_off);
     p.tile_off = const_cast<int32_t*>(a.tile_off);
     p.wg_first = const_cast<int32_t*>(a.wg_first);
+    p.wg_start = const_cast<int32_t*>(a.wg_start);
+    p.req_first = const_cast<int32_t*>(a.req_first);
+    p.fb_time = a.fb_time;
+    p.fb_tiles = a.fb_tiles;
+    p.fb_speed = a.fb_speed;
+    p.fixed_split = a.fixed_split;
     p.items = const_cast<WorkItem*>(a.items);
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);
     return hipGetLastError();
@@ -370,7 +487,7 @@ int validate_params(const seer_attn_params* p) {
     if (p->B < 0 || p->num_pages < 1 || p->max_pages_per_seq < 1 || p->page_size < 1) return SEER_EINVAL;
     if (p->T < 1 || p->T > SEER_MAX_T || p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SEER_ESHAPE;
     if (p->max_splits < 0 || p->max_splits > 256) return SEER_ESHAPE;
-    if (p->flags & ~SEER_ATTN_GENERAL_KERNEL) return SEER_EINVAL;
+    if (p->flags & ~(SEER_ATTN_GENERAL_KERNEL | SEER_ATTN_FIXED_SPLIT)) return SEER_EINVAL;
     if (p->Hq > 65535 || p->T * (int64_t)p->Hq * p->B > 0x7fffffffLL) return SEER_ESHAPE;
     if (!(p->scale > 0.f) || p->scale > 3.0e38f) return SEER_EINVAL;   // positive and finite
     if (!seer::general_supports(p->Dqk, p->Dv)) return SEER_EUNSUPPORTED;
@@ -419,6 +536,12 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.split_off = reinterpret_cast<const int32_t*>(ws + w.off_split);
     a.tile_off = reinterpret_cast<const int32_t*>(ws + w.off_tiles);
     a.wg_first = reinterpret_cast<const int32_t*>(ws + w.off_first);
+    a.wg_start = reinterpret_cast<const int32_t*>(ws + w.off_start);
+    a.req_first = reinterpret_cast<const int32_t*>(ws + w.off_reqfirst);
+    a.fb_time = reinterpret_cast<uint32_t*>(ws + w.off_fb);
+    a.fb_tiles = a.fb_time + (w.wgs_per_head + 1);
+    a.fb_speed = reinterpret_cast<float*>(a.fb_tiles + (w.wgs_per_head + 1));
+    a.fixed_split = (p->flags & SEER_ATTN_FIXED_SPLIT) ? 1 : 0;
     a.items = reinterpret_cast<const seer::WorkItem*>(ws + w.off_items);
     a.part_ml = reinterpret_cast<float*>(ws + w.off_ml);
     a.part_acc = reinterpret_cast<float*>(ws + w.off_acc);

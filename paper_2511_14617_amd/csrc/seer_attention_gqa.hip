@@ -381,7 +381,13 @@ void attn_gqa128_kernel(AttnArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * NSLOT * kKBytes];   // K ring, then V ring
     constexpr int kVRing = NSLOT * kKBytes;
 
-    const int kvh = blockIdx.y;
+    // Workgroup ids are dealt round-robin to the 8 XCDs and dispatched in id order.  The grid is laid
+    // out in groups of 8 stretches x Hkv heads so that the Hkv workgroups with the same stretch index
+    // share XCD (id % 8) and dispatch round: the plan's per-index speed history relies on that.
+    const int grp = blockIdx.x / (8 * a.Hkv), rem = blockIdx.x - grp * (8 * a.Hkv);
+    const int kvh = rem >> 3;
+    const int wg = grp * 8 + (rem & 7);
+    if (wg >= a.wgs_per_head) return;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -390,12 +396,13 @@ void attn_gqa128_kernel(AttnArgs a) {
     const int l16 = lane >> 4;
     const int p16 = lane & 15;
 
-    const int wg = blockIdx.x;
     const int L = uniform_load(&a.header->tiles_per_wg);
     int b = uniform_load(a.wg_first + wg);
     if (b < 0) return;
-    int g = L ? wg * L : uniform_load(a.tile_off + b);
-    const int g_end = L ? min((wg + 1) * L, uniform_load(&a.header->total_tiles)) : uniform_load(a.tile_off + b + 1);
+    int g = uniform_load(L ? a.wg_start + wg : a.tile_off + b);
+    const int g_end = uniform_load(L ? a.wg_start + wg + 1 : a.tile_off + b + 1);
+    const int g_first = g;
+    const uint64_t clock_begin = __builtin_amdgcn_s_memrealtime();
     bool bad_page = false;
 
     const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
@@ -418,7 +425,7 @@ void attn_gqa128_kernel(AttnArgs a) {
   for (; g < g_end; ++b) {
     const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
     if (t_hi == t_lo) continue;
-    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - t_lo / L : 0);
+    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - uniform_load(a.req_first + b) : 0);
     const int n = uniform_load(a.ctx_len + b);
     const int tok_begin = (g - t_lo) * kTile;
     const int tok_end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
@@ -685,6 +692,12 @@ void attn_gqa128_kernel(AttnArgs a) {
     }
   }  // pieces of the stretch
     if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
+    // speed history for the next call's plan: tiles streamed and time taken, by stretch index
+    if (L && !a.fixed_split && tid == 0) {
+        const uint64_t ticks = __builtin_amdgcn_s_memrealtime() - clock_begin;
+        atomicAdd(a.fb_time + wg, static_cast<uint32_t>(ticks > 0xffffffu ? 0xffffffu : ticks));
+        atomicAdd(a.fb_tiles + wg, static_cast<uint32_t>(g_end - g_first));
+    }
 }
 
 bool gqa128_supports(const AttnArgs& a) {
@@ -695,7 +708,7 @@ bool gqa128_supports(const AttnArgs& a) {
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int R = a.G * a.T;
     const int nw = (R + 31) / 32;
-    const dim3 grid(a.wgs_per_head, a.Hkv);
+    const dim3 grid(static_cast<unsigned>((a.wgs_per_head + 7) / 8) * 8u * static_cast<unsigned>(a.Hkv));
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                                     \
     case NW_:                                                                                                  \

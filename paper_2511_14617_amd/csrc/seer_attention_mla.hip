@@ -281,8 +281,8 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     const int L = uniform_load(&a.header->tiles_per_wg);
     int b = uniform_load(a.wg_first + wg);
     if (b < 0) return;
-    int g = L ? wg * L : uniform_load(a.tile_off + b);
-    const int g_end = L ? min((wg + 1) * L, uniform_load(&a.header->total_tiles)) : uniform_load(a.tile_off + b + 1);
+    int g = uniform_load(L ? a.wg_start + wg : a.tile_off + b);
+    const int g_end = uniform_load(L ? a.wg_start + wg + 1 : a.tile_off + b + 1);
     bool bad_page = false;
 
     const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
@@ -307,7 +307,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
   for (; g < g_end; ++b) {
     const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
     if (t_hi == t_lo) continue;
-    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - t_lo / L : 0);
+    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - uniform_load(a.req_first + b) : 0);
     const int n = uniform_load(a.ctx_len + b);
     const int tok_begin = (g - t_lo) * kTile;
     const int tok_end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
