@@ -37,21 +37,22 @@ struct PlanArgs {
 
 // Block-wide primitives for the 256 threads of the plan kernel (4 waves): wave shuffles, then one
 // value per wave through LDS.  s_tmp: at least 2 * (kPlanThreads / kWave) words, reused call after call.
-__device__ __forceinline__ int plan_excl_scan(int v, int* s_tmp, int& total) {
+template <typename T>
+__device__ __forceinline__ T plan_excl_scan(T v, T* s_tmp, T& total) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    int incl = v;
+    T incl = v;
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) {
-        const int up = __shfl_up(incl, o, kWave);
+        const T up = __shfl_up(incl, o, kWave);
         if (lane >= o) incl += up;
     }
     __syncthreads();                     // s_tmp may still be read by the previous call
     if (lane == kWave - 1) s_tmp[wave] = incl;
     __syncthreads();
-    int base = 0, sum = 0;
+    T base = 0, sum = 0;
 #pragma unroll
     for (int w = 0; w < kPlanThreads / kWave; ++w) {
-        const int x = s_tmp[w];
+        const T x = s_tmp[w];
         if (w < wave) base += x;
         sum += x;
     }
@@ -162,31 +163,30 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         sum = plan_sum(sum, reinterpret_cast<float*>(s_tmp));
         known = plan_sum(known, reinterpret_cast<float*>(s_tmp));
         const float mean = known > 0.f ? sum / known : 1.f;
+        // Stretch w begins at the tile nearest to total * (r_0 + .. + r_{w-1}) / R.  When the line is too
+        // short for that to keep every stretch at Lmin tiles or more, cut it into equal stretches of
+        // max(Lmin, ceil(total / W)) tiles instead (the last ones are then short or empty).
+        const bool weighted = static_cast<long long>(total) >= 2ll * Lmin * W;
         float rsum = 0.f;
 #pragma unroll
         for (int i = 0; i < kPerW; ++i) {
             if (i < per_w && w0 + i < W) {
-                const float r = speed[i] > 0.f ? speed[i] / mean : 1.f;
+                const float r = (weighted && speed[i] > 0.f) ? speed[i] / mean : 1.f;
                 speed[i] = fminf(fmaxf(r, 0.75f), 4.f / 3.f);
                 rsum += speed[i];
             }
         }
-        const float R = plan_sum(rsum, reinterpret_cast<float*>(s_tmp));
-        int want[kPerW], mine = 0;
-#pragma unroll
-        for (int i = 0; i < kPerW; ++i) {
-            want[i] = 0;
-            if (i < per_w && w0 + i < W)
-                want[i] = max(Lmin, static_cast<int>(ceilf(static_cast<float>(total) * speed[i] / R)));
-            mine += want[i];
-        }
-        int all = 0;
-        int start = plan_excl_scan(mine, s_tmp, all);      // (the ceilings make the stretches reach the end)
+        float R = 0.f;
+        float before = plan_excl_scan(rsum, reinterpret_cast<float*>(s_tmp), R);
+        const int L_equal = max(Lmin, L);
 #pragma unroll
         for (int i = 0; i < kPerW; ++i) {
             if (i < per_w && w0 + i < W) {
-                s_start[w0 + i] = min(total, start);
-                start += want[i];
+                const int w = w0 + i;
+                const long long cut = weighted ? static_cast<long long>(static_cast<double>(total) * before / R + 0.5)
+                                               : static_cast<long long>(w) * L_equal;
+                s_start[w] = static_cast<int>(cut < total ? cut : total);
+                before += speed[i];
             }
         }
         if (tid == 0) s_start[W] = total;
