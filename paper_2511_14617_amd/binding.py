@@ -31,6 +31,7 @@ class SeerAttnParams(ctypes.Structure):
                 ("scale", ctypes.c_float)]
 
 SEER_ATTN_GENERAL_KERNEL = 1
+SEER_ATTN_FIXED_SPLIT = 2
 
 
 class SeerError(RuntimeError):
