@@ -180,6 +180,17 @@ def main() -> int:
                                                          workspace=ws_att))
     acc_ms = 0.0 if args.attention_only else timed(
         lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out))
+    # gather-read ceiling: the same call with the arithmetic left out of the tiled kernel (D = 128 shapes)
+    ceiling_ms = None
+    if not cfg.shared_latent and cfg.Dqk == 128 and cfg.page_size == 16:
+        ev2 = HipEvents(10)
+        for i in range(10):
+            binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
+                                          d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att,
+                                          flags=binding.SEER_ATTN_STREAM_ONLY, events=ev2.pairs[i])
+        torch.cuda.synchronize()
+        ceiling_ms = float(np.mean(ev2.elapsed_ms()[2:]))
+        ev2.close()
     # the calls around the step (not part of `value`): acceptance under sampling, and the commit of the
     # accepted path (on a copy of the lengths, so that every repetition moves the same rows)
     sampled_ms = commit_ms = None
@@ -220,6 +231,11 @@ def main() -> int:
         roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "algorithmic_bytes": ab,
                     "kernel_ms_avg": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms))}
+        if ceiling_ms:
+            # what the memory system allows for this access pattern and launch shape (arithmetic left out)
+            ceil_gbps = ab["total"] / (ceiling_ms * 1e-3) / 1e9
+            roofline["gather_read_ceiling"] = {"GBps": ceil_gbps, "kernel_ms": ceiling_ms,
+                                               "achieved_over_ceiling": achieved / ceil_gbps}
     line = {
         "metric": METRIC,
         "value": tokens / (ms_per_step * 1e-3),

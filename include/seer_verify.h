@@ -79,6 +79,11 @@ typedef struct seer_attn_params {
  * The result is the same up to the rounding order of the partial sums; with this flag the cut, and
  * therefore the result, does not depend on earlier calls. */
 #define SEER_ATTN_FIXED_SPLIT 2
+/* flags: measurement aid.  The tiled D = 128 kernel runs its whole load path (plan, page lookups,
+ * loads into LDS, waits, partial-result writes) without the arithmetic; out is written as zeros.
+ * The time of such a call is the gather-read ceiling of the memory system for this workload and
+ * launch shape.  Ignored by the other kernels. */
+#define SEER_ATTN_STREAM_ONLY 4
 
 /* Supported shapes: (Dqk, Dv) in {(64,64), (128,128), (256,256), (192,128),
  * (576,512)} with any page_size >= 1.  Tiled matrix-core kernels exist for

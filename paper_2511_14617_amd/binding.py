@@ -32,6 +32,7 @@ class SeerAttnParams(ctypes.Structure):
 
 SEER_ATTN_GENERAL_KERNEL = 1
 SEER_ATTN_FIXED_SPLIT = 2
+SEER_ATTN_STREAM_ONLY = 4
 
 
 class SeerError(RuntimeError):

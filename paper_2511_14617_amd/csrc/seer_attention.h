@@ -145,6 +145,7 @@ struct AttnArgs {
     uint32_t* fb_tiles;         // [wgs_per_head] sum over KV heads of the tiles it streamed
     float* fb_speed;            // [wgs_per_head] smoothed tiles per tick (owned by the plan kernel)
     int32_t fixed_split;        // 1: equal stretches, no history read or written
+    int32_t stream_only;        // 1: the tiled D = 128 kernel only streams its tiles (diagnostic)
     const WorkItem* items;
     float* part_ml;             // [max_items][T][Hq][2]  (running max in log2 units, sum)
     float* part_acc;            // [max_items][T][Hq][Dv] unnormalised

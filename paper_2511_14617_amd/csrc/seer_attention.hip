@@ -487,7 +487,7 @@ int validate_params(const seer_attn_params* p) {
     if (p->B < 0 || p->num_pages < 1 || p->max_pages_per_seq < 1 || p->page_size < 1) return SEER_EINVAL;
     if (p->T < 1 || p->T > SEER_MAX_T || p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SEER_ESHAPE;
     if (p->max_splits < 0 || p->max_splits > 256) return SEER_ESHAPE;
-    if (p->flags & ~(SEER_ATTN_GENERAL_KERNEL | SEER_ATTN_FIXED_SPLIT)) return SEER_EINVAL;
+    if (p->flags & ~(SEER_ATTN_GENERAL_KERNEL | SEER_ATTN_FIXED_SPLIT | SEER_ATTN_STREAM_ONLY)) return SEER_EINVAL;
     if (p->Hq > 65535 || p->T * (int64_t)p->Hq * p->B > 0x7fffffffLL) return SEER_ESHAPE;
     if (!(p->scale > 0.f) || p->scale > 3.0e38f) return SEER_EINVAL;   // positive and finite
     if (!seer::general_supports(p->Dqk, p->Dv)) return SEER_EUNSUPPORTED;
@@ -542,6 +542,7 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.fb_tiles = a.fb_time + (w.wgs_per_head + 1);
     a.fb_speed = reinterpret_cast<float*>(a.fb_tiles + (w.wgs_per_head + 1));
     a.fixed_split = (p->flags & SEER_ATTN_FIXED_SPLIT) ? 1 : 0;
+    a.stream_only = (p->flags & SEER_ATTN_STREAM_ONLY) ? 1 : 0;
     a.items = reinterpret_cast<const seer::WorkItem*>(ws + w.off_items);
     a.part_ml = reinterpret_cast<float*>(ws + w.off_ml);
     a.part_acc = reinterpret_cast<float*>(ws + w.off_acc);

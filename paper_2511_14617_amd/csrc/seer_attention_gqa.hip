@@ -368,7 +368,11 @@ __device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, 
     (f(std::integral_constant<int, I>{}), ...);
 }
 
-template <int NW, int D>
+// STREAM: diagnostic variant that keeps the whole load path (plan, page lookups, direct-to-LDS loads,
+// waits, barriers, partial-result writes) and leaves out the arithmetic.  Its time is what the memory
+// system allows for exactly this access pattern and launch shape: the ceiling the kernel's
+// bytes-per-second should be read against.  It writes "saw nothing" partials, so the output is zero.
+template <int NW, int D, bool STREAM>
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
 void attn_gqa128_kernel(AttnArgs a) {
     constexpr int NT = NW * kWave;
@@ -563,20 +567,23 @@ void attn_gqa128_kernel(AttnArgs a) {
     wait_step(0);
     bare_barrier();
     issue_step(0);
-    pipe_step<true, false, false>(lds, k_off(0), 0, k_rd, v_rd, qreg, s_b, s_a, pk_b, pk_a, acc, m_run, l_run, alpha,
-                                  a.scale_log2, 0u);
+    if constexpr (!STREAM)
+        pipe_step<true, false, false>(lds, k_off(0), 0, k_rd, v_rd, qreg, s_b, s_a, pk_b, pk_a, acc, m_run, l_run, alpha,
+                                      a.scale_log2, 0u);
     // step 1: softmax of tile 0 (s_a -> pk_a), scores of tile 1 -> s_b
     wait_step(1);
     bare_barrier();
     issue_step(1);
     {
         const uint32_t vis = vis_of(0);
-        if (n_tiles > 1)
-            pipe_step<true, true, false>(lds, k_off(1), 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run,
-                                         alpha, a.scale_log2, vis);
-        else
-            pipe_step<false, true, false>(lds, 0, 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run, alpha,
-                                          a.scale_log2, vis);
+        if constexpr (!STREAM) {
+            if (n_tiles > 1)
+                pipe_step<true, true, false>(lds, k_off(1), 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run,
+                                             l_run, alpha, a.scale_log2, vis);
+            else
+                pipe_step<false, true, false>(lds, 0, 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run,
+                                              alpha, a.scale_log2, vis);
+        }
     }
     // steps 2 .. n_tiles - 1: P.V of tile u-2 (pk_a), softmax of tile u-1 (s_b -> pk_b), scores of tile u -> s_a,
     // after which the two register sets have swapped roles.  Tiles are masked from some tile on
@@ -586,10 +593,16 @@ void attn_gqa128_kernel(AttnArgs a) {
                          uint32_t (&pk_sm)[8]) __attribute__((always_inline)) {
         wait_step(u);
         bare_barrier();                        // all waves: loads of step u - D landed, step u - 1 computed
-        fused_step<decltype(masked)::value, 0, 0>(
-            k_off(u), v_off(u - 2), k_rd, v_rd, qreg, s_sm, s_qk, pk_pv, pk_sm, acc, m_run, l_run, alpha, a.scale_log2,
-            decltype(masked)::value ? vis_of(u - 1) : 0u, [&]() __attribute__((always_inline)) { issue_k(u); },
-            [&]() __attribute__((always_inline)) { issue_v(u); });
+        if constexpr (STREAM) {
+            issue_k(u);
+            issue_v(u);
+        } else {
+            fused_step<decltype(masked)::value, 0, 0>(
+                k_off(u), v_off(u - 2), k_rd, v_rd, qreg, s_sm, s_qk, pk_pv, pk_sm, acc, m_run, l_run, alpha,
+                a.scale_log2, decltype(masked)::value ? vis_of(u - 1) : 0u,
+                [&]() __attribute__((always_inline)) { issue_k(u); },
+                [&]() __attribute__((always_inline)) { issue_v(u); });
+        }
     };
     auto swap_roles = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -618,7 +631,10 @@ void attn_gqa128_kernel(AttnArgs a) {
                 issue_v_at(kVIssueSlot * kKBytes);
                 shift_pages();
             };
-            if constexpr (I % 2 == 0)
+            if constexpr (STREAM) {
+                ik();
+                iv();
+            } else if constexpr (I % 2 == 0)
                 fused_step<false, kReadSlot * kKBytes, kVRing + kVReadSlot * kKBytes>(
                     0, 0, k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run, l_run, alpha, a.scale_log2, 0u, ik, iv);
             else
@@ -649,8 +665,9 @@ void attn_gqa128_kernel(AttnArgs a) {
         wait_step(u);
         bare_barrier();
         issue_step(u);
-        pipe_step<false, true, true>(lds, 0, v_off(u - 2), k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run, l_run,
-                                     alpha, a.scale_log2, vis_of(u - 1));
+        if constexpr (!STREAM)
+            pipe_step<false, true, true>(lds, 0, v_off(u - 2), k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run, l_run,
+                                         alpha, a.scale_log2, vis_of(u - 1));
 #pragma unroll
         for (int i = 0; i < 8; ++i) pk_a[i] = pk_b[i];
     }
@@ -669,8 +686,9 @@ void attn_gqa128_kernel(AttnArgs a) {
             __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the clears are done
             bare_barrier();
         }
-        pipe_step<false, false, true>(lds, 0, v_off(n_tiles - 1), k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run,
-                                      l_run, alpha, a.scale_log2, 0u);
+        if constexpr (!STREAM)
+            pipe_step<false, false, true>(lds, 0, v_off(n_tiles - 1), k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run,
+                                          l_run, alpha, a.scale_log2, 0u);
     }
 
     // ---- partial result: (reference exponent, sum, unnormalised O) per row ------------
@@ -712,8 +730,12 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                                     \
     case NW_:                                                                                                  \
-        hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_)>), grid, dim3(NW_ * kWave), 0,    \
-                           stream, a);                                                                         \
+        if (a.stream_only)                                                                                     \
+            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), true>), grid, dim3(NW_ * kWave), 0,   \
+                               stream, a);                                                                     \
+        else                                                                                                   \
+            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), false>), grid, dim3(NW_ * kWave), 0,  \
+                               stream, a);                                                                     \
         break;
         SEER_GQA_CASE(1)
         SEER_GQA_CASE(2)

@@ -50,6 +50,12 @@ CASES = {
     "rows168_G8_T21": (W.CONFIGS[2].scaled(B=3, group_size=3, Hq=16, Hkv=2, T=21, ctx=("uniform", 300, 1500)), {}),
     "rows224_G8_T28": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=16, Hkv=2, T=28, ctx=("uniform", 200, 1200)), {}),
     "rows256_G8_T32": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=8, Hkv=1, T=32, ctx=("uniform", 200, 1200)), {}),
+    # one GPU's share of a 72B-class model under 8-way tensor parallelism (Section 4.1: 64 query / 8 KV
+    # heads split over 8 GPUs -> Hq = 8, Hkv = 1, G = 8), groups of 16 requests, gamma = 8 and a 4 x 8 tree
+    "tp8_share_72b_chain": (W.CONFIGS[2].scaled(B=16, group_size=16, Hq=8, Hkv=1, T=9, ctx=("uniform", 200, 2500),
+                                               shared_prefix=256), {}),
+    "tp8_share_72b_tree": (W.CONFIGS[5].scaled(B=16, group_size=16, Hq=8, Hkv=1, ctx=("uniform", 100, 1500),
+                                              shared_prefix=256), {"dedup_fraction": 0.3}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
     "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
                                            ctx=("uniform", 50, 900)), {}),
@@ -176,3 +182,11 @@ def test_bad_ctx_len_is_flagged_not_faulted():
     ref_abs = _oracle_abs(inp)
     assert_attention_close(out[0:1], ref[0:1], "valid request beside bad ones", hardened=True, ref_abs=ref_abs[0:1])
     assert_attention_close(out[3:4], ref[3:4], "valid request beside bad ones", hardened=True, ref_abs=ref_abs[3:4])
+
+
+def test_stream_only_diagnostic_runs_the_load_path_and_writes_zeros():
+    from paper_2511_14617_amd import binding
+    cfg, kw = CASES["chain_T9_multi_split"]
+    inp = W.make_attention_inputs(cfg, **kw)
+    out = _gpu(inp, flags=binding.SEER_ATTN_STREAM_ONLY)
+    assert float(out.float().abs().max()) == 0.0
