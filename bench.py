@@ -100,6 +100,58 @@ def cpu_baseline(att, acc, row_token_budget: float = 4.0e8) -> dict:
                           cfg.Hq, tokens, t1 - t0, t2 - t1)}
 
 
+def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
+    """T(B, gamma) of the verify step on this GPU for the 8B-class shape (config 2: 32/8 heads, D = 128,
+    lognormal contexts), B = 1 .. 256, gamma = 0 .. 8, and what Algorithm 1 of the paper makes of it.
+    One KV pool for 256 requests is generated once; batch size B uses its first B requests; queries and
+    logits are random device tensors (timing only, no parity here)."""
+    base = W.CONFIGS[2]
+    gamma_max = 8
+    cfg = base.scaled(B=256, group_size=8, T=gamma_max + 1)
+    att = W.make_attention_inputs(cfg)
+    d = attention_device_inputs(att)
+    dev = d["q"].device
+    batches = [1, 4, 16, 64, 128, 256]
+    table = {}
+    for B in batches:
+        row = []
+        for gamma in range(gamma_max + 1):
+            T = gamma + 1
+            q = torch.randn((B, T, cfg.Hq, cfg.Dqk), device=dev).to(torch.bfloat16)
+            logits = torch.randn((B, T, cfg.V), device=dev)
+            draft = torch.zeros((B, T), dtype=torch.int32, device=dev)
+            # the pool's contexts count 9 verify slots; shorten by the slots this gamma does not use
+            n = (d["ctx_len"][:B] - (gamma_max + 1 - T)).contiguous()
+            bt = d["block_table"][:B].contiguous()
+            p = binding.attn_params(q, d["k_pages"], d["v_pages"], bt, att.scale)
+            ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device=dev)
+            ws2 = torch.empty(max(16, binding.seer_accept_workspace(B, T, cfg.V)), dtype=torch.uint8, device=dev)
+
+            def step():
+                binding.seer_verify_attention(q, d["k_pages"], d["v_pages"], bt, n, None, att.scale, workspace=ws)
+                binding.seer_accept(logits, draft, None, workspace=ws2)
+            for _ in range(5):
+                step()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(20):
+                step()
+            b.record()
+            torch.cuda.synchronize()
+            row.append(a.elapsed_time(b) / 20)
+        table[B] = row
+    beta = [0.85 ** k for k in range(1, gamma_max + 2)]          # acceptance probability by draft position
+    decisions = {}
+    for B in batches:
+        B_h = max(1, B // 4)
+        gh, gl, gs = binding.seer_mba_draft_lengths(B_h, B - B_h, beta, gamma_max, 2.0, table[B])
+        decisions[B] = {"B_h": B_h, "B_l": B - B_h, "gamma_star": gs, "gamma_h": gh, "gamma_l": gl}
+    print(json.dumps({"what": "verify step time (ms) of one layer-call, attention + accept, config-2 shape; "
+                              "row = batch size, column = gamma 0..8", "step_time_ms": table,
+                      "beta": beta, "lambda": 2.0, "policy": decisions}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +165,10 @@ def main() -> int:
                          "kernel of known size against which rocprofv3 FETCH_SIZE / WRITE_SIZE are scaled")
     ap.add_argument("--ctx-scale", type=float, default=1.0,
                     help="experiment aid: scale every context-length bound of the workload (not the headline run)")
+    ap.add_argument("--sweep-step-time", action="store_true",
+                    help="instead of the benchmark: measure the verify step (attention + accept) of the config-2 "
+                         "model shape over batch sizes and draft lengths, the T(B, gamma) table that the "
+                         "draft-length policy consumes, and print it with the policy's decisions as JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange step; "
@@ -127,6 +183,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.sweep_step_time:
+        return sweep_step_time(torch, binding, W, attention_device_inputs)
     cfg = W.CONFIGS[args.config]
     if args.ctx_scale != 1.0:
         c = cfg.ctx

@@ -224,6 +224,26 @@ int seer_kv_commit(const seer_attn_params* p, void* k_pages, void* v_pages, cons
                    const int32_t* draft_tokens, const int32_t* bonus_token, int32_t* emitted_tokens,
                    int32_t* n_emitted, int32_t* status, void* hip_stream);
 
+/*
+ * Draft lengths for the next steps (Algorithm 1 of the paper, Marginal-Benefit-Aware adaptive
+ * speculation, with the throughput model of Section 3.4.1).  Host arithmetic only, no GPU work.
+ *
+ *  B_h, B_l    requests of the high- and the low-priority class in the batch (B_h >= 1, B_l >= 0)
+ *  beta        host [n_beta] acceptance probability of draft position 1, 2, ... (each in [0, 1]);
+ *              n_beta >= gamma_max + 1; position 0, the token already accepted, counts as 1
+ *  gamma_max   cap on draft tokens per request, 0 .. 63
+ *  lambda      priority factor >= 1 (the paper suggests 2)
+ *  step_time   host [gamma_max + 1], > 0: measured time of one draft + verify step of the whole batch
+ *              with gamma = 0 .. gamma_max draft tokens per request (gamma = 0: a plain decode step)
+ *  gamma_h, gamma_l   written: draft tokens per request of each class
+ *  gamma_star  written if not NULL: argmin over gamma of (1 - alpha) step_time[gamma] /
+ *              (1 - alpha^(gamma + 1)), alpha = mean of beta[0 .. gamma_max - 1]; ties -> smaller gamma
+ * Returns SEER_OK or SEER_EINVAL / SEER_ESHAPE.
+ */
+int seer_mba_draft_lengths(int32_t B_h, int32_t B_l, const double* beta, int32_t n_beta, int32_t gamma_max,
+                           double lambda, const double* step_time, int32_t* gamma_h, int32_t* gamma_l,
+                           int32_t* gamma_star);
+
 /* Static text for a return code of either call (negative SEER_E*, or a
  * positive hipError_t). */
 const char* seer_strerror(int code);

@@ -20,7 +20,7 @@ SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALI
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
            "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
-           "seer_kv_commit", "seer_strerror")
+           "seer_kv_commit", "seer_mba_draft_lengths", "seer_strerror")
 
 
 class SeerAttnParams(ctypes.Structure):
@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
         lib.seer_accept_sampled.restype = ctypes.c_int
         lib.seer_kv_commit.argtypes = [ctypes.POINTER(SeerAttnParams)] + [vp] * 12
         lib.seer_kv_commit.restype = ctypes.c_int
+        lib.seer_mba_draft_lengths.argtypes = [i32, i32, vp, i32, i32, ctypes.c_double, vp, vp, vp, vp]
+        lib.seer_mba_draft_lengths.restype = ctypes.c_int
         lib.seer_strerror.argtypes = [ctypes.c_int]
         lib.seer_strerror.restype = ctypes.c_char_p
         _lib = lib
@@ -243,3 +245,17 @@ def seer_kv_commit(k_pages: torch.Tensor, v_pages: Optional[torch.Tensor], block
                               _ptr(accepted_len), _ptr(accepted_path), _ptr(draft_tokens), _ptr(bonus_token),
                               _ptr(emitted), _ptr(n_emitted), _ptr(status), _stream_handle(stream)))
     return None if emitted is None else (emitted, n_emitted)
+
+
+def seer_mba_draft_lengths(B_h: int, B_l: int, beta, gamma_max: int, lam: float, step_time):
+    """(gamma_h, gamma_l, gamma_star) by the paper's Algorithm 1; beta[i] = acceptance probability of
+    draft position i + 1, step_time[gamma] = measured time of a step with gamma draft tokens."""
+    lib = load_library()
+    bt = (ctypes.c_double * len(beta))(*[float(x) for x in beta])
+    st = (ctypes.c_double * len(step_time))(*[float(x) for x in step_time])
+    if len(step_time) < gamma_max + 1:
+        raise ValueError("step_time needs gamma_max + 1 entries")
+    gh, gl, gs = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib.seer_mba_draft_lengths(B_h, B_l, bt, len(beta), gamma_max, float(lam), st, ctypes.byref(gh),
+                                      ctypes.byref(gl), ctypes.byref(gs)))
+    return gh.value, gl.value, gs.value

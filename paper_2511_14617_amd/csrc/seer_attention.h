@@ -82,7 +82,9 @@ inline int resident_wgs_per_cu(const seer_attn_params& p) {
     const int waves = ((p.Hq / p.Hkv) * p.T + 31) / 32;   // one wave per 32 query rows
     const int by_waves = 8 / waves;                       // 2 waves per SIMD, 4 SIMDs
     const int depth = gqa_pipe_depth(waves);
-    const int by_lds = 160 / (16 * (depth + 1));          // 160 KB of LDS per CU, 16 KB per ring slot pair
+    // 160 KB of LDS per CU, 16 KB per ring slot pair; five 32 KB workgroups would need all of it and
+    // do not become resident together (measured: a fifth of the grid ran as a second round)
+    const int by_lds = 159 / (16 * (depth + 1));
     return by_waves < 1 ? 1 : (by_waves < by_lds ? by_waves : by_lds);
 }
 
