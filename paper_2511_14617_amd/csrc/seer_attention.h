@@ -74,12 +74,22 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Measured on the 8B- to 72B-class shapes: between depths 1 and 4 the time changes by a few per cent only.
 constexpr int gqa_pipe_depth(int waves) { return waves <= 2 ? 1 : 3; }
 
+// The tiled D = 128 kernel handles up to 256 query rows (8 waves) of a KV head per workgroup; a request
+// with more rows per KV head (large groups of heads times a wide draft tree) is cut into row blocks of
+// equal size, each a workgroup of its own walking the same stretch (placed on the same XCD, so all but
+// the first find the tiles in that XCD's L2).
+inline int gqa_row_blocks(int rows) { return (rows + 255) / 256; }
+inline int gqa_rows_per_block(int rows) {
+    const int nb = gqa_row_blocks(rows);
+    return ((rows + nb - 1) / nb + 31) / 32 * 32;
+}
+
 // Workgroups of the partition kernel that one CU holds at once, by kernel shape.
 inline int resident_wgs_per_cu(const seer_attn_params& p) {
     const bool tiled = p.Dqk == 128 && p.Dv == 128 && p.page_size == 16 && !p.kv_shared_latent &&
                        !(p.flags & SEER_ATTN_GENERAL_KERNEL);
     if (!tiled) return 4;
-    const int waves = ((p.Hq / p.Hkv) * p.T + 31) / 32;   // one wave per 32 query rows
+    const int waves = gqa_rows_per_block((p.Hq / p.Hkv) * p.T) / 32;   // one wave per 32 query rows
     const int by_waves = 8 / waves;                       // 2 waves per SIMD, 4 SIMDs
     const int depth = gqa_pipe_depth(waves);
     // 160 KB of LDS per CU, 16 KB per ring slot pair; five 32 KB workgroups would need all of it and
@@ -105,7 +115,10 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
             w.wgs_per_head = 8 * (kNumCU / (8 * row_blocks * p.Hkv));
             if (w.wgs_per_head < 1) w.wgs_per_head = kNumCU / (row_blocks * p.Hkv);
         } else {
-            w.wgs_per_head = kNumCU * resident_wgs_per_cu(p) / p.Hkv;
+            const bool tiled = p.Dqk == 128 && p.Dv == 128 && p.page_size == 16 && !p.kv_shared_latent &&
+                               !(p.flags & SEER_ATTN_GENERAL_KERNEL);
+            const int row_blocks = tiled ? gqa_row_blocks((p.Hq / p.Hkv) * p.T) : 1;
+            w.wgs_per_head = kNumCU * resident_wgs_per_cu(p) / (p.Hkv * row_blocks);
         }
         if (w.wgs_per_head < 1) w.wgs_per_head = 1;
         // a stretch adds one piece per request boundary it crosses: pieces <= W + B
@@ -148,6 +161,7 @@ struct AttnArgs {
     float* fb_speed;            // [wgs_per_head] smoothed tiles per tick (owned by the plan kernel)
     int32_t fixed_split;        // 1: equal stretches, no history read or written
     int32_t stream_only;        // 1: the tiled D = 128 kernel only streams its tiles (diagnostic)
+    int32_t row_blocks, rows_per_block;   // tiled D = 128 kernel: workgroups per (stretch, KV head), rows of each
     const WorkItem* items;
     float* part_ml;             // [max_items][T][Hq][2]  (running max in log2 units, sum)
     float* part_acc;            // [max_items][T][Hq][Dv] unnormalised
@@ -159,7 +173,7 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
 hipError_t launch_general(const AttnArgs& a, hipStream_t stream);   // any supported shape
 hipError_t launch_combine(const AttnArgs& a, hipStream_t stream);
 bool general_supports(int Dqk, int Dv);
-bool gqa128_supports(const AttnArgs& a);                            // D = 128, 16-token pages, G*T <= 256
+bool gqa128_supports(const AttnArgs& a);                            // D = 128, 16-token pages
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream);
 bool mla_supports(const AttnArgs& a);                               // shared latent 576/512, 64-token pages
 hipError_t launch_mla(const AttnArgs& a, hipStream_t stream);

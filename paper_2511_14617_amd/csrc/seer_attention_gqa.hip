@@ -388,9 +388,12 @@ void attn_gqa128_kernel(AttnArgs a) {
     // Workgroup ids are dealt round-robin to the 8 XCDs and dispatched in id order.  The grid is laid
     // out in groups of 8 stretches x Hkv heads so that the Hkv workgroups with the same stretch index
     // share XCD (id % 8) and dispatch round: the plan's per-index speed history relies on that.
-    const int grp = blockIdx.x / (8 * a.Hkv), rem = blockIdx.x - grp * (8 * a.Hkv);
-    const int kvh = rem >> 3;
-    const int wg = grp * 8 + (rem & 7);
+    // The row blocks of a (stretch, head) are further workgroups with the same id % 8, so they share the XCD.
+    int rest = blockIdx.x >> 3;
+    const int kvh = rest % a.Hkv;
+    rest /= a.Hkv;
+    const int rb = rest % a.row_blocks;
+    const int wg = (rest / a.row_blocks) * 8 + (blockIdx.x & 7);
     if (wg >= a.wgs_per_head) return;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -438,8 +441,8 @@ void attn_gqa128_kernel(AttnArgs a) {
     const int n_tiles = (tok_end - tok_begin + kTile - 1) / kTile;
     bare_barrier();                                // every wave is done with the previous piece's slots
 
-    const int R = a.G * a.T;
-    const int r = wave * 32 + ln;
+    const int R = min(a.G * a.T, (rb + 1) * a.rows_per_block);     // rows of this row block end here
+    const int r = rb * a.rows_per_block + wave * 32 + ln;
     const bool row_ok = r < R;
     const int t = row_ok ? r / a.G : 0;
     const int hq = kvh * a.G + (row_ok ? r - t * a.G : 0);
@@ -719,14 +722,13 @@ void attn_gqa128_kernel(AttnArgs a) {
 }
 
 bool gqa128_supports(const AttnArgs& a) {
-    return a.Dqk == kD && a.Dv == kD && a.P == kPage && a.v_pages != nullptr && a.G * a.T <= 8 * 32 &&
-           a.Hkv <= 65535;
+    return a.Dqk == kD && a.Dv == kD && a.P == kPage && a.v_pages != nullptr && a.Hkv <= 65535;
 }
 
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
-    const int R = a.G * a.T;
-    const int nw = (R + 31) / 32;
-    const dim3 grid(static_cast<unsigned>((a.wgs_per_head + 7) / 8) * 8u * static_cast<unsigned>(a.Hkv));
+    const int nw = a.rows_per_block / 32;
+    const dim3 grid(static_cast<unsigned>((a.wgs_per_head + 7) / 8) * 8u * static_cast<unsigned>(a.Hkv) *
+                    static_cast<unsigned>(a.row_blocks));
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                                     \
     case NW_:                                                                                                  \

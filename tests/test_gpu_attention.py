@@ -56,6 +56,9 @@ CASES = {
                                                shared_prefix=256), {}),
     "tp8_share_72b_tree": (W.CONFIGS[5].scaled(B=16, group_size=16, Hq=8, Hkv=1, ctx=("uniform", 100, 1500),
                                               shared_prefix=256), {"dedup_fraction": 0.3}),
+    # more than 256 query rows per KV head: the tiled kernel cuts them into row blocks (528 rows -> 3 blocks)
+    "rows528_G16_T33": (W.CONFIGS[5].scaled(B=3, group_size=3, Hq=32, Hkv=2, ctx=("uniform", 200, 1500),
+                                            shared_prefix=0), {"dedup_fraction": 0.3}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
     "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
                                            ctx=("uniform", 50, 900)), {}),
