@@ -240,7 +240,7 @@ def main() -> int:
         lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out))
     # gather-read ceiling: the same call with the arithmetic left out of the tiled kernel (D = 128 shapes)
     ceiling_ms = None
-    if not cfg.shared_latent and cfg.Dqk == 128 and cfg.page_size == 16:
+    if not cfg.shared_latent and cfg.Dqk == 128 and cfg.page_size in (16, 32, 64, 128, 256, 512, 1024):
         ev2 = HipEvents(10)
         for i in range(10):
             binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
@@ -275,7 +275,7 @@ def main() -> int:
     achieved = ab["total"] / (kern_avg_ms * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(cfg.config_id) if args.ctx_scale == 1.0 else None
     tokens = cfg.B * cfg.T
-    kernel_name = ("attn_gqa128_kernel" if (cfg.Dqk == 128 and cfg.page_size == 16 and not cfg.shared_latent) else
+    kernel_name = ("attn_gqa128_kernel" if (cfg.Dqk == 128 and cfg.page_size in (16, 32, 64, 128, 256, 512, 1024) and not cfg.shared_latent) else
                    "attn_mla_kernel" if (cfg.shared_latent and cfg.Dqk == 576 and cfg.page_size == 64) else
                    "attn_general_kernel") + " (verify-attention partition kernel)"
     if cfg.shared_latent:

@@ -78,6 +78,7 @@ constexpr int gqa_pipe_depth(int waves) { return waves <= 2 ? 1 : 3; }
 // with more rows per KV head (large groups of heads times a wide draft tree) is cut into row blocks of
 // equal size, each a workgroup of its own walking the same stretch (placed on the same XCD, so all but
 // the first find the tiles in that XCD's L2).
+inline bool gqa_page_size_ok(int P) { return P >= 16 && P <= 1024 && (P & (P - 1)) == 0; }
 inline int gqa_row_blocks(int rows) { return (rows + 255) / 256; }
 inline int gqa_rows_per_block(int rows) {
     const int nb = gqa_row_blocks(rows);
@@ -86,7 +87,7 @@ inline int gqa_rows_per_block(int rows) {
 
 // Workgroups of the partition kernel that one CU holds at once, by kernel shape.
 inline int resident_wgs_per_cu(const seer_attn_params& p) {
-    const bool tiled = p.Dqk == 128 && p.Dv == 128 && p.page_size == 16 && !p.kv_shared_latent &&
+    const bool tiled = p.Dqk == 128 && p.Dv == 128 && gqa_page_size_ok(p.page_size) && !p.kv_shared_latent &&
                        !(p.flags & SEER_ATTN_GENERAL_KERNEL);
     if (!tiled) return 4;
     const int waves = gqa_rows_per_block((p.Hq / p.Hkv) * p.T) / 32;   // one wave per 32 query rows
@@ -115,7 +116,7 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
             w.wgs_per_head = 8 * (kNumCU / (8 * row_blocks * p.Hkv));
             if (w.wgs_per_head < 1) w.wgs_per_head = kNumCU / (row_blocks * p.Hkv);
         } else {
-            const bool tiled = p.Dqk == 128 && p.Dv == 128 && p.page_size == 16 && !p.kv_shared_latent &&
+            const bool tiled = p.Dqk == 128 && p.Dv == 128 && gqa_page_size_ok(p.page_size) && !p.kv_shared_latent &&
                                !(p.flags & SEER_ATTN_GENERAL_KERNEL);
             const int row_blocks = tiled ? gqa_row_blocks((p.Hq / p.Hkv) * p.T) : 1;
             w.wgs_per_head = kNumCU * resident_wgs_per_cu(p) / (p.Hkv * row_blocks);
@@ -173,7 +174,7 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
 hipError_t launch_general(const AttnArgs& a, hipStream_t stream);   // any supported shape
 hipError_t launch_combine(const AttnArgs& a, hipStream_t stream);
 bool general_supports(int Dqk, int Dv);
-bool gqa128_supports(const AttnArgs& a);                            // D = 128, 16-token pages
+bool gqa128_supports(const AttnArgs& a);                            // D = 128, pages of 16..1024 tokens (power of two)
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream);
 bool mla_supports(const AttnArgs& a);                               // shared latent 576/512, 64-token pages
 hipError_t launch_mla(const AttnArgs& a, hipStream_t stream);

@@ -1,5 +1,5 @@
 // Tiled verify-attention partition kernel for grouped-query heads with
-// D = 128 and 16-token pages (the shape of the paper's dense 8B- to 72B-class
+// D = 128 and pages of 16 (or a larger power of two) tokens (the shape of the paper's dense 8B- to 72B-class
 // rollout models), on the gfx950 matrix cores.
 //
 // Why matrix cores although decoding is "memory bound": verification reads a
@@ -58,7 +58,7 @@
 namespace seer {
 
 constexpr int kD = 128;                  // head dim
-constexpr int kPage = 16;                // tokens per page
+constexpr int kMinPage = 16;             // tokens per page: 16, or a larger power of two (a 32-token tile is then inside one page)
 constexpr int kTile = 32;                // tokens per tile
 constexpr int kRowBytes = kD * 2;        // 256
 constexpr int kKBytes = kTile * kRowBytes;   // 8192
@@ -414,8 +414,9 @@ void attn_gqa128_kernel(AttnArgs a) {
 
     const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
     const unsigned char* __restrict__ vbase = static_cast<const unsigned char*>(a.v_pages);
-    const uint32_t page_bytes32 = static_cast<uint32_t>(a.Hkv) * kPage * kRowBytes;   // one page, all kv heads
-    const size_t head_off = static_cast<size_t>(kvh) * kPage * kRowBytes;
+    const int page_shift = __builtin_ctz(static_cast<unsigned>(a.P));              // pages hold 2^page_shift tokens
+    const uint32_t page_bytes32 = static_cast<uint32_t>(a.Hkv) * a.P * kRowBytes;   // one page, all kv heads
+    const size_t head_off = static_cast<size_t>(kvh) * a.P * kRowBytes;
     const int goff_k0 = l16 * kRowBytes + ((p16 ^ k_swz(l16)) << 4);
     const int goff_v = l16 * kRowBytes + ((p16 ^ v_swz(l16)) << 4);
     int k_rd[8];
@@ -483,13 +484,14 @@ void attn_gqa128_kernel(AttnArgs a) {
     float m_run = kNegInf, l_run = 0.f, alpha = 1.f;
 
     // page ids, 64 at a time (lane l holds logical page cache_base + l), handed out with v_readlane.
-    // A tile is one even-numbered page and its successor, and windows start at even pages, so one
-    // window test covers both.
+    // With 16-token pages a tile is one even-numbered page and its successor, and windows start at even
+    // pages, so one window test covers both; with larger pages a tile is 32 rows inside one page.
     const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
     int cache_base = -0x40000000;
     int pg_cache = 0;
-    const int last_page = (n - 1) / kPage;
-    auto page_pair = [&](int lp, size_t& p0, size_t& p1) __attribute__((always_inline)) {
+    const int last_page = (n - 1) >> page_shift;
+    auto page_pair = [&](int tb, size_t& p0, size_t& p1) __attribute__((always_inline)) {
+        const int lp = tb >> page_shift;
         if (lp < cache_base || lp >= cache_base + kWave) {   // uniform
             cache_base = lp;
             const int idx = cache_base + lane;
@@ -501,9 +503,11 @@ void attn_gqa128_kernel(AttnArgs a) {
             pg_cache = pg;
         }
         const int i0 = __builtin_amdgcn_readfirstlane(lp - cache_base);
-        const uint32_t g0 = __builtin_amdgcn_readlane(pg_cache, i0), g1 = __builtin_amdgcn_readlane(pg_cache, i0 + 1);
-        p0 = static_cast<uint64_t>(g0) * page_bytes32 + head_off;
-        p1 = static_cast<uint64_t>(g1) * page_bytes32 + head_off;
+        const int i1 = a.P == kMinPage ? i0 + 1 : i0;
+        const uint32_t g0 = __builtin_amdgcn_readlane(pg_cache, i0), g1 = __builtin_amdgcn_readlane(pg_cache, i1);
+        const uint32_t in_page = static_cast<uint32_t>(tb & (a.P - 1));              // first row of the tile in its page
+        p0 = static_cast<uint64_t>(g0) * page_bytes32 + head_off + in_page * kRowBytes;
+        p1 = static_cast<uint64_t>(g1) * page_bytes32 + head_off + ((in_page + 16u) & (a.P - 1)) * kRowBytes;
     };
 
     // loads of step j: K tile j + D and V tile j + D - 2, where they exist.  The V tile sits in
@@ -511,7 +515,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     size_t pq0 = 0, pq1 = 0, pr0 = 0, pr1 = 0;     // page offsets of the K tiles of steps j - 1 and j - 2
     size_t pn0 = 0, pn1 = 0;
     auto issue_k_at = [&](int kt, int slot_bytes) __attribute__((always_inline)) {
-        page_pair((tok_begin + kt * kTile) / kPage, pn0, pn1);
+        page_pair(tok_begin + kt * kTile, pn0, pn1);
         issue_half_tile<NW>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
     };
     auto issue_v_at = [&](int slot_bytes) __attribute__((always_inline)) {
@@ -722,7 +726,8 @@ void attn_gqa128_kernel(AttnArgs a) {
 }
 
 bool gqa128_supports(const AttnArgs& a) {
-    return a.Dqk == kD && a.Dv == kD && a.P == kPage && a.v_pages != nullptr && a.Hkv <= 65535;
+    return a.Dqk == kD && a.Dv == kD && a.P >= kMinPage && a.P <= 1024 && (a.P & (a.P - 1)) == 0 &&
+           a.v_pages != nullptr && a.Hkv <= 65535;
 }
 
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {

@@ -59,6 +59,10 @@ CASES = {
     # more than 256 query rows per KV head: the tiled kernel cuts them into row blocks (528 rows -> 3 blocks)
     "rows528_G16_T33": (W.CONFIGS[5].scaled(B=3, group_size=3, Hq=32, Hkv=2, ctx=("uniform", 200, 1500),
                                             shared_prefix=0), {"dedup_fraction": 0.3}),
+    # larger pages with the tiled D = 128 kernel (a 32-token tile lies inside one page)
+    "d128_page64": (W.CONFIGS[2].scaled(B=5, group_size=5, page_size=64, ctx=("uniform", 9, 1500), shared_prefix=128), {}),
+    "d128_page256_tree": (W.CONFIGS[5].scaled(B=4, group_size=4, page_size=256, ctx=("uniform", 33, 1200),
+                                              shared_prefix=256), {"dedup_fraction": 0.3}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
     "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
                                            ctx=("uniform", 50, 900)), {}),
