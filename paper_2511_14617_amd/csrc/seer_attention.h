@@ -107,7 +107,7 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
         w.wgs_per_head = p.B;
         w.max_items = p.B;
     } else {
-        const bool mla_tiled = p.Dqk == 576 && p.Dv == 512 && p.page_size == 64 && p.kv_shared_latent &&
+        const bool mla_tiled = p.Dqk == 576 && p.Dv == 512 && p.page_size >= 32 && gqa_page_size_ok(p.page_size) && p.kv_shared_latent &&
                                !(p.flags & SEER_ATTN_GENERAL_KERNEL);
         if (mla_tiled) {
             // one 4-wave workgroup per CU; a request's rows are cut into blocks of 128, and the
@@ -176,7 +176,7 @@ hipError_t launch_combine(const AttnArgs& a, hipStream_t stream);
 bool general_supports(int Dqk, int Dv);
 bool gqa128_supports(const AttnArgs& a);                            // D = 128, pages of 16..1024 tokens (power of two)
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream);
-bool mla_supports(const AttnArgs& a);                               // shared latent 576/512, 64-token pages
+bool mla_supports(const AttnArgs& a);                               // shared latent 576/512, pages of 32..1024 tokens
 hipError_t launch_mla(const AttnArgs& a, hipStream_t stream);
 
 }  // namespace seer

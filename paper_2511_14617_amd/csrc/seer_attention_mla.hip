@@ -1,7 +1,7 @@
 // Tiled verify-attention partition kernel for the shared-latent (MLA, absorbed
 // form) shape: all query heads of a request attend to ONE compressed KV latent
 // of 576 dims per token (512 latent + 64 rope); the value of a token is the
-// first 512 dims of that same vector.  Pages hold 64 tokens.
+// first 512 dims of that same vector.  Pages hold 32 tokens or a larger power of two (64 in the workload).
 //
 // This is the shape of the paper's largest rollout model (a 1 TB MoE served with
 // data + expert parallelism, so each GPU sees all 128 attention heads of its own
@@ -35,7 +35,7 @@ namespace seer {
 
 namespace mla {
 constexpr int kDqk = 576, kDv = 512;
-constexpr int kPage = 64;
+constexpr int kMinPage = 32;                       // pages of 32 tokens or a larger power of two: a tile lies inside one page
 constexpr int kTile = 32;
 constexpr int kRowBytes = kDqk * 2;               // 1152
 constexpr int kChunksPerRow = kRowBytes / 16;      // 72
@@ -286,8 +286,9 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     bool bad_page = false;
 
     const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
-    const size_t page_bytes = static_cast<size_t>(a.Hkv) * kPage * kRowBytes;
-    const size_t head_off = static_cast<size_t>(kvh) * kPage * kRowBytes;
+    const int page_shift = __builtin_ctz(static_cast<unsigned>(a.P));
+    const size_t page_bytes = static_cast<size_t>(a.Hkv) * a.P * kRowBytes;
+    const size_t head_off = static_cast<size_t>(kvh) * a.P * kRowBytes;
 
     // K operand: row ln, chunk 2*kk + lg; the swizzle only touches the low 3 bits of the chunk index
     int k_rd[4];
@@ -365,7 +366,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
     int cache_base = -0x40000000;
     int pg_cache = 0;
-    const int last_page = (n - 1) / kPage;
+    const int last_page = (n - 1) >> page_shift;
     auto page_offset = [&](int logical_page) __attribute__((always_inline)) -> size_t {
         if (logical_page < cache_base || logical_page >= cache_base + kWave) {
             cache_base = logical_page;
@@ -382,7 +383,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     };
     auto issue_tile = [&](int tile) __attribute__((always_inline)) {
         const int tb = tok_begin + tile * kTile;
-        const unsigned char* src = kbase + page_offset(tb / kPage) + static_cast<size_t>(tb % kPage) * kRowBytes;
+        const unsigned char* src = kbase + page_offset(tb >> page_shift) + static_cast<size_t>(tb & (a.P - 1)) * kRowBytes;
         unsigned char* stage = lds + (tile % kStages) * kStageBytes;
 #pragma unroll
         for (int i = 0; i < kLoadsPerWave; ++i) {
@@ -513,7 +514,8 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
 }
 
 bool mla_supports(const AttnArgs& a) {
-    return a.Dqk == mla::kDqk && a.Dv == mla::kDv && a.P == mla::kPage && a.v_pages == nullptr && a.Hkv <= 65535;
+    return a.Dqk == mla::kDqk && a.Dv == mla::kDv && a.P >= mla::kMinPage && a.P <= 1024 && (a.P & (a.P - 1)) == 0 &&
+           a.v_pages == nullptr && a.Hkv <= 65535;
 }
 
 hipError_t launch_mla(const AttnArgs& a, hipStream_t stream) {

@@ -63,6 +63,8 @@ CASES = {
     "d128_page64": (W.CONFIGS[2].scaled(B=5, group_size=5, page_size=64, ctx=("uniform", 9, 1500), shared_prefix=128), {}),
     "d128_page256_tree": (W.CONFIGS[5].scaled(B=4, group_size=4, page_size=256, ctx=("uniform", 33, 1200),
                                               shared_prefix=256), {"dedup_fraction": 0.3}),
+    "mla_page32": (W.CONFIGS[4].scaled(B=2, Hq=16, page_size=32, ctx=("uniform", 100, 700)), {}),
+    "mla_page128": (W.CONFIGS[4].scaled(B=2, Hq=16, page_size=128, ctx=("uniform", 100, 700)), {}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
     "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
                                            ctx=("uniform", 50, 900)), {}),
