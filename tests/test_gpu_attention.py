@@ -199,3 +199,37 @@ def test_stream_only_diagnostic_runs_the_load_path_and_writes_zeros():
     inp = W.make_attention_inputs(cfg, **kw)
     out = _gpu(inp, flags=binding.SEER_ATTN_STREAM_ONLY)
     assert float(out.float().abs().max()) == 0.0
+
+
+def _random_shape(rng):
+    """A seeded random small workload: group width, slots, tree or chain, page size, context mix."""
+    G = int(rng.choice([1, 2, 4, 5, 8, 16]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    if rng.random() < 0.5:
+        n_paths, path_len = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        T, tree = 1 + n_paths * path_len, (n_paths, path_len)
+    else:
+        T, tree = int(rng.integers(1, 40)), None
+    P = int(rng.choice([16, 16, 32, 64, 128]))
+    B = int(rng.integers(1, 7))
+    hi = int(rng.choice([T + 3, 100, 700, 2500]))
+    lo = int(rng.integers(T, max(T + 1, hi // 2)))
+    shared = int(rng.choice([0, 0, 32, 96])) if lo > 200 else 0
+    cfg = W.CONFIGS[2].scaled(B=B, group_size=B, Hq=G * Hkv, Hkv=Hkv, T=T, tree=tree, page_size=P,
+                              ctx=("uniform", lo, max(lo, hi)), shared_prefix=shared)
+    return cfg
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_parity_random_shapes(seed):
+    """Random shapes of the tiled D = 128 kernel against the oracle, hardened values: every combination of
+    wave count, row blocks, page size, chain or tree, ragged tails and very short prefixes that the seeds hit."""
+    rng = np.random.default_rng(1000 + seed)
+    cfg = _random_shape(rng)
+    inp = W.make_attention_inputs(cfg, seed=cfg.seed + seed, values="peaked",
+                                  **({"dedup_fraction": 0.3} if cfg.tree else {}))
+    ref = _oracle(inp)
+    out = _gpu(inp)
+    what = "random %d: G=%d Hkv=%d T=%d tree=%s P=%d B=%d ctx=%s" % (seed, cfg.G, cfg.Hkv, cfg.T, cfg.tree,
+                                                                     cfg.page_size, cfg.B, inp.ctx_len.tolist())
+    assert_attention_close(out, ref, what, hardened=True, ref_abs=_oracle_abs(inp))
