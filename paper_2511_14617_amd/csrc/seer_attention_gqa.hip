@@ -76,13 +76,22 @@ static_assert(kTile == kPlanTile, "the plan counts work in tiles of this kernel"
 __device__ __forceinline__ int k_swz(int row) { return row & 15; }
 __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
 
-// Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the NW waves.
+// Which waves issue the tile loads.  A direct-to-LDS load holds the issuing wave for about 27 ns (the
+// vector memory path of a CU moves 64 bytes per clock), and with five waves on four SIMDs, waves 0 and 4
+// share a SIMD and are the ones every step waits for: they are left out, waves 1..3 load.
+template <int NW> struct Loaders { static constexpr int kFirst = 0, kCount = NW; };
+template <> struct Loaders<5> { static constexpr int kFirst = 1, kCount = 3; };
+
+// Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the loading waves.
 template <int NW>
 __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, size_t p0, size_t p1,
                                                 const unsigned char* base, int goff, bool is_k) {
+    constexpr int NL = Loaders<NW>::kCount;
+    const int li = wave - Loaders<NW>::kFirst;
+    if (li < 0 || li >= NL) return;
 #pragma unroll
-    for (int i = 0; i < (8 + NW - 1) / NW; ++i) {
-        const int j = wave + i * NW;
+    for (int i = 0; i < (8 + NL - 1) / NL; ++i) {
+        const int j = li + i * NL;
         if (j < 8) {
             const size_t pg = (j < 4) ? p0 : p1;
             const int lane_off = is_k ? goff ^ ((j & 3) << 6) : goff;   // K rows 4j + l16: f = 4(j & 3) + l16
@@ -377,9 +386,10 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW =
 void attn_gqa128_kernel(AttnArgs a) {
     constexpr int NT = NW * kWave;
     constexpr int NSLOT = D + 1;                    // slots in the K ring and in the V ring
-    constexpr int CEIL = (8 + NW - 1) / NW;         // half-tile blocks of the busiest waves
-    constexpr int FLOOR = 8 / NW;
-    constexpr int REM = 8 % NW;                     // waves below this index load CEIL blocks, the others FLOOR
+    constexpr int NL = Loaders<NW>::kCount;         // waves that issue loads (the others have nothing to wait for)
+    constexpr int CEIL = (8 + NL - 1) / NL;         // half-tile blocks of the busiest loading waves
+    constexpr int FLOOR = 8 / NL;
+    constexpr int REM = 8 % NL;                     // loaders below this index load CEIL blocks, the others FLOOR
     static_assert(D >= 1 && (D - 1) * 2 * CEIL < 64, "vmcnt range");
 
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * NSLOT * kKBytes];   // K ring, then V ring
@@ -541,7 +551,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     auto wait_step = [&](int u) __attribute__((always_inline)) {
         const bool full = D > 1 && u >= 1 && u + D - 1 < n_tiles;
         if (full) {
-            if (REM == 0 || wave < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            if (REM == 0 || wave - Loaders<NW>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
             else wait_vmcnt<(D - 1) * 2 * FLOOR>();
         } else {
             wait_vmcnt<0>();
@@ -629,7 +639,7 @@ void attn_gqa128_kernel(AttnArgs a) {
             constexpr int I = decltype(ic)::value;
             constexpr int kReadSlot = (2 + I) % NSLOT, kVReadSlot = I % NSLOT;
             constexpr int kIssueSlot = (1 + I) % NSLOT, kVIssueSlot = (I + NSLOT - 1) % NSLOT;
-            if (REM == 0 || wave < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            if (REM == 0 || wave - Loaders<NW>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
             else wait_vmcnt<(D - 1) * 2 * FLOOR>();
             bare_barrier();
             const int uu = u + I;
