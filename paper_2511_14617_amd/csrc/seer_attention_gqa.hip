@@ -79,15 +79,15 @@ __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
 // Which waves issue the tile loads.  A direct-to-LDS load holds the issuing wave for about 27 ns (the
 // vector memory path of a CU moves 64 bytes per clock), and with five waves on four SIMDs, waves 0 and 4
 // share a SIMD and are the ones every step waits for: they are left out, waves 1..3 load.
-template <int NW, bool LIGHT> struct Loaders { static constexpr int kFirst = 0, kCount = LIGHT ? NW - 1 : NW; };
-template <> struct Loaders<5, false> { static constexpr int kFirst = 1, kCount = 3; };
+template <int NW> struct Loaders { static constexpr int kFirst = 0, kCount = NW; };
+template <> struct Loaders<5> { static constexpr int kFirst = 1, kCount = 3; };
 
 // Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the loading waves.
-template <int NW, bool LIGHT>
+template <int NW>
 __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, size_t p0, size_t p1,
                                                 const unsigned char* base, int goff, bool is_k) {
-    constexpr int NL = Loaders<NW, LIGHT>::kCount;
-    const int li = wave - Loaders<NW, LIGHT>::kFirst;
+    constexpr int NL = Loaders<NW>::kCount;
+    const int li = wave - Loaders<NW>::kFirst;
     if (li < 0 || li >= NL) return;
 #pragma unroll
     for (int i = 0; i < (8 + NL - 1) / NL; ++i) {
@@ -372,197 +372,6 @@ __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_r
     }
 }
 
-
-// ---------------------------------------------------------------------------------------------
-// The light last wave.  R = G*T is rarely a multiple of 32 (T = gamma + 1 with gamma a power of two
-// leaves G rows over), and a wave that holds a handful of rows costs as much as a full one in the
-// path above.  When the last wave has at most 16 rows it runs this path instead: the same three
-// products on v_mfma_f32_16x16x32_bf16 (M = 16 tokens or 16 d, N = 16 rows), a quarter of the matrix
-// work and half of the softmax work of a full wave.  It follows the same step sequence and executes
-// the same barriers as the other waves of the workgroup, and it issues no tile loads.
-//   lane = 16 q + i: row i (of 16), contraction group q (of 4)
-//   scores  S^T[token][row]: per 16-token block 4 MFMAs over d; C register j of block tb holds token
-//           16 tb + 4 q + j of the tile
-//   P.V     O^T[d][row]: per 16-d block one MFMA over the tile's 32 tokens; contraction slot j of
-//           group q is token 16 (j / 4) + 4 q + j % 4, which is the order the score registers have
-// ---------------------------------------------------------------------------------------------
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-
-struct LightState {
-    f32x4 acc[8];        // O^T: d block x (4 d values per lane)
-    f32x4 s_cur[2];      // scores of the tile whose softmax comes next
-    uint32_t pk[4];      // probabilities of the tile whose P.V comes next
-    float m_run, l_run, alpha;
-};
-
-__device__ __forceinline__ void light_scores(const unsigned char* lds, int k_slot, const int (&k_rd)[2][4],
-                                             const u32x4 (&qh)[4], f32x4 (&s_out)[2]) {
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ds = 0; ds < 4; ++ds) {
-            const u32x4 kv = *reinterpret_cast<const u32x4*>(lds + k_slot + k_rd[tb][ds]);
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv), as_bf16x8(qh[ds]), s, 0, 0, 0);
-        }
-        s_out[tb] = s;
-    }
-}
-
-__device__ __forceinline__ void light_softmax(LightState& st, uint32_t vis, int q, float scale_log2) {
-    // register j of block tb is token 16 tb + 4 q + j; vis has one bit per token of the tile
-    float mx = kNegInf;
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (!((vis >> (16 * tb + 4 * q + j)) & 1u)) st.s_cur[tb][j] = kNegInf;
-            mx = fmaxf(mx, st.s_cur[tb][j]);
-        }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * scale_log2;
-    const float m_new = (mx > st.m_run + 8.f) ? mx : st.m_run;
-    const float m_use = (m_new == kNegInf) ? 0.f : m_new;
-    st.alpha = fast_exp2(st.m_run - m_use);
-    st.m_run = m_new;
-    float p[2][4], psum = 0.f;
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            p[tb][j] = fast_exp2(fmaf(st.s_cur[tb][j], scale_log2, -m_use));
-            psum += p[tb][j];
-        }
-    st.pk[0] = cvt_pk_bf16(p[0][0], p[0][1]);
-    st.pk[1] = cvt_pk_bf16(p[0][2], p[0][3]);
-    st.pk[2] = cvt_pk_bf16(p[1][0], p[1][1]);
-    st.pk[3] = cvt_pk_bf16(p[1][2], p[1][3]);
-    st.l_run = st.l_run * st.alpha + psum;
-}
-
-__device__ __forceinline__ void light_pv(const unsigned char* lds, int v_slot, const int (&v_rd)[8], LightState& st) {
-    if (__any(st.alpha != 1.f)) {
-#pragma unroll
-        for (int blk = 0; blk < 8; ++blk)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) st.acc[blk][j] *= st.alpha;
-    }
-    st.alpha = 1.f;
-    const u32x4 pb = {st.pk[0], st.pk[1], st.pk[2], st.pk[3]};
-#pragma unroll
-    for (int blk = 0; blk < 8; ++blk) {
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (SEER_AS3 s16x4*)(lds + v_slot + v_rd[blk]));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (SEER_AS3 s16x4*)(lds + v_slot + v_rd[blk] + 16 * kRowBytes));
-        const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
-        const u32x4 va = {lo2[0], lo2[1], hi2[0], hi2[1]};
-        st.acc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(va), as_bf16x8(pb), st.acc[blk], 0, 0, 0);
-    }
-}
-
-// One piece of the stretch for the light wave.  first_row: first query row of the wave; R: rows end.
-template <int NT, int NSLOT>
-__device__ __forceinline__ void light_piece(const AttnArgs& a, unsigned char* lds, int tid, int lane, int kvh, int b,
-                                            int item_idx, int n, int tok_begin, int n_tiles, int first_row, int R) {
-    constexpr int kVRing = NSLOT * kKBytes;
-    const int i16 = lane & 15, q = lane >> 4;
-    const int n0 = n - a.T;
-    const int r = first_row + i16;
-    const bool row_ok = r < R;
-    const int t = row_ok ? r / a.G : 0;
-    const int hq = kvh * a.G + (row_ok ? r - t * a.G : 0);
-    uint64_t word = 0;
-    if (row_ok) {
-        word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
-                           : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
-        if (a.T < 64) word &= (1ull << a.T) - 1;
-    }
-    u32x4 qh[4];       // Q[row][32 ds + 8 q .. + 7]
-    {
-        const u32x4* qp = reinterpret_cast<const u32x4*>(
-            static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * kD + q * 8);
-#pragma unroll
-        for (int ds = 0; ds < 4; ++ds) qh[ds] = row_ok ? qp[ds * 4] : u32x4{0u, 0u, 0u, 0u};
-    }
-    // K operand: token row 16 tb + i, chunk 4 ds + q.  V^T operand (transposing read): lane s = 4 k + c of
-    // its 16-lane group points at token row 4 q + k (then + 16), d columns 16 blk + 4 c .. + 3.
-    int k_rd[2][4], v_rd[8];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-        for (int ds = 0; ds < 4; ++ds) {
-            const int row = 16 * tb + i16;
-            k_rd[tb][ds] = row * kRowBytes + (((4 * ds + q) ^ k_swz(row)) << 4);
-        }
-    {
-        const int k = i16 >> 2, c = i16 & 3, row = 4 * q + k;
-#pragma unroll
-        for (int blk = 0; blk < 8; ++blk)
-            v_rd[blk] = row * kRowBytes + (((2 * blk + (c >> 1)) ^ v_swz(row)) << 4) + (c & 1) * 8;   // (row + 16: same swizzle)
-    }
-    LightState st;
-#pragma unroll
-    for (int blk = 0; blk < 8; ++blk) st.acc[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
-    st.m_run = kNegInf, st.l_run = 0.f, st.alpha = 1.f;
-    auto vis_of = [&](int j) __attribute__((always_inline)) -> uint32_t {
-        const int rel = tok_begin + j * kTile - n0;
-        if (rel <= -kTile) return ~0u;
-        return rel >= 0 ? static_cast<uint32_t>(word >> rel)
-                        : (static_cast<uint32_t>(word << (-rel)) | ((1u << (-rel)) - 1u));
-    };
-    auto k_slot = [&](int j) __attribute__((always_inline)) -> int { return (j % NSLOT) * kKBytes; };
-    auto v_slot = [&](int j) __attribute__((always_inline)) -> int { return kVRing + (j % NSLOT) * kKBytes; };
-    f32x4 s_next[2];
-    // step 0
-    bare_barrier();
-    light_scores(lds, k_slot(0), k_rd, qh, st.s_cur);
-    // step 1
-    bare_barrier();
-    if (n_tiles > 1) light_scores(lds, k_slot(1), k_rd, qh, s_next);
-    light_softmax(st, vis_of(0), q, a.scale_log2);
-    // steps 2 .. n_tiles - 1
-    for (int u = 2; u < n_tiles; ++u) {
-        bare_barrier();
-        light_pv(lds, v_slot(u - 2), v_rd, st);
-        st.s_cur[0] = s_next[0], st.s_cur[1] = s_next[1];
-        light_scores(lds, k_slot(u), k_rd, qh, s_next);
-        light_softmax(st, vis_of(u - 1), q, a.scale_log2);
-    }
-    if (n_tiles > 1) {
-        bare_barrier();
-        light_pv(lds, v_slot(n_tiles - 2), v_rd, st);
-        st.s_cur[0] = s_next[0], st.s_cur[1] = s_next[1];
-        light_softmax(st, vis_of(n_tiles - 1), q, a.scale_log2);
-    }
-    {
-        bare_barrier();
-        const int tb = tok_begin + (n_tiles - 1) * kTile;
-        if (tb + kTile > n) {      // this wave's share of clearing the V rows past the end (see the full path)
-            unsigned char* vl = lds + v_slot(n_tiles - 1);
-            const int first_bad = n - tb;
-            for (int c = tid; c < kTile * 16; c += NT)
-                if ((c >> 4) >= first_bad) *reinterpret_cast<u32x4*>(vl + c * 16) = u32x4{0u, 0u, 0u, 0u};
-            __builtin_amdgcn_s_waitcnt(0xc07f);
-            bare_barrier();
-        }
-        light_pv(lds, v_slot(n_tiles - 1), v_rd, st);
-    }
-    // partial result: lane (row i, group q) holds d = 16 blk + 4 q + j
-    float l_tot = st.l_run + __shfl_xor(st.l_run, 16, kWave);
-    l_tot += __shfl_xor(l_tot, 32, kWave);
-    if (row_ok) {
-        const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
-        if (q == 0) {
-            a.part_ml[2 * prow] = st.m_run;
-            a.part_ml[2 * prow + 1] = l_tot;
-        }
-        float* __restrict__ po = a.part_acc + prow * kD;
-#pragma unroll
-        for (int blk = 0; blk < 8; ++blk) *reinterpret_cast<f32x4*>(po + blk * 16 + q * 4) = st.acc[blk];
-    }
-}
-
 template <typename F, int... I>
 __device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, I...>) {
     (f(std::integral_constant<int, I>{}), ...);
@@ -572,14 +381,12 @@ __device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, 
 // waits, barriers, partial-result writes) and leaves out the arithmetic.  Its time is what the memory
 // system allows for exactly this access pattern and launch shape: the ceiling the kernel's
 // bytes-per-second should be read against.  It writes "saw nothing" partials, so the output is zero.
-// LIGHT: the last wave has at most 16 query rows and takes the light path (light_piece).
-template <int NW, int D, bool STREAM, bool LIGHT>
+template <int NW, int D, bool STREAM>
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
 void attn_gqa128_kernel(AttnArgs a) {
-    static_assert(!LIGHT || (NW >= 2 && !STREAM), "a light last wave needs another wave to load the tiles");
     constexpr int NT = NW * kWave;
     constexpr int NSLOT = D + 1;                    // slots in the K ring and in the V ring
-    constexpr int NL = Loaders<NW, LIGHT>::kCount;         // waves that issue loads (the others have nothing to wait for)
+    constexpr int NL = Loaders<NW>::kCount;         // waves that issue loads (the others have nothing to wait for)
     constexpr int CEIL = (8 + NL - 1) / NL;         // half-tile blocks of the busiest loading waves
     constexpr int FLOOR = 8 / NL;
     constexpr int REM = 8 % NL;                     // loaders below this index load CEIL blocks, the others FLOOR
@@ -646,13 +453,6 @@ void attn_gqa128_kernel(AttnArgs a) {
     bare_barrier();                                // every wave is done with the previous piece's slots
 
     const int R = min(a.G * a.T, (rb + 1) * a.rows_per_block);     // rows of this row block end here
-    if constexpr (LIGHT) {
-        if (wave == NW - 1) {
-            light_piece<NT, NSLOT>(a, lds, tid, lane, kvh, b, item_idx, n, tok_begin, n_tiles,
-                                   rb * a.rows_per_block + wave * 32, R);
-            continue;
-        }
-    }
     const int r = rb * a.rows_per_block + wave * 32 + ln;
     const bool row_ok = r < R;
     const int t = row_ok ? r / a.G : 0;
@@ -726,10 +526,10 @@ void attn_gqa128_kernel(AttnArgs a) {
     size_t pn0 = 0, pn1 = 0;
     auto issue_k_at = [&](int kt, int slot_bytes) __attribute__((always_inline)) {
         page_pair(tok_begin + kt * kTile, pn0, pn1);
-        issue_half_tile<NW, LIGHT>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
+        issue_half_tile<NW>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
     };
     auto issue_v_at = [&](int slot_bytes) __attribute__((always_inline)) {
-        issue_half_tile<NW, LIGHT>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
+        issue_half_tile<NW>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
     };
     auto shift_pages = [&]() __attribute__((always_inline)) { pr0 = pq0, pr1 = pq1, pq0 = pn0, pq1 = pn1; };
     auto issue_k = [&](int j) __attribute__((always_inline)) {
@@ -751,7 +551,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     auto wait_step = [&](int u) __attribute__((always_inline)) {
         const bool full = D > 1 && u >= 1 && u + D - 1 < n_tiles;
         if (full) {
-            if (REM == 0 || wave - Loaders<NW, LIGHT>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            if (REM == 0 || wave - Loaders<NW>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
             else wait_vmcnt<(D - 1) * 2 * FLOOR>();
         } else {
             wait_vmcnt<0>();
@@ -839,7 +639,7 @@ void attn_gqa128_kernel(AttnArgs a) {
             constexpr int I = decltype(ic)::value;
             constexpr int kReadSlot = (2 + I) % NSLOT, kVReadSlot = I % NSLOT;
             constexpr int kIssueSlot = (1 + I) % NSLOT, kVIssueSlot = (I + NSLOT - 1) % NSLOT;
-            if (REM == 0 || wave - Loaders<NW, LIGHT>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            if (REM == 0 || wave - Loaders<NW>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
             else wait_vmcnt<(D - 1) * 2 * FLOOR>();
             bare_barrier();
             const int uu = u + I;
@@ -942,22 +742,17 @@ bool gqa128_supports(const AttnArgs& a) {
 
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int nw = a.rows_per_block / 32;
-    // the last wave of a single row block with at most 16 rows takes the light path
-    const bool light = a.row_blocks == 1 && a.G * a.T - 32 * (nw - 1) <= 16;
     const dim3 grid(static_cast<unsigned>((a.wgs_per_head + 7) / 8) * 8u * static_cast<unsigned>(a.Hkv) *
                     static_cast<unsigned>(a.row_blocks));
     switch (nw) {
 #define SEER_GQA_CASE(NW_)                                                                                     \
     case NW_:                                                                                                  \
         if (a.stream_only)                                                                                     \
-            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), true, false>), grid,              \
-                               dim3(NW_ * kWave), 0, stream, a);                                               \
-        else if (light && NW_ >= 2)                                                                            \
-            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), false, (NW_ >= 2)>), grid,        \
-                               dim3(NW_ * kWave), 0, stream, a);                                               \
+            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), true>), grid, dim3(NW_ * kWave), 0,   \
+                               stream, a);                                                                     \
         else                                                                                                   \
-            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), false, false>), grid,             \
-                               dim3(NW_ * kWave), 0, stream, a);                                               \
+            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), false>), grid, dim3(NW_ * kWave), 0,  \
+                               stream, a);                                                                     \
         break;
         SEER_GQA_CASE(1)
         SEER_GQA_CASE(2)
