@@ -502,3 +502,147 @@ def make_accept_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *,
                 logits[b, node] = logits[b, rep]
         logits[b, np.arange(T), target[b]] = bump[b]
     return AcceptInputs(cfg, logits, draft, tree_parent, out_len, target)
+
+
+# --------------------------------------------------------------------------
+# grouped token histories for drafting
+# --------------------------------------------------------------------------
+@dataclass
+class DraftInputs:
+    """Token histories of prompt groups and the lookup patterns of the live requests."""
+
+    tokens: np.ndarray            # [pool] int32: every sequence's tokens, gaps hold decoy tokens
+    seq_start: np.ndarray         # [n_seq] int32
+    seq_len: np.ndarray           # [n_seq] int32
+    group_first: np.ndarray       # [n_groups + 1] int32: group g owns sequences group_first[g] .. group_first[g+1]-1
+    req_group: np.ndarray         # [B] int32
+    req_seq: np.ndarray           # [B] int32: the sequence that is the request's own history
+    pattern: np.ndarray           # [B, p_max] int32, right-aligned, newest token last
+    pattern_len: np.ndarray       # [B] int32
+    max_spec_tokens: np.ndarray   # [B] int32
+    future: np.ndarray            # [B, horizon] int32: the tokens the request produces next (not in the pool)
+    gamma_max: int
+    top_k: int
+    p_min: int
+    p_max: int
+    min_confidence: float
+    vocab: int
+
+    @property
+    def T(self) -> int:
+        return 1 + self.top_k * self.gamma_max
+
+    @property
+    def max_group_tokens(self) -> int:
+        tot = [int(self.seq_len[self.group_first[g]:self.group_first[g + 1]].sum())
+               for g in range(len(self.group_first) - 1)]
+        return max(tot) if tot else 0
+
+
+class _Zipf:
+    """Ranks in [0, n) with probability proportional to 1 / (rank + 1)^a (inverse-CDF draws)."""
+
+    def __init__(self, n: int, a: float = 1.1):
+        self.n = n
+        self.cdf = np.cumsum(1.0 / np.power(np.arange(1, n + 1, dtype=np.float64), a))
+
+    def draw(self, rng: np.random.Generator, size: int) -> np.ndarray:
+        u = rng.random(size) * self.cdf[-1]
+        return np.minimum(np.searchsorted(self.cdf, u, side="right"), self.n - 1).astype(np.int64)
+
+
+def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_max: int = 8, top_k: int = 1,
+                      p_min: int = 2, p_max: int = 8, min_confidence: float = 0.0, horizon: int = 16,
+                      n_phrases: int = 1024, phrase_prob: float = 0.3, own_only: bool = False,
+                      refs_per_group: Optional[int] = None, max_spec_tokens=None) -> DraftInputs:
+    """Responses of a prompt group as the paper describes them (Section 2.3: responses to one prompt
+    share recurring phrases; later requests find more of them in their group's history): every group
+    draws a bank of `n_phrases` phrases (3..24 tokens, Zipf-distributed token ids under a seeded
+    permutation of the vocabulary; half of them repeat the first tokens of an earlier phrase, so that
+    a pattern can have several continuations); a response is a run of pieces, each with probability `phrase_prob`
+    a phrase of the bank (Zipf-distributed choice), otherwise 1..8 free Zipf tokens.  Sequence lengths
+    follow the configuration's context lengths (without the shared prompt and the verify slots).  The
+    pool gives every sequence some spare room after its tokens, filled with decoy tokens that repeat
+    the sequence's own tail (so a reader that runs past seq_len finds plausible matches and fails).
+    `refs_per_group` = number of sequences of each group that are in the pool (default: all
+    group_size); `own_only` keeps just the request's own sequence (the no-reference baseline)."""
+    seed = cfg.seed if seed is None else seed
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 3])))
+    B, V, gs = cfg.B, cfg.V, cfg.group_size
+    n_groups = (B + gs - 1) // gs
+    ctx = draw_ctx_len(cfg, rng).astype(np.int64)
+    resp_len = np.maximum(ctx - cfg.T - cfg.shared_prefix, 0)
+    perm = rng.permutation(V)
+    zip_v, zip_ph = _Zipf(V), _Zipf(max(1, n_phrases))
+    seqs, futures = [], []
+    for g in range(n_groups):
+        ph_len = rng.integers(3, 25, size=zip_ph.n)
+        bank = []
+        for l in ph_len:                                  # half of the phrases start like an earlier one
+            ph = perm[zip_v.draw(rng, int(l))]
+            if bank and rng.random() < 0.5:
+                src = bank[int(rng.integers(0, len(bank)))]
+                n_same = int(rng.integers(1, min(len(src), len(ph))))
+                ph[:n_same] = src[:n_same]
+            bank.append(ph)
+        for m in range(gs):
+            b = g * gs + m
+            want = int(resp_len[min(b, B - 1)]) + horizon
+            n_pieces = want // 2 + 2                      # every piece has at least one token
+            is_ph = rng.random(n_pieces) < phrase_prob
+            ph_id = zip_ph.draw(rng, n_pieces)
+            free_n = rng.integers(1, 9, size=n_pieces)
+            free_tok = perm[zip_v.draw(rng, int(free_n.sum()))]
+            free_at = np.concatenate([[0], np.cumsum(free_n)])
+            parts, have, i = [], 0, 0
+            while have < want:
+                piece = bank[int(ph_id[i])] if is_ph[i] else free_tok[free_at[i]:free_at[i + 1]]
+                parts.append(piece)
+                have += len(piece)
+                i += 1
+            full = np.concatenate(parts)[:want].astype(np.int32)
+            seqs.append(full[:want - horizon])
+            futures.append(full[want - horizon:])
+    # pool layout: the sequences of a group are neighbours; each is followed by 0..63 decoy tokens
+    n_in_pool = gs if refs_per_group is None else max(1, min(gs, refs_per_group))
+    starts, lens, chunks, group_first, seq_of = [], [], [], [0], {}
+    pos = int(rng.integers(0, 8))
+    chunks.append(rng.integers(0, V, size=pos).astype(np.int32))
+    for g in range(n_groups):
+        for m in range(g * gs, g * gs + gs):
+            live = m < B
+            if own_only and not live:
+                continue
+            if not own_only and (m - g * gs) >= n_in_pool and not live:
+                continue
+            s_ = seqs[m]
+            gap = int(rng.integers(0, 64))
+            decoy = np.resize(s_[-64:], gap) if len(s_) else rng.integers(0, V, size=gap)
+            seq_of[m] = len(starts)
+            starts.append(pos)
+            lens.append(len(s_))
+            chunks += [s_, np.asarray(decoy, np.int32)]
+            pos += len(s_) + gap
+            if own_only:
+                group_first.append(len(starts))       # a group of its own: no references
+        if not own_only:
+            group_first.append(len(starts))
+    req_group = np.arange(B, dtype=np.int32) if own_only else (np.arange(B) // gs).astype(np.int32)
+    tokens = np.concatenate(chunks + [np.zeros(4, np.int32)]).astype(np.int32)
+    pattern = np.full((B, p_max), -1, np.int32)
+    pattern_len = np.zeros(B, np.int32)
+    for b in range(B):
+        s = seqs[b]
+        n = min(len(s), p_max)
+        pattern_len[b] = n
+        if n:
+            pattern[b, p_max - n:] = s[-n:]
+    if max_spec_tokens is None:
+        max_spec_tokens = np.full(B, gamma_max, np.int32)
+    return DraftInputs(tokens=tokens, seq_start=np.asarray(starts, np.int32), seq_len=np.asarray(lens, np.int32),
+                       group_first=np.asarray(group_first, np.int32), req_group=req_group,
+                       req_seq=np.asarray([seq_of[b] for b in range(B)], np.int32), pattern=pattern,
+                       pattern_len=pattern_len, max_spec_tokens=np.asarray(max_spec_tokens, np.int32),
+                       future=np.stack(futures[:B]) if B else np.zeros((0, horizon), np.int32),
+                       gamma_max=gamma_max, top_k=top_k, p_min=p_min, p_max=p_max,
+                       min_confidence=float(min_confidence), vocab=V)
