@@ -244,6 +244,76 @@ int seer_mba_draft_lengths(int32_t B_h, int32_t B_l, const double* beta, int32_t
                            double lambda, const double* step_time, int32_t* gamma_h, int32_t* gamma_l,
                            int32_t* gamma_star);
 
+/*
+ * Grouped n-gram drafting: the step right before verification (Section 2.3, pattern level: the
+ * token histories of all requests of a prompt group serve as n-gram reference; Section 3.4.2 and
+ * Appendix A.2, draft client call batch_speculate with SpeculationArgs max_spec_tokens,
+ * pattern_lookup_max, pattern_lookup_min, top_k: confidence scores from the suffix statistics,
+ * low-probability candidates dropped, several paths by beam search).  It writes exactly the
+ * draft_tokens / tree_parent / tree_mask that seer_verify_attention and seer_accept read.
+ *
+ * Token histories live in one caller-owned pool: sequence q holds tokens[seq_start[q] ..
+ * seq_start[q] + seq_len[q]); group g owns sequences group_first[g] .. group_first[g+1]-1.  The
+ * caller appends new tokens in place and raises seq_len (nothing is indexed, so there is nothing
+ * else to update).  No n-gram runs from one sequence into another.
+ *
+ * For request b, with its newest tokens as pattern (pattern[b] is right-aligned: the newest token
+ * is pattern[b][pattern_lookup_max - 1], the first pattern_lookup_max - pattern_len[b] entries are
+ * not read):
+ *   match  = the longest pattern suffix, of max(pattern_lookup_min, 1) .. min(pattern_len[b],
+ *            pattern_lookup_max) tokens, that occurs in a sequence of the group FOLLOWED by at
+ *            least one more token of that sequence; none -> root-only draft, match_len 0.
+ *   count  of a path c_1..c_d = number of places where match c_1..c_d occurs; n_root = number of
+ *            places where the match occurs with a continuation.  Confidence = count / n_root.
+ *   beam   level d (1 .. min(max_spec_tokens[b], gamma_max)) = the first top_k, ordered by (count
+ *            descending, rank of the parent in level d-1 ascending, token ascending), of the
+ *            one-token extensions of level d-1 with count >= 1, token in [0, vocab) and
+ *            (float)count >= min_confidence * (float)n_root (fp32); stops at an empty level.
+ *   slots  T = 1 + top_k * gamma_max <= 64.  Slot 0 = root (token = newest pattern token, parent
+ *            -1).  Rank j of level d -> slot 1 + (d-1)*top_k + j, parent = its parent's slot.
+ *            Every member of every level is a draft node.  Unused slots: token -1, parent -2,
+ *            count 0, mask = own bit.  tree_mask[t] = own bit | tree_mask[parent].
+ * The result is unique (integer counts, total order), whatever order the places are found in.
+ *
+ * Limits: top_k <= 16, pattern_lookup_max <= 32, vocab <= 2^24, at most 128 sequences per group,
+ * sequences shorter than 2^20 tokens, pool_tokens < 2^31.  A request whose group id, sequence
+ * table or sequence ranges are out of range gets a root-only draft and raises bit 0 of *status; one
+ * whose group holds more than max_group_tokens tokens raises bit 1 (the caller clears status).
+ */
+typedef struct seer_draft_params {
+    int32_t B;                  /* requests                                                   */
+    int32_t n_groups, n_seq;    /* entries of group_first minus one; of seq_start / seq_len   */
+    int64_t pool_tokens;        /* entries of tokens                                          */
+    int32_t max_group_tokens;   /* bound on the sum of seq_len over one group (sizes the workspace) */
+    int32_t gamma_max, top_k;
+    int32_t pattern_lookup_min, pattern_lookup_max;
+    int32_t vocab;
+    float min_confidence;       /* 0 .. 1                                                     */
+} seer_draft_params;
+
+/* Bytes of device scratch seer_draft needs (two place lists of max_group_tokens entries per
+ * request); 0 on invalid params.  Host-only. */
+size_t seer_draft_workspace(const seer_draft_params* p);
+
+/*
+ *  tokens, seq_start, seq_len, group_first   device int32, as above
+ *  req_group        device [B] int32
+ *  pattern          device [B, pattern_lookup_max] int32;  pattern_len device [B] int32
+ *  max_spec_tokens  device [B] int32 (the per-request draft length, e.g. from seer_mba_draft_lengths)
+ *  draft_tokens, tree_parent  device [B,T] int32, written;  tree_mask device [B,T] uint64, written
+ *  node_count       device [B,T] int32 or NULL, written: count of each node, slot 0 = n_root
+ *  match_len        device [B] int32 or NULL, written
+ *  status           device [1] int32 or NULL, bits OR-ed in
+ *  workspace        device, >= seer_draft_workspace(p) bytes, 16-byte aligned
+ * Asynchronous on hip_stream; returns SEER_OK, a negative SEER_E* or a positive hipError_t.
+ */
+int seer_draft(const int32_t* tokens, const int32_t* seq_start, const int32_t* seq_len,
+               const int32_t* group_first, const int32_t* req_group, const int32_t* pattern,
+               const int32_t* pattern_len, const int32_t* max_spec_tokens, const seer_draft_params* p,
+               int32_t* draft_tokens, int32_t* tree_parent, uint64_t* tree_mask, int32_t* node_count,
+               int32_t* match_len, int32_t* status, void* workspace, size_t workspace_bytes,
+               void* hip_stream);
+
 /* Static text for a return code of either call (negative SEER_E*, or a
  * positive hipError_t). */
 const char* seer_strerror(int code);

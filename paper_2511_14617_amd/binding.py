@@ -20,7 +20,7 @@ SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALI
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
            "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
-           "seer_kv_commit", "seer_mba_draft_lengths", "seer_strerror")
+           "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_strerror")
 
 
 class SeerAttnParams(ctypes.Structure):
@@ -29,6 +29,13 @@ class SeerAttnParams(ctypes.Structure):
                 ("num_pages", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
                 ("max_splits", ctypes.c_int32), ("kv_shared_latent", ctypes.c_int32), ("flags", ctypes.c_int32),
                 ("scale", ctypes.c_float)]
+
+class SeerDraftParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("n_groups", ctypes.c_int32), ("n_seq", ctypes.c_int32),
+                ("pool_tokens", ctypes.c_int64), ("max_group_tokens", ctypes.c_int32), ("gamma_max", ctypes.c_int32),
+                ("top_k", ctypes.c_int32), ("pattern_lookup_min", ctypes.c_int32),
+                ("pattern_lookup_max", ctypes.c_int32), ("vocab", ctypes.c_int32), ("min_confidence", ctypes.c_float)]
+
 
 SEER_ATTN_GENERAL_KERNEL = 1
 SEER_ATTN_FIXED_SPLIT = 2
@@ -72,6 +79,10 @@ def load_library() -> ctypes.CDLL:
         lib.seer_kv_commit.restype = ctypes.c_int
         lib.seer_mba_draft_lengths.argtypes = [i32, i32, vp, i32, i32, ctypes.c_double, vp, vp, vp, vp]
         lib.seer_mba_draft_lengths.restype = ctypes.c_int
+        lib.seer_draft_workspace.argtypes = [ctypes.POINTER(SeerDraftParams)]
+        lib.seer_draft_workspace.restype = sz
+        lib.seer_draft.argtypes = [vp] * 8 + [ctypes.POINTER(SeerDraftParams)] + [vp] * 7 + [sz, vp]
+        lib.seer_draft.restype = ctypes.c_int
         lib.seer_strerror.argtypes = [ctypes.c_int]
         lib.seer_strerror.restype = ctypes.c_char_p
         _lib = lib
@@ -259,3 +270,58 @@ def seer_mba_draft_lengths(B_h: int, B_l: int, beta, gamma_max: int, lam: float,
     _check(lib.seer_mba_draft_lengths(B_h, B_l, bt, len(beta), gamma_max, float(lam), st, ctypes.byref(gh),
                                       ctypes.byref(gl), ctypes.byref(gs)))
     return gh.value, gl.value, gs.value
+
+
+def seer_draft_workspace(params: SeerDraftParams) -> int:
+    return int(load_library().seer_draft_workspace(ctypes.byref(params)))
+
+
+def seer_draft(tokens: torch.Tensor, seq_start: torch.Tensor, seq_len: torch.Tensor, group_first: torch.Tensor,
+               req_group: torch.Tensor, pattern: torch.Tensor, pattern_len: torch.Tensor, max_spec_tokens: torch.Tensor,
+               *, gamma_max: int, top_k: int, pattern_lookup_min: int, vocab: int, max_group_tokens: int,
+               min_confidence: float = 0.0, status: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+               out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """Draft trees from the token histories of each request's prompt group.  All tensors int32 on the device:
+    tokens [pool], seq_start/seq_len [n_seq], group_first [n_groups + 1], req_group [B], pattern [B, p_max]
+    (right-aligned), pattern_len [B], max_spec_tokens [B].  Returns (draft_tokens [B,T] int32, tree_parent
+    [B,T] int32, tree_mask [B,T] int64 holding the uint64 bits, node_count [B,T] int32, match_len [B] int32),
+    T = 1 + top_k * gamma_max."""
+    lib = load_library()
+    B, p_max = pattern.shape
+    n_seq, n_groups = seq_start.shape[0], group_first.shape[0] - 1
+    T = 1 + top_k * gamma_max
+    _want(tokens, torch.int32, (tokens.shape[0],), "tokens")
+    _want(seq_start, torch.int32, (n_seq,), "seq_start")
+    _want(seq_len, torch.int32, (n_seq,), "seq_len")
+    _want(group_first, torch.int32, (n_groups + 1,), "group_first")
+    _want(req_group, torch.int32, (B,), "req_group")
+    _want(pattern, torch.int32, (B, p_max), "pattern")
+    _want(pattern_len, torch.int32, (B,), "pattern_len")
+    _want(max_spec_tokens, torch.int32, (B,), "max_spec_tokens")
+    p = SeerDraftParams(B, n_groups, n_seq, tokens.shape[0], int(max_group_tokens), gamma_max, top_k,
+                        pattern_lookup_min, p_max, vocab, float(min_confidence))
+    dev = tokens.device
+    if out is None:
+        d_tok = torch.empty((B, T), dtype=torch.int32, device=dev)
+        d_par = torch.empty((B, T), dtype=torch.int32, device=dev)
+        d_msk = torch.empty((B, T), dtype=torch.int64, device=dev)
+        d_cnt = torch.empty((B, T), dtype=torch.int32, device=dev)
+        d_len = torch.empty(B, dtype=torch.int32, device=dev)
+    else:
+        d_tok, d_par, d_msk, d_cnt, d_len = out
+        _want(d_tok, torch.int32, (B, T), "draft_tokens")
+        _want(d_par, torch.int32, (B, T), "tree_parent")
+        _want(d_msk, torch.int64, (B, T), "tree_mask")
+        _want(d_cnt, torch.int32, (B, T), "node_count")
+        _want(d_len, torch.int32, (B,), "match_len")
+    if status is not None:
+        _want(status, torch.int32, (1,), "status")
+    need = int(lib.seer_draft_workspace(ctypes.byref(p)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _check(lib.seer_draft(_ptr(tokens), _ptr(seq_start), _ptr(seq_len), _ptr(group_first), _ptr(req_group),
+                          _ptr(pattern), _ptr(pattern_len), _ptr(max_spec_tokens), ctypes.byref(p), _ptr(d_tok),
+                          _ptr(d_par), _ptr(d_msk), _ptr(d_cnt), _ptr(d_len), _ptr(status), _ptr(workspace),
+                          workspace.numel(), _stream_handle(stream)))
+    return d_tok, d_par, d_msk, d_cnt, d_len

@@ -152,6 +152,62 @@ def test_sampled_accept_and_commit_argument_errors_before_any_launch(lib):
     assert commit(_params(B=0)) == b.SEER_OK
 
 
+def _draft_params(**kw):
+    from paper_2511_14617_amd.binding import SeerDraftParams
+    base = dict(B=4, n_groups=1, n_seq=4, pool_tokens=5000, max_group_tokens=4000, gamma_max=8, top_k=4,
+                pattern_lookup_min=2, pattern_lookup_max=8, vocab=152064, min_confidence=0.0)
+    base.update(kw)
+    return SeerDraftParams(**base)
+
+
+def test_draft_params_struct_matches_header():
+    from paper_2511_14617_amd.binding import SeerDraftParams
+    header = open(os.path.join(ROOT, "include", "seer_verify.h")).read()
+    struct = re.search(r"typedef struct seer_draft_params \{(.*?)\} seer_draft_params;", header, flags=re.S).group(1)
+    struct = re.sub(r"/\*.*?\*/", "", struct, flags=re.S)
+    fields = []
+    for decl in struct.split(";"):
+        decl = decl.strip()
+        if decl:
+            ctype, names = decl.split(None, 1)
+            fields += [(n.strip(), ctype) for n in names.split(",")]
+    want = {"int32_t": ctypes.c_int32, "int64_t": ctypes.c_int64, "float": ctypes.c_float}
+    assert [(n, want[t]) for n, t in fields] == list(SeerDraftParams._fields_)
+
+
+def test_draft_argument_errors_before_any_launch(lib):
+    from paper_2511_14617_amd import binding as b
+    fake = 0x1000
+
+    def run(p, tokens=fake, out=fake, ws=0x10000, ws_bytes=1 << 40):
+        return lib.seer_draft(tokens, fake, fake, fake, fake, fake, fake, fake, ctypes.byref(p), out, fake, fake,
+                              None, None, None, ws, ws_bytes, None)
+
+    assert lib.seer_draft(*([fake] * 8), None, fake, fake, fake, None, None, None, fake, 1 << 40, None) == b.SEER_EINVAL
+    assert run(_draft_params(top_k=0)) == b.SEER_EINVAL
+    assert run(_draft_params(gamma_max=0)) == b.SEER_EINVAL
+    assert run(_draft_params(vocab=0)) == b.SEER_EINVAL
+    assert run(_draft_params(min_confidence=float("nan"))) == b.SEER_EINVAL
+    assert run(_draft_params(min_confidence=1.5)) == b.SEER_EINVAL
+    assert run(_draft_params(max_group_tokens=0)) == b.SEER_EINVAL
+    assert run(_draft_params(top_k=8, gamma_max=8)) == b.SEER_ESHAPE          # 65 slots
+    assert run(_draft_params(pattern_lookup_min=9)) == b.SEER_ESHAPE
+    assert run(_draft_params(top_k=17, gamma_max=2)) == b.SEER_EUNSUPPORTED
+    assert run(_draft_params(pattern_lookup_max=33)) == b.SEER_EUNSUPPORTED
+    assert run(_draft_params(vocab=(1 << 24) + 1)) == b.SEER_EUNSUPPORTED
+    assert run(_draft_params(pool_tokens=1 << 31)) == b.SEER_EUNSUPPORTED
+    assert run(_draft_params(), tokens=None) == b.SEER_EINVAL
+    assert run(_draft_params(), out=None) == b.SEER_EINVAL
+    assert run(_draft_params(), ws=None) == b.SEER_EWORKSPACE
+    assert run(_draft_params(), ws_bytes=1024) == b.SEER_EWORKSPACE
+    assert run(_draft_params(), ws=0x10004) == b.SEER_EALIGN
+    assert run(_draft_params(B=0)) == b.SEER_OK
+    small = b.seer_draft_workspace(_draft_params())
+    assert small > 0 and small % 256 == 0
+    assert b.seer_draft_workspace(_draft_params(max_group_tokens=800000, B=8)) >= 2 * 8 * 800000 * 4
+    assert b.seer_draft_workspace(_draft_params(top_k=17)) == 0
+
+
 def test_product_path_fails_loudly_without_the_library(tmp_path, monkeypatch):
     from paper_2511_14617_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

@@ -1,0 +1,240 @@
+"""GPU parity, through the C ABI, of grouped n-gram drafting (seer_draft) against the CPU oracle: draft
+tokens, parents, ancestor masks, node counts and match lengths, bit for bit.  The result is unique (integer
+counts, a total order), so everything is compared."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import draft_oracle as D
+import oracle
+from paper_2511_14617_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _gpu_draft(d, *, status=None, max_group_tokens=None, workspace=None):
+    from paper_2511_14617_amd import binding
+    dev = "cuda"
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+    out = binding.seer_draft(t(d.tokens), t(d.seq_start), t(d.seq_len), t(d.group_first), t(d.req_group), t(d.pattern),
+                             t(d.pattern_len), t(d.max_spec_tokens), gamma_max=d.gamma_max, top_k=d.top_k,
+                             pattern_lookup_min=d.p_min, vocab=d.vocab,
+                             max_group_tokens=max(d.max_group_tokens, 1) if max_group_tokens is None else max_group_tokens,
+                             min_confidence=d.min_confidence, status=status, workspace=workspace)
+    torch.cuda.synchronize()
+    tok, par, msk, cnt, mlen = [x.cpu().numpy() for x in out]
+    return tok, par, msk.view(np.uint64), cnt, mlen
+
+
+def _oracle_draft(d):
+    return D.batch_speculate(d.tokens, d.seq_start, d.seq_len, d.group_first, d.req_group, d.pattern, d.pattern_len,
+                             d.max_spec_tokens, gamma_max=d.gamma_max, top_k=d.top_k, p_min=d.p_min, p_max=d.p_max,
+                             min_confidence=d.min_confidence, vocab=d.vocab)
+
+
+def _compare(d, what=""):
+    got, want = _gpu_draft(d), _oracle_draft(d)
+    for name, g, w in zip(("match_len", "node_count", "tree_parent", "draft_tokens", "tree_mask"),
+                          (got[4], got[3], got[1], got[0], got[2]), (want[4], want[3], want[1], want[0], want[2])):
+        bad = np.argwhere(g != w)
+        assert bad.size == 0, "%s %s: first difference at %s: gpu %s, oracle %s" % (
+            what, name, bad[0], g[tuple(bad[0])], w[tuple(bad[0])])
+    return want
+
+
+def _from_lists(seqs_per_group, req_group, patterns, *, gamma_max, top_k, p_min, p_max, vocab, min_confidence=0.0,
+                max_spec=None, gap=3):
+    """DraftInputs from explicit token lists (decoy tokens that repeat the sequence's tail fill the gaps)."""
+    chunks, starts, lens, group_first, pos = [], [], [], [0], 0
+    for seqs in seqs_per_group:
+        for s in seqs:
+            s = np.asarray(s, np.int32)
+            starts.append(pos)
+            lens.append(len(s))
+            decoy = np.resize(s[-gap:], gap) if len(s) else np.zeros(gap, np.int32)
+            chunks += [s, decoy.astype(np.int32)]
+            pos += len(s) + gap
+        group_first.append(len(starts))
+    B = len(req_group)
+    pattern = np.full((B, p_max), -1, np.int32)
+    plen = np.zeros(B, np.int32)
+    for b, p in enumerate(patterns):
+        p = list(p)[-p_max:]
+        plen[b] = len(p)
+        if p:
+            pattern[b, p_max - len(p):] = p
+    return W.DraftInputs(tokens=np.concatenate(chunks + [np.zeros(4, np.int32)]).astype(np.int32),
+                         seq_start=np.asarray(starts, np.int32), seq_len=np.asarray(lens, np.int32),
+                         group_first=np.asarray(group_first, np.int32), req_group=np.asarray(req_group, np.int32),
+                         req_seq=np.zeros(B, np.int32), pattern=pattern, pattern_len=plen,
+                         max_spec_tokens=np.full(B, gamma_max, np.int32) if max_spec is None else np.asarray(max_spec, np.int32),
+                         future=np.zeros((B, 1), np.int32), gamma_max=gamma_max, top_k=top_k, p_min=p_min, p_max=p_max,
+                         min_confidence=min_confidence, vocab=vocab)
+
+
+def test_hand_counted_examples_on_the_gpu():
+    ints = lambda txt: [int(x) for x in txt.split()]
+    n = 0
+    for line in open(os.path.join(ROOT, "tests", "golden", "draft_worked_examples.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        seqs, pat, args, mlen, tok, par, cnt = [f.strip() for f in line.split("|")]
+        a = args.split()
+        d = _from_lists([[ints(s) for s in seqs.split(";")]], [0], [ints(pat)], gamma_max=int(a[2]), top_k=int(a[3]),
+                        p_min=int(a[0]), p_max=int(a[1]), vocab=int(a[5]), min_confidence=float(a[4]))
+        got = _gpu_draft(d)
+        assert got[4][0] == int(mlen) and got[0][0].tolist() == ints(tok)
+        assert got[1][0].tolist() == ints(par) and got[3][0].tolist() == ints(cnt)
+        n += 1
+    assert n >= 7
+
+
+@pytest.mark.parametrize("top_k,gamma_max,p_min,p_max,conf", [(1, 8, 2, 8, 0.0), (4, 8, 2, 8, 0.0), (2, 6, 1, 4, 0.05),
+                                                                (7, 9, 1, 32, 0.0), (16, 3, 3, 5, 0.01), (3, 21, 0, 6, 0.3)])
+def test_grouped_histories_reduced(top_k, gamma_max, p_min, p_max, conf):
+    cfg = W.CONFIGS[2].scaled(B=24, ctx=("lognormal", 2500, 0.7, 530, 9000))
+    d = W.make_draft_inputs(cfg, seed=500 + top_k, gamma_max=gamma_max, top_k=top_k, p_min=p_min, p_max=p_max,
+                            min_confidence=conf)
+    rng = np.random.default_rng(top_k)
+    d.max_spec_tokens[:] = rng.integers(0, gamma_max + 1, size=cfg.B)
+    d.max_spec_tokens[:4] = gamma_max
+    d.pattern_len[5] = 0                                   # a request with no history yet
+    d.pattern_len[6] = min(1, p_max)                       # shorter than p_min for most cases
+    want = _compare(d, "reduced k=%d" % top_k)
+    assert (want[4] > 0).sum() >= cfg.B // 2               # most requests find a match
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_tiny_vocabulary_many_places(seed):
+    """A vocabulary of 2..4 tokens: every pattern occurs thousands of times (the hash table runs full-size,
+    member lists are long) and almost every count ties with another."""
+    rng = np.random.default_rng(900 + seed)
+    vocab = int(rng.integers(2, 5))
+    groups = [[rng.integers(0, vocab, size=int(rng.integers(0, 6000))).tolist() for _ in range(int(rng.integers(1, 6)))]
+              for _ in range(3)]
+    B = 9
+    p_max = int(rng.integers(1, 4))
+    pats = [rng.integers(0, vocab, size=int(rng.integers(1, 7))).tolist() for _ in range(B)]
+    d = _from_lists(groups, rng.integers(0, 3, size=B), pats, gamma_max=int(rng.integers(2, 7)), top_k=int(rng.integers(1, 5)),
+                    p_min=1, p_max=p_max, vocab=vocab, min_confidence=float(rng.choice([0.0, 0.1, 0.26])))
+    want = _compare(d, "tiny vocabulary")
+    assert want[3][:, 0].max() > 100
+
+
+def test_more_distinct_continuations_than_table_slots():
+    """The newest token is followed by 6000 different tokens: the hash table (4096 slots) overflows and the
+    counting falls back to passes over token ranges.  A few continuations are repeated so that the top of
+    the order is decided by counts, the rest by token ids."""
+    rng = np.random.default_rng(31)
+    vocab = 20000
+    follow = rng.permutation(vocab - 1)[:6000] + 1
+    follow = np.concatenate([follow, follow[:3], follow[:2], follow[10:11]])     # counts 3, 3, 2, 2 (one of them 11th)
+    seq = np.stack([np.zeros(len(follow), np.int64), rng.permutation(follow)], axis=1).reshape(-1)
+    seq2 = np.stack([np.zeros(500, np.int64), follow[:500][::-1], follow[1:501]], axis=1).reshape(-1)
+    d = _from_lists([[seq.tolist(), seq2.tolist()]], [0, 0], [[5, 0], [0]], gamma_max=3, top_k=4, p_min=1, p_max=2,
+                    vocab=vocab)
+    want = _compare(d, "table overflow")
+    assert want[3][0, 0] >= 6000 and want[3][0, 1] >= 3
+
+
+def test_long_sequences_span_many_parts():
+    cfg = W.CONFIGS[3].scaled(B=3, group_size=3, ctx=("uniform", 30000, 50000))
+    d = W.make_draft_inputs(cfg, gamma_max=8, top_k=2, p_min=2, p_max=8)
+    _compare(d, "long sequences")
+
+
+def test_requests_with_unusable_inputs_get_a_root_only_draft_and_a_status_bit():
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[1].scaled(B=8, group_size=4)
+    d = W.make_draft_inputs(cfg, gamma_max=4, top_k=2, p_min=1, p_max=4)
+    good = _oracle_draft(d)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    got = _gpu_draft(d, status=status)
+    assert int(status.item()) == 0 and np.array_equal(got[0], good[0])
+    d.req_group[2] = 7                                      # no such group
+    d.seq_len[d.group_first[1]] = 1 << 21                   # group 1: a sequence running out of the pool
+    status.zero_()
+    got = _gpu_draft(d, status=status)
+    assert int(status.item()) == 1
+    for b in range(cfg.B):
+        if b == 2 or d.req_group[b] == 1:
+            assert got[4][b] == 0 and (got[1][b, 1:] == -2).all() and got[0][b, 0] == d.pattern[b, -1]
+        else:
+            assert np.array_equal(got[0][b], good[0][b]) and np.array_equal(got[1][b], good[1][b])
+    # a group that holds more tokens than the workspace was sized for
+    d = W.make_draft_inputs(cfg, gamma_max=4, top_k=2, p_min=1, p_max=4)
+    sizes = [int(d.seq_len[d.group_first[g]:d.group_first[g + 1]].sum()) for g in range(2)]
+    status.zero_()
+    got = _gpu_draft(d, status=status, max_group_tokens=min(sizes))
+    assert int(status.item()) == 2
+    small = int(np.argmin(sizes))
+    for b in range(cfg.B):
+        if d.req_group[b] == small:
+            assert np.array_equal(got[0][b], good[0][b])
+        else:
+            assert got[4][b] == 0 and (got[1][b, 1:] == -2).all()
+
+
+def test_workspace_contents_do_not_matter():
+    """Two calls on one workspace filled with ones, a smaller batch second: same results as fresh calls."""
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[2].scaled(B=16, ctx=("lognormal", 2500, 0.7, 530, 9000))
+    d1 = W.make_draft_inputs(cfg, seed=1, gamma_max=8, top_k=4)
+    d2 = W.make_draft_inputs(cfg.scaled(B=8), seed=2, gamma_max=8, top_k=4)
+    p = binding.SeerDraftParams(cfg.B, 2, 16, len(d1.tokens), max(d1.max_group_tokens, d2.max_group_tokens), 8, 4, 2, 8,
+                                cfg.V, 0.0)
+    ws = torch.full((binding.seer_draft_workspace(p),), 0xFF, dtype=torch.uint8, device="cuda")
+    for d in (d1, d2):
+        got = _gpu_draft(d, workspace=ws, max_group_tokens=max(d1.max_group_tokens, d2.max_group_tokens))
+        want = _oracle_draft(d)
+        assert all(np.array_equal(g, w) for g, w in zip(got, want))
+
+
+@pytest.mark.parametrize("config_id,top_k,gamma_max", [(2, 1, 8), (3, 1, 16), (5, 4, 8)])
+def test_full_size_configs(config_id, top_k, gamma_max):
+    """The token histories that go with the verification workloads, at full size, every request compared."""
+    cfg = W.CONFIGS[config_id]
+    d = W.make_draft_inputs(cfg, gamma_max=gamma_max, top_k=top_k)
+    assert d.T == cfg.T
+    _compare(d, "config %d" % config_id)
+
+
+def test_draft_feeds_verification():
+    """seer_draft -> seer_accept on the device: logits that put the request's true next tokens on top accept
+    exactly the drafted root path that agrees with them."""
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[5].scaled(B=32, V=4099)
+    d = W.make_draft_inputs(cfg, gamma_max=8, top_k=4, n_phrases=64, phrase_prob=0.6)
+    dev = "cuda"
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+    tok, par, msk, cnt, mlen = binding.seer_draft(
+        t(d.tokens), t(d.seq_start), t(d.seq_len), t(d.group_first), t(d.req_group), t(d.pattern), t(d.pattern_len),
+        t(d.max_spec_tokens), gamma_max=8, top_k=4, pattern_lookup_min=d.p_min, vocab=cfg.V,
+        max_group_tokens=d.max_group_tokens)
+    h_tok, h_par = tok.cpu().numpy(), par.cpu().numpy()
+    T = h_tok.shape[1]
+    rng = np.random.default_rng(3)
+    logits = rng.normal(size=(cfg.B, T, cfg.V)).astype(np.float32)
+    expect = np.zeros(cfg.B, np.int32)
+    for b in range(cfg.B):
+        depth, ok = {0: 0}, {0: True}
+        logits[b, 0, d.future[b, 0]] = 9.0
+        for s in range(1, T):
+            p = int(h_par[b, s])
+            if p < 0:
+                continue
+            depth[s] = depth[p] + 1
+            ok[s] = ok[p] and h_tok[b, s] == d.future[b, depth[s] - 1]
+            if ok[s]:
+                expect[b] = max(expect[b], depth[s])
+                logits[b, s, d.future[b, depth[s]]] = 9.0     # a model that continues the true sequence
+    alen, path, bonus, tgt = binding.seer_accept(torch.from_numpy(logits).to(dev), tok, par)
+    torch.cuda.synchronize()
+    assert np.array_equal(alen.cpu().numpy(), expect)
+    ra, rp, rb = oracle.accept(logits.argmax(-1).astype(np.int32), h_tok, h_par)
+    assert np.array_equal(alen.cpu().numpy(), ra) and np.array_equal(path.cpu().numpy(), rp)
+    assert expect.mean() > 1.0
+    assert np.array_equal(bonus.cpu().numpy(), d.future[np.arange(cfg.B), expect])
