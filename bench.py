@@ -262,6 +262,31 @@ def main() -> int:
             n_copy.copy_(d["ctx_len"])
             binding.seer_kv_commit(d["k_pages"], d["v_pages"], d["block_table"], n_copy, acc_out[0], acc_out[1])
         commit_ms = timed(commit)
+    # the step before verification (not part of `value` either): drafts from the groups' token histories
+    draft_info = None
+    if not args.attention_only:
+        top_k, gamma = cfg.tree if cfg.tree else (1, cfg.T - 1)
+        dr = W.make_draft_inputs(cfg, gamma_max=gamma, top_k=top_k)
+        t32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+        dd = [t32(x) for x in (dr.tokens, dr.seq_start, dr.seq_len, dr.group_first, dr.req_group, dr.pattern,
+                               dr.pattern_len, dr.max_spec_tokens)]
+        dp = binding.SeerDraftParams(cfg.B, len(dr.group_first) - 1, len(dr.seq_start), len(dr.tokens),
+                                     dr.max_group_tokens, gamma, top_k, dr.p_min, dr.p_max, cfg.V, 0.0)
+        ws_dr = torch.empty(binding.seer_draft_workspace(dp), dtype=torch.uint8, device=dev)
+        dr_out = (torch.empty((cfg.B, dr.T), dtype=torch.int32, device=dev), torch.empty((cfg.B, dr.T), dtype=torch.int32, device=dev),
+                  torch.empty((cfg.B, dr.T), dtype=torch.int64, device=dev), torch.empty((cfg.B, dr.T), dtype=torch.int32, device=dev),
+                  torch.empty(cfg.B, dtype=torch.int32, device=dev))
+
+        def draft():
+            binding.seer_draft(*dd, gamma_max=gamma, top_k=top_k, pattern_lookup_min=dr.p_min, vocab=cfg.V,
+                               max_group_tokens=dr.max_group_tokens, workspace=ws_dr, out=dr_out)
+        draft()
+        draft_ms = timed(draft, n=20)
+        scanned = int(sum(int(dr.seq_len[dr.group_first[g]:dr.group_first[g + 1]].sum()) for g in dr.req_group))
+        draft_info = {"draft_ms": draft_ms, "top_k": top_k, "gamma_max": gamma, "history_tokens": int(dr.seq_len.sum()),
+                      "tokens_scanned": scanned, "scan_GBps": scanned * 4 / (draft_ms * 1e-3) / 1e9,
+                      "mean_match_len": float(dr_out[4].float().mean().item()),
+                      "mean_draft_nodes": float((dr_out[1][:, 1:] >= 0).sum(1).float().mean().item())}
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -318,7 +343,7 @@ def main() -> int:
         "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
         "accept_logits_GBps": (acc.logits.nbytes / (acc_ms * 1e-3) / 1e9) if acc_ms > 0 else None,
         "attention_status_word": status,
-        "accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms,
+        "accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms, "draft": draft_info,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(att, acc)

@@ -276,7 +276,7 @@ int seer_mba_draft_lengths(int32_t B_h, int32_t B_l, const double* beta, int32_t
  * The result is unique (integer counts, total order), whatever order the places are found in.
  *
  * Limits: top_k <= 16, pattern_lookup_max <= 32, vocab <= 2^24, at most 128 sequences per group,
- * sequences shorter than 2^20 tokens, pool_tokens < 2^31.  A request whose group id, sequence
+ * sequences shorter than 2^20 tokens, pool_tokens <= 2^31 - 2^16, tokens 16-byte aligned.  A request whose group id, sequence
  * table or sequence ranges are out of range gets a root-only draft and raises bit 0 of *status; one
  * whose group holds more than max_group_tokens tokens raises bit 1 (the caller clears status).
  */

@@ -39,8 +39,14 @@ constexpr int kMaxPattern = 32;           // pattern_lookup_max (5 bits of a pla
 constexpr int kMaxTopK = 16;
 constexpr int kTableSlots = 4096;         // LDS hash table: 4096 x (key, count) = 32 KB
 constexpr uint32_t kEmpty = 0xffffffffu;
-constexpr int kTokensPerPart = 8192;      // target stretch of one match workgroup
+#ifndef SEER_DRAFT_PART_TOKENS
+#define SEER_DRAFT_PART_TOKENS 8192
+#endif
+constexpr int kTokensPerPart = SEER_DRAFT_PART_TOKENS;   // target stretch of one match workgroup
 constexpr int kMaxParts = 64;
+constexpr int kSmall = 2048;              // places that the LDS-resident mode of the expansion holds
+constexpr int kAhead = 8;                 // levels of continuation tokens it fetches at a time, at most
+constexpr int kSolo = 256;                // at most this many live places: one wave finishes the search alone
 
 // A place = (sequence inside the group, offset of the token that follows the occurrence); while the
 // match is still being searched it also carries the match length.
@@ -76,7 +82,20 @@ struct Args {
     float min_confidence;
 };
 
-// The group's sequence table in LDS.  Returns 0 if usable, else the status bits to raise.
+__device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & 63; }
+
+// Index for each lane whose `hit` is set, from a counter in LDS: one atomic per wave instead of one per lane.
+__device__ __forceinline__ int wave_append(int* counter, bool hit) {
+    const uint64_t mask = __ballot(hit);
+    if (mask == 0) return 0;
+    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+    int base = 0;
+    if (lane_id() == leader) base = atomicAdd(counter, __popcll(mask));
+    base = __shfl(base, leader, 64);
+    return base + __popcll(mask & ((1ull << lane_id()) - 1));
+}
+
+// The group's sequence table in LDS; n_seq = 0 and bad != 0 if it cannot be used.
 struct GroupTable {
     int start[kMaxGroupSeqs];
     int len[kMaxGroupSeqs];
@@ -154,24 +173,38 @@ __global__ __launch_bounds__(kThreads) void draft_match_kernel(Args a) {
             const int i0 = max(lo - gt.flat[j], 0), i1 = min(hi - gt.flat[j], gt.len[j] - 1);
             if (i0 >= i1) continue;
             const int32_t* seq = a.tokens + gt.start[j];
-            for (int base = i0; base < i1; base += 4 * kThreads) {
-                int tok[4];
+            // 16-byte loads of aligned token quads; a quad may begin before the stretch or end after it
+            const int abs0 = gt.start[j] + i0, abs1 = gt.start[j] + i1;
+            for (int w0 = abs0 & ~3; w0 < abs1; w0 += 8 * kThreads) {      // the same trip count for every lane
+                const int q0 = w0 + 4 * tid;
+                int tok[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = base + u * kThreads + tid;
-                    tok[u] = i < i1 ? seq[i] : ~newest;
+                for (int u = 0; u < 2; ++u) {
+                    const int q = q0 + u * 4 * kThreads;
+                    if (q < abs1 && static_cast<int64_t>(q) + 4 <= a.pool_tokens) {
+                        const int4 v = *reinterpret_cast<const int4*>(a.tokens + q);
+                        tok[4 * u] = v.x, tok[4 * u + 1] = v.y, tok[4 * u + 2] = v.z, tok[4 * u + 3] = v.w;
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) tok[4 * u + c] = q + c < abs1 ? a.tokens[q + c] : ~newest;
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (tok[u] != newest) continue;
-                    const int i = base + u * kThreads + tid;
-                    const int limit = min(plen, i + 1);
-                    int m = 1;
-                    while (m < limit && seq[i - m] == s_pat[a.p_max - 1 - m]) ++m;
-                    if (m >= s_best) {             // a shorter match than one already seen can never win
-                        atomicMax(&s_best, m);
-                        out[atomicAdd(&s_kept, 1)] = pack_place(j, m, i + 1);
+                for (int c = 0; c < 8; ++c) {
+                    const int t = q0 + (c >> 2) * 4 * kThreads + (c & 3);
+                    int m = 0;
+                    if (tok[c] == newest && t >= abs0 && t < abs1) {
+                        const int i = t - gt.start[j];
+                        const int limit = min(plen, i + 1);
+                        m = 1;
+                        while (m < limit && seq[i - m] == s_pat[a.p_max - 1 - m]) ++m;
                     }
+                    // a shorter match than one already seen in this stretch can never win
+                    const bool keep = m >= s_best;
+                    if (__ballot(keep) == 0) continue;
+                    if (keep) atomicMax(&s_best, m);
+                    const int at = wave_append(&s_kept, keep);
+                    if (keep) out[at] = pack_place(j, m, t - gt.start[j] + 1);
                 }
             }
         }
@@ -193,203 +226,392 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 }
 
 struct Member {            // one beam member of the current level
-    int base, n, slot;     // its places are list[base .. base + n)
+    int base, n, slot;     // its places are list[base .. base + n) while the places live in global memory
 };
 
-__global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
-    __shared__ GroupTable gt;
-    __shared__ uint32_t s_key[kTableSlots];
-    __shared__ uint32_t s_cnt[kTableSlots];
-    __shared__ Member s_mem[kMaxTopK], s_next[kMaxTopK];
-    __shared__ uint64_t s_red[kThreads / 64];
-    __shared__ uint64_t s_pick[kMaxTopK];          // chosen children: count << 32 | ~key
-    __shared__ int s_fill[kMaxTopK];
-    __shared__ int s_tok[SEER_MAX_T], s_par[SEER_MAX_T], s_num[SEER_MAX_T];
-    __shared__ uint64_t s_msk[SEER_MAX_T];
-    __shared__ int s_n, s_best, s_nmem, s_overflow;
+// What the expansion keeps in LDS.
+struct Expand {
+    GroupTable gt;
+    uint32_t key[kTableSlots];
+    uint32_t cnt[kTableSlots];
+    int cont[kSmall * kAhead];             // LDS-resident mode: the next tokens of every place
+    uint32_t place[kSmall];
+    int8_t owner[kSmall];                  // rank of the member a place belongs to, -1 = dropped
+    int2 hdr[kMaxParts];
+    Member mem[kMaxTopK], next[kMaxTopK];
+    uint64_t red[kThreads / 64];
+    uint64_t pick[kMaxTopK];               // chosen children: count << 32 | ~key, best first
+    int fill[kMaxTopK];
+    int tok[SEER_MAX_T], par[SEER_MAX_T], num[SEER_MAX_T];
+    uint64_t msk[SEER_MAX_T];
+    int n, best, total, nmem, overflow;
+};
 
+// Workgroup barrier, or (SOLO: wave 0 works alone) only an ordering point for the wave's own LDS traffic.
+template <bool SOLO>
+__device__ __forceinline__ void level_sync() {
+    if (SOLO) {
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    } else {
+        __syncthreads();
+    }
+}
+
+// count[key] += n in the hash table (open addressing, linear probing).
+__device__ __forceinline__ void hash_add(Expand& x, int table, int shift, uint32_t key, uint32_t n) {
+    uint32_t h = (key * 2654435761u) >> shift;
+    for (int probes = 0; probes < table; ++probes) {
+        const uint32_t old = atomicCAS(&x.key[h], kEmpty, key);
+        if (old == kEmpty || old == key) {
+            atomicAdd(&x.cnt[h], n);
+            return;
+        }
+        h = (h + 1) & (table - 1);
+    }
+    x.overflow = 1;
+}
+
+// The lanes of a wave count their keys.  Places of one member mostly show the same few tokens, and atomics
+// of many lanes on one LDS word run one after the other, so lanes that hold the key of the first
+// uncounted lane are counted by that lane alone (two rounds), the rest one by one.
+__device__ __forceinline__ void hash_count(Expand& x, int table, int shift, uint32_t key, bool active) {
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+        const uint64_t act = __ballot(active);
+        if (act == 0) return;
+        const int leader = __ffsll(static_cast<long long>(act)) - 1;
+        const uint32_t k0 = __shfl(key, leader, 64);
+        const bool same = active && key == k0;
+        const uint64_t grp = __ballot(same);
+        if (lane_id() == leader) hash_add(x, table, shift, k0, static_cast<uint32_t>(__popcll(grp)));
+        active = active && !same;
+    }
+    if (active) hash_add(x, table, shift, key, 1u);
+}
+
+// The first top_k table entries in the order (count descending, key ascending) that pass the confidence
+// test join x.pick (kept sorted, best first, at most top_k long).  Every thread returns the new length.
+template <bool SOLO>
+__device__ __forceinline__ int pick_top(Expand& x, int slots, float threshold, int top_k, int n_pick) {
+    const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
+    for (int round = 0; round < top_k; ++round) {
+        uint64_t best = 0;
+        for (int s = me; s < slots; s += stride) {
+            const uint32_t c = x.cnt[s];
+            if (c == 0 || static_cast<float>(c) < threshold) continue;
+            const uint64_t v = (static_cast<uint64_t>(c) << 32) | static_cast<uint32_t>(~x.key[s]);
+            best = v > best ? v : best;
+        }
+        uint64_t win = wave_max_u64(best);
+        if (!SOLO) {
+            if (lane_id() == 0) x.red[threadIdx.x >> 6] = win;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < kThreads / 64; ++w) win = x.red[w] > win ? x.red[w] : win;
+        }
+        if (win == 0) {
+            level_sync<SOLO>();
+            break;
+        }
+        const uint32_t win_key = ~static_cast<uint32_t>(win);
+        for (int s = me; s < slots; s += stride)
+            if (x.key[s] == win_key) x.cnt[s] = 0;
+        if (me == 0) {
+            int at = n_pick < top_k ? n_pick : top_k - 1;
+            if (n_pick < top_k || win > x.pick[at]) {
+                while (at > 0 && x.pick[at - 1] < win) {
+                    x.pick[at] = x.pick[at - 1];
+                    --at;
+                }
+                x.pick[at] = win;
+            }
+        }
+        n_pick = min(n_pick + 1, top_k);
+        level_sync<SOLO>();
+    }
+    return n_pick;
+}
+
+// The picks of level d become draft nodes (thread `me == 0` only).
+__device__ __forceinline__ void emit_nodes(Expand& x, int d, int top_k, int n_pick) {
+    int base = 0;
+    for (int j = 0; j < n_pick; ++j) {
+        const uint32_t key = ~static_cast<uint32_t>(x.pick[j]);
+        const int c = static_cast<int>(x.pick[j] >> 32), r = static_cast<int>(key >> 24);
+        const int slot = 1 + (d - 1) * top_k + j, parent = x.mem[r].slot;
+        x.tok[slot] = static_cast<int>(key & 0xffffffu);
+        x.par[slot] = parent;
+        x.num[slot] = c;
+        x.msk[slot] = (1ull << slot) | x.msk[parent];
+        x.next[j] = Member{base, c, slot};            // x.mem is still needed until the places are reassigned
+        x.fill[j] = 0;
+        base += c;
+    }
+}
+
+// Levels d .. levels with the places in LDS.  !SOLO: the whole workgroup, until at most kSolo places are
+// alive; SOLO: wave 0 alone, no workgroup barriers.  Returns the next level (levels + 1 = finished).
+template <bool SOLO>
+__device__ __forceinline__ int lds_levels(const Args& a, Expand& x, int d, int levels, float threshold, int& n_places,
+                                          int& n_alive) {
+    const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
+    int fetched_from = 0, fetched = 0;                 // x.cont holds levels fetched_from .. fetched_from + fetched - 1
+    for (; d <= levels; ++d) {
+        if (!SOLO && n_alive <= kSolo) return d;
+        if (d >= fetched_from + fetched) {
+            if (SOLO) {
+                // drop the dead places first (one wave, chunk by chunk, writes never pass the reads)
+                int kept = 0;
+                for (int i0 = 0; i0 < n_places; i0 += 64) {
+                    const int i = i0 + me;
+                    const bool live = i < n_places && x.owner[i] >= 0;
+                    const uint32_t pl = live ? x.place[i] : 0u;
+                    const int8_t ow = live ? x.owner[i] : static_cast<int8_t>(-1);
+                    const uint64_t mask = __ballot(live);
+                    level_sync<true>();
+                    if (live) {
+                        const int at = kept + __popcll(mask & ((1ull << me) - 1));
+                        x.place[at] = pl, x.owner[at] = ow;
+                    }
+                    kept += __popcll(mask);
+                }
+                n_places = kept;
+                level_sync<true>();
+            }
+            // fewer levels ahead while many places are alive: most of them will not survive the next level
+            fetched = n_alive > 1024 ? 1 : n_alive > 512 ? 2 : n_alive > 256 ? 4 : kAhead;
+            fetched = min(fetched, levels - d + 1);
+            fetched_from = d;
+            for (int idx = me; idx < n_places * fetched; idx += stride) {
+                const int i = idx / fetched, ahead = idx - i * fetched;
+                int t = -1;
+                if (x.owner[i] >= 0) {
+                    const uint32_t pl = x.place[i];
+                    const int j = place_seq(pl), off = place_off(pl) + d - 1 + ahead;
+                    if (off < x.gt.len[j]) t = a.tokens[x.gt.start[j] + off];
+                    if (t >= a.vocab) t = -1;
+                }
+                x.cont[i * kAhead + ahead] = t;
+            }
+        }
+        const int l = d - fetched_from;
+        int table = 64;
+        while (table < kTableSlots && table < 2 * n_alive) table <<= 1;
+        const int shift = 32 - __builtin_ctz(static_cast<unsigned>(table));
+        for (int s = me; s < table; s += stride) x.key[s] = kEmpty, x.cnt[s] = 0;
+        level_sync<SOLO>();
+        for (int i0 = 0; i0 < n_places; i0 += stride) {
+            const int i = i0 + me;
+            int r = -1, t = -1;
+            if (i < n_places) {
+                r = x.owner[i];
+                t = x.cont[i * kAhead + l];
+                if (r >= 0 && t < 0) x.owner[i] = -1;          // the sequence ends here, or the token cannot be proposed
+            }
+            hash_count(x, table, shift, (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t), r >= 0 && t >= 0);
+        }
+        level_sync<SOLO>();
+        const int n_pick = pick_top<SOLO>(x, table, threshold, a.top_k, 0);
+        if (n_pick == 0) return levels + 1;
+        if (me == 0) emit_nodes(x, d, a.top_k, n_pick);
+        int alive = 0;
+        for (int j = 0; j < n_pick; ++j) alive += static_cast<int>(x.pick[j] >> 32);
+        n_alive = alive;
+        for (int i = me; i < n_places; i += stride) {
+            const int r = x.owner[i];
+            if (r < 0) continue;
+            const uint32_t key = (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(x.cont[i * kAhead + l]);
+            int owner = -1;
+            for (int j = 0; j < n_pick; ++j)
+                if (~static_cast<uint32_t>(x.pick[j]) == key) owner = j;
+            x.owner[i] = static_cast<int8_t>(owner);
+        }
+        level_sync<SOLO>();
+        if (me < n_pick) x.mem[me] = x.next[me];
+        level_sync<SOLO>();
+    }
+    return d;
+}
+
+__global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
+    __shared__ Expand x;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int T = 1 + a.top_k * a.gamma_max;
-    load_group(a, b, gt);
+    load_group(a, b, x.gt);
     const int plen = min(max(a.pattern_len[b], 0), a.p_max);
     if (tid < T) {
-        s_tok[tid] = tid == 0 && plen > 0 ? a.pattern[static_cast<size_t>(b) * a.p_max + a.p_max - 1] : -1;
-        s_par[tid] = tid == 0 ? -1 : -2;
-        s_num[tid] = 0;
-        s_msk[tid] = 1ull << tid;
+        x.tok[tid] = tid == 0 && plen > 0 ? a.pattern[static_cast<size_t>(b) * a.p_max + a.p_max - 1] : -1;
+        x.par[tid] = tid == 0 ? -1 : -2;
+        x.num[tid] = 0;
+        x.msk[tid] = 1ull << tid;
     }
-    if (tid == 0) s_n = 0, s_best = 0;
+    if (tid == 0) x.n = 0, x.best = 0, x.total = 0;
     __syncthreads();
-    if (gt.bad && tid == 0 && a.status) atomicOr(a.status, gt.bad);
+    if (x.gt.bad && tid == 0 && a.status) atomicOr(a.status, x.gt.bad);
 
-    // longest match over the parts, then its places
-    const int2* hdr = a.part_hdr + static_cast<size_t>(b) * a.parts;
-    if (gt.n_seq > 0)
-        for (int p = tid; p < a.parts; p += kThreads)
-            if (hdr[p].x > 0) atomicMax(&s_best, hdr[p].y);
+    // longest match over the parts, then its places: into LDS if they surely fit, else into a global list
+    if (tid < a.parts) {
+        const int2 h = x.gt.n_seq > 0 ? a.part_hdr[static_cast<size_t>(b) * a.parts + tid] : make_int2(0, 0);
+        x.hdr[tid] = h;
+        if (h.x > 0) {
+            atomicMax(&x.best, h.y);
+            atomicAdd(&x.total, h.x);
+        }
+    }
     __syncthreads();
-    const int p_star = s_best;
+    const int p_star = x.best;
     uint32_t* cur = a.list_b + static_cast<size_t>(b) * a.cap;
     uint32_t* nxt = a.list_a + static_cast<size_t>(b) * a.cap;
+    bool in_lds = x.total <= kSmall;
     if (p_star > 0) {
         for (int p = 0; p < a.parts; ++p) {
-            const int kept = hdr[p].x;
-            if (kept == 0 || hdr[p].y < p_star) continue;
+            const int2 h = x.hdr[p];
+            if (h.x == 0 || h.y < p_star) continue;
             const uint32_t* src = nxt + static_cast<size_t>(p) * a.chunk;
-            for (int e = tid; e < kept; e += kThreads) {
-                const uint32_t pl = src[e];
-                if (place_len(pl) == p_star) cur[atomicAdd(&s_n, 1)] = pl;
+            for (int e0 = 0; e0 < h.x; e0 += kThreads) {
+                const int e = e0 + tid;
+                const uint32_t pl = e < h.x ? src[e] : 0u;
+                const bool hit = e < h.x && place_len(pl) == p_star;
+                const int at = wave_append(&x.n, hit);
+                if (hit) {
+                    if (in_lds)
+                        x.place[at] = pl, x.owner[at] = 0;
+                    else
+                        cur[at] = pl;
+                }
             }
         }
     }
     __syncthreads();
-    const int n_root = s_n;
+    const int n_root = x.n;
     const int levels = p_star > 0 ? min(max(a.max_spec_tokens[b], 0), a.gamma_max) : 0;
     const float threshold = a.min_confidence * static_cast<float>(n_root);
     if (tid == 0) {
-        s_num[0] = n_root;
-        s_mem[0] = Member{0, n_root, 0};
-        s_nmem = 1;
+        x.num[0] = n_root;
+        x.mem[0] = Member{0, n_root, 0};
+        x.nmem = 1;
     }
     __syncthreads();
 
-    for (int d = 1; d <= levels; ++d) {
-        const int nmem = s_nmem;
-        const int n_level = s_mem[nmem - 1].base + s_mem[nmem - 1].n;
+    int d = 1;
+    // ---- places in global memory: as long as a level holds more places than the LDS mode takes ----
+    for (; d <= levels && !in_lds; ++d) {
+        const int nmem = x.nmem;
+        const int n_level = x.mem[nmem - 1].base + x.mem[nmem - 1].n;
+        if (n_level <= kSmall) {
+            for (int e = tid; e < n_level; e += kThreads) {
+                int r = 0;
+                while (r + 1 < nmem && e >= x.mem[r + 1].base) ++r;
+                x.place[e] = cur[e], x.owner[e] = static_cast<int8_t>(r);
+            }
+            in_lds = true;
+            __syncthreads();
+            break;
+        }
         // the token a place shows at this level, with the rank of the member that owns the place
         auto key_of = [&](int e, uint32_t pl) -> uint32_t {
             int r = 0;
-            while (r + 1 < nmem && e >= s_mem[r + 1].base) ++r;
+            while (r + 1 < nmem && e >= x.mem[r + 1].base) ++r;
             const int j = place_seq(pl), off = place_off(pl) + d - 1;
-            if (off >= gt.len[j]) return kEmpty;
-            const int x = a.tokens[gt.start[j] + off];
-            if (x < 0 || x >= a.vocab) return kEmpty;
-            return (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(x);
+            if (off >= x.gt.len[j]) return kEmpty;
+            const int t = a.tokens[x.gt.start[j] + off];
+            if (t < 0 || t >= a.vocab) return kEmpty;
+            return (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t);
         };
         int n_pick = 0;
         // Pass 0 counts in a hash table.  Only if more distinct (member, token) pairs turn up than the
         // table has slots do further passes count token ranges in a directly indexed table.
-        int table = 64;
-        while (table < kTableSlots && table < 2 * n_level) table <<= 1;
         const int range = kTableSlots / nmem;                     // tokens per member in a ranged pass
         const int n_pass_ranged = (a.vocab + range - 1) / range;
+        const int shift = 32 - __builtin_ctz(static_cast<unsigned>(kTableSlots));
         for (int pass = 0; pass <= n_pass_ranged; ++pass) {
             const bool hashed = pass == 0;
-            const int slots = hashed ? table : kTableSlots;
-            for (int s = tid; s < slots; s += kThreads) s_key[s] = kEmpty, s_cnt[s] = 0;
-            if (tid == 0) s_overflow = 0;
+            for (int s = tid; s < kTableSlots; s += kThreads) x.key[s] = kEmpty, x.cnt[s] = 0;
+            if (tid == 0) x.overflow = 0;
             __syncthreads();
-            const int shift = 32 - __builtin_ctz(static_cast<unsigned>(table));
             const int lo_tok = (pass - 1) * range;
-            for (int e = tid; e < n_level; e += kThreads) {
-                const uint32_t key = key_of(e, cur[e]);
-                if (key == kEmpty) continue;
-                if (hashed) {
-                    uint32_t h = (key * 2654435761u) >> shift;
-                    int probes = 0;
-                    for (; probes < table; ++probes) {
-                        const uint32_t old = atomicCAS(&s_key[h], kEmpty, key);
-                        if (old == kEmpty || old == key) {
-                            atomicAdd(&s_cnt[h], 1u);
-                            break;
+            for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
+                uint32_t key[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + u * kThreads + tid;
+                    key[u] = e < n_level ? key_of(e, cur[e]) : kEmpty;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (hashed) {
+                        hash_count(x, kTableSlots, shift, key[u], key[u] != kEmpty);
+                    } else if (key[u] != kEmpty) {
+                        const int t = static_cast<int>(key[u] & 0xffffffu) - lo_tok;
+                        if (t >= 0 && t < range) {
+                            const int s = static_cast<int>(key[u] >> 24) * range + t;
+                            x.key[s] = key[u];
+                            atomicAdd(&x.cnt[s], 1u);
                         }
-                        h = (h + 1) & (table - 1);
-                    }
-                    if (probes == table) s_overflow = 1;
-                } else {
-                    const int x = static_cast<int>(key & 0xffffffu) - lo_tok;
-                    if (x >= 0 && x < range) {
-                        const int s = static_cast<int>(key >> 24) * range + x;
-                        s_key[s] = key;
-                        atomicAdd(&s_cnt[s], 1u);
                     }
                 }
             }
             __syncthreads();
-            const bool overflow = s_overflow != 0;
-            if (!(hashed && overflow)) {
-                // the top_k of this table join the picks so far; the best top_k of both stay
-                for (int round = 0; round < a.top_k; ++round) {
-                    uint64_t best = 0;
-                    for (int s = tid; s < slots; s += kThreads) {
-                        const uint32_t c = s_cnt[s];
-                        if (c == 0 || static_cast<float>(c) < threshold) continue;
-                        const uint64_t v = (static_cast<uint64_t>(c) << 32) | static_cast<uint32_t>(~s_key[s]);
-                        best = v > best ? v : best;
-                    }
-                    best = wave_max_u64(best);
-                    if ((tid & 63) == 0) s_red[tid >> 6] = best;
-                    __syncthreads();
-                    uint64_t win = s_red[0];
-#pragma unroll
-                    for (int w = 1; w < kThreads / 64; ++w) win = s_red[w] > win ? s_red[w] : win;
-                    __syncthreads();
-                    if (win == 0) break;
-                    const uint32_t win_key = ~static_cast<uint32_t>(win);
-                    for (int s = tid; s < slots; s += kThreads)
-                        if (s_key[s] == win_key) s_cnt[s] = 0;
-                    if (tid == 0) {
-                        // insertion into the sorted picks (descending), at most top_k kept
-                        int at = n_pick < a.top_k ? n_pick : a.top_k - 1;
-                        if (n_pick < a.top_k || win > s_pick[at]) {
-                            while (at > 0 && s_pick[at - 1] < win) {
-                                s_pick[at] = s_pick[at - 1];
-                                --at;
-                            }
-                            s_pick[at] = win;
-                        }
-                    }
-                    n_pick = min(n_pick + 1, a.top_k);
-                    __syncthreads();
-                }
-            }
+            const bool overflow = x.overflow != 0;
+            if (!(hashed && overflow)) n_pick = pick_top<false>(x, kTableSlots, threshold, a.top_k, n_pick);
             if (hashed && !overflow) break;
         }
-        if (n_pick == 0) break;
-        // the picks become draft nodes and the members of the next level
-        if (tid == 0) {
-            int base = 0;
-            for (int j = 0; j < n_pick; ++j) {
-                const uint32_t key = ~static_cast<uint32_t>(s_pick[j]);
-                const int c = static_cast<int>(s_pick[j] >> 32), r = static_cast<int>(key >> 24);
-                const int slot = 1 + (d - 1) * a.top_k + j, parent = s_mem[r].slot;
-                s_tok[slot] = static_cast<int>(key & 0xffffffu);
-                s_par[slot] = parent;
-                s_num[slot] = c;
-                s_msk[slot] = (1ull << slot) | s_msk[parent];
-                s_next[j] = Member{base, c, slot};       // s_mem is still read by the split below
-                s_fill[j] = 0;
-                base += c;
-            }
+        if (n_pick == 0) {
+            d = levels + 1;
+            break;
         }
+        if (tid == 0) emit_nodes(x, d, a.top_k, n_pick);
         __syncthreads();
         if (d < levels) {
-            for (int e = tid; e < n_level; e += kThreads) {
-                const uint32_t pl = cur[e];
-                const uint32_t key = key_of(e, pl);
-                if (key == kEmpty) continue;
-                for (int j = 0; j < n_pick; ++j)
-                    if (~static_cast<uint32_t>(s_pick[j]) == key) {
-                        nxt[s_next[j].base + atomicAdd(&s_fill[j], 1)] = pl;
-                        break;
+            for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
+                uint32_t pl[4], key[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + u * kThreads + tid;
+                    pl[u] = e < n_level ? cur[e] : 0u;
+                    key[u] = e < n_level ? key_of(e, pl[u]) : kEmpty;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    int child = -1;
+                    if (key[u] != kEmpty)
+                        for (int j = 0; j < n_pick; ++j)
+                            if (~static_cast<uint32_t>(x.pick[j]) == key[u]) child = j;
+                    // one member's places mostly go to one child: append wave by wave, child by child
+                    for (int j = 0; j < n_pick; ++j) {
+                        if (__ballot(child == j) == 0) continue;
+                        const int at = wave_append(&x.fill[j], child == j);
+                        if (child == j) nxt[x.next[j].base + at] = pl[u];
                     }
+                }
             }
         }
         __syncthreads();
-        if (tid < n_pick) s_mem[tid] = s_next[tid];
-        if (tid == 0) s_nmem = n_pick;
+        if (tid < n_pick) x.mem[tid] = x.next[tid];
+        if (tid == 0) x.nmem = n_pick;
         uint32_t* t = cur;
         cur = nxt;
         nxt = t;
         __syncthreads();
     }
 
+    // ---- places in LDS: the next tokens of every place are fetched a few levels at a time; the whole
+    //      workgroup works while many places are alive, then wave 0 finishes alone without barriers ----
+    if (in_lds && d <= levels) {
+        int n_places = min(x.mem[x.nmem - 1].base + x.mem[x.nmem - 1].n, kSmall);
+        int n_alive = n_places;
+        d = lds_levels<false>(a, x, d, levels, threshold, n_places, n_alive);
+        if (d <= levels && tid < 64) lds_levels<true>(a, x, d, levels, threshold, n_places, n_alive);
+    }
+    __syncthreads();
+
     if (tid < T) {
         const size_t o = static_cast<size_t>(b) * T + tid;
-        a.draft_tokens[o] = s_tok[tid];
-        a.tree_parent[o] = s_par[tid];
-        a.tree_mask[o] = s_msk[tid];
-        if (a.node_count) a.node_count[o] = s_num[tid];
+        a.draft_tokens[o] = x.tok[tid];
+        a.tree_parent[o] = x.par[tid];
+        a.tree_mask[o] = x.msk[tid];
+        if (a.node_count) a.node_count[o] = x.num[tid];
     }
     if (tid == 0 && a.match_len) a.match_len[b] = p_star;
 }
@@ -413,7 +635,7 @@ int draft_shape(const seer_draft_params* p, DraftShape* s) {
     if (p->pattern_lookup_min > p->pattern_lookup_max) return SEER_ESHAPE;
     if (1 + static_cast<int64_t>(p->top_k) * p->gamma_max > SEER_MAX_T) return SEER_ESHAPE;
     if (p->top_k > kMaxTopK || p->pattern_lookup_max > kMaxPattern || p->vocab > (1 << 24) ||
-        p->pool_tokens > 0x7fffffffll)
+        p->pool_tokens > 0x7fff0000ll)
         return SEER_EUNSUPPORTED;
     int parts = (p->max_group_tokens + kTokensPerPart - 1) / kTokensPerPart;
     parts = parts < 1 ? 1 : (parts > kMaxParts ? kMaxParts : parts);
@@ -450,7 +672,7 @@ extern "C" int seer_draft(const int32_t* tokens, const int32_t* seq_start, const
         !draft_tokens || !tree_parent || !tree_mask)
         return SEER_EINVAL;
     if (!workspace || workspace_bytes < s.total) return SEER_EWORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return SEER_EALIGN;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(tokens) % 16 != 0) return SEER_EALIGN;
     seer::draft::Args a{};
     a.tokens = tokens, a.seq_start = seq_start, a.seq_len = seq_len, a.group_first = group_first;
     a.req_group = req_group, a.pattern = pattern, a.pattern_len = pattern_len, a.max_spec_tokens = max_spec_tokens;

@@ -201,6 +201,7 @@ def test_draft_argument_errors_before_any_launch(lib):
     assert run(_draft_params(), ws=None) == b.SEER_EWORKSPACE
     assert run(_draft_params(), ws_bytes=1024) == b.SEER_EWORKSPACE
     assert run(_draft_params(), ws=0x10004) == b.SEER_EALIGN
+    assert run(_draft_params(), tokens=fake + 4) == b.SEER_EALIGN
     assert run(_draft_params(B=0)) == b.SEER_OK
     small = b.seer_draft_workspace(_draft_params())
     assert small > 0 and small % 256 == 0
