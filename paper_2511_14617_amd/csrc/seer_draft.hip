@@ -134,19 +134,14 @@ __device__ __forceinline__ void load_group(const Args& a, int b, GroupTable& gt)
         }
     }
     __syncthreads();
-    if (tid == 0) {
-        int64_t acc = 0;
-        for (int j = 0; j < n; ++j) {
-            gt.flat[j] = static_cast<int>(acc);
-            acc += gt.len[j];
-            if (acc > a.max_group_tokens) {
-                gt.bad |= 2;
-                acc = 0;
-            }
-        }
-        gt.flat[n] = static_cast<int>(acc);
-        gt.n_seq = gt.bad ? 0 : n;
+    if (tid <= n) {                               // tokens of the group before sequence tid (lengths are below 2^20)
+        int acc = 0;
+        for (int j = 0; j < tid; ++j) acc += gt.len[j];
+        gt.flat[tid] = acc;
+        if (tid == n && acc > a.max_group_tokens) gt.bad |= 2;
     }
+    __syncthreads();
+    if (tid == 0) gt.n_seq = gt.bad ? 0 : n;
     __syncthreads();
 }
 
@@ -234,17 +229,21 @@ struct Expand {
     GroupTable gt;
     uint32_t key[kTableSlots];
     uint32_t cnt[kTableSlots];
-    int cont[kSmall * kAhead];             // LDS-resident mode: the next tokens of every place
-    uint32_t place[kSmall];
+    uint64_t cand[kSmall];                 // candidates of a level: count << 32 | ~key
+    uint32_t place[kSmall];                // hand-over of places between the phases
     int8_t owner[kSmall];                  // rank of the member a place belongs to, -1 = dropped
     int2 hdr[kMaxParts];
-    Member mem[kMaxTopK], next[kMaxTopK];
+    int first[kMaxParts + 1];              // places of the longest match before part p
+    Member mem[kMaxTopK], next[kMaxTopK];  // members while the places live in global memory
+    int mem_slot[2][kMaxTopK];             // members while the places live in registers: slot and ancestor mask,
+    uint64_t mem_msk[2][kMaxTopK];         //   level d - 1 in buffer (d - 1) & 1
     uint64_t red[kThreads / 64];
+    uint64_t best[kMaxTopK];
     uint64_t pick[kMaxTopK];               // chosen children: count << 32 | ~key, best first
     int fill[kMaxTopK];
     int tok[SEER_MAX_T], par[SEER_MAX_T], num[SEER_MAX_T];
     uint64_t msk[SEER_MAX_T];
-    int n, best, total, nmem, overflow;
+    int n, best_len, nmem, overflow, n_cand;
 };
 
 // Workgroup barrier, or (SOLO: wave 0 works alone) only an ordering point for the wave's own LDS traffic.
@@ -350,86 +349,192 @@ __device__ __forceinline__ void emit_nodes(Expand& x, int d, int top_k, int n_pi
     }
 }
 
-// Levels d .. levels with the places in LDS.  !SOLO: the whole workgroup, until at most kSolo places are
-// alive; SOLO: wave 0 alone, no workgroup barriers.  Returns the next level (levels + 1 = finished).
-template <bool SOLO>
-__device__ __forceinline__ int lds_levels(const Args& a, Expand& x, int d, int levels, float threshold, int& n_places,
+// One level for the places a thread holds in registers (own[u] = rank of the member the place belongs to
+// or -1, t[u] = the token the place shows at this level or -1).  Counting in the LDS hash table, then the
+// candidates (one per distinct (member, token) pair, held by the thread that entered the pair) are ranked:
+// against each other if they are few, else by top_k rounds of a maximum.  The thread that holds the pick
+// of rank j writes draft node j of the level.  Returns the number of picks; n_alive = places they own.
+template <bool SOLO, int PER>
+__device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float threshold, int (&own)[PER],
+                                         const int (&t)[PER], int& n_alive) {
+    const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
+    const uint64_t below = (1ull << lane_id()) - 1;
+    int table = 64;
+    while (table < kTableSlots && table < 2 * n_alive) table <<= 1;      // at most n_alive distinct keys
+    const int shift = 32 - __builtin_ctz(static_cast<unsigned>(table));
+    for (int s = me; s < table; s += stride) x.key[s] = kEmpty, x.cnt[s] = 0;
+    if (me < kMaxTopK) x.best[me] = 0;
+    if (me == 0) x.n_cand = 0;
+    level_sync<SOLO>();
+    uint32_t k[PER], h[PER], old[PER];
+    bool act[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        act[u] = own[u] >= 0 && t[u] >= 0;       // else the sequence ends here, or the token cannot be proposed
+        k[u] = (static_cast<uint32_t>(own[u]) << 24) | static_cast<uint32_t>(t[u]);
+        h[u] = (k[u] * 2654435761u) >> shift;
+        old[u] = kEmpty;
+        if (act[u]) old[u] = atomicCAS(&x.key[h[u]], kEmpty, k[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        if (!act[u]) continue;
+        for (int probes = 0; old[u] != kEmpty && old[u] != k[u] && probes < table; ++probes) {
+            h[u] = (h[u] + 1) & (table - 1);
+            old[u] = atomicCAS(&x.key[h[u]], kEmpty, k[u]);
+        }
+        atomicAdd(&x.cnt[h[u]], 1u);
+    }
+    level_sync<SOLO>();
+    uint64_t v[PER];
+    int wave_total = 0;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        v[u] = 0;
+        if (act[u] && old[u] == kEmpty) {                       // this thread entered the pair: it speaks for it
+            const uint32_t c = x.cnt[h[u]];
+            if (static_cast<float>(c) >= threshold) v[u] = (static_cast<uint64_t>(c) << 32) | static_cast<uint32_t>(~k[u]);
+        }
+        wave_total += __popcll(__ballot(v[u] != 0));
+    }
+    int base = 0;
+    if (!SOLO) {
+        if (lane_id() == 0 && wave_total) base = atomicAdd(&x.n_cand, wave_total);
+        base = __builtin_amdgcn_readfirstlane(base);
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const uint64_t mask = __ballot(v[u] != 0);
+        if (v[u] != 0) x.cand[base + __popcll(mask & below)] = v[u];
+        base += __popcll(mask);
+    }
+    level_sync<SOLO>();
+    const int n_cand = SOLO ? base : x.n_cand;
+    const int n_pick = min(n_cand, a.top_k);
+    if (n_pick == 0) return 0;
+    const int from = (d - 1) & 1;
+    auto emit = [&](int rank, uint64_t val) {
+        const uint32_t key = ~static_cast<uint32_t>(val);
+        const int r = static_cast<int>(key >> 24), slot = 1 + (d - 1) * a.top_k + rank;
+        const int parent = x.mem_slot[from][r];
+        const uint64_t m = (1ull << slot) | x.mem_msk[from][r];
+        x.tok[slot] = static_cast<int>(key & 0xffffffu);
+        x.par[slot] = parent;
+        x.num[slot] = static_cast<int>(val >> 32);
+        x.msk[slot] = m;
+        x.mem_slot[from ^ 1][rank] = slot;
+        x.mem_msk[from ^ 1][rank] = m;
+        x.pick[rank] = val;
+    };
+    if (n_cand <= 256) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            if (v[u] == 0) continue;
+            int rank = 0;
+            for (int j = 0; j < n_cand; ++j) rank += x.cand[j] > v[u] ? 1 : 0;
+            if (rank < a.top_k) emit(rank, v[u]);
+        }
+    } else {
+        for (int round = 0; round < n_pick; ++round) {
+            uint64_t mine = 0;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) mine = v[u] > mine ? v[u] : mine;
+            if (mine != 0) atomicMax(reinterpret_cast<unsigned long long*>(&x.best[round]), static_cast<unsigned long long>(mine));
+            level_sync<SOLO>();
+            const uint64_t win = x.best[round];
+#pragma unroll
+            for (int u = 0; u < PER; ++u)
+                if (v[u] == win && win != 0) {
+                    emit(round, win);
+                    v[u] = 0;
+                }
+        }
+    }
+    level_sync<SOLO>();
+    int alive = 0;
+    int now[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) now[u] = -1;
+    for (int j = 0; j < n_pick; ++j) {
+        const uint64_t pj = x.pick[j];
+        alive += static_cast<int>(pj >> 32);
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+            if (act[u] && k[u] == ~static_cast<uint32_t>(pj)) now[u] = j;
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) own[u] = now[u];
+    n_alive = alive;
+    return n_pick;
+}
+
+// Levels d .. levels with the places in registers, PER per thread, taken from x.place / x.owner.  The next
+// kAhead tokens of every place are fetched at once, so that most levels run without touching global memory.
+// !SOLO: the whole workgroup, until at most kSolo places are alive; then the live places go back to
+// x.place / x.owner.  SOLO: wave 0 alone, no workgroup barriers.  Returns the next level (levels + 1 = finished).
+template <bool SOLO, int PER>
+__device__ __forceinline__ int reg_levels(const Args& a, Expand& x, int d, int levels, float threshold, int& n_places,
                                           int& n_alive) {
     const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
-    int fetched_from = 0, fetched = 0;                 // x.cont holds levels fetched_from .. fetched_from + fetched - 1
-    for (; d <= levels; ++d) {
-        if (!SOLO && n_alive <= kSolo) return d;
-        if (d >= fetched_from + fetched) {
-            if (SOLO) {
-                // drop the dead places first (one wave, chunk by chunk, writes never pass the reads)
-                int kept = 0;
-                for (int i0 = 0; i0 < n_places; i0 += 64) {
-                    const int i = i0 + me;
-                    const bool live = i < n_places && x.owner[i] >= 0;
-                    const uint32_t pl = live ? x.place[i] : 0u;
-                    const int8_t ow = live ? x.owner[i] : static_cast<int8_t>(-1);
-                    const uint64_t mask = __ballot(live);
-                    level_sync<true>();
-                    if (live) {
-                        const int at = kept + __popcll(mask & ((1ull << me) - 1));
-                        x.place[at] = pl, x.owner[at] = ow;
-                    }
-                    kept += __popcll(mask);
-                }
-                n_places = kept;
-                level_sync<true>();
-            }
-            // fewer levels ahead while many places are alive: most of them will not survive the next level
-            fetched = n_alive > 1024 ? 1 : n_alive > 512 ? 2 : n_alive > 256 ? 4 : kAhead;
-            fetched = min(fetched, levels - d + 1);
-            fetched_from = d;
-            for (int idx = me; idx < n_places * fetched; idx += stride) {
-                const int i = idx / fetched, ahead = idx - i * fetched;
+    uint32_t place[PER];
+    int own[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int i = me + u * stride;
+        own[u] = i < n_places ? x.owner[i] : -1;
+        place[u] = i < n_places ? x.place[i] : 0u;
+    }
+    while (d <= levels && (SOLO || n_alive > kSolo)) {
+        int cont[PER][kAhead];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int j = place_seq(place[u]), off = place_off(place[u]) + d - 1;
+            const int have = own[u] >= 0 ? min(x.gt.len[j] - off, levels - d + 1) : 0;
+            const int32_t* src = a.tokens + x.gt.start[j] + off;
+#pragma unroll
+            for (int l = 0; l < kAhead; ++l) {
                 int t = -1;
-                if (x.owner[i] >= 0) {
-                    const uint32_t pl = x.place[i];
-                    const int j = place_seq(pl), off = place_off(pl) + d - 1 + ahead;
-                    if (off < x.gt.len[j]) t = a.tokens[x.gt.start[j] + off];
-                    if (t >= a.vocab) t = -1;
-                }
-                x.cont[i * kAhead + ahead] = t;
+                if (l < have) t = src[l];
+                cont[u][l] = t >= a.vocab ? -1 : t;
             }
         }
-        const int l = d - fetched_from;
-        int table = 64;
-        while (table < kTableSlots && table < 2 * n_alive) table <<= 1;
-        const int shift = 32 - __builtin_ctz(static_cast<unsigned>(table));
-        for (int s = me; s < table; s += stride) x.key[s] = kEmpty, x.cnt[s] = 0;
-        level_sync<SOLO>();
-        for (int i0 = 0; i0 < n_places; i0 += stride) {
-            const int i = i0 + me;
-            int r = -1, t = -1;
-            if (i < n_places) {
-                r = x.owner[i];
-                t = x.cont[i * kAhead + l];
-                if (r >= 0 && t < 0) x.owner[i] = -1;          // the sequence ends here, or the token cannot be proposed
+        bool done = false;
+#pragma unroll
+        for (int l = 0; l < kAhead; ++l) {
+            if (done || d > levels || (!SOLO && n_alive <= kSolo)) continue;      // the same for every thread
+            int t[PER];
+#pragma unroll
+            for (int u = 0; u < PER; ++u) t[u] = cont[u][l];
+            if (reg_level<SOLO, PER>(a, x, d, threshold, own, t, n_alive) == 0) {
+                done = true;
+                d = levels + 1;
+            } else {
+                ++d;
             }
-            hash_count(x, table, shift, (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t), r >= 0 && t >= 0);
         }
-        level_sync<SOLO>();
-        const int n_pick = pick_top<SOLO>(x, table, threshold, a.top_k, 0);
-        if (n_pick == 0) return levels + 1;
-        if (me == 0) emit_nodes(x, d, a.top_k, n_pick);
-        int alive = 0;
-        for (int j = 0; j < n_pick; ++j) alive += static_cast<int>(x.pick[j] >> 32);
-        n_alive = alive;
-        for (int i = me; i < n_places; i += stride) {
-            const int r = x.owner[i];
-            if (r < 0) continue;
-            const uint32_t key = (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(x.cont[i * kAhead + l]);
-            int owner = -1;
-            for (int j = 0; j < n_pick; ++j)
-                if (~static_cast<uint32_t>(x.pick[j]) == key) owner = j;
-            x.owner[i] = static_cast<int8_t>(owner);
+    }
+    if (!SOLO && d <= levels) {
+        // the live places go to wave 0
+        if (threadIdx.x == 0) x.n = 0;
+        __syncthreads();
+        int wave_total = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) wave_total += __popcll(__ballot(own[u] >= 0));
+        int base = 0;
+        if (lane_id() == 0 && wave_total) base = atomicAdd(&x.n, wave_total);
+        base = __builtin_amdgcn_readfirstlane(base);
+        const uint64_t below = (1ull << lane_id()) - 1;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const uint64_t mask = __ballot(own[u] >= 0);
+            if (own[u] >= 0) {
+                const int at = base + __popcll(mask & below);
+                x.place[at] = place[u], x.owner[at] = static_cast<int8_t>(own[u]);
+            }
+            base += __popcll(mask);
         }
-        level_sync<SOLO>();
-        if (me < n_pick) x.mem[me] = x.next[me];
-        level_sync<SOLO>();
+        __syncthreads();
+        n_places = x.n;
     }
     return d;
 }
@@ -438,54 +543,61 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
     __shared__ Expand x;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int T = 1 + a.top_k * a.gamma_max;
-    load_group(a, b, x.gt);
+    // what the match workgroups left (requested before the group table, whose loads it does not depend on)
+    int2 h = make_int2(0, 0);
+    if (tid < a.parts) h = a.part_hdr[static_cast<size_t>(b) * a.parts + tid];
     const int plen = min(max(a.pattern_len[b], 0), a.p_max);
+    const int want = a.max_spec_tokens[b];
+    load_group(a, b, x.gt);
     if (tid < T) {
         x.tok[tid] = tid == 0 && plen > 0 ? a.pattern[static_cast<size_t>(b) * a.p_max + a.p_max - 1] : -1;
         x.par[tid] = tid == 0 ? -1 : -2;
         x.num[tid] = 0;
         x.msk[tid] = 1ull << tid;
     }
-    if (tid == 0) x.n = 0, x.best = 0, x.total = 0;
+    if (tid == 0) x.n = 0, x.best_len = 0;
     __syncthreads();
     if (x.gt.bad && tid == 0 && a.status) atomicOr(a.status, x.gt.bad);
-
-    // longest match over the parts, then its places: into LDS if they surely fit, else into a global list
-    if (tid < a.parts) {
-        const int2 h = x.gt.n_seq > 0 ? a.part_hdr[static_cast<size_t>(b) * a.parts + tid] : make_int2(0, 0);
-        x.hdr[tid] = h;
-        if (h.x > 0) {
-            atomicMax(&x.best, h.y);
-            atomicAdd(&x.total, h.x);
-        }
+    if (x.gt.n_seq == 0) h = make_int2(0, 0);
+    if (h.x > 0) atomicMax(&x.best_len, h.y);
+    __syncthreads();
+    const int p_star = x.best_len;
+    // places of the longest match, part by part: how many come before part p
+    if (tid < a.parts) x.hdr[tid] = make_int2(h.y == p_star ? h.x : 0, h.y);
+    __syncthreads();
+    if (tid <= a.parts) {
+        int acc = 0;
+        for (int p = 0; p < tid; ++p) acc += x.hdr[p].x;
+        x.first[tid] = acc;
     }
     __syncthreads();
-    const int p_star = x.best;
+    const int n_kept = p_star > 0 ? x.first[a.parts] : 0;        // >= the places of the longest match
     uint32_t* cur = a.list_b + static_cast<size_t>(b) * a.cap;
     uint32_t* nxt = a.list_a + static_cast<size_t>(b) * a.cap;
-    bool in_lds = x.total <= kSmall;
-    if (p_star > 0) {
-        for (int p = 0; p < a.parts; ++p) {
-            const int2 h = x.hdr[p];
-            if (h.x == 0 || h.y < p_star) continue;
-            const uint32_t* src = nxt + static_cast<size_t>(p) * a.chunk;
-            for (int e0 = 0; e0 < h.x; e0 += kThreads) {
-                const int e = e0 + tid;
-                const uint32_t pl = e < h.x ? src[e] : 0u;
-                const bool hit = e < h.x && place_len(pl) == p_star;
-                const int at = wave_append(&x.n, hit);
-                if (hit) {
-                    if (in_lds)
-                        x.place[at] = pl, x.owner[at] = 0;
-                    else
-                        cur[at] = pl;
-                }
+    bool in_lds = n_kept <= kSmall;
+    for (int i0 = 0; i0 < n_kept; i0 += kThreads) {
+        const int i = i0 + tid;
+        uint32_t pl = 0;
+        if (i < n_kept) {
+            int lo = 0, hi = a.parts;                              // the part that holds kept place i
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (x.first[mid] <= i) lo = mid; else hi = mid;
             }
+            pl = nxt[static_cast<size_t>(lo) * a.chunk + (i - x.first[lo])];
+        }
+        const bool hit = i < n_kept && place_len(pl) == p_star;
+        const int at = wave_append(&x.n, hit);
+        if (hit) {
+            if (in_lds)
+                x.place[at] = pl, x.owner[at] = 0;
+            else
+                cur[at] = pl;
         }
     }
     __syncthreads();
     const int n_root = x.n;
-    const int levels = p_star > 0 ? min(max(a.max_spec_tokens[b], 0), a.gamma_max) : 0;
+    const int levels = p_star > 0 ? min(max(want, 0), a.gamma_max) : 0;
     const float threshold = a.min_confidence * static_cast<float>(n_root);
     if (tid == 0) {
         x.num[0] = n_root;
@@ -596,13 +708,18 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
         __syncthreads();
     }
 
-    // ---- places in LDS: the next tokens of every place are fetched a few levels at a time; the whole
-    //      workgroup works while many places are alive, then wave 0 finishes alone without barriers ----
+    // ---- few enough places: they move into registers; the whole workgroup works while many are alive,
+    //      then wave 0 finishes alone without barriers ----
     if (in_lds && d <= levels) {
         int n_places = min(x.mem[x.nmem - 1].base + x.mem[x.nmem - 1].n, kSmall);
         int n_alive = n_places;
-        d = lds_levels<false>(a, x, d, levels, threshold, n_places, n_alive);
-        if (d <= levels && tid < 64) lds_levels<true>(a, x, d, levels, threshold, n_places, n_alive);
+        if (tid < x.nmem) {
+            x.mem_slot[(d - 1) & 1][tid] = x.mem[tid].slot;
+            x.mem_msk[(d - 1) & 1][tid] = x.msk[x.mem[tid].slot];
+        }
+        __syncthreads();
+        if (n_alive > kSolo) d = reg_levels<false, kSmall / kThreads>(a, x, d, levels, threshold, n_places, n_alive);
+        if (d <= levels && tid < 64) reg_levels<true, kSolo / 64>(a, x, d, levels, threshold, n_places, n_alive);
     }
     __syncthreads();
 
