@@ -32,7 +32,8 @@
 namespace seer {
 namespace draft {
 
-constexpr int kThreads = 256;
+constexpr int kMatchThreads = 256;        // match workgroup
+constexpr int kThreads = 1024;            // expansion workgroup
 constexpr int kMaxGroupSeqs = 128;        // sequences per group (7 bits of a place)
 constexpr int kMaxSeqLenLog2 = 20;        // tokens per sequence < 2^20 (20 bits of a place)
 constexpr int kMaxPattern = 32;           // pattern_lookup_max (5 bits of a place hold match length - 1)
@@ -44,8 +45,11 @@ constexpr uint32_t kEmpty = 0xffffffffu;
 #endif
 constexpr int kTokensPerPart = SEER_DRAFT_PART_TOKENS;   // target stretch of one match workgroup
 constexpr int kMaxParts = 64;
+constexpr int kQuads = 4;                 // 16-byte loads a match thread has in flight
+constexpr int kTile = 4 * kQuads * kMatchThreads;   // tokens a match workgroup takes per round
 constexpr int kSmall = 2048;              // places that the LDS-resident mode of the expansion holds
 constexpr int kAhead = 8;                 // levels of continuation tokens it fetches at a time, at most
+constexpr int kRankAll = 32;            // up to this many candidates of a level are ranked against each other
 constexpr int kSolo = 256;                // at most this many live places: one wave finishes the search alone
 
 // A place = (sequence inside the group, offset of the token that follows the occurrence); while the
@@ -148,15 +152,16 @@ __device__ __forceinline__ void load_group(const Args& a, int b, GroupTable& gt)
 // ------------------------------------------------------------------------------------------------
 // Match: how many pattern tokens end at each place of one stretch of the group's tokens.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void draft_match_kernel(Args a) {
+__global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a) {
     __shared__ GroupTable gt;
     __shared__ int s_pat[kMaxPattern];
+    __shared__ __attribute__((aligned(16))) int s_tile[kMaxPattern + kTile];   // the tokens before the tile, then the tile
     __shared__ int s_best, s_kept;
     const int b = blockIdx.y, part = blockIdx.x, tid = threadIdx.x;
-    load_group(a, b, gt);
     const int plen = min(max(a.pattern_len[b], 0), a.p_max);
-    const int need = max(a.p_min, 1);
     if (tid < a.p_max) s_pat[tid] = a.pattern[static_cast<size_t>(b) * a.p_max + tid];
+    load_group(a, b, gt);
+    const int need = max(a.p_min, 1);
     if (tid == 0) s_best = need, s_kept = 0;
     __syncthreads();
     uint32_t* out = a.list_a + static_cast<size_t>(b) * a.cap + static_cast<size_t>(part) * a.chunk;
@@ -167,15 +172,16 @@ __global__ __launch_bounds__(kThreads) void draft_match_kernel(Args a) {
             // places i of sequence j inside [lo, hi) whose next token exists
             const int i0 = max(lo - gt.flat[j], 0), i1 = min(hi - gt.flat[j], gt.len[j] - 1);
             if (i0 >= i1) continue;
-            const int32_t* seq = a.tokens + gt.start[j];
-            // 16-byte loads of aligned token quads; a quad may begin before the stretch or end after it
+            // Tiles of aligned token quads (16-byte loads); a tile may begin before the stretch and end after
+            // it.  The tile and the kMaxPattern tokens before it also go to LDS: a place that holds the newest
+            // pattern token compares backwards there instead of through dependent global loads.
             const int abs0 = gt.start[j] + i0, abs1 = gt.start[j] + i1;
-            for (int w0 = abs0 & ~3; w0 < abs1; w0 += 8 * kThreads) {      // the same trip count for every lane
+            for (int w0 = abs0 & ~3; w0 < abs1; w0 += kTile) {             // the same trip count for every thread
                 const int q0 = w0 + 4 * tid;
-                int tok[8];
+                int tok[4 * kQuads];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int q = q0 + u * 4 * kThreads;
+                for (int u = 0; u < kQuads; ++u) {
+                    const int q = q0 + u * 4 * kMatchThreads;
                     if (q < abs1 && static_cast<int64_t>(q) + 4 <= a.pool_tokens) {
                         const int4 v = *reinterpret_cast<const int4*>(a.tokens + q);
                         tok[4 * u] = v.x, tok[4 * u + 1] = v.y, tok[4 * u + 2] = v.z, tok[4 * u + 3] = v.w;
@@ -184,22 +190,31 @@ __global__ __launch_bounds__(kThreads) void draft_match_kernel(Args a) {
                         for (int c = 0; c < 4; ++c) tok[4 * u + c] = q + c < abs1 ? a.tokens[q + c] : ~newest;
                     }
                 }
+                int before = -1;
+                if (tid < kMaxPattern && w0 - kMaxPattern + tid >= 0) before = a.tokens[w0 - kMaxPattern + tid];
+                __syncthreads();                                            // the previous tile is no longer read
+                if (tid < kMaxPattern) s_tile[tid] = before;
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const int t = q0 + (c >> 2) * 4 * kThreads + (c & 3);
+                for (int u = 0; u < kQuads; ++u)
+                    *reinterpret_cast<int4*>(&s_tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads]) =
+                        make_int4(tok[4 * u], tok[4 * u + 1], tok[4 * u + 2], tok[4 * u + 3]);
+                __syncthreads();
+#pragma unroll
+                for (int c = 0; c < 4 * kQuads; ++c) {
+                    const int t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
                     int m = 0;
                     if (tok[c] == newest && t >= abs0 && t < abs1) {
-                        const int i = t - gt.start[j];
-                        const int limit = min(plen, i + 1);
+                        const int limit = min(plen, t - gt.start[j] + 1);      // not past the start of the sequence
+                        const int* at = &s_tile[kMaxPattern + (t - w0)];
                         m = 1;
-                        while (m < limit && seq[i - m] == s_pat[a.p_max - 1 - m]) ++m;
+                        while (m < limit && at[-m] == s_pat[a.p_max - 1 - m]) ++m;
                     }
                     // a shorter match than one already seen in this stretch can never win
                     const bool keep = m >= s_best;
                     if (__ballot(keep) == 0) continue;
                     if (keep) atomicMax(&s_best, m);
-                    const int at = wave_append(&s_kept, keep);
-                    if (keep) out[at] = pack_place(j, m, t - gt.start[j] + 1);
+                    const int slot = wave_append(&s_kept, keep);
+                    if (keep) out[slot] = pack_place(j, m, t - gt.start[j] + 1);
                 }
             }
         }
@@ -269,24 +284,6 @@ __device__ __forceinline__ void hash_add(Expand& x, int table, int shift, uint32
         h = (h + 1) & (table - 1);
     }
     x.overflow = 1;
-}
-
-// The lanes of a wave count their keys.  Places of one member mostly show the same few tokens, and atomics
-// of many lanes on one LDS word run one after the other, so lanes that hold the key of the first
-// uncounted lane are counted by that lane alone (two rounds), the rest one by one.
-__device__ __forceinline__ void hash_count(Expand& x, int table, int shift, uint32_t key, bool active) {
-#pragma unroll
-    for (int round = 0; round < 2; ++round) {
-        const uint64_t act = __ballot(active);
-        if (act == 0) return;
-        const int leader = __ffsll(static_cast<long long>(act)) - 1;
-        const uint32_t k0 = __shfl(key, leader, 64);
-        const bool same = active && key == k0;
-        const uint64_t grp = __ballot(same);
-        if (lane_id() == leader) hash_add(x, table, shift, k0, static_cast<uint32_t>(__popcll(grp)));
-        active = active && !same;
-    }
-    if (active) hash_add(x, table, shift, key, 1u);
 }
 
 // The first top_k table entries in the order (count descending, key ascending) that pass the confidence
@@ -426,12 +423,20 @@ __device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float 
         x.mem_msk[from ^ 1][rank] = m;
         x.pick[rank] = val;
     };
-    if (n_cand <= 256) {
+    if (n_cand <= kRankAll) {
+        // few candidates: every holder counts how many of the others beat its own (reads in batches that
+        // do not wait for each other; entries past n_cand are stale and masked)
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             if (v[u] == 0) continue;
             int rank = 0;
-            for (int j = 0; j < n_cand; ++j) rank += x.cand[j] > v[u] ? 1 : 0;
+            for (int j0 = 0; j0 < n_cand; j0 += 8) {
+                uint64_t other[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) other[j] = x.cand[j0 + j];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) rank += (j0 + j < n_cand && other[j] > v[u]) ? 1 : 0;
+            }
             if (rank < a.top_k) emit(rank, v[u]);
         }
     } else {
@@ -455,12 +460,16 @@ __device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float 
     int now[PER];
 #pragma unroll
     for (int u = 0; u < PER; ++u) now[u] = -1;
-    for (int j = 0; j < n_pick; ++j) {
-        const uint64_t pj = x.pick[j];
-        alive += static_cast<int>(pj >> 32);
+    uint64_t picks[kMaxTopK];
+#pragma unroll
+    for (int j = 0; j < kMaxTopK; ++j) picks[j] = j < n_pick ? x.pick[j] : 0;
+#pragma unroll
+    for (int j = 0; j < kMaxTopK; ++j) {
+        if (j >= n_pick) continue;
+        alive += static_cast<int>(picks[j] >> 32);
 #pragma unroll
         for (int u = 0; u < PER; ++u)
-            if (act[u] && k[u] == ~static_cast<uint32_t>(pj)) now[u] = j;
+            if (act[u] && k[u] == ~static_cast<uint32_t>(picks[j])) now[u] = j;
     }
 #pragma unroll
     for (int u = 0; u < PER; ++u) own[u] = now[u];
@@ -653,7 +662,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (hashed) {
-                        hash_count(x, kTableSlots, shift, key[u], key[u] != kEmpty);
+                        if (key[u] != kEmpty) hash_add(x, kTableSlots, shift, key[u], 1u);
                     } else if (key[u] != kEmpty) {
                         const int t = static_cast<int>(key[u] & 0xffffffu) - lo_tok;
                         if (t >= 0 && t < range) {
@@ -804,7 +813,7 @@ extern "C" int seer_draft(const int32_t* tokens, const int32_t* seq_start, const
     a.gamma_max = p->gamma_max, a.top_k = p->top_k, a.p_min = p->pattern_lookup_min, a.p_max = p->pattern_lookup_max;
     a.vocab = p->vocab, a.parts = s.parts, a.chunk = s.chunk, a.cap = s.cap, a.min_confidence = p->min_confidence;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipLaunchKernelGGL(seer::draft::draft_match_kernel, dim3(s.parts, p->B), dim3(seer::draft::kThreads), 0, stream, a);
+    hipLaunchKernelGGL(seer::draft::draft_match_kernel, dim3(s.parts, p->B), dim3(seer::draft::kMatchThreads), 0, stream, a);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return static_cast<int>(err);
     hipLaunchKernelGGL(seer::draft::draft_expand_kernel, dim3(p->B), dim3(seer::draft::kThreads), 0, stream, a);
