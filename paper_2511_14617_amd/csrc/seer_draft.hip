@@ -41,10 +41,11 @@ constexpr int kMaxTopK = 16;
 constexpr int kTableSlots = 4096;         // LDS hash table: 4096 x (key, count) = 32 KB
 constexpr uint32_t kEmpty = 0xffffffffu;
 #ifndef SEER_DRAFT_PART_TOKENS
-#define SEER_DRAFT_PART_TOKENS 8192
+#define SEER_DRAFT_PART_TOKENS 4096
 #endif
 constexpr int kTokensPerPart = SEER_DRAFT_PART_TOKENS;   // target stretch of one match workgroup
-constexpr int kMaxParts = 64;
+constexpr int kMaxParts = 256;
+constexpr int kReqWindow = 64;            // request ids a match workgroup looks at per round
 constexpr int kQuads = 4;                 // 16-byte loads a match thread has in flight
 constexpr int kTile = 4 * kQuads * kMatchThreads;   // tokens a match workgroup takes per round
 constexpr int kSmall = 2048;              // places that the LDS-resident mode of the expansion holds
@@ -108,14 +109,13 @@ struct GroupTable {
     int bad;
 };
 
-__device__ __forceinline__ void load_group(const Args& a, int b, GroupTable& gt) {
+__device__ __forceinline__ void load_group(const Args& a, int g, GroupTable& gt) {
     const int tid = threadIdx.x;
     if (tid == 0) {
         gt.bad = 0;
         gt.n_seq = 0;
     }
     __syncthreads();
-    const int g = a.req_group[b];
     int q0 = 0, q1 = 0;
     if (g < 0 || g >= a.n_groups) {
         if (tid == 0) gt.bad = 1;
@@ -150,77 +150,117 @@ __device__ __forceinline__ void load_group(const Args& a, int b, GroupTable& gt)
 }
 
 // ------------------------------------------------------------------------------------------------
-// Match: how many pattern tokens end at each place of one stretch of the group's tokens.
+// Match: how many pattern tokens end at each place of one stretch of a group's tokens, for every
+// request of the group at once (the stretch is read once, whatever the number of requests).
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a) {
-    __shared__ GroupTable gt;
-    __shared__ int s_pat[kMaxPattern];
-    __shared__ __attribute__((aligned(16))) int s_tile[kMaxPattern + kTile];   // the tokens before the tile, then the tile
-    __shared__ int s_best, s_kept;
-    const int b = blockIdx.y, part = blockIdx.x, tid = threadIdx.x;
-    const int plen = min(max(a.pattern_len[b], 0), a.p_max);
-    if (tid < a.p_max) s_pat[tid] = a.pattern[static_cast<size_t>(b) * a.p_max + tid];
-    load_group(a, b, gt);
+struct MatchShared {
+    GroupTable gt;
+    __attribute__((aligned(16))) int tile[kMaxPattern + kTile];   // the tokens before the tile, then the tile
+    int pat[kReqWindow][kMaxPattern];
+    int req[kReqWindow], plen[kReqWindow], best[kReqWindow], kept[kReqWindow];
+    int n_req;
+};
+
+__global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int B) {
+    __shared__ MatchShared sh;
+    const int g = blockIdx.y, part = blockIdx.x, tid = threadIdx.x;
+    load_group(a, g, sh.gt);
     const int need = max(a.p_min, 1);
-    if (tid == 0) s_best = need, s_kept = 0;
-    __syncthreads();
-    uint32_t* out = a.list_a + static_cast<size_t>(b) * a.cap + static_cast<size_t>(part) * a.chunk;
-    if (gt.n_seq > 0 && plen >= need) {
-        const int newest = s_pat[a.p_max - 1];
-        const int lo = part * a.chunk, hi = min(lo + a.chunk, gt.flat[gt.n_seq]);
-        for (int j = 0; j < gt.n_seq; ++j) {
-            // places i of sequence j inside [lo, hi) whose next token exists
-            const int i0 = max(lo - gt.flat[j], 0), i1 = min(hi - gt.flat[j], gt.len[j] - 1);
-            if (i0 >= i1) continue;
-            // Tiles of aligned token quads (16-byte loads); a tile may begin before the stretch and end after
-            // it.  The tile and the kMaxPattern tokens before it also go to LDS: a place that holds the newest
-            // pattern token compares backwards there instead of through dependent global loads.
-            const int abs0 = gt.start[j] + i0, abs1 = gt.start[j] + i1;
-            for (int w0 = abs0 & ~3; w0 < abs1; w0 += kTile) {             // the same trip count for every thread
-                const int q0 = w0 + 4 * tid;
-                int tok[4 * kQuads];
+    // requests are taken in windows of kReqWindow consecutive ids: at most that many belong to this group
+    for (int b0 = 0; b0 < B; b0 += kReqWindow) {
+        if (tid == 0) sh.n_req = 0;
+        __syncthreads();
+        if (tid < kReqWindow && b0 + tid < B && a.req_group[b0 + tid] == g) {
+            const int r = atomicAdd(&sh.n_req, 1);
+            sh.req[r] = b0 + tid;
+            sh.plen[r] = min(max(a.pattern_len[b0 + tid], 0), a.p_max);
+            sh.best[r] = need, sh.kept[r] = 0;
+        }
+        __syncthreads();
+        const int n_req = sh.n_req;
+        if (n_req == 0) continue;
+        for (int i = tid; i < n_req * a.p_max; i += kMatchThreads) {
+            const int r = i / a.p_max, c = i - r * a.p_max;
+            sh.pat[r][c] = a.pattern[static_cast<size_t>(sh.req[r]) * a.p_max + c];
+        }
+        __syncthreads();
+        if (sh.gt.n_seq > 0) {
+            const int lo = part * a.chunk, hi = min(lo + a.chunk, sh.gt.flat[sh.gt.n_seq]);
+            for (int j = 0; j < sh.gt.n_seq; ++j) {
+                // places i of sequence j inside [lo, hi) whose next token exists
+                const int start = sh.gt.start[j];
+                const int i0 = max(lo - sh.gt.flat[j], 0), i1 = min(hi - sh.gt.flat[j], sh.gt.len[j] - 1);
+                if (i0 >= i1) continue;
+                // Tiles of aligned token quads (16-byte loads); a tile may begin before the stretch and end
+                // after it.  The tile and the kMaxPattern tokens before it also go to LDS: a place that holds a
+                // request's newest token compares backwards there instead of through dependent global loads.
+                const int abs0 = start + i0, abs1 = start + i1;
+                for (int w0 = abs0 & ~3; w0 < abs1; w0 += kTile) {          // the same trip count for every thread
+                    const int q0 = w0 + 4 * tid;
+                    int tok[4 * kQuads];
 #pragma unroll
-                for (int u = 0; u < kQuads; ++u) {
-                    const int q = q0 + u * 4 * kMatchThreads;
-                    if (q < abs1 && static_cast<int64_t>(q) + 4 <= a.pool_tokens) {
-                        const int4 v = *reinterpret_cast<const int4*>(a.tokens + q);
-                        tok[4 * u] = v.x, tok[4 * u + 1] = v.y, tok[4 * u + 2] = v.z, tok[4 * u + 3] = v.w;
-                    } else {
+                    for (int u = 0; u < kQuads; ++u) {
+                        const int q = q0 + u * 4 * kMatchThreads;
+                        if (q < abs1 && static_cast<int64_t>(q) + 4 <= a.pool_tokens) {
+                            const int4 v = *reinterpret_cast<const int4*>(a.tokens + q);
+                            tok[4 * u] = v.x, tok[4 * u + 1] = v.y, tok[4 * u + 2] = v.z, tok[4 * u + 3] = v.w;
+                        } else {
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) tok[4 * u + c] = q + c < abs1 ? a.tokens[q + c] : ~newest;
+                            for (int c = 0; c < 4; ++c) tok[4 * u + c] = q + c < abs1 ? a.tokens[q + c] : 0;
+                        }
                     }
-                }
-                int before = -1;
-                if (tid < kMaxPattern && w0 - kMaxPattern + tid >= 0) before = a.tokens[w0 - kMaxPattern + tid];
-                __syncthreads();                                            // the previous tile is no longer read
-                if (tid < kMaxPattern) s_tile[tid] = before;
+                    int before = -1;
+                    if (tid < kMaxPattern && w0 - kMaxPattern + tid >= 0) before = a.tokens[w0 - kMaxPattern + tid];
+                    __syncthreads();                                        // the previous tile is no longer read
+                    if (tid < kMaxPattern) sh.tile[tid] = before;
 #pragma unroll
-                for (int u = 0; u < kQuads; ++u)
-                    *reinterpret_cast<int4*>(&s_tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads]) =
-                        make_int4(tok[4 * u], tok[4 * u + 1], tok[4 * u + 2], tok[4 * u + 3]);
-                __syncthreads();
+                    for (int u = 0; u < kQuads; ++u)
+                        *reinterpret_cast<int4*>(&sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads]) =
+                            make_int4(tok[4 * u], tok[4 * u + 1], tok[4 * u + 2], tok[4 * u + 3]);
+                    uint32_t inside = 0;                                    // places outside the stretch end no match
 #pragma unroll
-                for (int c = 0; c < 4 * kQuads; ++c) {
-                    const int t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
-                    int m = 0;
-                    if (tok[c] == newest && t >= abs0 && t < abs1) {
-                        const int limit = min(plen, t - gt.start[j] + 1);      // not past the start of the sequence
-                        const int* at = &s_tile[kMaxPattern + (t - w0)];
-                        m = 1;
-                        while (m < limit && at[-m] == s_pat[a.p_max - 1 - m]) ++m;
+                    for (int c = 0; c < 4 * kQuads; ++c) {
+                        const int t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
+                        if (t >= abs0 && t < abs1) inside |= 1u << c;
                     }
-                    // a shorter match than one already seen in this stretch can never win
-                    const bool keep = m >= s_best;
-                    if (__ballot(keep) == 0) continue;
-                    if (keep) atomicMax(&s_best, m);
-                    const int slot = wave_append(&s_kept, keep);
-                    if (keep) out[slot] = pack_place(j, m, t - gt.start[j] + 1);
+                    __syncthreads();
+                    for (int r = 0; r < n_req; ++r) {
+                        const int plen = sh.plen[r];
+                        if (plen < need) continue;
+                        const int newest = sh.pat[r][a.p_max - 1];
+                        int best = sh.best[r];
+                        uint32_t* out = a.list_a + static_cast<size_t>(sh.req[r]) * a.cap + static_cast<size_t>(part) * a.chunk;
+#pragma unroll
+                        for (int c = 0; c < 4 * kQuads; ++c) {
+                            const bool hit = tok[c] == newest && ((inside >> c) & 1u) != 0;
+                            if (__ballot(hit) == 0) continue;
+                            const int t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
+                            int m = 0;
+                            if (hit) {
+                                const int limit = min(plen, t - start + 1);        // not past the start of the sequence
+                                const int* at = &sh.tile[kMaxPattern + (t - w0)];
+                                m = 1;
+                                while (m < limit && at[-m] == sh.pat[r][a.p_max - 1 - m]) ++m;
+                            }
+                            // a shorter match than one already seen in this stretch can never win
+                            const bool keep = m >= best;
+                            if (__ballot(keep) == 0) continue;
+                            if (keep && m > best) {
+                                atomicMax(&sh.best[r], m);
+                                best = m;
+                            }
+                            const int slot = wave_append(&sh.kept[r], keep);
+                            if (keep) out[slot] = pack_place(j, m, t - start + 1);
+                        }
+                    }
                 }
             }
         }
+        __syncthreads();
+        if (tid < n_req)
+            a.part_hdr[static_cast<size_t>(sh.req[tid]) * a.parts + part] = make_int2(sh.kept[tid], sh.kept[tid] > 0 ? sh.best[tid] : 0);
+        __syncthreads();
     }
-    __syncthreads();
-    if (tid == 0) a.part_hdr[static_cast<size_t>(b) * a.parts + part] = make_int2(s_kept, s_kept > 0 ? s_best : 0);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -557,7 +597,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
     if (tid < a.parts) h = a.part_hdr[static_cast<size_t>(b) * a.parts + tid];
     const int plen = min(max(a.pattern_len[b], 0), a.p_max);
     const int want = a.max_spec_tokens[b];
-    load_group(a, b, x.gt);
+    load_group(a, a.req_group[b], x.gt);
     if (tid < T) {
         x.tok[tid] = tid == 0 && plen > 0 ? a.pattern[static_cast<size_t>(b) * a.p_max + a.p_max - 1] : -1;
         x.par[tid] = tid == 0 ? -1 : -2;
@@ -761,7 +801,7 @@ int draft_shape(const seer_draft_params* p, DraftShape* s) {
     if (p->pattern_lookup_min > p->pattern_lookup_max) return SEER_ESHAPE;
     if (1 + static_cast<int64_t>(p->top_k) * p->gamma_max > SEER_MAX_T) return SEER_ESHAPE;
     if (p->top_k > kMaxTopK || p->pattern_lookup_max > kMaxPattern || p->vocab > (1 << 24) ||
-        p->pool_tokens > 0x7fff0000ll)
+        p->pool_tokens > 0x7fff0000ll || p->n_groups > 65535)
         return SEER_EUNSUPPORTED;
     int parts = (p->max_group_tokens + kTokensPerPart - 1) / kTokensPerPart;
     parts = parts < 1 ? 1 : (parts > kMaxParts ? kMaxParts : parts);
@@ -813,7 +853,8 @@ extern "C" int seer_draft(const int32_t* tokens, const int32_t* seq_start, const
     a.gamma_max = p->gamma_max, a.top_k = p->top_k, a.p_min = p->pattern_lookup_min, a.p_max = p->pattern_lookup_max;
     a.vocab = p->vocab, a.parts = s.parts, a.chunk = s.chunk, a.cap = s.cap, a.min_confidence = p->min_confidence;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipLaunchKernelGGL(seer::draft::draft_match_kernel, dim3(s.parts, p->B), dim3(seer::draft::kMatchThreads), 0, stream, a);
+    hipLaunchKernelGGL(seer::draft::draft_match_kernel, dim3(s.parts, p->n_groups), dim3(seer::draft::kMatchThreads), 0, stream, a,
+                       p->B);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return static_cast<int>(err);
     hipLaunchKernelGGL(seer::draft::draft_expand_kernel, dim3(p->B), dim3(seer::draft::kThreads), 0, stream, a);
