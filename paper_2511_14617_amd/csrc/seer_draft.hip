@@ -224,22 +224,39 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
                         if (t >= abs0 && t < abs1) inside |= 1u << c;
                     }
                     __syncthreads();
+                    // the token before each of this thread's quads (the others are in its registers)
+                    int prev_quad[kQuads];
+#pragma unroll
+                    for (int u = 0; u < kQuads; ++u) prev_quad[u] = sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads - 1];
                     for (int r = 0; r < n_req; ++r) {
                         const int plen = sh.plen[r];
                         if (plen < need) continue;
                         const int newest = sh.pat[r][a.p_max - 1];
+                        // A place counts only if at least `need` pattern tokens end there: with need >= 2 the
+                        // token before it is tested too, in registers, which leaves few places to look at closely.
+                        const bool two = need >= 2;
+                        const int second = two ? sh.pat[r][a.p_max - 2] : 0;
                         int best = sh.best[r];
-                        uint32_t* out = a.list_a + static_cast<size_t>(sh.req[r]) * a.cap + static_cast<size_t>(part) * a.chunk;
+                        uint32_t hits = 0;
 #pragma unroll
                         for (int c = 0; c < 4 * kQuads; ++c) {
-                            const bool hit = tok[c] == newest && ((inside >> c) & 1u) != 0;
-                            if (__ballot(hit) == 0) continue;
                             const int t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
-                            int m = 0;
-                            if (hit) {
+                            const int prev = (c & 3) ? tok[c - 1] : prev_quad[c >> 2];
+                            bool h = tok[c] == newest && ((inside >> c) & 1u) != 0;
+                            if (two) h = h && prev == second && t > start;
+                            hits |= static_cast<uint32_t>(h) << c;
+                        }
+                        uint32_t* out = a.list_a + static_cast<size_t>(sh.req[r]) * a.cap + static_cast<size_t>(part) * a.chunk;
+                        // every lane that has candidate places takes one of them per round
+                        while (__ballot(hits != 0) != 0) {
+                            int m = 0, t = 0;
+                            if (hits != 0) {
+                                const int c = __builtin_ctz(hits);
+                                hits &= hits - 1;
+                                t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
                                 const int limit = min(plen, t - start + 1);        // not past the start of the sequence
                                 const int* at = &sh.tile[kMaxPattern + (t - w0)];
-                                m = 1;
+                                m = two ? 2 : 1;
                                 while (m < limit && at[-m] == sh.pat[r][a.p_max - 1 - m]) ++m;
                             }
                             // a shorter match than one already seen in this stretch can never win
