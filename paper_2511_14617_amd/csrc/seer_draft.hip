@@ -158,6 +158,7 @@ struct MatchShared {
     __attribute__((aligned(16))) int tile[kMaxPattern + kTile];   // the tokens before the tile, then the tile
     int pat[kReqWindow][kMaxPattern];
     int req[kReqWindow], plen[kReqWindow], best[kReqWindow], kept[kReqWindow];
+    int4 info[kReqWindow + 1];                     // (newest token, the one before it, pattern length, -) per request
     int n_req;
 };
 
@@ -166,6 +167,7 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
     const int g = blockIdx.y, part = blockIdx.x, tid = threadIdx.x;
     load_group(a, g, sh.gt);
     const int need = max(a.p_min, 1);
+    const int last_quad = static_cast<int>((a.pool_tokens - 4) & ~3ll);      // the last quad that lies inside the pool
     // requests are taken in windows of kReqWindow consecutive ids: at most that many belong to this group
     for (int b0 = 0; b0 < B; b0 += kReqWindow) {
         if (tid == 0) sh.n_req = 0;
@@ -184,6 +186,10 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
             sh.pat[r][c] = a.pattern[static_cast<size_t>(sh.req[r]) * a.p_max + c];
         }
         __syncthreads();
+        if (tid <= n_req)
+            sh.info[tid] = tid < n_req ? make_int4(sh.pat[tid][a.p_max - 1], a.p_max >= 2 ? sh.pat[tid][a.p_max - 2] : 0, sh.plen[tid], 0)
+                                       : make_int4(0, 0, 0, 0);
+        __syncthreads();
         if (sh.gt.n_seq > 0) {
             const int lo = part * a.chunk, hi = min(lo + a.chunk, sh.gt.flat[sh.gt.n_seq]);
             for (int j = 0; j < sh.gt.n_seq; ++j) {
@@ -197,14 +203,18 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
                 const int abs0 = start + i0, abs1 = start + i1;
                 for (int w0 = abs0 & ~3; w0 < abs1; w0 += kTile) {          // the same trip count for every thread
                     const int q0 = w0 + 4 * tid;
+                    // All loads of the tile are requested before any is used: every quad comes from an address
+                    // clamped into the pool; only the pool's last, partial quad is patched token by token.
                     int tok[4 * kQuads];
+                    int4 quad[kQuads];
+#pragma unroll
+                    for (int u = 0; u < kQuads; ++u)
+                        quad[u] = *reinterpret_cast<const int4*>(a.tokens + min(q0 + u * 4 * kMatchThreads, last_quad));
 #pragma unroll
                     for (int u = 0; u < kQuads; ++u) {
+                        tok[4 * u] = quad[u].x, tok[4 * u + 1] = quad[u].y, tok[4 * u + 2] = quad[u].z, tok[4 * u + 3] = quad[u].w;
                         const int q = q0 + u * 4 * kMatchThreads;
-                        if (q < abs1 && static_cast<int64_t>(q) + 4 <= a.pool_tokens) {
-                            const int4 v = *reinterpret_cast<const int4*>(a.tokens + q);
-                            tok[4 * u] = v.x, tok[4 * u + 1] = v.y, tok[4 * u + 2] = v.z, tok[4 * u + 3] = v.w;
-                        } else {
+                        if (q > last_quad && q < abs1) {
 #pragma unroll
                             for (int c = 0; c < 4; ++c) tok[4 * u + c] = q + c < abs1 ? a.tokens[q + c] : 0;
                         }
@@ -228,15 +238,23 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
                     int prev_quad[kQuads];
 #pragma unroll
                     for (int u = 0; u < kQuads; ++u) prev_quad[u] = sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads - 1];
+                    const bool two = need >= 2;
+                    int4 info = sh.info[0];
                     for (int r = 0; r < n_req; ++r) {
-                        const int plen = sh.plen[r];
-                        if (plen < need) continue;
-                        const int newest = sh.pat[r][a.p_max - 1];
                         // A place counts only if at least `need` pattern tokens end there: with need >= 2 the
                         // token before it is tested too, in registers, which leaves few places to look at closely.
-                        const bool two = need >= 2;
-                        const int second = two ? sh.pat[r][a.p_max - 2] : 0;
-                        int best = sh.best[r];
+                        // (The next request's constants are requested before this one's are used.)
+                        const int newest = info.x, second = info.y, plen = info.z;
+                        info = sh.info[r + 1];
+                        if (plen < need) continue;
+                        // first only whether any lane holds a candidate at all: two compares per place
+                        bool any = false;
+#pragma unroll
+                        for (int c = 0; c < 4 * kQuads; ++c) {
+                            const int prev = (c & 3) ? tok[c - 1] : prev_quad[c >> 2];
+                            any |= (tok[c] == newest) & (!two | (prev == second));
+                        }
+                        if (__ballot(any) == 0) continue;
                         uint32_t hits = 0;
 #pragma unroll
                         for (int c = 0; c < 4 * kQuads; ++c) {
@@ -246,7 +264,9 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
                             if (two) h = h && prev == second && t > start;
                             hits |= static_cast<uint32_t>(h) << c;
                         }
+                        if (__ballot(hits != 0) == 0) continue;
                         uint32_t* out = a.list_a + static_cast<size_t>(sh.req[r]) * a.cap + static_cast<size_t>(part) * a.chunk;
+                        int best = sh.best[r];
                         // every lane that has candidate places takes one of them per round
                         while (__ballot(hits != 0) != 0) {
                             int m = 0, t = 0;
@@ -687,15 +707,30 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
             __syncthreads();
             break;
         }
-        // the token a place shows at this level, with the rank of the member that owns the place
-        auto key_of = [&](int e, uint32_t pl) -> uint32_t {
-            int r = 0;
-            while (r + 1 < nmem && e >= x.mem[r + 1].base) ++r;
-            const int j = place_seq(pl), off = place_off(pl) + d - 1;
-            if (off >= x.gt.len[j]) return kEmpty;
-            const int t = a.tokens[x.gt.start[j] + off];
-            if (t < 0 || t >= a.vocab) return kEmpty;
-            return (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t);
+        // The tokens that four places per thread show at this level, with the rank of the member that owns
+        // each place, as keys.  The four places are requested together, then the four tokens (from addresses
+        // clamped into the pool), so that a thread waits twice per round, not eight times.
+        auto keys_of = [&](int e0, uint32_t (&pl)[4], uint32_t (&key)[4]) {
+            int at[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) pl[u] = cur[min(e0 + u * kThreads + tid, n_level - 1)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = place_seq(pl[u]), off = place_off(pl[u]) + d - 1;
+                ok[u] = e0 + u * kThreads + tid < n_level && off < x.gt.len[j];
+                at[u] = ok[u] ? x.gt.start[j] + off : 0;
+            }
+            int t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u] = a.tokens[at[u]];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * kThreads + tid;
+                int r = 0;
+                while (r + 1 < nmem && e >= x.mem[r + 1].base) ++r;
+                key[u] = ok[u] && t[u] >= 0 && t[u] < a.vocab ? (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t[u]) : kEmpty;
+            }
         };
         int n_pick = 0;
         // Pass 0 counts in a hash table.  Only if more distinct (member, token) pairs turn up than the
@@ -710,12 +745,8 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
             __syncthreads();
             const int lo_tok = (pass - 1) * range;
             for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
-                uint32_t key[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int e = e0 + u * kThreads + tid;
-                    key[u] = e < n_level ? key_of(e, cur[e]) : kEmpty;
-                }
+                uint32_t pl[4], key[4];
+                keys_of(e0, pl, key);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (hashed) {
@@ -744,12 +775,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
         if (d < levels) {
             for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
                 uint32_t pl[4], key[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int e = e0 + u * kThreads + tid;
-                    pl[u] = e < n_level ? cur[e] : 0u;
-                    key[u] = e < n_level ? key_of(e, pl[u]) : kEmpty;
-                }
+                keys_of(e0, pl, key);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     int child = -1;
@@ -811,7 +837,7 @@ struct DraftShape {
 
 int draft_shape(const seer_draft_params* p, DraftShape* s) {
     using namespace seer::draft;
-    if (!p || p->B < 0 || p->n_groups < 1 || p->n_seq < 1 || p->pool_tokens < 1 || p->max_group_tokens < 1) return SEER_EINVAL;
+    if (!p || p->B < 0 || p->n_groups < 1 || p->n_seq < 1 || p->pool_tokens < 4 || p->max_group_tokens < 1) return SEER_EINVAL;
     if (p->gamma_max < 1 || p->top_k < 1 || p->pattern_lookup_max < 1 || p->pattern_lookup_min < 0 || p->vocab < 1)
         return SEER_EINVAL;
     if (!(p->min_confidence >= 0.0f) || !(p->min_confidence <= 1.0f)) return SEER_EINVAL;
