@@ -96,7 +96,7 @@ __device__ __forceinline__ int wave_append(int* counter, bool hit) {
     const int leader = __ffsll(static_cast<long long>(mask)) - 1;
     int base = 0;
     if (lane_id() == leader) base = atomicAdd(counter, __popcll(mask));
-    base = __shfl(base, leader, 64);
+    base = __builtin_amdgcn_readlane(base, leader);
     return base + __popcll(mask & ((1ull << lane_id()) - 1));
 }
 
@@ -159,6 +159,7 @@ struct MatchShared {
     int pat[kReqWindow][kMaxPattern];
     int req[kReqWindow], plen[kReqWindow], best[kReqWindow], kept[kReqWindow];
     int4 info[kReqWindow + 1];                     // (newest token, the one before it, pattern length, -) per request
+    int4 older[kReqWindow + 1];                    // the four pattern tokens before those two
     int n_req;
 };
 
@@ -186,9 +187,11 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
             sh.pat[r][c] = a.pattern[static_cast<size_t>(sh.req[r]) * a.p_max + c];
         }
         __syncthreads();
-        if (tid <= n_req)
-            sh.info[tid] = tid < n_req ? make_int4(sh.pat[tid][a.p_max - 1], a.p_max >= 2 ? sh.pat[tid][a.p_max - 2] : 0, sh.plen[tid], 0)
-                                       : make_int4(0, 0, 0, 0);
+        if (tid <= n_req) {
+            auto back = [&](int k) { return tid < n_req && a.p_max > k ? sh.pat[tid][a.p_max - 1 - k] : 0; };
+            sh.info[tid] = make_int4(back(0), back(1), tid < n_req ? sh.plen[tid] : 0, 0);
+            sh.older[tid] = make_int4(back(2), back(3), back(4), back(5));
+        }
         __syncthreads();
         if (sh.gt.n_seq > 0) {
             const int lo = part * a.chunk, hi = min(lo + a.chunk, sh.gt.flat[sh.gt.n_seq]);
@@ -239,13 +242,14 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
 #pragma unroll
                     for (int u = 0; u < kQuads; ++u) prev_quad[u] = sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads - 1];
                     const bool two = need >= 2;
-                    int4 info = sh.info[0];
+                    int4 info = sh.info[0], older = sh.older[0];
                     for (int r = 0; r < n_req; ++r) {
                         // A place counts only if at least `need` pattern tokens end there: with need >= 2 the
                         // token before it is tested too, in registers, which leaves few places to look at closely.
                         // (The next request's constants are requested before this one's are used.)
                         const int newest = info.x, second = info.y, plen = info.z;
-                        info = sh.info[r + 1];
+                        const int p2 = older.x, p3 = older.y, p4 = older.z, p5 = older.w;
+                        info = sh.info[r + 1], older = sh.older[r + 1];
                         if (plen < need) continue;
                         // first only whether any lane holds a candidate at all: two compares per place
                         bool any = false;
@@ -276,8 +280,26 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
                                 t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
                                 const int limit = min(plen, t - start + 1);        // not past the start of the sequence
                                 const int* at = &sh.tile[kMaxPattern + (t - w0)];
-                                m = two ? 2 : 1;
-                                while (m < limit && at[-m] == sh.pat[r][a.p_max - 1 - m]) ++m;
+                                // the five tokens before the place are requested together and compared in
+                                // registers; only a longer match goes on through LDS
+                                const int v1 = at[-1], v2 = at[-2], v3 = at[-3], v4 = at[-4], v5 = at[-5];
+                                m = 1;
+                                if (1 < limit && v1 == second) {
+                                    m = 2;
+                                    if (2 < limit && v2 == p2) {
+                                        m = 3;
+                                        if (3 < limit && v3 == p3) {
+                                            m = 4;
+                                            if (4 < limit && v4 == p4) {
+                                                m = 5;
+                                                if (5 < limit && v5 == p5) {
+                                                    m = 6;
+                                                    while (m < limit && at[-m] == sh.pat[r][a.p_max - 1 - m]) ++m;
+                                                }
+                                            }
+                                        }
+                                    }
+                                }
                             }
                             // a shorter match than one already seen in this stretch can never win
                             const bool keep = m >= best;
