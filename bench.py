@@ -282,10 +282,13 @@ def main() -> int:
                                max_group_tokens=dr.max_group_tokens, workspace=ws_dr, out=dr_out)
         draft()
         draft_ms = timed(draft, n=20)
-        scanned = int(sum(int(dr.seq_len[dr.group_first[g]:dr.group_first[g + 1]].sum()) for g in dr.req_group))
-        draft_info = {"draft_ms": draft_ms, "top_k": top_k, "gamma_max": gamma, "history_tokens": int(dr.seq_len.sum()),
-                      "tokens_scanned": scanned, "scan_GBps": scanned * 4 / (draft_ms * 1e-3) / 1e9,
+        # algorithmic bytes of the match scan: the tokens of every group that has a live request, read once
+        live_groups = sorted(set(int(g) for g in dr.req_group))
+        scanned = int(sum(int(dr.seq_len[dr.group_first[g]:dr.group_first[g + 1]].sum()) for g in live_groups))
+        draft_info = {"draft_ms": draft_ms, "top_k": top_k, "gamma_max": gamma, "pattern_lookup": [dr.p_min, dr.p_max],
+                      "history_tokens": scanned, "history_bytes": scanned * 4,
                       "mean_match_len": float(dr_out[4].float().mean().item()),
+                      "max_match_places": int(dr_out[3][:, 0].max().item()),
                       "mean_draft_nodes": float((dr_out[1][:, 1:] >= 0).sum(1).float().mean().item())}
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
