@@ -1,6 +1,6 @@
 """MI355X-native batched draft verification (the verify step of grouped
-speculative decoding): `seer_verify_attention` and `seer_accept` (plus `seer_accept_sampled` and
-`seer_kv_commit`, the calls around them), hand-written
+speculative decoding): `seer_verify_attention` and `seer_accept` (plus `seer_accept_sampled`,
+`seer_kv_commit` and `seer_draft`, the calls around them), hand-written
 HIP for gfx950 behind a C ABI (include/seer_verify.h).
 
 The binding is imported lazily so that the input generators in `workloads` can
