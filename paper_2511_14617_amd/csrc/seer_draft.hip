@@ -353,6 +353,7 @@ struct Expand {
     uint64_t mem_msk[2][kMaxTopK];         //   level d - 1 in buffer (d - 1) & 1
     uint64_t red[kThreads / 64];
     uint64_t best[kMaxTopK];
+    int ref[kMaxTopK], ref_cnt[kMaxTopK];  // the token all places of a member show, and how many show it
     uint64_t pick[kMaxTopK];               // chosen children: count << 32 | ~key, best first
     int fill[kMaxTopK];
     int tok[SEER_MAX_T], par[SEER_MAX_T], num[SEER_MAX_T];
@@ -451,48 +452,87 @@ __device__ __forceinline__ void emit_nodes(Expand& x, int d, int top_k, int n_pi
 // against each other if they are few, else by top_k rounds of a maximum.  The thread that holds the pick
 // of rank j writes draft node j of the level.  Returns the number of picks; n_alive = places they own.
 template <bool SOLO, int PER>
-__device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float threshold, int (&own)[PER],
+__device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float threshold, int n_mem, int (&own)[PER],
                                          const int (&t)[PER], int& n_alive) {
     const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
     const uint64_t below = (1ull << lane_id()) - 1;
-    int table = 64;
-    while (table < kTableSlots && table < 2 * n_alive) table <<= 1;      // at most n_alive distinct keys
-    const int shift = 32 - __builtin_ctz(static_cast<unsigned>(table));
-    for (int s = me; s < table; s += stride) x.key[s] = kEmpty, x.cnt[s] = 0;
-    if (me < kMaxTopK) x.best[me] = 0;
-    if (me == 0) x.n_cand = 0;
-    level_sync<SOLO>();
-    uint32_t k[PER], h[PER], old[PER];
+    uint32_t k[PER];
     bool act[PER];
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
         act[u] = own[u] >= 0 && t[u] >= 0;       // else the sequence ends here, or the token cannot be proposed
         k[u] = (static_cast<uint32_t>(own[u]) << 24) | static_cast<uint32_t>(t[u]);
-        h[u] = (k[u] * 2654435761u) >> shift;
-        old[u] = kEmpty;
-        if (act[u]) old[u] = atomicCAS(&x.key[h[u]], kEmpty, k[u]);
     }
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-        if (!act[u]) continue;
-        for (int probes = 0; old[u] != kEmpty && old[u] != k[u] && probes < table; ++probes) {
-            h[u] = (h[u] + 1) & (table - 1);
-            old[u] = atomicCAS(&x.key[h[u]], kEmpty, k[u]);
-        }
-        atomicAdd(&x.cnt[h[u]], 1u);
-    }
-    level_sync<SOLO>();
     uint64_t v[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) v[u] = 0;
+    // Inside a phrase that recurs, all places of a member show the same token: then there is nothing to
+    // count pair by pair.  Every place writes its token as its member's reference (any one wins), and if
+    // all places agree with their member's reference the members themselves are the candidates.
+    bool unanimous = false;
+    if (!SOLO && n_mem == 1) {                   // (several members are rarely all of one mind: not tried)
+        if (me < kMaxTopK) x.ref_cnt[me] = 0;
+        if (me == 0) x.n_cand = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+            if (act[u]) x.ref[own[u]] = t[u];
+        __syncthreads();
+        bool agree = true;
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+            if (act[u]) agree = agree && t[u] == x.ref[own[u]];
+        unanimous = __syncthreads_and(agree ? 1 : 0) != 0;
+    }
+    if (unanimous) {
+        for (int r = 0; r < n_mem; ++r) {
+            int c = 0;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) c += __popcll(__ballot(act[u] && own[u] == r));
+            if (lane_id() == 0 && c) atomicAdd(&x.ref_cnt[r], c);
+        }
+        __syncthreads();
+        if (me < n_mem) {
+            const uint32_t c = static_cast<uint32_t>(x.ref_cnt[me]);
+            if (c > 0 && static_cast<float>(c) >= threshold)
+                v[0] = (static_cast<uint64_t>(c) << 32) |
+                       static_cast<uint32_t>(~((static_cast<uint32_t>(me) << 24) | static_cast<uint32_t>(x.ref[me])));
+        }
+    } else {
+        int table = 64;
+        while (table < kTableSlots && table < 2 * n_alive) table <<= 1;      // at most n_alive distinct keys
+        const int shift = 32 - __builtin_ctz(static_cast<unsigned>(table));
+        for (int s = me; s < table; s += stride) x.key[s] = kEmpty, x.cnt[s] = 0;
+        if (me < kMaxTopK) x.best[me] = 0;
+        if (me == 0) x.n_cand = 0;
+        level_sync<SOLO>();
+        uint32_t h[PER], old[PER];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            h[u] = (k[u] * 2654435761u) >> shift;
+            old[u] = kEmpty;
+            if (act[u]) old[u] = atomicCAS(&x.key[h[u]], kEmpty, k[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            if (!act[u]) continue;
+            for (int probes = 0; old[u] != kEmpty && old[u] != k[u] && probes < table; ++probes) {
+                h[u] = (h[u] + 1) & (table - 1);
+                old[u] = atomicCAS(&x.key[h[u]], kEmpty, k[u]);
+            }
+            atomicAdd(&x.cnt[h[u]], 1u);
+        }
+        level_sync<SOLO>();
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            if (act[u] && old[u] == kEmpty) {                       // this thread entered the pair: it speaks for it
+                const uint32_t c = x.cnt[h[u]];
+                if (static_cast<float>(c) >= threshold) v[u] = (static_cast<uint64_t>(c) << 32) | static_cast<uint32_t>(~k[u]);
+            }
+        }
+    }
     int wave_total = 0;
 #pragma unroll
-    for (int u = 0; u < PER; ++u) {
-        v[u] = 0;
-        if (act[u] && old[u] == kEmpty) {                       // this thread entered the pair: it speaks for it
-            const uint32_t c = x.cnt[h[u]];
-            if (static_cast<float>(c) >= threshold) v[u] = (static_cast<uint64_t>(c) << 32) | static_cast<uint32_t>(~k[u]);
-        }
-        wave_total += __popcll(__ballot(v[u] != 0));
-    }
+    for (int u = 0; u < PER; ++u) wave_total += __popcll(__ballot(v[u] != 0));
     int base = 0;
     if (!SOLO) {
         if (lane_id() == 0 && wave_total) base = atomicAdd(&x.n_cand, wave_total);
@@ -582,7 +622,7 @@ __device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float 
 // x.place / x.owner.  SOLO: wave 0 alone, no workgroup barriers.  Returns the next level (levels + 1 = finished).
 template <bool SOLO, int PER>
 __device__ __forceinline__ int reg_levels(const Args& a, Expand& x, int d, int levels, float threshold, int& n_places,
-                                          int& n_alive) {
+                                          int& n_alive, int& n_mem) {
     const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
     uint32_t place[PER];
     int own[PER];
@@ -613,10 +653,12 @@ __device__ __forceinline__ int reg_levels(const Args& a, Expand& x, int d, int l
             int t[PER];
 #pragma unroll
             for (int u = 0; u < PER; ++u) t[u] = cont[u][l];
-            if (reg_level<SOLO, PER>(a, x, d, threshold, own, t, n_alive) == 0) {
+            const int n_pick = reg_level<SOLO, PER>(a, x, d, threshold, n_mem, own, t, n_alive);
+            if (n_pick == 0) {
                 done = true;
                 d = levels + 1;
             } else {
+                n_mem = n_pick;
                 ++d;
             }
         }
@@ -732,7 +774,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
         // The tokens that four places per thread show at this level, with the rank of the member that owns
         // each place, as keys.  The four places are requested together, then the four tokens (from addresses
         // clamped into the pool), so that a thread waits twice per round, not eight times.
-        auto keys_of = [&](int e0, uint32_t (&pl)[4], uint32_t (&key)[4]) {
+        auto keys_of = [&](int e0, uint32_t (&pl)[4], uint32_t (&key)[4], bool (&outside)[4]) {
             int at[4];
             bool ok[4];
 #pragma unroll
@@ -751,9 +793,51 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
                 const int e = e0 + u * kThreads + tid;
                 int r = 0;
                 while (r + 1 < nmem && e >= x.mem[r + 1].base) ++r;
-                key[u] = ok[u] && t[u] >= 0 && t[u] < a.vocab ? (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t[u]) : kEmpty;
+                outside[u] = ok[u] && (t[u] < 0 || t[u] >= a.vocab);       // a token that cannot be proposed
+                key[u] = ok[u] && !outside[u] ? (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t[u]) : kEmpty;
             }
         };
+        // A single member whose places all show the same token (inside a phrase that recurs): one pass finds
+        // that out and counts them; the place list stays as it is (places whose sequence ended stay ended).
+        if (nmem == 1) {
+            if (tid == 0) x.ref[0] = -1, x.ref_cnt[0] = 0;
+            __syncthreads();
+            bool agree = true;
+            int wave_count = 0;
+            for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
+                uint32_t pl[4], key[4];
+                bool outside[4];
+                keys_of(e0, pl, key, outside);
+                if (e0 == 0) {                     // any token of the first round serves as the reference
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (key[u] != kEmpty) x.ref[0] = static_cast<int>(key[u] & 0xffffffu);
+                    __syncthreads();
+                }
+                const int ref = x.ref[0];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (outside[u]) agree = false;
+                    if (key[u] != kEmpty && static_cast<int>(key[u] & 0xffffffu) != ref) agree = false;
+                    wave_count += __popcll(__ballot(key[u] != kEmpty));
+                }
+            }
+            if (lane_id() == 0 && wave_count) atomicAdd(&x.ref_cnt[0], wave_count);
+            if (__syncthreads_and(agree ? 1 : 0)) {
+                const int c = x.ref_cnt[0];
+                if (c == 0 || static_cast<float>(c) < threshold) {
+                    d = levels + 1;
+                    break;
+                }
+                if (tid == 0) {
+                    x.pick[0] = (static_cast<uint64_t>(c) << 32) | static_cast<uint32_t>(~static_cast<uint32_t>(x.ref[0]));
+                    emit_nodes(x, d, a.top_k, 1);
+                    x.mem[0] = Member{0, n_level, x.next[0].slot};
+                }
+                __syncthreads();
+                continue;
+            }
+        }
         int n_pick = 0;
         // Pass 0 counts in a hash table.  Only if more distinct (member, token) pairs turn up than the
         // table has slots do further passes count token ranges in a directly indexed table.
@@ -768,7 +852,8 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
             const int lo_tok = (pass - 1) * range;
             for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
                 uint32_t pl[4], key[4];
-                keys_of(e0, pl, key);
+                bool outside[4];
+                keys_of(e0, pl, key, outside);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (hashed) {
@@ -797,7 +882,8 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
         if (d < levels) {
             for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
                 uint32_t pl[4], key[4];
-                keys_of(e0, pl, key);
+                bool outside[4];
+                keys_of(e0, pl, key, outside);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     int child = -1;
@@ -832,8 +918,9 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
             x.mem_msk[(d - 1) & 1][tid] = x.msk[x.mem[tid].slot];
         }
         __syncthreads();
-        if (n_alive > kSolo) d = reg_levels<false, kSmall / kThreads>(a, x, d, levels, threshold, n_places, n_alive);
-        if (d <= levels && tid < 64) reg_levels<true, kSolo / 64>(a, x, d, levels, threshold, n_places, n_alive);
+        int n_mem = x.nmem;
+        if (n_alive > kSolo) d = reg_levels<false, kSmall / kThreads>(a, x, d, levels, threshold, n_places, n_alive, n_mem);
+        if (d <= levels && tid < 64) reg_levels<true, kSolo / 64>(a, x, d, levels, threshold, n_places, n_alive, n_mem);
     }
     __syncthreads();
 
