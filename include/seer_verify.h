@@ -314,6 +314,36 @@ int seer_draft(const int32_t* tokens, const int32_t* seq_start, const int32_t* s
                int32_t* match_len, int32_t* status, void* workspace, size_t workspace_bytes,
                void* hip_stream);
 
+/*
+ * Appending what a step emitted to the token histories that seer_draft reads: the counterpart of
+ * the draft server's update call (Appendix A.2: the new tokens of a request go to that request's
+ * own sequence of its group), here one store per token because nothing is indexed.
+ *
+ * For request b with q = req_seq[b] and n = n_emitted[b] (as written by seer_kv_commit): the tokens
+ * emitted_tokens[b][0 .. n) are written behind the seq_len[q] tokens of sequence q, seq_len[q]
+ * grows by n, and (if pattern is given) pattern[b] / pattern_len[b] are refreshed to the newest
+ * min(pattern_lookup_max, seq_len[q]) tokens of the sequence, right-aligned as seer_draft reads them
+ * (unused leading entries -1).
+ *
+ *  tokens         device [pool_tokens] int32, written behind the sequences' current ends
+ *  seq_start      device [n_seq] int32;  seq_len device [n_seq] int32, read and written
+ *  seq_capacity   device [n_seq] int32: room of each sequence in the pool (>= seq_len)
+ *  req_seq        device [B] int32: the sequence that holds request b's own tokens; two requests
+ *                 of one call must not name the same sequence
+ *  emitted_tokens device [B,T] int32;  n_emitted device [B] int32, 0 .. T
+ *  pattern        device [B, pattern_lookup_max] int32 or NULL;  pattern_len device [B] int32,
+ *                 NULL iff pattern is NULL
+ *  status         device [1] int32 or NULL; bits OR-ed in: 1 = req_seq or the sequence's range out
+ *                 of range (request skipped), 2 = no room for n more tokens or n out of range
+ *                 (nothing appended, pattern still refreshed).  The caller clears it.
+ * Asynchronous on hip_stream; returns SEER_OK, a negative SEER_E* or a positive hipError_t.
+ */
+int seer_history_append(int32_t* tokens, const int32_t* seq_start, int32_t* seq_len,
+                        const int32_t* seq_capacity, const int32_t* req_seq,
+                        const int32_t* emitted_tokens, const int32_t* n_emitted, int32_t B, int32_t T,
+                        int32_t n_seq, int64_t pool_tokens, int32_t pattern_lookup_max, int32_t* pattern,
+                        int32_t* pattern_len, int32_t* status, void* hip_stream);
+
 /* Static text for a return code of either call (negative SEER_E*, or a
  * positive hipError_t). */
 const char* seer_strerror(int code);

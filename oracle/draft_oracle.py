@@ -148,3 +148,27 @@ def batch_speculate(tokens: np.ndarray, seq_start: np.ndarray, seq_len: np.ndarr
         d_msk[b] = np.array(r["mask"], dtype=np.uint64)
         d_len[b] = r["match_len"]
     return d_tok, d_par, d_msk, d_cnt, d_len
+
+
+def history_append(tokens: np.ndarray, seq_start: np.ndarray, seq_len: np.ndarray, seq_capacity: np.ndarray,
+                   req_seq: np.ndarray, emitted_tokens: np.ndarray, n_emitted: np.ndarray, p_max: int):
+    """What a step emitted goes behind the request's own sequence (Appendix A.2: updates are kept apart per
+    request); the request's pattern becomes the newest p_max tokens of that sequence, right-aligned, -1 in
+    front.  A request without room for its tokens appends nothing.  Returns new (tokens, seq_len, pattern,
+    pattern_len)."""
+    tokens, seq_len = tokens.copy(), seq_len.copy()
+    B = len(req_seq)
+    pattern = np.full((B, p_max), -1, np.int32)
+    pattern_len = np.zeros(B, np.int32)
+    for b in range(B):
+        q, n = int(req_seq[b]), int(n_emitted[b])
+        start, length = int(seq_start[q]), int(seq_len[q])
+        if 0 <= n <= emitted_tokens.shape[1] and length + n <= int(seq_capacity[q]):
+            tokens[start + length: start + length + n] = emitted_tokens[b, :n]
+            length += n
+            seq_len[q] = length
+        tail = tokens[start + max(0, length - p_max): start + length]
+        pattern_len[b] = len(tail)
+        if len(tail):
+            pattern[b, p_max - len(tail):] = tail
+    return tokens, seq_len, pattern, pattern_len

@@ -20,7 +20,8 @@ SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALI
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
            "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
-           "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_strerror")
+           "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_history_append",
+           "seer_strerror")
 
 
 class SeerAttnParams(ctypes.Structure):
@@ -83,6 +84,8 @@ def load_library() -> ctypes.CDLL:
         lib.seer_draft_workspace.restype = sz
         lib.seer_draft.argtypes = [vp] * 8 + [ctypes.POINTER(SeerDraftParams)] + [vp] * 7 + [sz, vp]
         lib.seer_draft.restype = ctypes.c_int
+        lib.seer_history_append.argtypes = [vp] * 7 + [i32, i32, i32, ctypes.c_int64, i32, vp, vp, vp, vp]
+        lib.seer_history_append.restype = ctypes.c_int
         lib.seer_strerror.argtypes = [ctypes.c_int]
         lib.seer_strerror.restype = ctypes.c_char_p
         _lib = lib
@@ -325,3 +328,31 @@ def seer_draft(tokens: torch.Tensor, seq_start: torch.Tensor, seq_len: torch.Ten
                           _ptr(d_par), _ptr(d_msk), _ptr(d_cnt), _ptr(d_len), _ptr(status), _ptr(workspace),
                           workspace.numel(), _stream_handle(stream)))
     return d_tok, d_par, d_msk, d_cnt, d_len
+
+
+def seer_history_append(tokens: torch.Tensor, seq_start: torch.Tensor, seq_len: torch.Tensor, seq_capacity: torch.Tensor,
+                        req_seq: torch.Tensor, emitted_tokens: torch.Tensor, n_emitted: torch.Tensor, *,
+                        pattern: Optional[torch.Tensor] = None, pattern_len: Optional[torch.Tensor] = None,
+                        status: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Appends emitted_tokens[b, :n_emitted[b]] to sequence req_seq[b] of the pool (in place), advances seq_len
+    (in place) and, if given, refreshes pattern [B, p_max] / pattern_len [B] to the sequences' newest tokens."""
+    lib = load_library()
+    B, T = emitted_tokens.shape
+    n_seq = seq_start.shape[0]
+    _want(tokens, torch.int32, (tokens.shape[0],), "tokens")
+    _want(seq_start, torch.int32, (n_seq,), "seq_start")
+    _want(seq_len, torch.int32, (n_seq,), "seq_len")
+    _want(seq_capacity, torch.int32, (n_seq,), "seq_capacity")
+    _want(req_seq, torch.int32, (B,), "req_seq")
+    _want(emitted_tokens, torch.int32, (B, T), "emitted_tokens")
+    _want(n_emitted, torch.int32, (B,), "n_emitted")
+    p_max = 1
+    if pattern is not None:
+        p_max = pattern.shape[1]
+        _want(pattern, torch.int32, (B, p_max), "pattern")
+        _want(pattern_len, torch.int32, (B,), "pattern_len")
+    if status is not None:
+        _want(status, torch.int32, (1,), "status")
+    _check(lib.seer_history_append(_ptr(tokens), _ptr(seq_start), _ptr(seq_len), _ptr(seq_capacity), _ptr(req_seq),
+                                   _ptr(emitted_tokens), _ptr(n_emitted), B, T, n_seq, tokens.shape[0], p_max,
+                                   _ptr(pattern), _ptr(pattern_len), _ptr(status), _stream_handle(stream)))

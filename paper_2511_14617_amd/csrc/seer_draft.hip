@@ -1013,3 +1013,86 @@ extern "C" int seer_draft(const int32_t* tokens, const int32_t* seq_start, const
     err = hipGetLastError();
     return err == hipSuccess ? SEER_OK : static_cast<int>(err);
 }
+
+// ------------------------------------------------------------------------------------------------
+// Appending the tokens a step emitted to the histories (the counterpart of the draft server's
+// update call, Appendix A.2: new tokens of one request go to that request's own sequence).
+// ------------------------------------------------------------------------------------------------
+namespace seer {
+namespace draft {
+
+struct AppendArgs {
+    int32_t* tokens;
+    const int32_t* seq_start;
+    int32_t* seq_len;
+    const int32_t* seq_capacity;
+    const int32_t* req_seq;
+    const int32_t* emitted_tokens;
+    const int32_t* n_emitted;
+    int32_t* pattern;
+    int32_t* pattern_len;
+    int32_t* status;
+    int64_t pool_tokens;
+    int T, n_seq, p_max;
+};
+
+__global__ __launch_bounds__(64) void history_append_kernel(AppendArgs a) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int q = a.req_seq[b];
+    int n = a.n_emitted[b];
+    int bad = 0;
+    int start = 0, len = 0;
+    if (q < 0 || q >= a.n_seq) {
+        bad = 1;
+    } else {
+        start = a.seq_start[q];
+        len = a.seq_len[q];
+        const int cap = a.seq_capacity[q];
+        if (start < 0 || len < 0 || cap < len || static_cast<int64_t>(start) + cap > a.pool_tokens) bad = 1;
+        else if (n < 0 || n > a.T || len + n > cap) bad = 2;
+    }
+    if (bad) {
+        if (lane == 0 && a.status) atomicOr(a.status, bad);
+        if (bad == 1) return;                        // no sequence to speak of: nothing is touched
+        n = 0;                                       // no room (or a count out of range): nothing is appended
+    }
+    if (lane < n) a.tokens[start + len + lane] = a.emitted_tokens[static_cast<size_t>(b) * a.T + lane];
+    const int total = len + n;
+    if (lane == 0) {
+        a.seq_len[q] = total;
+        if (a.pattern_len) a.pattern_len[b] = min(total, a.p_max);
+    }
+    if (a.pattern && lane < a.p_max) {
+        // the request's newest tokens, right-aligned: the appended ones come from the emitted row, the
+        // older ones from the pool
+        const int back = a.p_max - 1 - lane;         // 0 = the newest token
+        int t = -1;
+        if (back < n) t = a.emitted_tokens[static_cast<size_t>(b) * a.T + (n - 1 - back)];
+        else if (back < total) t = a.tokens[start + total - 1 - back];
+        a.pattern[static_cast<size_t>(b) * a.p_max + lane] = t;
+    }
+}
+
+}  // namespace draft
+}  // namespace seer
+
+extern "C" int seer_history_append(int32_t* tokens, const int32_t* seq_start, int32_t* seq_len,
+                                   const int32_t* seq_capacity, const int32_t* req_seq,
+                                   const int32_t* emitted_tokens, const int32_t* n_emitted, int32_t B, int32_t T,
+                                   int32_t n_seq, int64_t pool_tokens, int32_t pattern_lookup_max, int32_t* pattern,
+                                   int32_t* pattern_len, int32_t* status, void* hip_stream) {
+    if (B < 0 || n_seq < 1 || pool_tokens < 1) return SEER_EINVAL;
+    if (T < 1 || T > SEER_MAX_T) return SEER_ESHAPE;
+    if (pattern_lookup_max < 1 || pattern_lookup_max > seer::draft::kMaxPattern) return pattern_lookup_max < 1 ? SEER_EINVAL : SEER_EUNSUPPORTED;
+    if (pool_tokens > 0x7fff0000ll) return SEER_EUNSUPPORTED;
+    if (B == 0) return SEER_OK;
+    if (!tokens || !seq_start || !seq_len || !seq_capacity || !req_seq || !emitted_tokens || !n_emitted) return SEER_EINVAL;
+    if ((pattern == nullptr) != (pattern_len == nullptr)) return SEER_EINVAL;
+    seer::draft::AppendArgs a{};
+    a.tokens = tokens, a.seq_start = seq_start, a.seq_len = seq_len, a.seq_capacity = seq_capacity, a.req_seq = req_seq;
+    a.emitted_tokens = emitted_tokens, a.n_emitted = n_emitted, a.pattern = pattern, a.pattern_len = pattern_len;
+    a.status = status, a.pool_tokens = pool_tokens, a.T = T, a.n_seq = n_seq, a.p_max = pattern_lookup_max;
+    hipLaunchKernelGGL(seer::draft::history_append_kernel, dim3(B), dim3(64), 0, static_cast<hipStream_t>(hip_stream), a);
+    const hipError_t err = hipGetLastError();
+    return err == hipSuccess ? SEER_OK : static_cast<int>(err);
+}

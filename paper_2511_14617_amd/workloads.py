@@ -514,6 +514,7 @@ class DraftInputs:
     tokens: np.ndarray            # [pool] int32: every sequence's tokens, gaps hold decoy tokens
     seq_start: np.ndarray         # [n_seq] int32
     seq_len: np.ndarray           # [n_seq] int32
+    seq_capacity: np.ndarray      # [n_seq] int32: room of each sequence in the pool (its tokens + the gap behind it)
     group_first: np.ndarray       # [n_groups + 1] int32: group g owns sequences group_first[g] .. group_first[g+1]-1
     req_group: np.ndarray         # [B] int32
     req_seq: np.ndarray           # [B] int32: the sequence that is the request's own history
@@ -553,7 +554,7 @@ class _Zipf:
 
 def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_max: int = 8, top_k: int = 1,
                       p_min: int = 2, p_max: int = 8, min_confidence: float = 0.0, horizon: int = 16,
-                      n_phrases: int = 1024, phrase_prob: float = 0.3, own_only: bool = False,
+                      n_phrases: int = 1024, phrase_prob: float = 0.3, own_only: bool = False, spare: int = 0,
                       refs_per_group: Optional[int] = None, max_spec_tokens=None) -> DraftInputs:
     """Responses of a prompt group as the paper describes them (Section 2.3: responses to one prompt
     share recurring phrases; later requests find more of them in their group's history): every group
@@ -563,7 +564,8 @@ def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_ma
     a phrase of the bank (Zipf-distributed choice), otherwise 1..8 free Zipf tokens.  Sequence lengths
     follow the configuration's context lengths (without the shared prompt and the verify slots).  The
     pool gives every sequence some spare room after its tokens, filled with decoy tokens that repeat
-    the sequence's own tail (so a reader that runs past seq_len finds plausible matches and fails).
+    the sequence's own tail (so a reader that runs past seq_len finds plausible matches and fails); `spare`
+    more tokens of room are left behind every sequence (for tests that append).
     `refs_per_group` = number of sequences of each group that are in the pool (default: all
     group_size); `own_only` keeps just the request's own sequence (the no-reference baseline)."""
     seed = cfg.seed if seed is None else seed
@@ -605,7 +607,7 @@ def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_ma
             futures.append(full[want - horizon:])
     # pool layout: the sequences of a group are neighbours; each is followed by 0..63 decoy tokens
     n_in_pool = gs if refs_per_group is None else max(1, min(gs, refs_per_group))
-    starts, lens, chunks, group_first, seq_of = [], [], [], [0], {}
+    starts, lens, caps, chunks, group_first, seq_of = [], [], [], [], [0], {}
     pos = int(rng.integers(0, 8))
     chunks.append(rng.integers(0, V, size=pos).astype(np.int32))
     for g in range(n_groups):
@@ -616,11 +618,12 @@ def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_ma
             if not own_only and (m - g * gs) >= n_in_pool and not live:
                 continue
             s_ = seqs[m]
-            gap = int(rng.integers(0, 64))
+            gap = spare + int(rng.integers(0, 64))
             decoy = np.resize(s_[-64:], gap) if len(s_) else rng.integers(0, V, size=gap)
             seq_of[m] = len(starts)
             starts.append(pos)
             lens.append(len(s_))
+            caps.append(len(s_) + gap)
             chunks += [s_, np.asarray(decoy, np.int32)]
             pos += len(s_) + gap
             if own_only:
@@ -640,7 +643,7 @@ def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_ma
     if max_spec_tokens is None:
         max_spec_tokens = np.full(B, gamma_max, np.int32)
     return DraftInputs(tokens=tokens, seq_start=np.asarray(starts, np.int32), seq_len=np.asarray(lens, np.int32),
-                       group_first=np.asarray(group_first, np.int32), req_group=req_group,
+                       seq_capacity=np.asarray(caps, np.int32), group_first=np.asarray(group_first, np.int32), req_group=req_group,
                        req_seq=np.asarray([seq_of[b] for b in range(B)], np.int32), pattern=pattern,
                        pattern_len=pattern_len, max_spec_tokens=np.asarray(max_spec_tokens, np.int32),
                        future=np.stack(futures[:B]) if B else np.zeros((0, horizon), np.int32),

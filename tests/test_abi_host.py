@@ -209,6 +209,27 @@ def test_draft_argument_errors_before_any_launch(lib):
     assert b.seer_draft_workspace(_draft_params(top_k=17)) == 0
 
 
+def test_history_append_argument_errors_before_any_launch(lib):
+    from paper_2511_14617_amd import binding as b
+    fake = 0x1000
+
+    def run(B=4, T=9, n_seq=8, pool=5000, p_max=8, tokens=fake, pattern=fake, plen=fake):
+        return lib.seer_history_append(tokens, fake, fake, fake, fake, fake, fake, B, T, n_seq, pool, p_max, pattern, plen,
+                                       None, None)
+
+    assert run(B=-1) == b.SEER_EINVAL
+    assert run(n_seq=0) == b.SEER_EINVAL
+    assert run(pool=0) == b.SEER_EINVAL
+    assert run(T=0) == b.SEER_ESHAPE
+    assert run(T=65) == b.SEER_ESHAPE
+    assert run(p_max=0) == b.SEER_EINVAL
+    assert run(p_max=33) == b.SEER_EUNSUPPORTED
+    assert run(pool=1 << 31) == b.SEER_EUNSUPPORTED
+    assert run(tokens=None) == b.SEER_EINVAL
+    assert run(pattern=None) == b.SEER_EINVAL                     # pattern and pattern_len come together
+    assert run(B=0) == b.SEER_OK
+
+
 def test_product_path_fails_loudly_without_the_library(tmp_path, monkeypatch):
     from paper_2511_14617_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

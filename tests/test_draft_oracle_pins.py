@@ -275,3 +275,77 @@ def test_more_references_and_more_paths_accept_more():
             res[name, k] = mean_accepted(d, tok, par)
     assert res["group", 1] > res["own", 1] + 0.2
     assert res["group", 4] >= res["group", 1] and res["own", 4] >= res["own", 1]
+
+
+# ---------------------------------------------------------------- appending what a step emitted --
+def test_history_append_against_list_concatenation_and_composition():
+    cfg = W.CONFIGS[1].scaled(V=500, B=8, group_size=4)
+    d = W.make_draft_inputs(cfg, seed=3, gamma_max=4, top_k=1, p_max=6, spare=12)
+    rng = np.random.default_rng(0)
+    T = 5
+    e1 = rng.integers(0, 500, size=(cfg.B, T)).astype(np.int32)
+    e2 = rng.integers(0, 500, size=(cfg.B, T)).astype(np.int32)
+    n1 = rng.integers(0, T + 1, size=cfg.B).astype(np.int32)
+    n2 = rng.integers(0, T + 1, size=cfg.B).astype(np.int32)
+    seqs = [d.tokens[s:s + n].tolist() for s, n in zip(d.seq_start, d.seq_len)]
+    t1, l1, p1, pl1 = D.history_append(d.tokens, d.seq_start, d.seq_len, d.seq_capacity, d.req_seq, e1, n1, d.p_max)
+    t2, l2, p2, pl2 = D.history_append(t1, d.seq_start, l1, d.seq_capacity, d.req_seq, e2, n2, d.p_max)
+    touched = np.zeros(len(d.tokens), bool)
+    for b in range(cfg.B):
+        q = int(d.req_seq[b])
+        grown = seqs[q] + e1[b, :n1[b]].tolist() + e2[b, :n2[b]].tolist()
+        assert t2[d.seq_start[q]:d.seq_start[q] + l2[q]].tolist() == grown
+        tail = grown[-d.p_max:]
+        assert pl2[b] == len(tail) and p2[b, d.p_max - len(tail):].tolist() == tail and (p2[b, :d.p_max - len(tail)] == -1).all()
+        touched[d.seq_start[q] + d.seq_len[q]:d.seq_start[q] + l2[q]] = True
+    assert np.array_equal(t2[~touched], d.tokens[~touched])            # nothing else in the pool moved
+    # two steps in one call (tokens joined) give the same histories
+    both = np.full((cfg.B, 2 * T), -1, np.int32)
+    for b in range(cfg.B):
+        both[b, :n1[b] + n2[b]] = e1[b, :n1[b]].tolist() + e2[b, :n2[b]].tolist()
+    t12, l12, p12, pl12 = D.history_append(d.tokens, d.seq_start, d.seq_len, d.seq_capacity, d.req_seq, both, n1 + n2, d.p_max)
+    assert np.array_equal(t12, t2) and np.array_equal(l12, l2) and np.array_equal(p12, p2) and np.array_equal(pl12, pl2)
+    # a sequence without room for all of a step's tokens takes none of them
+    cap = d.seq_capacity.copy()
+    q0 = int(d.req_seq[0])
+    cap[q0] = d.seq_len[q0] + 2
+    n = np.full(cfg.B, 3, np.int32)
+    t3, l3, p3, pl3 = D.history_append(d.tokens, d.seq_start, d.seq_len, cap, d.req_seq, e1, n, d.p_max)
+    assert l3[q0] == d.seq_len[q0] and p3[0, -1] == seqs[q0][-1] and l3[int(d.req_seq[1])] == d.seq_len[int(d.req_seq[1])] + 3
+
+
+def test_decode_loop_with_the_oracles_emits_the_true_sequence():
+    """Draft, verify against a stand-in model that knows the true continuation, append: whatever is drafted,
+    what reaches the histories is the true sequence (Section 3.1: the output is that of plain decoding), and a
+    step emits accepted + 1 tokens (Section 3.4.1)."""
+    import oracle
+    cfg = W.CONFIGS[2].scaled(B=8, V=997, ctx=("lognormal", 1200, 0.6, 600, 4000))
+    gamma, top_k, steps = 4, 2, 5
+    d = W.make_draft_inputs(cfg, seed=5, gamma_max=gamma, top_k=top_k, horizon=steps * (gamma + 1) + 1,
+                            spare=steps * (gamma + 1), n_phrases=64, phrase_prob=0.6)
+    tokens, lens, pat, plen = d.tokens, d.seq_len, d.pattern, d.pattern_len
+    done = np.zeros(cfg.B, np.int64)
+    T = 1 + top_k * gamma
+    for _ in range(steps):
+        tok, par, msk, cnt, mlen = D.batch_speculate(tokens, d.seq_start, lens, d.group_first, d.req_group, pat, plen,
+                                                     d.max_spec_tokens, gamma_max=gamma, top_k=top_k, p_min=d.p_min,
+                                                     p_max=d.p_max, min_confidence=0.0, vocab=cfg.V)
+        target = np.zeros((cfg.B, T), np.int32)
+        for b in range(cfg.B):
+            truth = d.future[b, done[b]:]
+            depth, ok = {0: 0}, {0: True}
+            target[b, 0] = truth[0]
+            for s in range(1, T):
+                if par[b, s] < 0:
+                    continue
+                depth[s] = depth[int(par[b, s])] + 1
+                ok[s] = ok[int(par[b, s])] and tok[b, s] == truth[depth[s] - 1]
+                target[b, s] = truth[depth[s]] if ok[s] else (tok[b, s] + 1) % cfg.V
+        alen, path, bonus = oracle.accept(target, tok, par)
+        emitted, n_emitted = oracle.emitted_tokens(tok, alen, path, bonus)
+        assert np.array_equal(n_emitted, alen + 1)
+        for b in range(cfg.B):
+            assert np.array_equal(emitted[b, :n_emitted[b]], d.future[b, done[b]:done[b] + n_emitted[b]])
+        tokens, lens, pat, plen = D.history_append(tokens, d.seq_start, lens, d.seq_capacity, d.req_seq, emitted, n_emitted, d.p_max)
+        done += n_emitted
+    assert done.sum() > cfg.B * steps                      # some drafts were accepted

@@ -68,6 +68,7 @@ def _from_lists(seqs_per_group, req_group, patterns, *, gamma_max, top_k, p_min,
             pattern[b, p_max - len(p):] = p
     return W.DraftInputs(tokens=np.concatenate(chunks + [np.zeros(4, np.int32)]).astype(np.int32),
                          seq_start=np.asarray(starts, np.int32), seq_len=np.asarray(lens, np.int32),
+                         seq_capacity=np.asarray(lens, np.int32) + gap,
                          group_first=np.asarray(group_first, np.int32), req_group=np.asarray(req_group, np.int32),
                          req_seq=np.zeros(B, np.int32), pattern=pattern, pattern_len=plen,
                          max_spec_tokens=np.full(B, gamma_max, np.int32) if max_spec is None else np.asarray(max_spec, np.int32),
@@ -238,3 +239,122 @@ def test_draft_feeds_verification():
     assert np.array_equal(alen.cpu().numpy(), ra) and np.array_equal(path.cpu().numpy(), rp)
     assert expect.mean() > 1.0
     assert np.array_equal(bonus.cpu().numpy(), d.future[np.arange(cfg.B), expect])
+
+
+# ------------------------------------------------------------------ appending what a step emitted
+def _dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to("cuda")
+
+
+def test_history_append_parity_and_refusals():
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[2].scaled(B=24, ctx=("lognormal", 1200, 0.7, 513, 4000))
+    d = W.make_draft_inputs(cfg, seed=9, gamma_max=8, top_k=1, spare=5)
+    rng = np.random.default_rng(4)
+    T = 9
+    emitted = rng.integers(0, cfg.V, size=(cfg.B, T)).astype(np.int32)
+    n_emitted = rng.integers(0, T + 1, size=cfg.B).astype(np.int32)
+    n_emitted[:3] = [0, T, 1]
+    for b in (1, 6, 7, 8):                               # these sequences are one token short of room
+        d.seq_capacity[d.req_seq[b]] = d.seq_len[d.req_seq[b]] + max(int(n_emitted[b]) - 1, 0)
+    n_emitted[6] = max(n_emitted[6], 1)
+    room = d.seq_capacity[d.req_seq] - d.seq_len[d.req_seq]
+    assert (n_emitted > room).any() and (n_emitted <= room).any()      # some requests have no room: they append nothing
+    want = D.history_append(d.tokens, d.seq_start, d.seq_len, d.seq_capacity, d.req_seq, emitted, n_emitted, d.p_max)
+    tok, ln = _dev(d.tokens), _dev(d.seq_len)
+    pat = torch.full((cfg.B, d.p_max), 77, dtype=torch.int32, device="cuda")
+    plen = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    binding.seer_history_append(tok, _dev(d.seq_start), ln, _dev(d.seq_capacity), _dev(d.req_seq), _dev(emitted),
+                                _dev(n_emitted), pattern=pat, pattern_len=plen, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 2
+    assert np.array_equal(tok.cpu().numpy(), want[0]) and np.array_equal(ln.cpu().numpy(), want[1])
+    assert np.array_equal(pat.cpu().numpy(), want[2]) and np.array_equal(plen.cpu().numpy(), want[3])
+    # a request that names no sequence is skipped and reported; the others are served
+    req = d.req_seq.copy()
+    req[5] = len(d.seq_start) + 3
+    keep = np.ones(cfg.B, bool)
+    keep[5] = False
+    tok, ln = _dev(d.tokens), _dev(d.seq_len)
+    status.zero_()
+    binding.seer_history_append(tok, _dev(d.seq_start), ln, _dev(d.seq_capacity), _dev(req), _dev(emitted), _dev(n_emitted),
+                                pattern=pat, pattern_len=plen, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 3
+    skipped = int(d.req_seq[5])
+    assert ln.cpu().numpy()[skipped] == d.seq_len[skipped]
+    others = np.delete(np.arange(len(d.seq_len)), skipped)
+    assert np.array_equal(ln.cpu().numpy()[others], want[1][others])
+
+
+@pytest.mark.parametrize("top_k,gamma_max", [(1, 8), (4, 4)])
+def test_decode_loop_emits_exactly_the_true_sequence(top_k, gamma_max):
+    """draft -> accept -> append, six steps in a row on the device.  The stand-in for the model puts the
+    request's true next token on top wherever a draft node's path agrees with the true sequence, so
+    whatever is drafted, the tokens appended to the histories must be the true sequence, token for token
+    (Section 3.1: speculative decoding changes the speed, not the output), and every step's drafts must
+    be the oracle's for the histories as they are at that step."""
+    from paper_2511_14617_amd import binding
+    steps, V = 6, 3001
+    cfg = W.CONFIGS[2].scaled(B=16, V=V, ctx=("lognormal", 1500, 0.6, 600, 5000))
+    T = 1 + top_k * gamma_max
+    d = W.make_draft_inputs(cfg, seed=21, gamma_max=gamma_max, top_k=top_k, horizon=steps * (gamma_max + 1) + 1,
+                            spare=steps * (gamma_max + 1), n_phrases=96, phrase_prob=0.6)
+    tokens, seq_len = _dev(d.tokens), _dev(d.seq_len)
+    seq_start, seq_cap, group_first = _dev(d.seq_start), _dev(d.seq_capacity), _dev(d.group_first)
+    req_group, req_seq, max_spec = _dev(d.req_group), _dev(d.req_seq), _dev(d.max_spec_tokens)
+    pattern, pattern_len = _dev(d.pattern), _dev(d.pattern_len)
+    h_tokens, h_len, h_pat, h_plen = d.tokens.copy(), d.seq_len.copy(), d.pattern.copy(), d.pattern_len.copy()
+    done = np.zeros(cfg.B, np.int64)                    # tokens of the true continuation emitted so far
+    rng = np.random.default_rng(8)
+    total_accepted = 0
+    max_group = int(d.max_group_tokens + cfg.group_size * steps * (gamma_max + 1))
+    for step in range(steps):
+        tok, par, msk, cnt, mlen = binding.seer_draft(tokens, seq_start, seq_len, group_first, req_group, pattern,
+                                                       pattern_len, max_spec, gamma_max=gamma_max, top_k=top_k,
+                                                       pattern_lookup_min=d.p_min, vocab=V, max_group_tokens=max_group)
+        torch.cuda.synchronize()
+        h_tok, h_par = tok.cpu().numpy(), par.cpu().numpy()
+        want = D.batch_speculate(h_tokens, d.seq_start, h_len, d.group_first, d.req_group, h_pat, h_plen, d.max_spec_tokens,
+                                 gamma_max=gamma_max, top_k=top_k, p_min=d.p_min, p_max=d.p_max, min_confidence=0.0, vocab=V)
+        assert np.array_equal(h_tok, want[0]) and np.array_equal(h_par, want[1]), "step %d" % step
+        logits = rng.normal(size=(cfg.B, T, V)).astype(np.float32)
+        for b in range(cfg.B):
+            truth = d.future[b, done[b]:]
+            depth, ok = {0: 0}, {0: True}
+            logits[b, 0, truth[0]] = 9.0
+            for s_ in range(1, T):
+                p_ = int(h_par[b, s_])
+                if p_ < 0:
+                    continue
+                depth[s_] = depth[p_] + 1
+                ok[s_] = ok[p_] and h_tok[b, s_] == truth[depth[s_] - 1]
+                if ok[s_]:
+                    logits[b, s_, truth[depth[s_]]] = 9.0
+        alen, path, bonus, tgt = binding.seer_accept(torch.from_numpy(logits).to("cuda"), tok, par)
+        torch.cuda.synchronize()
+        a_, p_, bo = alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy()
+        emitted = np.full((cfg.B, T), -1, np.int32)
+        for b in range(cfg.B):
+            for i in range(a_[b]):
+                emitted[b, i] = h_tok[b, p_[b, i + 1]]
+            emitted[b, a_[b]] = bo[b]
+        n_emitted = (a_ + 1).astype(np.int32)
+        total_accepted += int(a_.sum())
+        binding.seer_history_append(tokens, seq_start, seq_len, seq_cap, req_seq, _dev(emitted), _dev(n_emitted),
+                                    pattern=pattern, pattern_len=pattern_len)
+        torch.cuda.synchronize()
+        h_tokens, h_len, h_pat, h_plen = D.history_append(h_tokens, d.seq_start, h_len, d.seq_capacity, d.req_seq, emitted,
+                                                          n_emitted, d.p_max)
+        assert np.array_equal(tokens.cpu().numpy(), h_tokens) and np.array_equal(seq_len.cpu().numpy(), h_len)
+        assert np.array_equal(pattern.cpu().numpy(), h_pat) and np.array_equal(pattern_len.cpu().numpy(), h_plen)
+        for b in range(cfg.B):
+            assert np.array_equal(emitted[b, :n_emitted[b]], d.future[b, done[b]:done[b] + n_emitted[b]])
+        done += n_emitted
+    for b in range(cfg.B):                                # the histories grew by exactly the true continuation
+        q = int(d.req_seq[b])
+        start, old = int(d.seq_start[q]), int(d.seq_len[q])
+        assert h_len[q] == old + done[b]
+        assert np.array_equal(h_tokens[start + old:start + h_len[q]], d.future[b, :done[b]])
+    assert total_accepted > cfg.B                         # the drafts did shorten the loop
