@@ -152,6 +152,46 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
     return 0
 
 
+def sweep_draft_acceptance(torch, binding, W) -> int:
+    """Mean acceptance length (accepted draft tokens + the bonus token) of seer_draft's drafts against the tokens
+    each request really produces next, by number of grouped references and by beam width: the measurement of the
+    paper's Table 1 on this build's synthetic group histories (groups of 16 like the table's n = 15; one live
+    request per group; gamma_max = 8)."""
+    cfg = W.CONFIGS[5].scaled(B=16 * 64, group_size=16)
+    dev = "cuda"
+    t32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+    table = {}
+    for top_k in (1, 2, 4):
+        full = W.make_draft_inputs(cfg, gamma_max=8, top_k=top_k)
+        for refs in (0, 1, 5, 15):
+            d = W.restrict_draft_inputs(full, cfg.group_size, refs)
+            tok, par, msk, cnt, mlen = binding.seer_draft(
+                t32(d.tokens), t32(d.seq_start), t32(d.seq_len), t32(d.group_first), t32(d.req_group), t32(d.pattern),
+                t32(d.pattern_len), t32(d.max_spec_tokens), gamma_max=8, top_k=top_k, pattern_lookup_min=d.p_min,
+                vocab=cfg.V, max_group_tokens=max(d.max_group_tokens, 1))
+            torch.cuda.synchronize()
+            h_tok, h_par = tok.cpu().numpy(), par.cpu().numpy()
+            total = 0
+            for b in range(h_tok.shape[0]):
+                depth, ok, best = {0: 0}, {0: True}, 0
+                for s_ in range(1, h_tok.shape[1]):
+                    p_ = int(h_par[b, s_])
+                    if p_ < 0:
+                        continue
+                    depth[s_] = depth[p_] + 1
+                    ok[s_] = ok[p_] and h_tok[b, s_] == d.future[b, depth[s_] - 1]
+                    if ok[s_]:
+                        best = max(best, depth[s_])
+                total += best + 1
+            table.setdefault("n=%d" % refs, {})["k=%d" % top_k] = round(total / h_tok.shape[0], 3)
+    print(json.dumps({"what": "mean acceptance length incl. bonus token; rows = grouped references, columns = beam width "
+                              "(k=1: linear); 64 groups of 16, one live request each, gamma_max 8, pattern 2..8",
+                      "acceptance_length": table,
+                      "paper_table_1": {"n=0": [1.70, 1.77, 1.85], "n=1": [2.04, 2.14, 2.25], "n=5": [2.32, 2.44, 2.59],
+                                        "n=15": [2.53, 2.69, 2.85]}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,6 +209,9 @@ def main() -> int:
                     help="instead of the benchmark: measure the verify step (attention + accept) of the config-2 "
                          "model shape over batch sizes and draft lengths, the T(B, gamma) table that the "
                          "draft-length policy consumes, and print it with the policy's decisions as JSON")
+    ap.add_argument("--sweep-draft-acceptance", action="store_true",
+                    help="instead of the benchmark: mean acceptance length of seer_draft's drafts by number of grouped "
+                         "references and beam width (the measurement of the paper's Table 1, on synthetic histories)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange step; "
@@ -185,6 +228,8 @@ def main() -> int:
         return 2
     if args.sweep_step_time:
         return sweep_step_time(torch, binding, W, attention_device_inputs)
+    if args.sweep_draft_acceptance:
+        return sweep_draft_acceptance(torch, binding, W)
     cfg = W.CONFIGS[args.config]
     if args.ctx_scale != 1.0:
         c = cfg.ctx

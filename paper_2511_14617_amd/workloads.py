@@ -649,3 +649,31 @@ def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_ma
                        future=np.stack(futures[:B]) if B else np.zeros((0, horizon), np.int32),
                        gamma_max=gamma_max, top_k=top_k, p_min=p_min, p_max=p_max,
                        min_confidence=float(min_confidence), vocab=V)
+
+
+def restrict_draft_inputs(d: DraftInputs, group_size: int, refs: int) -> DraftInputs:
+    """The same pool seen by one live request per group (the group's first member) with `refs` of the other
+    members' sequences as references (0 = its own history only): the setting of the paper's Table 1, whose rows
+    are the number of grouped references."""
+    n_groups = len(d.group_first) - 1
+    keep_seq, group_first, live = [], [0], []
+    for g in range(n_groups):
+        q0, q1 = int(d.group_first[g]), int(d.group_first[g + 1])
+        members = [b for b in range(len(d.req_group)) if d.req_group[b] == g]
+        if not members:
+            group_first.append(len(keep_seq))
+            continue
+        b0 = members[0]
+        own = int(d.req_seq[b0])
+        others = [q for q in range(q0, q1) if q != own][:refs]
+        keep_seq += [own] + others
+        group_first.append(len(keep_seq))
+        live.append(b0)
+    keep_seq = np.asarray(keep_seq, np.int64)
+    live = np.asarray(live, np.int64)
+    new_index = {int(q): i for i, q in enumerate(keep_seq)}
+    return dataclasses.replace(
+        d, seq_start=d.seq_start[keep_seq], seq_len=d.seq_len[keep_seq], seq_capacity=d.seq_capacity[keep_seq],
+        group_first=np.asarray(group_first, np.int32), req_group=d.req_group[live],
+        req_seq=np.asarray([new_index[int(d.req_seq[b])] for b in live], np.int32), pattern=d.pattern[live],
+        pattern_len=d.pattern_len[live], max_spec_tokens=d.max_spec_tokens[live], future=d.future[live])
