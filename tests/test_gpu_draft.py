@@ -358,3 +358,44 @@ def test_decode_loop_emits_exactly_the_true_sequence(top_k, gamma_max):
         assert h_len[q] == old + done[b]
         assert np.array_equal(h_tokens[start + old:start + h_len[q]], d.future[b, :done[b]])
     assert total_accepted > cfg.B                         # the drafts did shorten the loop
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(seed):
+    """Seeded random batches: groups of 1..5 sequences of 0..3000 tokens (some empty), vocabularies from 3 tokens
+    to thousands, any pattern window, beam width, depth and threshold, requests spread over the groups in any
+    order, patterns taken from a sequence's end, from its middle, or random."""
+    rng = np.random.default_rng(5000 + seed)
+    vocab = int(rng.choice([3, 7, 50, 1000, 40000]))
+    n_groups = int(rng.integers(1, 5))
+    groups = []
+    for _ in range(n_groups):
+        seqs = []
+        for _ in range(int(rng.integers(1, 6))):
+            n = int(rng.choice([0, 1, 2, int(rng.integers(3, 400)), int(rng.integers(400, 3000))]))
+            base = rng.integers(0, vocab, size=max(n // 7, 1))
+            seqs.append(np.resize(base, n).tolist() if rng.random() < 0.4 else rng.integers(0, vocab, size=n).tolist())
+        groups.append(seqs)
+    top_k = int(rng.integers(1, 9))
+    gamma_max = int(rng.integers(1, min(63 // top_k, 12) + 1))
+    p_max = int(rng.integers(1, 13))
+    p_min = int(rng.integers(0, p_max + 1))
+    B = int(rng.integers(1, 70))
+    req_group = rng.integers(0, n_groups, size=B)
+    pats = []
+    for b in range(B):
+        seqs = [s for s in groups[req_group[b]] if len(s) >= 2]
+        kind = rng.random()
+        if seqs and kind < 0.45:
+            s = seqs[int(rng.integers(0, len(seqs)))]
+            pats.append(s[-int(rng.integers(1, p_max + 3)):])
+        elif seqs and kind < 0.9:
+            s = seqs[int(rng.integers(0, len(seqs)))]
+            e = int(rng.integers(1, len(s)))
+            pats.append(s[max(0, e - int(rng.integers(1, p_max + 3))):e])
+        else:
+            pats.append(rng.integers(0, vocab, size=int(rng.integers(0, p_max + 2))).tolist())
+    d = _from_lists(groups, req_group, pats, gamma_max=gamma_max, top_k=top_k, p_min=p_min, p_max=p_max, vocab=vocab,
+                    min_confidence=float(rng.choice([0.0, 0.0, 0.05, 0.34, 1.0])),
+                    max_spec=rng.integers(0, gamma_max + 1, size=B), gap=int(rng.integers(0, 9)))
+    _compare(d, "random shapes %d" % seed)
