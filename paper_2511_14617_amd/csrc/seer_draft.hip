@@ -161,14 +161,22 @@ struct MatchShared {
     int4 info[kReqWindow + 1];                     // (newest token, the one before it, pattern length, -) per request
     int4 older[kReqWindow + 1];                    // the four pattern tokens before those two
     int n_req;
+    int first_seq;                                 // the sequence that holds the first token a tile needs
 };
 
+// A tile is a run of kTile places of the group's tokens counted through all its sequences one after the
+// other ("flat" positions), so a workgroup takes its whole stretch in one round however many sequences it
+// touches.  No match runs from one sequence into the next: a place's match is bounded by its distance
+// from the start of its own sequence.
 __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int B) {
     __shared__ MatchShared sh;
     const int g = blockIdx.y, part = blockIdx.x, tid = threadIdx.x;
     load_group(a, g, sh.gt);
     const int need = max(a.p_min, 1);
-    const int last_quad = static_cast<int>((a.pool_tokens - 4) & ~3ll);      // the last quad that lies inside the pool
+    const bool two = need >= 2;
+    const int n_seq = sh.gt.n_seq;
+    const int total = n_seq > 0 ? sh.gt.flat[n_seq] : 0;
+    const int lo = part * a.chunk, hi = min(lo + a.chunk, total);
     // requests are taken in windows of kReqWindow consecutive ids: at most that many belong to this group
     for (int b0 = 0; b0 < B; b0 += kReqWindow) {
         if (tid == 0) sh.n_req = 0;
@@ -192,128 +200,125 @@ __global__ __launch_bounds__(kMatchThreads) void draft_match_kernel(Args a, int 
             sh.info[tid] = make_int4(back(0), back(1), tid < n_req ? sh.plen[tid] : 0, 0);
             sh.older[tid] = make_int4(back(2), back(3), back(4), back(5));
         }
-        __syncthreads();
-        if (sh.gt.n_seq > 0) {
-            const int lo = part * a.chunk, hi = min(lo + a.chunk, sh.gt.flat[sh.gt.n_seq]);
-            for (int j = 0; j < sh.gt.n_seq; ++j) {
-                // places i of sequence j inside [lo, hi) whose next token exists
-                const int start = sh.gt.start[j];
-                const int i0 = max(lo - sh.gt.flat[j], 0), i1 = min(hi - sh.gt.flat[j], sh.gt.len[j] - 1);
-                if (i0 >= i1) continue;
-                // Tiles of aligned token quads (16-byte loads); a tile may begin before the stretch and end
-                // after it.  The tile and the kMaxPattern tokens before it also go to LDS: a place that holds a
-                // request's newest token compares backwards there instead of through dependent global loads.
-                const int abs0 = start + i0, abs1 = start + i1;
-                for (int w0 = abs0 & ~3; w0 < abs1; w0 += kTile) {          // the same trip count for every thread
-                    const int q0 = w0 + 4 * tid;
-                    // All loads of the tile are requested before any is used: every quad comes from an address
-                    // clamped into the pool; only the pool's last, partial quad is patched token by token.
-                    int tok[4 * kQuads];
-                    int4 quad[kQuads];
+        for (int t0 = lo; t0 < hi; t0 += kTile) {
+            const int t1 = min(t0 + kTile, hi);                    // places of this tile: [t0, t1)
+            const int halo0 = max(t0 - kMaxPattern, 0);            // first flat position the tile needs
+            if (tid < n_seq && sh.gt.flat[tid] <= halo0 && halo0 < sh.gt.flat[tid + 1]) sh.first_seq = tid;
+            __syncthreads();                                        // also: the previous tile is no longer read
+            // Loads: for every sequence that reaches into the tile, each thread requests its 16 places (four
+            // quads) and one token of the run before the tile, all from addresses clamped into the pool, then
+            // keeps those that belong to the sequence.
+            int tok[4 * kQuads];
 #pragma unroll
-                    for (int u = 0; u < kQuads; ++u)
-                        quad[u] = *reinterpret_cast<const int4*>(a.tokens + min(q0 + u * 4 * kMatchThreads, last_quad));
+            for (int c = 0; c < 4 * kQuads; ++c) tok[c] = 0;
+            int before = 0;
+            uint32_t inside = 0, has_prev = 0;                      // per place: may end a match; has a token before it
+            for (int j = sh.first_seq; j < n_seq && sh.gt.flat[j] < t1; ++j) {
+                const int f0 = sh.gt.flat[j], f1 = sh.gt.flat[j + 1];
+                const int at0 = sh.gt.start[j] - f0;                // pool index of flat position 0 of this sequence
+                int got[4 * kQuads];
 #pragma unroll
-                    for (int u = 0; u < kQuads; ++u) {
-                        tok[4 * u] = quad[u].x, tok[4 * u + 1] = quad[u].y, tok[4 * u + 2] = quad[u].z, tok[4 * u + 3] = quad[u].w;
-                        const int q = q0 + u * 4 * kMatchThreads;
-                        if (q > last_quad && q < abs1) {
+                for (int c = 0; c < 4 * kQuads; ++c) {
+                    const int p = t0 + 4 * tid + (c >> 2) * 4 * kMatchThreads + (c & 3);
+                    const bool in = p >= f0 && p < f1 && p < t1;
+                    got[c] = a.tokens[in ? at0 + p : 0];
+                }
+                const int ph = t0 - kMaxPattern + tid;
+                const bool in_h = tid < kMaxPattern && ph >= f0 && ph < f1;
+                const int got_h = a.tokens[in_h ? at0 + ph : 0];
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) tok[4 * u + c] = q + c < abs1 ? a.tokens[q + c] : 0;
-                        }
-                    }
-                    int before = -1;
-                    if (tid < kMaxPattern && w0 - kMaxPattern + tid >= 0) before = a.tokens[w0 - kMaxPattern + tid];
-                    __syncthreads();                                        // the previous tile is no longer read
-                    if (tid < kMaxPattern) sh.tile[tid] = before;
+                for (int c = 0; c < 4 * kQuads; ++c) {
+                    const int p = t0 + 4 * tid + (c >> 2) * 4 * kMatchThreads + (c & 3);
+                    const bool in = p >= f0 && p < f1 && p < t1;
+                    tok[c] = in ? got[c] : tok[c];
+                    if (in && p + 1 < f1) inside |= 1u << c;       // the token that follows exists
+                    if (in && p > f0) has_prev |= 1u << c;
+                }
+                before = in_h ? got_h : before;
+            }
+            if (tid < kMaxPattern) sh.tile[tid] = before;
 #pragma unroll
-                    for (int u = 0; u < kQuads; ++u)
-                        *reinterpret_cast<int4*>(&sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads]) =
-                            make_int4(tok[4 * u], tok[4 * u + 1], tok[4 * u + 2], tok[4 * u + 3]);
-                    uint32_t inside = 0;                                    // places outside the stretch end no match
+            for (int u = 0; u < kQuads; ++u)
+                *reinterpret_cast<int4*>(&sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads]) =
+                    make_int4(tok[4 * u], tok[4 * u + 1], tok[4 * u + 2], tok[4 * u + 3]);
+            __syncthreads();
+            // the token before each of this thread's quads (the others are in its registers)
+            int prev_quad[kQuads];
 #pragma unroll
-                    for (int c = 0; c < 4 * kQuads; ++c) {
-                        const int t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
-                        if (t >= abs0 && t < abs1) inside |= 1u << c;
-                    }
-                    __syncthreads();
-                    // the token before each of this thread's quads (the others are in its registers)
-                    int prev_quad[kQuads];
+            for (int u = 0; u < kQuads; ++u) prev_quad[u] = sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads - 1];
+            int4 info = sh.info[0], older = sh.older[0];
+            for (int r = 0; r < n_req; ++r) {
+                // A place counts only if at least `need` pattern tokens end there: with need >= 2 the token
+                // before it is tested too, in registers, which leaves few places to look at closely.
+                // (The next request's constants are requested before this one's are used.)
+                const int newest = info.x, second = info.y, plen = info.z;
+                const int p2 = older.x, p3 = older.y, p4 = older.z, p5 = older.w;
+                info = sh.info[r + 1], older = sh.older[r + 1];
+                if (plen < need) continue;
+                // first only whether any lane holds a candidate at all: two compares per place
+                bool any = false;
 #pragma unroll
-                    for (int u = 0; u < kQuads; ++u) prev_quad[u] = sh.tile[kMaxPattern + 4 * tid + u * 4 * kMatchThreads - 1];
-                    const bool two = need >= 2;
-                    int4 info = sh.info[0], older = sh.older[0];
-                    for (int r = 0; r < n_req; ++r) {
-                        // A place counts only if at least `need` pattern tokens end there: with need >= 2 the
-                        // token before it is tested too, in registers, which leaves few places to look at closely.
-                        // (The next request's constants are requested before this one's are used.)
-                        const int newest = info.x, second = info.y, plen = info.z;
-                        const int p2 = older.x, p3 = older.y, p4 = older.z, p5 = older.w;
-                        info = sh.info[r + 1], older = sh.older[r + 1];
-                        if (plen < need) continue;
-                        // first only whether any lane holds a candidate at all: two compares per place
-                        bool any = false;
+                for (int c = 0; c < 4 * kQuads; ++c) {
+                    const int prev = (c & 3) ? tok[c - 1] : prev_quad[c >> 2];
+                    any |= (tok[c] == newest) & (!two | (prev == second));
+                }
+                if (__ballot(any) == 0) continue;
+                uint32_t hits = 0;
 #pragma unroll
-                        for (int c = 0; c < 4 * kQuads; ++c) {
-                            const int prev = (c & 3) ? tok[c - 1] : prev_quad[c >> 2];
-                            any |= (tok[c] == newest) & (!two | (prev == second));
-                        }
-                        if (__ballot(any) == 0) continue;
-                        uint32_t hits = 0;
-#pragma unroll
-                        for (int c = 0; c < 4 * kQuads; ++c) {
-                            const int t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
-                            const int prev = (c & 3) ? tok[c - 1] : prev_quad[c >> 2];
-                            bool h = tok[c] == newest && ((inside >> c) & 1u) != 0;
-                            if (two) h = h && prev == second && t > start;
-                            hits |= static_cast<uint32_t>(h) << c;
-                        }
-                        if (__ballot(hits != 0) == 0) continue;
-                        uint32_t* out = a.list_a + static_cast<size_t>(sh.req[r]) * a.cap + static_cast<size_t>(part) * a.chunk;
-                        int best = sh.best[r];
-                        // every lane that has candidate places takes one of them per round
-                        while (__ballot(hits != 0) != 0) {
-                            int m = 0, t = 0;
-                            if (hits != 0) {
-                                const int c = __builtin_ctz(hits);
-                                hits &= hits - 1;
-                                t = q0 + (c >> 2) * 4 * kMatchThreads + (c & 3);
-                                const int limit = min(plen, t - start + 1);        // not past the start of the sequence
-                                const int* at = &sh.tile[kMaxPattern + (t - w0)];
-                                // the five tokens before the place are requested together and compared in
-                                // registers; only a longer match goes on through LDS
-                                const int v1 = at[-1], v2 = at[-2], v3 = at[-3], v4 = at[-4], v5 = at[-5];
-                                m = 1;
-                                if (1 < limit && v1 == second) {
-                                    m = 2;
-                                    if (2 < limit && v2 == p2) {
-                                        m = 3;
-                                        if (3 < limit && v3 == p3) {
-                                            m = 4;
-                                            if (4 < limit && v4 == p4) {
-                                                m = 5;
-                                                if (5 < limit && v5 == p5) {
-                                                    m = 6;
-                                                    while (m < limit && at[-m] == sh.pat[r][a.p_max - 1 - m]) ++m;
-                                                }
-                                            }
+                for (int c = 0; c < 4 * kQuads; ++c) {
+                    const int prev = (c & 3) ? tok[c - 1] : prev_quad[c >> 2];
+                    bool h = tok[c] == newest && ((inside >> c) & 1u) != 0;
+                    if (two) h = h && prev == second && ((has_prev >> c) & 1u) != 0;
+                    hits |= static_cast<uint32_t>(h) << c;
+                }
+                if (__ballot(hits != 0) == 0) continue;
+                uint32_t* out = a.list_a + static_cast<size_t>(sh.req[r]) * a.cap + static_cast<size_t>(part) * a.chunk;
+                int best = sh.best[r];
+                // every lane that has candidate places takes one of them per round
+                while (__ballot(hits != 0) != 0) {
+                    int m = 0, seq_of = 0, off = 0;
+                    if (hits != 0) {
+                        const int c = __builtin_ctz(hits);
+                        hits &= hits - 1;
+                        const int p = t0 + 4 * tid + (c >> 2) * 4 * kMatchThreads + (c & 3);
+                        int j = sh.first_seq;                              // the sequence that holds place p
+                        while (p >= sh.gt.flat[j + 1]) ++j;
+                        seq_of = j, off = p - sh.gt.flat[j];
+                        const int limit = min(plen, off + 1);             // not past the start of the sequence
+                        const int* at = &sh.tile[kMaxPattern + (p - t0)];
+                        // the five tokens before the place are requested together and compared in registers;
+                        // only a longer match goes on through LDS
+                        const int v1 = at[-1], v2 = at[-2], v3 = at[-3], v4 = at[-4], v5 = at[-5];
+                        m = 1;
+                        if (1 < limit && v1 == second) {
+                            m = 2;
+                            if (2 < limit && v2 == p2) {
+                                m = 3;
+                                if (3 < limit && v3 == p3) {
+                                    m = 4;
+                                    if (4 < limit && v4 == p4) {
+                                        m = 5;
+                                        if (5 < limit && v5 == p5) {
+                                            m = 6;
+                                            while (m < limit && at[-m] == sh.pat[r][a.p_max - 1 - m]) ++m;
                                         }
                                     }
                                 }
                             }
-                            // a shorter match than one already seen in this stretch can never win
-                            const bool keep = m >= best;
-                            if (__ballot(keep) == 0) continue;
-                            if (keep && m > best) {
-                                atomicMax(&sh.best[r], m);
-                                best = m;
-                            }
-                            const int slot = wave_append(&sh.kept[r], keep);
-                            if (keep) out[slot] = pack_place(j, m, t - start + 1);
                         }
                     }
+                    // a shorter match than one already seen in this stretch can never win
+                    const bool keep = m >= best;
+                    if (__ballot(keep) == 0) continue;
+                    if (keep && m > best) {
+                        atomicMax(&sh.best[r], m);
+                        best = m;
+                    }
+                    const int slot = wave_append(&sh.kept[r], keep);
+                    if (keep) out[slot] = pack_place(seq_of, m, off + 1);
                 }
             }
+            __syncthreads();                                        // sh.first_seq and the tile are free again
         }
         __syncthreads();
         if (tid < n_req)
