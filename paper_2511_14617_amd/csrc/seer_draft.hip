@@ -14,16 +14,23 @@
 // with the group's tokens resident in L2 after the first request costs less than the tree's
 // upkeep would.  Two kernels:
 //
-//   draft_match_kernel   grid (parts, B): each workgroup scans one stretch of the group's
-//                        tokens, measures at every place how many pattern tokens end there,
-//                        and keeps the places that reach its running maximum
-//   draft_expand_kernel  grid (B): takes the longest match over all parts, gathers its places,
-//                        then level by level counts the next tokens of every beam member's
-//                        places in an LDS hash table, picks the top_k and splits the places
+//   draft_match_kernel   grid (stretches, groups): a workgroup reads one stretch of a group's tokens
+//                        once and, for every request of the group, measures at every place how many
+//                        of the request's newest tokens end there; the places that reach the
+//                        stretch's running maximum go to the request's place list
+//   draft_expand_kernel  grid (requests): takes the longest match over all stretches, gathers its
+//                        places, then searches level by level: the (member, next token) pairs of
+//                        the live places are counted, the top_k picked, the places reassigned.
+//                        Few places live in registers (one wave alone, or the whole workgroup),
+//                        many in two lists in global memory.
 //
 // Counts are integers, the order of the beam is (count descending, parent rank ascending, token
 // ascending) and the confidence test is one fp32 product and one comparison, so the result is
-// unique and does not depend on the order in which places are found.
+// unique and does not depend on the order in which places are found or atomics land.
+//
+// Both kernels are bound by the length of their dependent chains (a global round trip, an LDS round
+// trip, a barrier), not by bandwidth: loads are requested in batches from addresses clamped into
+// the pool and selected afterwards, so that a thread waits once per batch, not once per load.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -458,7 +465,7 @@ __device__ __forceinline__ void emit_nodes(Expand& x, int d, int top_k, int n_pi
 // of rank j writes draft node j of the level.  Returns the number of picks; n_alive = places they own.
 template <bool SOLO, int PER>
 __device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float threshold, int n_mem, int (&own)[PER],
-                                         const int (&t)[PER], int& n_alive) {
+                                         const int (&t)[PER], int& n_alive, int& chain_slot, uint64_t& chain_mask) {
     const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
     const uint64_t below = (1ull << lane_id()) - 1;
     uint32_t k[PER];
@@ -472,8 +479,44 @@ __device__ __forceinline__ int reg_level(const Args& a, Expand& x, int d, float 
 #pragma unroll
     for (int u = 0; u < PER; ++u) v[u] = 0;
     // Inside a phrase that recurs, all places of a member show the same token: then there is nothing to
-    // count pair by pair.  Every place writes its token as its member's reference (any one wins), and if
-    // all places agree with their member's reference the members themselves are the candidates.
+    // count pair by pair.
+    // One wave, one member: ballots settle it without touching LDS (chain_slot < 0: the member's slot and
+    // ancestor mask are not in registers yet).
+    if (SOLO && n_mem == 1) {
+        int count = 0, ref = -1;
+        bool have = false;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const uint64_t m = __ballot(act[u]);
+            count += __popcll(m);
+            if (!have && m != 0) {
+                ref = __builtin_amdgcn_readlane(t[u], __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(m)) - 1));
+                have = true;
+            }
+        }
+        if (!have) return 0;                                         // no place goes on
+        bool differ = false;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) differ = differ || __ballot(act[u] && t[u] != ref) != 0;
+        if (!differ) {
+            if (static_cast<float>(count) < threshold) return 0;
+            const int from = (d - 1) & 1, slot = 1 + (d - 1) * a.top_k;
+            if (chain_slot < 0) chain_slot = x.mem_slot[from][0], chain_mask = x.mem_msk[from][0];
+            const uint64_t m = (1ull << slot) | chain_mask;
+            if (me == 0) {
+                x.tok[slot] = ref, x.par[slot] = chain_slot, x.num[slot] = count, x.msk[slot] = m;
+                x.mem_slot[from ^ 1][0] = slot, x.mem_msk[from ^ 1][0] = m;
+            }
+            chain_slot = slot, chain_mask = m;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) own[u] = act[u] ? 0 : -1;
+            n_alive = count;
+            return 1;
+        }
+    }
+    chain_slot = -1;
+    // The whole workgroup, one member: every place writes its token as the member's reference (any one
+    // wins), and if all places agree with it the member itself is the candidate.
     bool unanimous = false;
     if (!SOLO && n_mem == 1) {                   // (several members are rarely all of one mind: not tried)
         if (me < kMaxTopK) x.ref_cnt[me] = 0;
@@ -631,6 +674,8 @@ __device__ __forceinline__ int reg_levels(const Args& a, Expand& x, int d, int l
     const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
     uint32_t place[PER];
     int own[PER];
+    int chain_slot = -1;                       // one member: its slot and ancestor mask, once they are in registers
+    uint64_t chain_mask = 0;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
         const int i = me + u * stride;
@@ -658,7 +703,7 @@ __device__ __forceinline__ int reg_levels(const Args& a, Expand& x, int d, int l
             int t[PER];
 #pragma unroll
             for (int u = 0; u < PER; ++u) t[u] = cont[u][l];
-            const int n_pick = reg_level<SOLO, PER>(a, x, d, threshold, n_mem, own, t, n_alive);
+            const int n_pick = reg_level<SOLO, PER>(a, x, d, threshold, n_mem, own, t, n_alive, chain_slot, chain_mask);
             if (n_pick == 0) {
                 done = true;
                 d = levels + 1;
