@@ -47,17 +47,14 @@ constexpr int kMaxPattern = 32;           // pattern_lookup_max (5 bits of a pla
 constexpr int kMaxTopK = 16;
 constexpr int kTableSlots = 4096;         // LDS hash table: 4096 x (key, count) = 32 KB
 constexpr uint32_t kEmpty = 0xffffffffu;
-#ifndef SEER_DRAFT_PART_TOKENS
-#define SEER_DRAFT_PART_TOKENS 4096
-#endif
-constexpr int kTokensPerPart = SEER_DRAFT_PART_TOKENS;   // target stretch of one match workgroup
-constexpr int kMaxParts = 256;
+constexpr int kMaxParts = 256;            // stretches a group's tokens are cut into, at most
 constexpr int kReqWindow = 64;            // request ids a match workgroup looks at per round
 constexpr int kQuads = 4;                 // 16-byte loads a match thread has in flight
 constexpr int kTile = 4 * kQuads * kMatchThreads;   // tokens a match workgroup takes per round
-constexpr int kSmall = 2048;              // places that the LDS-resident mode of the expansion holds
-constexpr int kAhead = 8;                 // levels of continuation tokens it fetches at a time, at most
-constexpr int kRankAll = 32;            // up to this many candidates of a level are ranked against each other
+constexpr int kTokensPerPart = kTile;     // target length of a stretch: one round
+constexpr int kSmall = 2048;              // up to this many places the expansion holds in registers
+constexpr int kAhead = 8;                 // levels whose tokens it fetches at a time
+constexpr int kRankAll = 32;              // up to this many candidates of a level are ranked against each other
 constexpr int kSolo = 256;                // at most this many live places: one wave finishes the search alone
 
 // A place = (sequence inside the group, offset of the token that follows the occurrence); while the
@@ -398,34 +395,32 @@ __device__ __forceinline__ void hash_add(Expand& x, int table, int shift, uint32
     x.overflow = 1;
 }
 
-// The first top_k table entries in the order (count descending, key ascending) that pass the confidence
-// test join x.pick (kept sorted, best first, at most top_k long).  Every thread returns the new length.
-template <bool SOLO>
+// Places in global memory: the first top_k table entries in the order (count descending, key ascending)
+// that pass the confidence test join x.pick (kept sorted, best first, at most top_k long).  Every thread
+// returns the new length.
 __device__ __forceinline__ int pick_top(Expand& x, int slots, float threshold, int top_k, int n_pick) {
-    const int me = SOLO ? lane_id() : static_cast<int>(threadIdx.x), stride = SOLO ? 64 : kThreads;
+    const int tid = threadIdx.x;
     for (int round = 0; round < top_k; ++round) {
         uint64_t best = 0;
-        for (int s = me; s < slots; s += stride) {
+        for (int s = tid; s < slots; s += kThreads) {
             const uint32_t c = x.cnt[s];
             if (c == 0 || static_cast<float>(c) < threshold) continue;
             const uint64_t v = (static_cast<uint64_t>(c) << 32) | static_cast<uint32_t>(~x.key[s]);
             best = v > best ? v : best;
         }
         uint64_t win = wave_max_u64(best);
-        if (!SOLO) {
-            if (lane_id() == 0) x.red[threadIdx.x >> 6] = win;
-            __syncthreads();
+        if (lane_id() == 0) x.red[tid >> 6] = win;
+        __syncthreads();
 #pragma unroll
-            for (int w = 0; w < kThreads / 64; ++w) win = x.red[w] > win ? x.red[w] : win;
-        }
+        for (int w = 0; w < kThreads / 64; ++w) win = x.red[w] > win ? x.red[w] : win;
         if (win == 0) {
-            level_sync<SOLO>();
+            __syncthreads();
             break;
         }
         const uint32_t win_key = ~static_cast<uint32_t>(win);
-        for (int s = me; s < slots; s += stride)
+        for (int s = tid; s < slots; s += kThreads)
             if (x.key[s] == win_key) x.cnt[s] = 0;
-        if (me == 0) {
+        if (tid == 0) {
             int at = n_pick < top_k ? n_pick : top_k - 1;
             if (n_pick < top_k || win > x.pick[at]) {
                 while (at > 0 && x.pick[at - 1] < win) {
@@ -436,12 +431,12 @@ __device__ __forceinline__ int pick_top(Expand& x, int slots, float threshold, i
             }
         }
         n_pick = min(n_pick + 1, top_k);
-        level_sync<SOLO>();
+        __syncthreads();
     }
     return n_pick;
 }
 
-// The picks of level d become draft nodes (thread `me == 0` only).
+// Places in global memory: the picks of level d become draft nodes (one thread).
 __device__ __forceinline__ void emit_nodes(Expand& x, int d, int top_k, int n_pick) {
     int base = 0;
     for (int j = 0; j < n_pick; ++j) {
@@ -774,7 +769,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
     const int n_kept = p_star > 0 ? x.first[a.parts] : 0;        // >= the places of the longest match
     uint32_t* cur = a.list_b + static_cast<size_t>(b) * a.cap;
     uint32_t* nxt = a.list_a + static_cast<size_t>(b) * a.cap;
-    bool in_lds = n_kept <= kSmall;
+    bool handed_over = n_kept <= kSmall;
     for (int i0 = 0; i0 < n_kept; i0 += kThreads) {
         const int i = i0 + tid;
         uint32_t pl = 0;
@@ -789,7 +784,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
         const bool hit = i < n_kept && place_len(pl) == p_star;
         const int at = wave_append(&x.n, hit);
         if (hit) {
-            if (in_lds)
+            if (handed_over)
                 x.place[at] = pl, x.owner[at] = 0;
             else
                 cur[at] = pl;
@@ -807,8 +802,8 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
     __syncthreads();
 
     int d = 1;
-    // ---- places in global memory: as long as a level holds more places than the LDS mode takes ----
-    for (; d <= levels && !in_lds; ++d) {
+    // ---- places in global memory: as long as a level holds more than kSmall places ----
+    for (; d <= levels && !handed_over; ++d) {
         const int nmem = x.nmem;
         const int n_level = x.mem[nmem - 1].base + x.mem[nmem - 1].n;
         if (n_level <= kSmall) {
@@ -817,7 +812,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
                 while (r + 1 < nmem && e >= x.mem[r + 1].base) ++r;
                 x.place[e] = cur[e], x.owner[e] = static_cast<int8_t>(r);
             }
-            in_lds = true;
+            handed_over = true;
             __syncthreads();
             break;
         }
@@ -920,7 +915,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
             }
             __syncthreads();
             const bool overflow = x.overflow != 0;
-            if (!(hashed && overflow)) n_pick = pick_top<false>(x, kTableSlots, threshold, a.top_k, n_pick);
+            if (!(hashed && overflow)) n_pick = pick_top(x, kTableSlots, threshold, a.top_k, n_pick);
             if (hashed && !overflow) break;
         }
         if (n_pick == 0) {
@@ -960,7 +955,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
 
     // ---- few enough places: they move into registers; the whole workgroup works while many are alive,
     //      then wave 0 finishes alone without barriers ----
-    if (in_lds && d <= levels) {
+    if (handed_over && d <= levels) {
         int n_places = min(x.mem[x.nmem - 1].base + x.mem[x.nmem - 1].n, kSmall);
         int n_alive = n_places;
         if (tid < x.nmem) {
