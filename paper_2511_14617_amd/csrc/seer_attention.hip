@@ -445,21 +445,44 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnArgs a, lo
     int ns = a.split_off[b + 1] - first;
     if (first + ns > a.max_items) ns = max(0, a.max_items - first);
 
+    // Both passes request the partial results of several pieces before using any of them (no branch
+    // between the loads): a thread otherwise waits one round trip per piece.
+    const float2* ml = reinterpret_cast<const float2*>(a.part_ml) + static_cast<size_t>(first) * per_b + r;
+    const float* acc = a.part_acc + (static_cast<size_t>(first) * per_b + r) * a.Dv + d;
+    const size_t acc_stride = static_cast<size_t>(per_b) * a.Dv;
     float M = kNegInf;
-    for (int s = 0; s < ns; ++s)
-        M = fmaxf(M, a.part_ml[2 * ((static_cast<size_t>(first) + s) * per_b + r)]);
+    int s = 0;
+    for (; s + 4 <= ns; s += 4) {
+        float m4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) m4[u] = ml[static_cast<size_t>(s + u) * per_b].x;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) M = fmaxf(M, m4[u]);
+    }
+    for (; s < ns; ++s) M = fmaxf(M, ml[static_cast<size_t>(s) * per_b].x);
     float L = 0.f;
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < ns; ++s) {
-        const size_t prow = (static_cast<size_t>(first) + s) * per_b + r;
-        const float ms = a.part_ml[2 * prow];
-        if (ms != kNegInf) {
-            const float w = fast_exp2(ms - M);
-            L += a.part_ml[2 * prow + 1] * w;
-            const f32x4 p = *reinterpret_cast<const f32x4*>(a.part_acc + prow * a.Dv + d);
-            v += p * w;
+    auto add = [&](float2 msl, f32x4 p) {
+        // a piece that saw nothing for this row (m = -inf) may hold anything in its accumulator
+        const bool live = msl.x != kNegInf;
+        const float w = live ? fast_exp2(msl.x - M) : 0.f;
+        L += live ? msl.y * w : 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] += live ? p[c] * w : 0.f;
+    };
+    s = 0;
+    for (; s + 4 <= ns; s += 4) {
+        float2 msl[4];
+        f32x4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            msl[u] = ml[static_cast<size_t>(s + u) * per_b];
+            p[u] = *reinterpret_cast<const f32x4*>(acc + (s + u) * acc_stride);
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) add(msl[u], p[u]);
     }
+    for (; s < ns; ++s) add(ml[static_cast<size_t>(s) * per_b], *reinterpret_cast<const f32x4*>(acc + s * acc_stride));
     const float inv = (L > 0.f) ? 1.f / L : 0.f;         // a row that saw nothing: zeros
     u32x2 o;
     o[0] = pack_bf16x2(v[0] * inv, v[1] * inv);
