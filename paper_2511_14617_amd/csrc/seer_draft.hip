@@ -691,13 +691,18 @@ __device__ __forceinline__ int reg_levels(const Args& a, Expand& x, int d, int l
                 cont[u][l] = t >= a.vocab ? -1 : t;
             }
         }
+        // One copy of the level's code, whatever the level: the fetched tokens are picked out of the registers
+        // by compares (unrolled eight times the code would not stay in the instruction cache).
         bool done = false;
-#pragma unroll
-        for (int l = 0; l < kAhead; ++l) {
-            if (done || d > levels || (!SOLO && n_alive <= kSolo)) continue;      // the same for every thread
+#pragma nounroll
+        for (int l = 0; l < kAhead && !done && d <= levels && (SOLO || n_alive > kSolo); ++l) {
             int t[PER];
 #pragma unroll
-            for (int u = 0; u < PER; ++u) t[u] = cont[u][l];
+            for (int u = 0; u < PER; ++u) {
+                t[u] = cont[u][0];
+#pragma unroll
+                for (int i = 1; i < kAhead; ++i) t[u] = l == i ? cont[u][i] : t[u];
+            }
             const int n_pick = reg_level<SOLO, PER>(a, x, d, threshold, n_mem, own, t, n_alive, chain_slot, chain_mask);
             if (n_pick == 0) {
                 done = true;
