@@ -112,9 +112,15 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
     d = attention_device_inputs(att)
     dev = d["q"].device
     batches = [1, 4, 16, 64, 128, 256]
-    table = {}
+    att_table, acc_table, draft_table = {}, {}, {}
+    busy = torch.randn((8192, 8192), device=dev, dtype=torch.bfloat16)
+    busy_out = torch.empty_like(busy)
+    # D(B, gamma): seer_draft on the token histories that go with the same 256 requests (chain of gamma tokens)
+    dr = W.make_draft_inputs(cfg, gamma_max=gamma_max, top_k=1)
+    t32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+    dr_dev = [t32(x) for x in (dr.tokens, dr.seq_start, dr.seq_len, dr.group_first)]
     for B in batches:
-        row = []
+        att_row, acc_row, drow = [], [], [0.0]
         for gamma in range(gamma_max + 1):
             T = gamma + 1
             q = torch.randn((B, T, cfg.Hq, cfg.Dqk), device=dev).to(torch.bfloat16)
@@ -127,28 +133,48 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
             ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device=dev)
             ws2 = torch.empty(max(16, binding.seer_accept_workspace(B, T, cfg.V)), dtype=torch.uint8, device=dev)
 
-            def step():
-                binding.seer_verify_attention(q, d["k_pages"], d["v_pages"], bt, n, None, att.scale, workspace=ws)
-                binding.seer_accept(logits, draft, None, workspace=ws2)
-            for _ in range(5):
-                step()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(20):
-                step()
-            b.record()
-            torch.cuda.synchronize()
-            row.append(a.elapsed_time(b) / 20)
-        table[B] = row
+            def timed(fn):
+                # a long matrix product first: while the GPU works on it the host enqueues all calls, so
+                # the events see GPU time, not the time Python needs to issue a call
+                for _ in range(3):
+                    fn()
+                torch.mm(busy, busy, out=busy_out)
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(20):
+                    fn()
+                b.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(b) / 20
+            att_row.append(timed(lambda: binding.seer_verify_attention(q, d["k_pages"], d["v_pages"], bt, n, None, att.scale,
+                                                                         workspace=ws)))
+            acc_row.append(timed(lambda: binding.seer_accept(logits, draft, None, workspace=ws2)))
+            if gamma >= 1:
+                req = [t32(x[:B]) for x in (dr.req_group, dr.pattern, dr.pattern_len)] + [torch.full((B,), gamma, dtype=torch.int32, device=dev)]
+                dp = binding.SeerDraftParams(B, len(dr.group_first) - 1, len(dr.seq_start), len(dr.tokens), dr.max_group_tokens,
+                                             gamma, 1, dr.p_min, dr.p_max, cfg.V, 0.0)
+                wsd = torch.empty(binding.seer_draft_workspace(dp), dtype=torch.uint8, device=dev)
+                outs = (torch.empty((B, T), dtype=torch.int32, device=dev), torch.empty((B, T), dtype=torch.int32, device=dev),
+                        torch.empty((B, T), dtype=torch.int64, device=dev), torch.empty((B, T), dtype=torch.int32, device=dev),
+                        torch.empty(B, dtype=torch.int32, device=dev))
+                drow.append(timed(lambda: binding.seer_draft(*dr_dev, *req, gamma_max=gamma, top_k=1, pattern_lookup_min=dr.p_min,
+                                                              vocab=cfg.V, max_group_tokens=dr.max_group_tokens, workspace=wsd,
+                                                              out=outs)))
+        att_table[B], acc_table[B], draft_table[B] = att_row, acc_row, drow
     beta = [0.85 ** k for k in range(1, gamma_max + 2)]          # acceptance probability by draft position
-    decisions = {}
+    decisions, step_table, n_layers = {}, {}, 32
     for B in batches:
         B_h = max(1, B // 4)
-        gh, gl, gs = binding.seer_mba_draft_lengths(B_h, B - B_h, beta, gamma_max, 2.0, table[B])
+        # the step time the policy sees (Section 3.4.1: D(B, gamma) + T(B, gamma)): the draft call, the attention
+        # call once per layer, one acceptance call; the model's GEMMs are outside this library
+        both = [n_layers * ta + tc + td for ta, tc, td in zip(att_table[B], acc_table[B], draft_table[B])]
+        step_table[B] = both
+        gh, gl, gs = binding.seer_mba_draft_lengths(B_h, B - B_h, beta, gamma_max, 2.0, both)
         decisions[B] = {"B_h": B_h, "B_l": B - B_h, "gamma_star": gs, "gamma_h": gh, "gamma_l": gl}
-    print(json.dumps({"what": "verify step time (ms) of one layer-call, attention + accept, config-2 shape; "
-                              "row = batch size, column = gamma 0..8", "step_time_ms": table,
-                      "beta": beta, "lambda": 2.0, "policy": decisions}))
+    print(json.dumps({"what": "GPU time (ms) of seer_verify_attention (one layer), seer_accept and seer_draft, config-2 shape; "
+                              "row = batch size, column = gamma 0..8; step_time = n_layers x attention + accept + draft",
+                      "n_layers": n_layers, "attention_ms": att_table, "accept_ms": acc_table, "draft_ms": draft_table,
+                      "step_time_ms": step_table, "beta": beta, "lambda": 2.0, "policy": decisions}))
     return 0
 
 
