@@ -27,8 +27,9 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the partition kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled against
-# a 1 GiB copy (profiles/attn_gqa128_config2_hbm_traffic.md); None where no counter run exists.
-MEASURED_TRAFFIC_BYTES = {2: 1.533e9, 4: 0.770e9}
+# a 1 GiB copy (profiles/attn_gqa128_config2_hbm_traffic.md, attn_gqa128_config3_config5_hbm_traffic.md,
+# attn_mla_config4_kernel_trace_and_hbm_traffic.md); None where no counter run exists.
+MEASURED_TRAFFIC_BYTES = {2: 1.533e9, 3: 3.078e9, 4: 0.770e9, 5: 5.820e9}
 METRIC = "verified tokens/s and verify-attention HBM GB/s (% of peak) on one MI355X"
 
 
