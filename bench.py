@@ -113,7 +113,7 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
     d = attention_device_inputs(att)
     dev = d["q"].device
     batches = [1, 4, 16, 64, 128, 256]
-    att_table, acc_table, draft_table = {}, {}, {}
+    att_table, reuse_table, acc_table, draft_table = {}, {}, {}, {}
     busy = torch.randn((8192, 8192), device=dev, dtype=torch.bfloat16)
     busy_out = torch.empty_like(busy)
     # D(B, gamma): seer_draft on the token histories that go with the same 256 requests (chain of gamma tokens)
@@ -121,7 +121,7 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
     t32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
     dr_dev = [t32(x) for x in (dr.tokens, dr.seq_start, dr.seq_len, dr.group_first)]
     for B in batches:
-        att_row, acc_row, drow = [], [], [0.0]
+        att_row, reuse_row, acc_row, drow = [], [], [], [0.0]
         for gamma in range(gamma_max + 1):
             T = gamma + 1
             q = torch.randn((B, T, cfg.Hq, cfg.Dqk), device=dev).to(torch.bfloat16)
@@ -149,6 +149,8 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
                 return a.elapsed_time(b) / 20
             att_row.append(timed(lambda: binding.seer_verify_attention(q, d["k_pages"], d["v_pages"], bt, n, None, att.scale,
                                                                          workspace=ws)))
+            reuse_row.append(timed(lambda: binding.seer_verify_attention(q, d["k_pages"], d["v_pages"], bt, n, None, att.scale,
+                                                                           workspace=ws, flags=binding.SEER_ATTN_REUSE_PLAN)))
             acc_row.append(timed(lambda: binding.seer_accept(logits, draft, None, workspace=ws2)))
             if gamma >= 1:
                 req = [t32(x[:B]) for x in (dr.req_group, dr.pattern, dr.pattern_len)] + [torch.full((B,), gamma, dtype=torch.int32, device=dev)]
@@ -161,20 +163,24 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
                 drow.append(timed(lambda: binding.seer_draft(*dr_dev, *req, gamma_max=gamma, top_k=1, pattern_lookup_min=dr.p_min,
                                                               vocab=cfg.V, max_group_tokens=dr.max_group_tokens, workspace=wsd,
                                                               out=outs)))
-        att_table[B], acc_table[B], draft_table[B] = att_row, acc_row, drow
+        att_table[B], reuse_table[B], acc_table[B], draft_table[B] = att_row, reuse_row, acc_row, drow
     beta = [0.85 ** k for k in range(1, gamma_max + 2)]          # acceptance probability by draft position
     decisions, step_table, n_layers = {}, {}, 32
     for B in batches:
         B_h = max(1, B // 4)
         # the step time the policy sees (Section 3.4.1: D(B, gamma) + T(B, gamma)): the draft call, the attention
-        # call once per layer, one acceptance call; the model's GEMMs are outside this library
-        both = [n_layers * ta + tc + td for ta, tc, td in zip(att_table[B], acc_table[B], draft_table[B])]
+        # call once per layer (the first plans, the others reuse its plan), one acceptance call; the model's
+        # GEMMs are outside this library
+        both = [ta + (n_layers - 1) * tr + tc + td
+                for ta, tr, tc, td in zip(att_table[B], reuse_table[B], acc_table[B], draft_table[B])]
         step_table[B] = both
         gh, gl, gs = binding.seer_mba_draft_lengths(B_h, B - B_h, beta, gamma_max, 2.0, both)
         decisions[B] = {"B_h": B_h, "B_l": B - B_h, "gamma_star": gs, "gamma_h": gh, "gamma_l": gl}
     print(json.dumps({"what": "GPU time (ms) of seer_verify_attention (one layer), seer_accept and seer_draft, config-2 shape; "
-                              "row = batch size, column = gamma 0..8; step_time = n_layers x attention + accept + draft",
-                      "n_layers": n_layers, "attention_ms": att_table, "accept_ms": acc_table, "draft_ms": draft_table,
+                              "row = batch size, column = gamma 0..8; step_time = attention + (n_layers - 1) x attention with the "
+                              "first layer's plan + accept + draft",
+                      "n_layers": n_layers, "attention_ms": att_table, "attention_reuse_plan_ms": reuse_table,
+                      "accept_ms": acc_table, "draft_ms": draft_table,
                       "step_time_ms": step_table, "beta": beta, "lambda": 2.0, "policy": decisions}))
     return 0
 
@@ -315,6 +321,10 @@ def main() -> int:
     att_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
                                                          d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
                                                          workspace=ws_att))
+    # the call as the second and later layers of a step issue it: the plan of the first layer is reused
+    att_reuse_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
+                                                               d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
+                                                               workspace=ws_att, flags=binding.SEER_ATTN_REUSE_PLAN))
     acc_ms = 0.0 if args.attention_only else timed(
         lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out))
     # gather-read ceiling: the same call with the arithmetic left out of the tiled kernel (D = 128 shapes)
@@ -421,7 +431,7 @@ def main() -> int:
                    "kv_tokens": int(att.ctx_len.sum()), "seed": cfg.seed,
                    "attention_only": bool(args.attention_only)},
         "roofline": roofline,
-        "attention_ms": att_ms, "accept_ms": acc_ms,
+        "attention_ms": att_ms, "attention_reuse_plan_ms": att_reuse_ms, "accept_ms": acc_ms,
         "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
         "accept_logits_GBps": (acc.logits.nbytes / (acc_ms * 1e-3) / 1e9) if acc_ms > 0 else None,
         "attention_status_word": status,

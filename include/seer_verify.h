@@ -84,6 +84,13 @@ typedef struct seer_attn_params {
  * The time of such a call is the gather-read ceiling of the memory system for this workload and
  * launch shape.  Ignored by the other kernels. */
 #define SEER_ATTN_STREAM_ONLY 4
+/* flags: use the plan that the previous call on this workspace computed instead of planning again.  How the
+ * KV stream is cut depends on the shape parameters and on ctx_len only, and a model calls this function
+ * once per layer with the same ctx_len: the first layer plans, the others pass this flag (saves a ~10 us
+ * kernel per call).  The caller guarantees that the previous call on this workspace had the same
+ * parameters (flags apart) and that ctx_len and block_table are unchanged; if not, the output is
+ * undefined (every access still stays in bounds).  The status word then accumulates over the calls. */
+#define SEER_ATTN_REUSE_PLAN 8
 
 /* Supported shapes: (Dqk, Dv) in {(64,64), (128,128), (256,256), (192,128),
  * (576,512)} with any page_size >= 1.  Tiled matrix-core kernels exist for

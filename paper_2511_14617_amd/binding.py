@@ -41,6 +41,7 @@ class SeerDraftParams(ctypes.Structure):
 SEER_ATTN_GENERAL_KERNEL = 1
 SEER_ATTN_FIXED_SPLIT = 2
 SEER_ATTN_STREAM_ONLY = 4
+SEER_ATTN_REUSE_PLAN = 8
 
 
 class SeerError(RuntimeError):

@@ -510,7 +510,8 @@ int validate_params(const seer_attn_params* p) {
     if (p->B < 0 || p->num_pages < 1 || p->max_pages_per_seq < 1 || p->page_size < 1) return SEER_EINVAL;
     if (p->T < 1 || p->T > SEER_MAX_T || p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SEER_ESHAPE;
     if (p->max_splits < 0 || p->max_splits > 256) return SEER_ESHAPE;
-    if (p->flags & ~(SEER_ATTN_GENERAL_KERNEL | SEER_ATTN_FIXED_SPLIT | SEER_ATTN_STREAM_ONLY)) return SEER_EINVAL;
+    if (p->flags & ~(SEER_ATTN_GENERAL_KERNEL | SEER_ATTN_FIXED_SPLIT | SEER_ATTN_STREAM_ONLY | SEER_ATTN_REUSE_PLAN))
+        return SEER_EINVAL;
     if (p->Hq > 65535 || p->T * (int64_t)p->Hq * p->B > 0x7fffffffLL) return SEER_ESHAPE;
     if (!(p->scale > 0.f) || p->scale > 3.0e38f) return SEER_EINVAL;   // positive and finite
     if (!seer::general_supports(p->Dqk, p->Dv)) return SEER_EUNSUPPORTED;
@@ -586,7 +587,8 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.scale_log2 = p->scale * seer::kLog2e;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipError_t err = seer::launch_plan(a, w, stream);
+    // the plan depends on the shape and on ctx_len only: the layers of one step can share it
+    hipError_t err = (p->flags & SEER_ATTN_REUSE_PLAN) ? hipSuccess : seer::launch_plan(a, w, stream);
     if (err != hipSuccess) return static_cast<int>(err);
     if (ev_begin && (err = hipEventRecord(ev_begin, stream)) != hipSuccess) return static_cast<int>(err);
     const bool tiled_ok = !(p->flags & SEER_ATTN_GENERAL_KERNEL);

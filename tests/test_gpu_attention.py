@@ -201,6 +201,33 @@ def test_stream_only_diagnostic_runs_the_load_path_and_writes_zeros():
     assert float(out.float().abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("case", ["chain_T9_multi_split", "tree_T33", "mla_latent"])
+def test_layers_of_one_step_share_the_plan(case):
+    """A second call on the same workspace with other queries (the next layer of the model) and
+    SEER_ATTN_REUSE_PLAN gives bit for bit what a call that plans again gives, and matches the oracle."""
+    from paper_2511_14617_amd import binding
+    cfg, kw = CASES[case]
+    inp = W.make_attention_inputs(cfg, **kw)
+    d = attention_device_inputs(inp)
+    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], inp.scale, Dv=cfg.Dv)
+    ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device="cuda")
+    fixed = binding.SEER_ATTN_FIXED_SPLIT                    # the cut must not depend on measured speeds here
+    q2 = torch.flip(d["q"], dims=[2]).contiguous()           # "another layer": the heads' queries swapped around
+
+    def call(q, flags):
+        return binding.seer_verify_attention(q, d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"], d["tree_mask"],
+                                             inp.scale, Dv=cfg.Dv, workspace=ws, flags=flags).clone()
+    call(d["q"], fixed)
+    reused = call(q2, fixed | binding.SEER_ATTN_REUSE_PLAN)
+    planned = call(q2, fixed)
+    torch.cuda.synchronize()
+    assert torch.equal(reused.view(torch.int16), planned.view(torch.int16))
+    assert binding.seer_verify_attention_status(ws) == 0
+    inp2 = W.make_attention_inputs(cfg, **kw)
+    inp2.q[...] = inp.q[:, :, ::-1, :]
+    assert_attention_close(reused, _oracle(inp2), case + " with a shared plan")
+
+
 def _random_shape(rng):
     """A seeded random small workload: group width, slots, tree or chain, page size, context mix."""
     G = int(rng.choice([1, 2, 4, 5, 8, 16]))
