@@ -399,3 +399,21 @@ def test_random_shapes(seed):
                     min_confidence=float(rng.choice([0.0, 0.0, 0.05, 0.34, 1.0])),
                     max_spec=rng.integers(0, gamma_max + 1, size=B), gap=int(rng.integers(0, 9)))
     _compare(d, "random shapes %d" % seed)
+
+
+def test_many_requests_per_group_in_any_order():
+    """300 requests spread at random over 5 groups: a group's requests come in several windows of request ids."""
+    rng = np.random.default_rng(77)
+    vocab = 60
+    groups = [[rng.integers(0, vocab, size=int(rng.integers(50, 1500))).tolist() for _ in range(int(rng.integers(1, 5)))]
+              for _ in range(5)]
+    B = 300
+    req_group = rng.integers(0, 5, size=B)
+    pats = []
+    for b in range(B):
+        s = groups[req_group[b]][0]
+        e = int(rng.integers(2, len(s)))
+        pats.append(s[max(0, e - 5):e])
+    d = _from_lists(groups, req_group, pats, gamma_max=5, top_k=3, p_min=2, p_max=5, vocab=vocab)
+    want = _compare(d, "many requests")
+    assert (want[4] >= 2).mean() > 0.9
