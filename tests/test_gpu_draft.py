@@ -417,3 +417,24 @@ def test_many_requests_per_group_in_any_order():
     d = _from_lists(groups, req_group, pats, gamma_max=5, top_k=3, p_min=2, p_max=5, vocab=vocab)
     want = _compare(d, "many requests")
     assert (want[4] >= 2).mean() > 0.9
+
+
+@pytest.mark.parametrize("top_k,gamma_max", [(1, 63), (2, 31), (16, 3), (3, 21)])
+def test_widest_and_deepest_trees(top_k, gamma_max):
+    """The extreme tree shapes (64 slots with a 63-token chain: the last bit of the mask word; 16 members per
+    level) on periodic and on phrase-like histories, where chains really run that deep."""
+    rng = np.random.default_rng(top_k * 100 + gamma_max)
+    period = [int(x) for x in rng.permutation(50)[:7]]
+    periodic = [period * 40, period * 25 + [99], (period[3:] + period[:3]) * 30]
+    phrases = [rng.integers(0, 40, size=int(rng.integers(5, 30))).tolist() for _ in range(6)]
+    mixed = []
+    for _ in range(4):
+        s = []
+        while len(s) < 2500:
+            s += phrases[int(rng.integers(0, len(phrases)))]
+        mixed.append(s)
+    pats = [period * 2, (period * 3)[:-2], mixed[0][-6:], mixed[1][100:108], [1, 2, 3]]
+    d = _from_lists([periodic, mixed], [0, 0, 1, 1, 1], pats, gamma_max=gamma_max, top_k=top_k, p_min=2, p_max=8, vocab=128)
+    want = _compare(d, "extreme trees %dx%d" % (top_k, gamma_max))
+    depth_reached = max(int((want[1][b] >= 0).sum()) for b in range(5))
+    assert depth_reached >= min(gamma_max, 20)
