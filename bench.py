@@ -233,8 +233,6 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (2 = the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="time only seer_verify_attention (profiling aid)")
-    ap.add_argument("--no-prefix-sharing", action="store_true",
-                    help="leave the prompt prefix that the requests of a group have in common on the tile line (comparison aid)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run three 1 GiB device-to-device tensor copies: a plain copy "
                          "kernel of known size against which rocprofv3 FETCH_SIZE / WRITE_SIZE are scaled")
@@ -276,8 +274,7 @@ def main() -> int:
     e = accept_device_inputs(acc)
     dev = d["q"].device
 
-    aflags = binding.SEER_ATTN_NO_PREFIX_SHARING if args.no_prefix_sharing else 0
-    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], att.scale, Dv=cfg.Dv, flags=aflags)
+    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], att.scale, Dv=cfg.Dv)
     ws_att = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device=dev)
     ws_acc = torch.empty(max(16, binding.seer_accept_workspace(cfg.B, cfg.T, cfg.V)), dtype=torch.uint8, device=dev)
     out = torch.empty((cfg.B, cfg.T, cfg.Hq, cfg.Dv), dtype=torch.bfloat16, device=dev)
@@ -287,8 +284,7 @@ def main() -> int:
 
     def step(ev=None):
         binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
-                                      d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att, events=ev,
-                                      flags=aflags)
+                                      d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att, events=ev)
         if not args.attention_only:
             binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out)
 
@@ -324,11 +320,11 @@ def main() -> int:
 
     att_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
                                                          d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
-                                                         workspace=ws_att, flags=aflags))
+                                                         workspace=ws_att))
     # the call as the second and later layers of a step issue it: the plan of the first layer is reused
     att_reuse_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
                                                                d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
-                                                               workspace=ws_att, flags=aflags | binding.SEER_ATTN_REUSE_PLAN))
+                                                               workspace=ws_att, flags=binding.SEER_ATTN_REUSE_PLAN))
     acc_ms = 0.0 if args.attention_only else timed(
         lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out))
     # gather-read ceiling: the same call with the arithmetic left out of the tiled kernel (D = 128 shapes)
@@ -338,7 +334,7 @@ def main() -> int:
         for i in range(10):
             binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
                                           d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att,
-                                          flags=aflags | binding.SEER_ATTN_STREAM_ONLY, events=ev2.pairs[i])
+                                          flags=binding.SEER_ATTN_STREAM_ONLY, events=ev2.pairs[i])
         torch.cuda.synchronize()
         ceiling_ms = float(np.mean(ev2.elapsed_ms()[2:]))
         ev2.close()
@@ -391,7 +387,6 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     status = binding.seer_verify_attention_status(ws_att)
-    shared_tiles = binding.seer_verify_attention_shared_tiles(ws_att)
 
     ab = algorithmic_bytes(att)
     achieved = ab["total"] / (kern_avg_ms * 1e-3) / 1e9
@@ -440,7 +435,6 @@ def main() -> int:
         "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
         "accept_logits_GBps": (acc.logits.nbytes / (acc_ms * 1e-3) / 1e9) if acc_ms > 0 else None,
         "attention_status_word": status,
-        "shared_prefix_tiles": shared_tiles,
         "accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms, "draft": draft_info,
     }
     if not args.no_cpu_baseline:

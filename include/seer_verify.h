@@ -88,15 +88,9 @@ typedef struct seer_attn_params {
  * KV stream is cut depends on the shape parameters and on ctx_len only, and a model calls this function
  * once per layer with the same ctx_len: the first layer plans, the others pass this flag (saves a ~10 us
  * kernel per call).  The caller guarantees that the previous call on this workspace had the same
- * parameters (this flag apart) and that ctx_len and block_table are unchanged; if not, the output is
+ * parameters (flags apart) and that ctx_len and block_table are unchanged; if not, the output is
  * undefined (every access still stays in bounds).  The status word then accumulates over the calls. */
 #define SEER_ATTN_REUSE_PLAN 8
-/* flags: do not look for common prompt prefixes.  By default the tiled D = 128 kernel's plan compares
- * the start of each block_table row with the row before it (requests of one prompt group normally list
- * the same pages there) and schedules the common part of such neighbours on workgroups that share an L2
- * and run it at the same moment, so that HBM delivers those pages once.  Which pieces the KV stream is cut
- * into changes with it, the result only in rounding order. */
-#define SEER_ATTN_NO_PREFIX_SHARING 16
 
 /* Supported shapes: (Dqk, Dv) in {(64,64), (128,128), (256,256), (192,128),
  * (576,512)} with any page_size >= 1.  Tiled matrix-core kernels exist for
@@ -109,14 +103,8 @@ size_t seer_verify_attention_workspace(const seer_attn_params* p);
 
 /* Byte offset, inside the workspace, of a uint32 status word that the call
  * zeroes and its kernels OR into: bit 0 = some request had ctx_len < T or
- * beyond the block table; bit 1 = some page id was outside the pool; bit 2 = the plan in the
- * workspace did not fit the call (SEER_ATTN_REUSE_PLAN on a workspace that holds no plan for it). */
+ * beyond the block table; bit 1 = some page id was outside the pool. */
 size_t seer_verify_attention_status_offset(void);
-
-/* Byte offset, inside the workspace, of an int32 that the plan of a call sets to the number of
- * 32-token KV tiles, summed over the requests, that it scheduled as common-prefix pieces (see
- * SEER_ATTN_NO_PREFIX_SHARING; 0 when nothing was found or the search is off).  For reports and tests. */
-size_t seer_verify_attention_shared_tiles_offset(void);
 
 /*
  * Multi-token paged-KV attention for the verify pass.
@@ -134,7 +122,7 @@ size_t seer_verify_attention_shared_tiles_offset(void);
  *  q           device [B,T,Hq,Dqk] bf16
  *  k_pages     device [num_pages,Hkv,page_size,Dqk] bf16
  *  v_pages     device [num_pages,Hkv,page_size,Dv]  bf16; must be NULL iff kv_shared_latent
- *  block_table device [B,max_pages_per_seq] int32; entries past ceil(n/page_size) do not influence the result
+ *  block_table device [B,max_pages_per_seq] int32; entries past ceil(n/page_size) are not read
  *  ctx_len     device [B] int32, INCLUDING the T verify slots
  *  tree_mask   device [B,T] uint64 ancestor-or-self bits, or NULL
  *  p           host

@@ -9,7 +9,7 @@ be used on machines without PyTorch-ROCm or the built library."""
 
 def __getattr__(name):
     if name in ("seer_verify_attention", "seer_accept", "seer_verify_attention_workspace",
-                "seer_accept_workspace", "seer_verify_attention_status", "seer_verify_attention_shared_tiles", "seer_strerror", "load_library",
+                "seer_accept_workspace", "seer_verify_attention_status", "seer_strerror", "load_library",
                 "seer_accept_sampled", "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft", "seer_draft_workspace", "seer_history_append",
                 "SeerDraftParams",
                 "SeerAttnParams", "SeerError", "attn_params"):

@@ -18,8 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libseer_verify.so")
 
 SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALIGN = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset",
-           "seer_verify_attention_shared_tiles_offset", "seer_verify_attention",
+EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
            "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
            "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_history_append",
            "seer_strerror")
@@ -43,7 +42,6 @@ SEER_ATTN_GENERAL_KERNEL = 1
 SEER_ATTN_FIXED_SPLIT = 2
 SEER_ATTN_STREAM_ONLY = 4
 SEER_ATTN_REUSE_PLAN = 8
-SEER_ATTN_NO_PREFIX_SHARING = 16
 
 
 class SeerError(RuntimeError):
@@ -68,8 +66,6 @@ def load_library() -> ctypes.CDLL:
         lib.seer_verify_attention_workspace.restype = sz
         lib.seer_verify_attention_status_offset.argtypes = []
         lib.seer_verify_attention_status_offset.restype = sz
-        lib.seer_verify_attention_shared_tiles_offset.argtypes = []
-        lib.seer_verify_attention_shared_tiles_offset.restype = sz
         lib.seer_verify_attention.argtypes = [vp] * 7 + [ctypes.POINTER(SeerAttnParams), vp, sz, vp]
         lib.seer_verify_attention.restype = ctypes.c_int
         lib.seer_verify_attention_timed.argtypes = lib.seer_verify_attention.argtypes + [vp, vp]
@@ -179,13 +175,6 @@ def seer_verify_attention_status(workspace: torch.Tensor) -> int:
     """The status word the last call on this workspace left (synchronises)."""
     off = int(load_library().seer_verify_attention_status_offset())
     return int(workspace[off:off + 4].view(torch.int32).item()) & 0xFFFFFFFF
-
-
-def seer_verify_attention_shared_tiles(workspace: torch.Tensor) -> int:
-    """Tiles (32 tokens, summed over requests) that the last plan on this workspace scheduled as
-    common-prefix pieces (synchronises)."""
-    off = int(load_library().seer_verify_attention_shared_tiles_offset())
-    return int(workspace[off:off + 4].view(torch.int32).item())
 
 
 def seer_accept_workspace(B: int, T: int, V: int) -> int:

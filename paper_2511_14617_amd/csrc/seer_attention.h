@@ -37,13 +37,12 @@ namespace seer {
 // [3/4, 4/3] of the mean).  A workspace that holds no valid history (first use,
 // other W) gives equal stretches; SEER_ATTN_FIXED_SPLIT always does.
 struct PlanHeader {
-    uint32_t status;     // bit 0: bad ctx_len somewhere; bit 1: page id out of range; bit 2: a piece of the plan was unusable
+    uint32_t status;     // bit 0: bad ctx_len somewhere; bit 1: page id out of range
     int32_t n_items;     // number of (request, stretch) pieces = partial slots in use
     int32_t tiles_per_wg;  // L; 0 = one workgroup per request (max_splits == 1)
     int32_t total_tiles;   // tiles per KV head over all requests
     uint32_t fb_magic;     // kFeedbackMagic once the speed history below the header is meaningful
     int32_t fb_w;          // W it was recorded for
-    int32_t shared_tiles;  // tiles, summed over requests, that this plan took off the line as common-prefix pieces
 };
 constexpr uint32_t kFeedbackMagic = 0x5ee2fb01u;
 constexpr int kMaxWgsPerHead = 1024;   // 256 CUs x 4 resident workgroups, one KV head
@@ -55,33 +54,16 @@ struct WorkItem {
     int32_t split;   // index of the piece inside the request
 };
 
-// A leading piece of a request that is scheduled apart from the tile line: the start of the prompt
-// that the request has in common with its neighbours in the batch (see the plan kernel).
-struct ExtraPiece {
-    int32_t b;       // request, -1 = this workgroup has none
-    int32_t begin;   // first logical KV position
-    int32_t end;     // one past the last
-    int32_t item;    // partial slot it writes
-};
-
 constexpr int kPlanTile = 32;          // tokens per scheduling tile
 constexpr int kMinTilesPerWg = 4;      // do not cut finer than 128 tokens
 constexpr int kDefaultMaxSplits = 256;
 constexpr int kNumCU = 256;            // MI355X
-// Common prompt prefixes (requests of one prompt group list the same pages at the start of their block
-// table rows): shorter ones than kShareMinTiles tiles are left on the line, a request gets at most
-// kShareMaxPieces pieces for its share of a prefix, and batches beyond kShareMaxB requests are not searched.
-constexpr int kShareMinTiles = 4;
-constexpr int kShareMaxPieces = 4;
-constexpr int kShareMaxB = 256;
 
 struct WorkspaceLayout {
     int max_items;
     int wgs_per_head;    // W (balanced mode) or B (one workgroup per request)
     int max_splits;
-    int share_prefix;    // 1: the plan looks for common prompt prefixes and schedules them apart (tiled D = 128 kernel)
-    size_t off_header, off_split, off_tiles, off_first, off_start, off_reqfirst, off_skip, off_lineslot, off_extra, off_fb,
-        off_items, off_ml, off_acc, total;
+    size_t off_header, off_split, off_tiles, off_first, off_start, off_reqfirst, off_fb, off_items, off_ml, off_acc, total;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -142,11 +124,6 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
         if (w.wgs_per_head < 1) w.wgs_per_head = 1;
         // a stretch adds one piece per request boundary it crosses: pieces <= W + B
         w.max_items = w.wgs_per_head + p.B;
-        const bool tiled = p.Dqk == 128 && p.Dv == 128 && gqa_page_size_ok(p.page_size) && !p.kv_shared_latent &&
-                           !(p.flags & SEER_ATTN_GENERAL_KERNEL);
-        w.share_prefix = tiled && !(p.flags & SEER_ATTN_NO_PREFIX_SHARING) && p.B >= 2 && p.B <= kShareMaxB &&
-                         w.max_splits >= kShareMaxPieces + 2;
-        if (w.share_prefix) w.max_items += w.wgs_per_head;    // at most one prefix piece per workgroup
     }
     const size_t rows = static_cast<size_t>(w.max_items) * p.T * p.Hq;
     const size_t per_b = sizeof(int32_t) * (static_cast<size_t>(p.B) + 1);
@@ -157,10 +134,7 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
     const size_t per_w = sizeof(int32_t) * (static_cast<size_t>(w.wgs_per_head) + 1);
     w.off_start = align_up(w.off_first + per_w, 256);
     w.off_reqfirst = align_up(w.off_start + per_w, 256);
-    w.off_skip = align_up(w.off_reqfirst + per_b, 256);
-    w.off_lineslot = align_up(w.off_skip + per_b, 256);
-    w.off_extra = align_up(w.off_lineslot + per_b, 256);
-    w.off_fb = align_up(w.off_extra + sizeof(ExtraPiece) * (static_cast<size_t>(w.wgs_per_head) + 1), 256);   // time[W], tiles[W], smoothed speed[W]
+    w.off_fb = align_up(w.off_reqfirst + per_b, 256);             // time[W], tiles[W], smoothed speed[W]
     w.off_items = align_up(w.off_fb + 3 * per_w, 256);
     w.off_ml = align_up(w.off_items + sizeof(WorkItem) * static_cast<size_t>(w.max_items), 256);
     w.off_acc = align_up(w.off_ml + 2 * sizeof(float) * rows, 256);
@@ -183,10 +157,6 @@ struct AttnArgs {
     const int32_t* wg_first;    // [wgs_per_head] request in which each workgroup's stretch starts, -1 = idle
     const int32_t* wg_start;    // [wgs_per_head + 1] first tile of each stretch on the tile line (balanced mode)
     const int32_t* req_first;   // [B] first stretch that touches each request (balanced mode)
-    const int32_t* req_skip;    // [B] leading tiles of each request that are not on the line (scheduled as prefix pieces)
-    const int32_t* line_slot;   // [B] partial slot of the request's first piece on the line (after its prefix pieces)
-    const ExtraPiece* wg_extra; // [wgs_per_head] prefix piece each workgroup handles before its stretch
-    int32_t share_prefix;       // 1: the plan may hand out prefix pieces
     uint32_t* fb_time;          // [wgs_per_head] sum over KV heads of the workgroup's duration, 10 ns ticks
     uint32_t* fb_tiles;         // [wgs_per_head] sum over KV heads of the tiles it streamed
     float* fb_speed;            // [wgs_per_head] smoothed tiles per tick (owned by the plan kernel)

@@ -22,18 +22,13 @@ constexpr int kPlanThreads = 256;
 
 struct PlanArgs {
     const int32_t* ctx_len;
-    const int32_t* block_table;
     int B, T, max_ctx, wgs_per_head, max_splits, max_items, fixed_split;
-    int max_pages, page_shift, share_prefix;
     PlanHeader* header;
     int32_t* split_off;
     int32_t* tile_off;
     int32_t* wg_first;
     int32_t* wg_start;
     int32_t* req_first;
-    int32_t* req_skip;
-    int32_t* line_slot;
-    ExtraPiece* wg_extra;
     uint32_t* fb_time;
     uint32_t* fb_tiles;
     float* fb_speed;
@@ -88,45 +83,13 @@ __device__ __forceinline__ int plan_max(int v, int* s_tmp) {
     for (int w = 1; w < kPlanThreads / kWave; ++w) m = max(m, s_tmp[w]);
     return m;
 }
-// running maximum over the threads up to and including this one
-__device__ __forceinline__ int plan_incl_max_scan(int v, int* s_tmp) {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const int up = __shfl_up(v, o, kWave);
-        if (lane >= o) v = max(v, up);
-    }
-    __syncthreads();
-    if (lane == kWave - 1) s_tmp[wave] = v;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kPlanThreads / kWave; ++w)
-        if (w < wave) v = max(v, s_tmp[w]);
-    return v;
-}
-
-// Tile index of the j-th of 16 probes that bracket the length of a common prefix: 0 1 2 3 5 7 11 15 .. 191 255.
-__device__ __forceinline__ int probe_tile(int j) {
-    return j == 0 ? 0 : (j & 1) ? (1 << ((j + 1) >> 1)) - 1 : (3 << ((j >> 1) - 1)) - 1;
-}
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
-    static_assert(kShareMaxB <= kPlanThreads, "one thread per request while prefixes are searched");
     __shared__ int s_tmp[2 * kPlanThreads / kWave];
     __shared__ int s_start[kMaxWgsPerHead + 1];
-    __shared__ int s_wx[kMaxWgsPerHead];            // tiles of the prefix piece each workgroup takes first
-    __shared__ int s_full[kShareMaxB];              // whole tiles of each request in front of its verify slots
-    __shared__ int s_lo[kShareMaxB], s_cnt[kShareMaxB], s_lcp[kShareMaxB];
-    __shared__ int s_c[kShareMaxB], s_n[kShareMaxB], s_base[kShareMaxB], s_pieces[kShareMaxB], s_each[kShareMaxB],
-        s_x[kShareMaxB];
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
     const int W = p.wgs_per_head;
-    for (int w = tid; w < W; w += kPlanThreads) {
-        p.wg_first[w] = -1;
-        p.wg_extra[w].b = -1;
-        s_wx[w] = 0;
-    }
+    for (int w = tid; w < W; w += kPlanThreads) p.wg_first[w] = -1;
 
     // thread `tid` owns a contiguous run of requests
     const int per = (p.B + kPlanThreads - 1) / kPlanThreads;
@@ -137,7 +100,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         return (n + kPlanTile - 1) / kPlanTile;
     };
 
-    // 1. tiles per request, their sum, and the longest request
+    // 1. tile line: exclusive prefix of tiles per request, and the longest request
     int cnt = 0, mx = 0, bad = 0;
     for (int b = b0; b < b1; ++b) {
         const int n = p.ctx_len[b];
@@ -147,157 +110,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         mx = max(mx, t);
     }
     int total = 0;
-    plan_excl_scan(cnt, s_tmp, total);
+    const int my_tile_off = plan_excl_scan(cnt, s_tmp, total);
     const int longest = plan_max(mx, s_tmp);
     bad = plan_max(bad, s_tmp);
-
-    // a request of t tiles touches at most ceil(t / Lmin) + 1 stretches, which together with its prefix
-    // pieces must fit max_splits
-    const int line_splits = p.max_splits - (p.share_prefix ? kShareMaxPieces : 0);
-    const int Lmin = line_splits > 1 ? max(kMinTilesPerWg, (longest + line_splits - 2) / (line_splits - 1)) : 1;
-
-    // 1b. Common prompt prefixes.  The requests of a prompt group list the same pages at the start of
-    // their block table rows (Section 2.3 of the paper: G responses per prompt).  Left on the tile line,
-    // those pages are fetched from HBM once per request: the copies are read far apart in time and on
-    // different XCDs, each with an L2 of its own.  Instead, the common tiles of a run of neighbouring
-    // requests are taken off the line and handed, one piece per request, to workgroups that share an XCD
-    // and start with that piece, all at the same moment: the first to ask brings a tile into that L2 and
-    // the others find it there.  This is scheduling only: a prefix piece is an ordinary piece of its
-    // request (own partial slot, merged by the combine), so a wrong guess here costs time, never
-    // correctness.  Only the batch order is searched (request b against b - 1), prefixes are measured in
-    // whole tiles in front of the verify slots, and a piece never exceeds a quarter of a workgroup's fair
-    // share, so that the stretch that follows it stays long enough.
-    const int e_max = total / (4 * W);
-    const int S8 = W / 8;                                  // workgroups per XCD (ids are dealt round-robin)
-    const int chunk = S8 >= 8 ? 8 : S8 >= 4 ? 4 : S8 >= 2 ? 2 : S8;    // neighbours that share an XCD
-    const int usable = chunk ? 8 * chunk * (S8 / chunk) : 0;
-    const bool share = p.share_prefix && p.max_splits > 1 && p.B <= kShareMaxB && e_max >= kShareMinTiles &&
-                       static_cast<long long>(total) >= 4ll * Lmin * W && usable > 0;
-    int my_skip = 0, my_nx = 0, my_each = 0, my_slot0 = 0, my_stride = 0;     // request tid (share implies per == 1)
-    if (share) {
-        if (tid < p.B) {
-            const int n = p.ctx_len[tid];
-            s_full[tid] = (n < p.T || n > p.max_ctx) ? 0 : (n - p.T) / kPlanTile;
-        }
-        __syncthreads();
-        // does request b hold tile t in the same page as request b - 1?  (the page of the tile's last token)
-        auto same_tile = [&](int b, int t) -> bool {
-            const int bc = min(max(b, 1), p.B - 1);                         // loads stay inside the table whatever b, t
-            const bool ok = b == bc && t >= 0 && t < min(s_full[bc], s_full[bc - 1]);
-            const int pg = ok ? ((t + 1) * kPlanTile - 1) >> p.page_shift : 0;
-            const int32_t* row = p.block_table + static_cast<size_t>(bc) * p.max_pages;
-            return ok & (row[pg] == row[pg - p.max_pages]);
-        };
-        // 16 threads per request, all loads of four rounds requested before any is used
-        auto probe_rounds = [&](auto&& tile_of_task, auto&& result) {
-            const int rounds = (p.B * 16 + kPlanThreads - 1) / kPlanThreads;
-            for (int r0 = 0; r0 < rounds; r0 += 4) {
-                bool eq[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int task = (r0 + i) * kPlanThreads + tid;
-                    eq[i] = same_tile(task >> 4, tile_of_task(task >> 4, task & 15));
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int task = (r0 + i) * kPlanThreads + tid;
-                    const uint64_t m = __ballot(eq[i]);
-                    const unsigned bits = static_cast<unsigned>(m >> (lane & 48)) & 0xffffu;
-                    const int ones = __builtin_ctz(~bits | 0x10000u);      // probes that agree, counted from the first
-                    if ((task & 15) == 0 && (task >> 4) < p.B) result(task >> 4, ones);
-                }
-            }
-        };
-        // round 1 brackets the common length between two probes ...
-        probe_rounds([&](int b, int j) { return b < p.B ? probe_tile(j) : -1; },
-                     [&](int b, int ones) {
-                         const int lo = ones ? probe_tile(ones - 1) + 1 : 0;
-                         int hi = ones < 16 ? probe_tile(ones) : lo;
-                         if (b >= 1) hi = min(hi, min(s_full[b], s_full[b - 1]));
-                         s_lo[b] = lo;
-                         s_cnt[b] = max(hi - lo, 0);
-                     });
-        __syncthreads();
-        // ... round 2 probes 16 evenly spaced tiles inside the bracket (exact up to 48 tiles, else rounded down)
-        const int more = __syncthreads_or(tid < p.B && s_cnt[tid] > 0);
-        if (more) {
-            probe_rounds(
-                [&](int b, int j) {
-                    if (b >= p.B) return -1;
-                    const int c = s_cnt[b], step = (c + 15) >> 4;
-                    const int t = s_lo[b] + (j + 1) * step - 1;
-                    return (c > 0 && t < s_lo[b] + c) ? t : -1;
-                },
-                [&](int b, int ones) { s_lcp[b] = s_lo[b] + ones * ((s_cnt[b] + 15) >> 4); });
-        } else if (tid < p.B) {
-            s_lcp[tid] = s_lo[tid];
-        }
-        __syncthreads();
-
-        // runs of neighbours with a common prefix of kShareMinTiles tiles or more; the run's common
-        // length is the smallest of its neighbour-to-neighbour lengths
-        const int lcp = (tid >= 1 && tid < p.B) ? s_lcp[tid] : 0;
-        const bool head = tid >= p.B || lcp < kShareMinTiles;
-        const int hd = plan_incl_max_scan(head ? tid : -1, s_tmp);
-        s_c[tid] = 0x7fffffff;
-        s_n[tid] = 0;
-        __syncthreads();
-        if (tid < p.B) {
-            if (!head) atomicMin(&s_c[hd], lcp);
-            atomicAdd(&s_n[hd], 1);
-        }
-        __syncthreads();
-        int need = 0, pieces = 0, each = 0, x = 0;
-        if (tid < p.B && head && s_n[tid] >= 2) {
-            const int c = s_c[tid];
-            pieces = min(kShareMaxPieces, (c + e_max - 1) / e_max);
-            each = min(e_max, (c + pieces - 1) / pieces);
-            x = min(c, pieces * each);
-            need = pieces * s_n[tid];
-        }
-        int all_needs = 0;
-        const int base = plan_excl_scan(need, s_tmp, all_needs);
-        s_base[tid] = (need > 0 && base + need <= usable) ? base : -1;
-        s_pieces[tid] = pieces;
-        s_each[tid] = each;
-        s_x[tid] = x;
-        __syncthreads();
-        if (tid < p.B && s_base[hd] >= 0) {
-            my_skip = s_x[hd];
-            my_nx = s_pieces[hd];
-            my_each = s_each[hd];
-            my_stride = s_n[hd];
-            my_slot0 = s_base[hd] + (tid - hd);
-            for (int j = 0; j < my_nx; ++j) {
-                const int s = my_slot0 + j * my_stride;
-                const int ch = s / chunk;
-                const int w = (ch & 7) + 8 * ((ch >> 3) * chunk + s % chunk);
-                s_wx[w] = min(my_skip, (j + 1) * my_each) - j * my_each;
-            }
-        }
-        __syncthreads();
-    }
-    auto skip_of = [&](int b) -> int { return share ? my_skip : 0; };      // share: b == tid
-    auto line_tiles_of = [&](int b) -> int { return tiles_of(b) - skip_of(b); };
-
-    // 1c. tile line: exclusive prefix of the tiles each request has on it
-    cnt = 0;
-    for (int b = b0; b < b1; ++b) cnt += line_tiles_of(b);
-    int total_line = 0;
-    const int my_tile_off = plan_excl_scan(cnt, s_tmp, total_line);
     {
         int off = my_tile_off;
         for (int b = b0; b < b1; ++b) {
             p.tile_off[b] = off;
-            off += line_tiles_of(b);
+            off += tiles_of(b);
         }
-        if (tid == 0) p.tile_off[p.B] = total_line;
+        if (tid == 0) p.tile_off[p.B] = total;
     }
 
     // 2. the stretches (balanced mode; L = 0 means one workgroup per request)
     int L = 0;
     if (p.max_splits > 1) {
         L = max((total + W - 1) / W, 1);
+        // a request of t tiles touches at most ceil(t / Lmin) + 1 stretches, which must fit max_splits
+        const int Lmin = max(kMinTilesPerWg, (longest + p.max_splits - 2) / (p.max_splits - 1));
         // relative speed of each stretch index from the history in the workspace; thread t owns the
         // stretch indices [t * per_w, t * per_w + per_w)
         constexpr int kPerW = kMaxWgsPerHead / kPlanThreads;
@@ -333,45 +163,37 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         sum = plan_sum(sum, reinterpret_cast<float*>(s_tmp));
         known = plan_sum(known, reinterpret_cast<float*>(s_tmp));
         const float mean = known > 0.f ? sum / known : 1.f;
-        // A workgroup's share of all tiles (those on the line and the prefix pieces) is proportional to
-        // its speed r_w: stretch w begins at the line tile nearest to total * (r_0 + .. + r_{w-1}) / R
-        // minus the prefix tiles of the workgroups before it.  When the line is too short for that to
-        // keep every stretch at Lmin tiles or more, cut it into equal stretches of
+        // Stretch w begins at the tile nearest to total * (r_0 + .. + r_{w-1}) / R.  When the line is too
+        // short for that to keep every stretch at Lmin tiles or more, cut it into equal stretches of
         // max(Lmin, ceil(total / W)) tiles instead (the last ones are then short or empty).
         const bool weighted = static_cast<long long>(total) >= 2ll * Lmin * W;
         float rsum = 0.f;
-        int xsum = 0;
 #pragma unroll
         for (int i = 0; i < kPerW; ++i) {
             if (i < per_w && w0 + i < W) {
                 const float r = (weighted && speed[i] > 0.f) ? speed[i] / mean : 1.f;
                 speed[i] = fminf(fmaxf(r, 0.75f), 4.f / 3.f);
                 rsum += speed[i];
-                xsum += s_wx[w0 + i];
             }
         }
         float R = 0.f;
         float before = plan_excl_scan(rsum, reinterpret_cast<float*>(s_tmp), R);
-        int x_all = 0;
-        int x_before = plan_excl_scan(xsum, s_tmp, x_all);
         const int L_equal = max(Lmin, L);
 #pragma unroll
         for (int i = 0; i < kPerW; ++i) {
             if (i < per_w && w0 + i < W) {
                 const int w = w0 + i;
-                long long cut = weighted ? static_cast<long long>(static_cast<double>(total) * before / R + 0.5) - x_before
-                                         : static_cast<long long>(w) * L_equal;
-                cut = cut > 0 ? cut : 0;
-                s_start[w] = static_cast<int>(cut < total_line ? cut : total_line);
+                const long long cut = weighted ? static_cast<long long>(static_cast<double>(total) * before / R + 0.5)
+                                               : static_cast<long long>(w) * L_equal;
+                s_start[w] = static_cast<int>(cut < total ? cut : total);
                 before += speed[i];
-                x_before += s_wx[w];
             }
         }
-        if (tid == 0) s_start[W] = total_line;
+        if (tid == 0) s_start[W] = total;
         __syncthreads();
         for (int w = tid; w <= W; w += kPlanThreads) p.wg_start[w] = s_start[w];
     }
-    // stretch that holds line tile x (x < total_line): the last one that starts at or before it
+    // stretch that holds tile x (x < total): the last one that starts at or before it
     auto stretch_of = [&](int x) -> int {
         int lo = 0, hi = W - 1;
         while (lo < hi) {
@@ -381,16 +203,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         return lo;
     };
 
-    // 3. pieces per request (prefix pieces, then pieces on the line) -> first partial slot of each request
+    // 3. pieces per request -> first partial slot of each request
     cnt = 0;
     {
         int lo = my_tile_off;
         for (int b = b0; b < b1; ++b) {
-            const int hi = lo + line_tiles_of(b);
+            const int hi = lo + tiles_of(b);
             if (hi > lo) cnt += L ? stretch_of(hi - 1) - stretch_of(lo) + 1 : 1;
             lo = hi;
         }
-        cnt += my_nx;
     }
     int n_pieces = 0;
     int slot = plan_excl_scan(cnt, s_tmp, n_pieces);
@@ -399,7 +220,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         p.header->n_items = min(n_pieces, p.max_items);
         p.header->tiles_per_wg = L;
         p.header->total_tiles = total;
-        p.header->shared_tiles = total - total_line;
         if (!p.fixed_split) {
             p.header->fb_magic = kFeedbackMagic;
             p.header->fb_w = W;
@@ -410,32 +230,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
     // 4. piece table and the request each stretch starts in
     int lo = my_tile_off;
     for (int b = b0; b < b1; ++b) {
-        const int hi = lo + line_tiles_of(b);
-        const int skip = skip_of(b), nx = share ? my_nx : 0;
+        const int hi = lo + tiles_of(b);
         p.split_off[b] = slot;
-        p.req_skip[b] = skip;
-        p.line_slot[b] = slot + nx;
         const int n = p.ctx_len[b];
-        for (int j = 0; j < nx; ++j) {
-            const int s = my_slot0 + j * my_stride;
-            const int ch = s / chunk;
-            const int w = (ch & 7) + 8 * ((ch >> 3) * chunk + s % chunk);
-            ExtraPiece e;
-            e.b = b;
-            e.begin = j * my_each * kPlanTile;
-            e.end = min(skip, (j + 1) * my_each) * kPlanTile;
-            e.item = slot + j;
-            if (slot + j < p.max_items) {
-                p.wg_extra[w] = e;
-                WorkItem it;
-                it.b = b;
-                it.begin = e.begin;
-                it.end = e.end;
-                it.split = j;
-                p.items[slot + j] = it;
-            }
-        }
-        slot += nx;
         const int w_first = hi > lo ? (L ? stretch_of(lo) : b) : 0;
         const int np = hi > lo ? (L ? stretch_of(hi - 1) - w_first + 1 : 1) : 0;
         p.req_first[b] = w_first;
@@ -447,9 +244,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
             if (slot + s < p.max_items) {
                 WorkItem it;
                 it.b = b;
-                it.begin = (skip + t_begin - lo) * kPlanTile;
-                it.end = min(n, (skip + t_end - lo) * kPlanTile);
-                it.split = nx + s;
+                it.begin = (t_begin - lo) * kPlanTile;
+                it.end = min(n, (t_end - lo) * kPlanTile);
+                it.split = s;
                 p.items[slot + s] = it;
             }
             if (t_begin == w_begin && w < W) p.wg_first[w] = b;   // stretch w starts here
@@ -463,11 +260,6 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
     const long long max_ctx_ll = static_cast<long long>(a.max_pages) * a.P;
     PlanArgs p;
     p.ctx_len = a.ctx_len;
-    p.block_table = a.block_table;
-    p.max_pages = a.max_pages;
-    p.page_shift = 0;
-    while ((1 << p.page_shift) < a.P && p.page_shift < 30) ++p.page_shift;   // used for power-of-two pages only
-    p.share_prefix = a.share_prefix;
     p.B = a.B;
     p.T = a.T;
     p.max_ctx = max_ctx_ll > 0x7fffffffLL - kPlanTile ? 0x7fffffff - kPlanTile : static_cast<int>(max_ctx_ll);
@@ -480,9 +272,6 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
     p.wg_first = const_cast<int32_t*>(a.wg_first);
     p.wg_start = const_cast<int32_t*>(a.wg_start);
     p.req_first = const_cast<int32_t*>(a.req_first);
-    p.req_skip = const_cast<int32_t*>(a.req_skip);
-    p.line_slot = const_cast<int32_t*>(a.line_slot);
-    p.wg_extra = const_cast<ExtraPiece*>(a.wg_extra);
     p.fb_time = a.fb_time;
     p.fb_tiles = a.fb_tiles;
     p.fb_speed = a.fb_speed;
@@ -721,8 +510,7 @@ int validate_params(const seer_attn_params* p) {
     if (p->B < 0 || p->num_pages < 1 || p->max_pages_per_seq < 1 || p->page_size < 1) return SEER_EINVAL;
     if (p->T < 1 || p->T > SEER_MAX_T || p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SEER_ESHAPE;
     if (p->max_splits < 0 || p->max_splits > 256) return SEER_ESHAPE;
-    if (p->flags & ~(SEER_ATTN_GENERAL_KERNEL | SEER_ATTN_FIXED_SPLIT | SEER_ATTN_STREAM_ONLY | SEER_ATTN_REUSE_PLAN |
-                     SEER_ATTN_NO_PREFIX_SHARING))
+    if (p->flags & ~(SEER_ATTN_GENERAL_KERNEL | SEER_ATTN_FIXED_SPLIT | SEER_ATTN_STREAM_ONLY | SEER_ATTN_REUSE_PLAN))
         return SEER_EINVAL;
     if (p->Hq > 65535 || p->T * (int64_t)p->Hq * p->B > 0x7fffffffLL) return SEER_ESHAPE;
     if (!(p->scale > 0.f) || p->scale > 3.0e38f) return SEER_EINVAL;   // positive and finite
@@ -739,7 +527,6 @@ extern "C" size_t seer_verify_attention_workspace(const seer_attn_params* p) {
 }
 
 extern "C" size_t seer_verify_attention_status_offset(void) { return offsetof(seer::PlanHeader, status); }
-extern "C" size_t seer_verify_attention_shared_tiles_offset(void) { return offsetof(seer::PlanHeader, shared_tiles); }
 
 namespace {
 
@@ -775,10 +562,6 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.wg_first = reinterpret_cast<const int32_t*>(ws + w.off_first);
     a.wg_start = reinterpret_cast<const int32_t*>(ws + w.off_start);
     a.req_first = reinterpret_cast<const int32_t*>(ws + w.off_reqfirst);
-    a.req_skip = reinterpret_cast<const int32_t*>(ws + w.off_skip);
-    a.line_slot = reinterpret_cast<const int32_t*>(ws + w.off_lineslot);
-    a.wg_extra = reinterpret_cast<const seer::ExtraPiece*>(ws + w.off_extra);
-    a.share_prefix = w.share_prefix;
     a.fb_time = reinterpret_cast<uint32_t*>(ws + w.off_fb);
     a.fb_tiles = a.fb_time + (w.wgs_per_head + 1);
     a.fb_speed = reinterpret_cast<float*>(a.fb_tiles + (w.wgs_per_head + 1));

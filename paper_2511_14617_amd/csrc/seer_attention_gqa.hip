@@ -414,26 +414,13 @@ void attn_gqa128_kernel(AttnArgs a) {
     const int p16 = lane & 15;
 
     const int L = uniform_load(&a.header->tiles_per_wg);
-    // the piece of a common prompt prefix that the plan gave this workgroup, if any: it comes first, so
-    // that the workgroups holding the same tiles for other requests (same XCD) read them at the same moment
-    int x_b = -1, x_begin = 0, x_end = 0, x_item = 0;
-    if (L) {
-        const int32_t* xp = reinterpret_cast<const int32_t*>(a.wg_extra + wg);
-        x_b = uniform_load(xp);
-        x_begin = uniform_load(xp + 1);
-        x_end = uniform_load(xp + 2);
-        x_item = uniform_load(xp + 3);
-    }
     int b = uniform_load(a.wg_first + wg);
-    if (b < 0 && x_b < 0) return;
-    int g = 0, g_end = 0;
-    if (b >= 0) {
-        g = uniform_load(L ? a.wg_start + wg : a.tile_off + b);
-        g_end = uniform_load(L ? a.wg_start + wg + 1 : a.tile_off + b + 1);
-    }
+    if (b < 0) return;
+    int g = uniform_load(L ? a.wg_start + wg : a.tile_off + b);
+    const int g_end = uniform_load(L ? a.wg_start + wg + 1 : a.tile_off + b + 1);
     const int g_first = g;
     const uint64_t clock_begin = __builtin_amdgcn_s_memrealtime();
-    bool bad_page = false, bad_plan = false;
+    bool bad_page = false;
 
     const unsigned char* __restrict__ kbase = static_cast<const unsigned char*>(a.k_pages);
     const unsigned char* __restrict__ vbase = static_cast<const unsigned char*>(a.v_pages);
@@ -453,30 +440,14 @@ void attn_gqa128_kernel(AttnArgs a) {
         v_rd[dt] = (lg * 4 + v_k) * kRowBytes + ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;   // token lg*4 + k
     }
 
-  for (bool prefix_piece = x_b >= 0; prefix_piece || g < g_end; prefix_piece = false) {
-    int rq, item_idx, n, tok_begin, tok_end;
-    if (prefix_piece) {
-        rq = x_b;
-        item_idx = x_item;
-        n = uniform_load(a.ctx_len + rq);
-        tok_begin = x_begin;
-        tok_end = min(n, x_end);
-    } else {
-        rq = b++;
-        const int t_lo = uniform_load(a.tile_off + rq), t_hi = uniform_load(a.tile_off + rq + 1);
-        if (t_hi == t_lo) continue;
-        const int skip = uniform_load(a.req_skip + rq);     // leading tiles that are not on the line
-        item_idx = uniform_load(a.line_slot + rq) +
-                   (L ? wg - uniform_load(a.req_first + rq) : 0);
-        n = uniform_load(a.ctx_len + rq);
-        tok_begin = (skip + g - t_lo) * kTile;
-        tok_end = min(n, (skip + min(g_end, t_hi) - t_lo) * kTile);
-        g = t_hi;
-    }
-    if (item_idx < 0 || item_idx >= a.max_items || tok_end <= tok_begin) {   // never with a plan of this library
-        bad_plan = true;
-        continue;
-    }
+  for (; g < g_end; ++b) {
+    const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
+    if (t_hi == t_lo) continue;
+    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - uniform_load(a.req_first + b) : 0);
+    const int n = uniform_load(a.ctx_len + b);
+    const int tok_begin = (g - t_lo) * kTile;
+    const int tok_end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
+    g = t_hi;
     const int n0 = n - a.T;
     const int n_tiles = (tok_end - tok_begin + kTile - 1) / kTile;
     bare_barrier();                                // every wave is done with the previous piece's slots
@@ -488,14 +459,14 @@ void attn_gqa128_kernel(AttnArgs a) {
     const int hq = kvh * a.G + (row_ok ? r - t * a.G : 0);
     uint64_t word = 0;
     if (row_ok) {
-        word = a.tree_mask ? a.tree_mask[static_cast<size_t>(rq) * a.T + t]
+        word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
                            : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
         if (a.T < 64) word &= (1ull << a.T) - 1;
     }
     bf16x8 qreg[8];
     {
         const u32x4* qp = reinterpret_cast<const u32x4*>(
-            static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(rq) * a.T + t) * a.Hq + hq) * kD + lg * 8);
+            static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * kD + lg * 8);
         u32x4 qv[8];
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
@@ -525,7 +496,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     // page ids, 64 at a time (lane l holds logical page cache_base + l), handed out with v_readlane.
     // With 16-token pages a tile is one even-numbered page and its successor, and windows start at even
     // pages, so one window test covers both; with larger pages a tile is 32 rows inside one page.
-    const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(rq) * a.max_pages;
+    const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
     int cache_base = -0x40000000;
     int pg_cache = 0;
     const int last_page = (n - 1) >> page_shift;
@@ -755,12 +726,12 @@ void attn_gqa128_kernel(AttnArgs a) {
             }
     }
   }  // pieces of the stretch
-    if ((bad_page || bad_plan) && lane == 0) atomicOr(&a.header->status, (bad_page ? 2u : 0u) | (bad_plan ? 4u : 0u));
+    if (bad_page && lane == 0) atomicOr(&a.header->status, 2u);
     // speed history for the next call's plan: tiles streamed and time taken, by stretch index
     if (L && !a.fixed_split && tid == 0) {
         const uint64_t ticks = __builtin_amdgcn_s_memrealtime() - clock_begin;
         atomicAdd(a.fb_time + wg, static_cast<uint32_t>(ticks > 0xffffffu ? 0xffffffu : ticks));
-        atomicAdd(a.fb_tiles + wg, static_cast<uint32_t>(g_end - g_first + (x_b >= 0 ? (x_end - x_begin) / kTile : 0)));
+        atomicAdd(a.fb_tiles + wg, static_cast<uint32_t>(g_end - g_first));
     }
 }
 

@@ -79,7 +79,7 @@ def test_attention_argument_errors_before_any_launch(lib):
     assert run(_params(Dqk=100)) == b.SEER_EUNSUPPORTED
     assert run(_params(Dqk=576, Dv=512, kv_shared_latent=1), v=None, ws_bytes=0) == b.SEER_EWORKSPACE
     assert run(_params(num_pages=0)) == b.SEER_EINVAL
-    assert run(_params(flags=32)) == b.SEER_EINVAL                       # unknown flag bit
+    assert run(_params(flags=16)) == b.SEER_EINVAL                       # unknown flag bit
     assert run(_params(scale=float("nan"))) == b.SEER_EINVAL
     assert run(_params(scale=0.0)) == b.SEER_EINVAL
     assert run(_params(scale=-0.1)) == b.SEER_EINVAL

@@ -260,47 +260,3 @@ def test_parity_random_shapes(seed):
     what = "random %d: G=%d Hkv=%d T=%d tree=%s P=%d B=%d ctx=%s" % (seed, cfg.G, cfg.Hkv, cfg.T, cfg.tree,
                                                                      cfg.page_size, cfg.B, inp.ctx_len.tolist())
     assert_attention_close(out, ref, what, hardened=True, ref_abs=_oracle_abs(inp))
-
-
-# Common prompt prefixes: big enough that the plan schedules them apart (Hkv = 16 gives 64 stretches;
-# the search needs 16 tiles or more per stretch), small enough for the oracle.
-_SHARE_BASE = W.CONFIGS[2].scaled(B=24, group_size=6, Hq=16, Hkv=16, T=9, ctx=("uniform", 800, 3000), shared_prefix=512)
-SHARE_CASES = {
-    "groups_of_6": (_SHARE_BASE, {}, True),
-    "prefix_not_a_whole_tile": (_SHARE_BASE.scaled(shared_prefix=592), {}, True),
-    "prefix_of_3_tiles_stays_on_the_line": (_SHARE_BASE.scaled(shared_prefix=96), {}, False),
-    "no_prefix": (_SHARE_BASE.scaled(shared_prefix=0), {}, False),
-    "one_group_of_24": (_SHARE_BASE.scaled(group_size=24, shared_prefix=256), {}, True),
-    "pairs": (_SHARE_BASE.scaled(group_size=2, shared_prefix=1024, ctx=("uniform", 1100, 3000)), {}, True),
-    "some_contexts_end_inside_the_prefix": (_SHARE_BASE.scaled(ctx=("uniform", 300, 3600)), {}, True),
-    "page64": (_SHARE_BASE.scaled(page_size=64, shared_prefix=640), {}, True),
-    "tree_T33": (W.CONFIGS[5].scaled(B=24, group_size=8, Hq=16, Hkv=16, ctx=("uniform", 800, 3000), shared_prefix=512),
-                 {"dedup_fraction": 0.3}, True),
-}
-
-
-@pytest.mark.parametrize("name", sorted(SHARE_CASES))
-def test_common_prefix_pieces(name):
-    """Requests of a group list the same pages at the start of their block tables; the plan schedules
-    those tiles as pieces of their own.  The result must match the oracle with the search on and off,
-    and the search must find the prefix where there is one worth a piece."""
-    from paper_2511_14617_amd import binding
-    cfg, kw, expect = SHARE_CASES[name]
-    inp = W.make_attention_inputs(cfg, values="peaked", **kw)
-    ref, ref_abs = _oracle(inp), _oracle_abs(inp)
-    d = attention_device_inputs(inp)
-    for flags in (0, binding.SEER_ATTN_NO_PREFIX_SHARING, binding.SEER_ATTN_FIXED_SPLIT):
-        p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], inp.scale, Dv=cfg.Dv, flags=flags)
-        ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device="cuda")
-        for call in range(3):          # the second and third call cut the line by the measured speeds
-            out = binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
-                                                d["tree_mask"], inp.scale, Dv=cfg.Dv, workspace=ws, flags=flags)
-            torch.cuda.synchronize()
-            assert binding.seer_verify_attention_status(ws) == 0
-            shared = binding.seer_verify_attention_shared_tiles(ws)
-            if flags & binding.SEER_ATTN_NO_PREFIX_SHARING or not expect:
-                assert shared == 0, (name, flags, shared)
-            else:
-                whole = (np.minimum(cfg.shared_prefix, inp.ctx_len - cfg.T) // 32).sum()
-                assert 0 < shared <= whole, (name, flags, shared, whole)
-            assert_attention_close(out, ref, "%s flags=%d call %d" % (name, flags, call), hardened=True, ref_abs=ref_abs)
