@@ -66,6 +66,13 @@ CASES = {
     "mla_page32": (W.CONFIGS[4].scaled(B=2, Hq=16, page_size=32, ctx=("uniform", 100, 700)), {}),
     "mla_page128": (W.CONFIGS[4].scaled(B=2, Hq=16, page_size=128, ctx=("uniform", 100, 700)), {}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
+    # the most verify slots a call takes (the mask word is full): every kernel, chain and tree
+    "T64_chain_rows256": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=8, Hkv=2, T=64, ctx=("uniform", 64, 1200),
+                                              shared_prefix=0), {}),
+    "T64_tree_two_row_blocks": (W.CONFIGS[5].scaled(B=3, group_size=3, Hq=16, Hkv=2, T=64, tree=(7, 9),
+                                                    ctx=("uniform", 64, 1200), shared_prefix=0), {"dedup_fraction": 0.3}),
+    "T64_mla": (W.CONFIGS[4].scaled(B=2, Hq=16, T=64, ctx=("uniform", 100, 700)), {}),
+    "T64_mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, T=64, ctx=("uniform", 64, 500)), {}),
     "g8_d256_page32": (W.CONFIGS[1].scaled(Hq=8, Hkv=1, Dqk=256, Dv=256, page_size=32,
                                            ctx=("uniform", 50, 900)), {}),
 }
