@@ -297,6 +297,8 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # secondary figure: tokens a step emits = accepted draft tokens + the bonus token of every request
+    emitted = None if args.attention_only else int(acc_out[0].sum().item()) + cfg.B
     kern_ms = events.elapsed_ms()
     kern_avg_ms = float(np.mean(kern_ms))
     events.close()
@@ -434,6 +436,8 @@ def main() -> int:
         "attention_ms": att_ms, "attention_reuse_plan_ms": att_reuse_ms, "accept_ms": acc_ms,
         "attention_kv_GBps": ab["kv_unique"] / (att_ms * 1e-3) / 1e9,
         "accept_logits_GBps": (acc.logits.nbytes / (acc_ms * 1e-3) / 1e9) if acc_ms > 0 else None,
+        "emitted_tokens_per_s": None if emitted is None else emitted / (ms_per_step * 1e-3),
+        "mean_emitted_per_request": None if emitted is None else emitted / cfg.B,
         "attention_status_word": status,
         "accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms, "draft": draft_info,
     }

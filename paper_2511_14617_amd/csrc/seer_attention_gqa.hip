@@ -82,6 +82,12 @@ __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
 template <int NW> struct Loaders { static constexpr int kFirst = 0, kCount = NW; };
 template <> struct Loaders<5> { static constexpr int kFirst = 1, kCount = 3; };
 
+// Cache policy of the tile loads: non-temporal.  A KV tile is used once per call by one workgroup, and
+// streaming it (no allocation for reuse in the L2 and the memory-side cache) is what lets a gather of 4 KB
+// blocks reach 6.9 TB/s on this part; the default policy tops out at 6.1 TB/s (bare read loops, plain loads
+// and loads into LDS alike).
+constexpr int kTileLoadPolicy = 2;   // the "nt" bit of the instruction's cache-policy field
+
 // Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the loading waves.
 template <int NW>
 __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, size_t p0, size_t p1,
@@ -96,7 +102,7 @@ __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, s
             const size_t pg = (j < 4) ? p0 : p1;
             const int lane_off = is_k ? goff ^ ((j & 3) << 6) : goff;   // K rows 4j + l16: f = 4(j & 3) + l16
             const unsigned char* src = base + pg + (j & 3) * (4 * kRowBytes) + lane_off;
-            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(slot + j * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(slot + j * 1024), 16, 0, kTileLoadPolicy);
         }
     }
 }
