@@ -214,7 +214,7 @@ def multipath_parent(B: int, n_paths: int, path_len: int, rng: np.random.Generat
     parent = np.full((B, T), -2, dtype=np.int32)
     parent[:, 0] = -1
     for b in range(B):
-        if dedup_fraction > 0.0 and rng.random() < dedup_fraction:
+        if dedup_fraction > 0.0 and rng.random() < dedup_fraction and path_len >= 2:   # one-node paths have no trunk to share
             trunk = int(rng.integers(1, path_len))  # shared trunk length 1..path_len-1
             t = 1
             prev = 0

@@ -254,7 +254,7 @@ def _random_shape(rng):
     return cfg
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_parity_random_shapes(seed):
     """Random shapes of the tiled D = 128 kernel against the oracle, hardened values: every combination of
     wave count, row blocks, page size, chain or tree, ragged tails and very short prefixes that the seeds hit."""

@@ -360,7 +360,7 @@ def test_decode_loop_emits_exactly_the_true_sequence(top_k, gamma_max):
     assert total_accepted > cfg.B                         # the drafts did shorten the loop
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_shapes(seed):
     """Seeded random batches: groups of 1..5 sequences of 0..3000 tokens (some empty), vocabularies from 3 tokens
     to thousands, any pattern window, beam width, depth and threshold, requests spread over the groups in any
