@@ -120,24 +120,35 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
     dr = W.make_draft_inputs(cfg, gamma_max=gamma_max, top_k=1)
     t32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
     dr_dev = [t32(x) for x in (dr.tokens, dr.seq_start, dr.seq_len, dr.group_first)]
+    # one allocation of each tensor at its largest size, cells take leading slices: the place of a buffer in
+    # memory (which channels its lines fall on) moves these times by several per cent, and must not differ
+    # from cell to cell
+    Bmax, Tmax = max(batches), gamma_max + 1
+    q_all = torch.randn(Bmax * Tmax * cfg.Hq * cfg.Dqk, device=dev).to(torch.bfloat16)
+    logits_all = torch.randn(Bmax * Tmax * cfg.V, device=dev)
+    ws_all = torch.empty(binding.seer_verify_attention_workspace(
+        binding.attn_params(q_all.view(Bmax, Tmax, cfg.Hq, cfg.Dqk), d["k_pages"], d["v_pages"], d["block_table"], att.scale)),
+        dtype=torch.uint8, device=dev)
     for B in batches:
         att_row, reuse_row, acc_row, drow = [], [], [], [0.0]
         for gamma in range(gamma_max + 1):
             T = gamma + 1
-            q = torch.randn((B, T, cfg.Hq, cfg.Dqk), device=dev).to(torch.bfloat16)
-            logits = torch.randn((B, T, cfg.V), device=dev)
+            q = q_all[:B * T * cfg.Hq * cfg.Dqk].view(B, T, cfg.Hq, cfg.Dqk)
+            logits = logits_all[:B * T * cfg.V].view(B, T, cfg.V)
             draft = torch.zeros((B, T), dtype=torch.int32, device=dev)
             # the pool's contexts count 9 verify slots; shorten by the slots this gamma does not use
             n = (d["ctx_len"][:B] - (gamma_max + 1 - T)).contiguous()
             bt = d["block_table"][:B].contiguous()
             p = binding.attn_params(q, d["k_pages"], d["v_pages"], bt, att.scale)
-            ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device=dev)
+            need = binding.seer_verify_attention_workspace(p)
+            assert need <= ws_all.numel()
+            ws = ws_all[:need]
             ws2 = torch.empty(max(16, binding.seer_accept_workspace(B, T, cfg.V)), dtype=torch.uint8, device=dev)
 
             def timed(fn):
                 # a long matrix product first: while the GPU works on it the host enqueues all calls, so
                 # the events see GPU time, not the time Python needs to issue a call
-                for _ in range(3):
+                for _ in range(12):         # also lets the stretch lengths settle on the measured speeds
                     fn()
                 torch.mm(busy, busy, out=busy_out)
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
