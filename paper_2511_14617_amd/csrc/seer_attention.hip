@@ -567,6 +567,7 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.fb_speed = reinterpret_cast<float*>(a.fb_tiles + (w.wgs_per_head + 1));
     a.fixed_split = (p->flags & SEER_ATTN_FIXED_SPLIT) ? 1 : 0;
     a.stream_only = (p->flags & SEER_ATTN_STREAM_ONLY) ? 1 : 0;
+    a.stream_partials = (w.total - w.off_acc) < seer::kStreamPartialsBelow ? 1 : 0;
     a.row_blocks = seer::gqa_row_blocks((p->Hq / p->Hkv) * p->T);
     a.rows_per_block = seer::gqa_rows_per_block((p->Hq / p->Hkv) * p->T);
     a.items = reinterpret_cast<const seer::WorkItem*>(ws + w.off_items);

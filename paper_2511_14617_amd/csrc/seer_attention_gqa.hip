@@ -387,7 +387,8 @@ __device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, 
 // waits, barriers, partial-result writes) and leaves out the arithmetic.  Its time is what the memory
 // system allows for exactly this access pattern and launch shape: the ceiling the kernel's
 // bytes-per-second should be read against.  It writes "saw nothing" partials, so the output is zero.
-template <int NW, int D, bool STREAM>
+// STREAM_PARTIALS: the partial results leave with non-temporal stores (see kStreamPartialsBelow).
+template <int NW, int D, bool STREAM, bool STREAM_PARTIALS>
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
 void attn_gqa128_kernel(AttnArgs a) {
     constexpr int NT = NW * kWave;
@@ -728,7 +729,11 @@ void attn_gqa128_kernel(AttnArgs a) {
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
-                *reinterpret_cast<f32x4*>(po + dt * 32 + i4 * 8 + lg * 4) = v;
+                f32x4* dst = reinterpret_cast<f32x4*>(po + dt * 32 + i4 * 8 + lg * 4);
+                // (a compile-time choice: in two arms of a run-time branch the compiler folds the two stores of
+                // the same value into one plain store)
+                if constexpr (STREAM_PARTIALS) __builtin_nontemporal_store(v, dst);
+                else *dst = v;
             }
     }
   }  // pieces of the stretch
@@ -751,14 +756,15 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const dim3 grid(static_cast<unsigned>((a.wgs_per_head + 7) / 8) * 8u * static_cast<unsigned>(a.Hkv) *
                     static_cast<unsigned>(a.row_blocks));
     switch (nw) {
+#define SEER_GQA_LAUNCH(NW_, STREAM_, PARTIALS_)                                                               \
+    hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), STREAM_, PARTIALS_>), grid, dim3(NW_ * kWave), 0, \
+                       stream, a)
 #define SEER_GQA_CASE(NW_)                                                                                     \
     case NW_:                                                                                                  \
-        if (a.stream_only)                                                                                     \
-            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), true>), grid, dim3(NW_ * kWave), 0,   \
-                               stream, a);                                                                     \
-        else                                                                                                   \
-            hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), false>), grid, dim3(NW_ * kWave), 0,  \
-                               stream, a);                                                                     \
+        if (a.stream_only && a.stream_partials) SEER_GQA_LAUNCH(NW_, true, true);                              \
+        else if (a.stream_only) SEER_GQA_LAUNCH(NW_, true, false);                                             \
+        else if (a.stream_partials) SEER_GQA_LAUNCH(NW_, false, true);                                         \
+        else SEER_GQA_LAUNCH(NW_, false, false);                                                               \
         break;
         SEER_GQA_CASE(1)
         SEER_GQA_CASE(2)
@@ -769,6 +775,7 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
         SEER_GQA_CASE(7)
         SEER_GQA_CASE(8)
 #undef SEER_GQA_CASE
+#undef SEER_GQA_LAUNCH
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
