@@ -717,23 +717,56 @@ void attn_gqa128_kernel(AttnArgs a) {
 
     // ---- partial result: (reference exponent, sum, unnormalised O) per row ------------
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    if (row_ok) {
+    if (row_ok && lg == 0) {
         const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
-        if (lg == 0) {
-            a.part_ml[2 * prow] = m_run;
-            a.part_ml[2 * prow + 1] = l_tot;
+        a.part_ml[2 * prow] = m_run;
+        a.part_ml[2 * prow + 1] = l_tot;
+    }
+    auto store_partial = [&](float* dst, const f32x4& v) __attribute__((always_inline)) {
+        // (a compile-time choice: in two arms of a run-time branch the compiler folds the two stores of the
+        // same value into one plain store)
+        if constexpr (STREAM_PARTIALS) __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+        else *reinterpret_cast<f32x4*>(dst) = v;
+    };
+    if constexpr (NW <= 2 && NW * 16384 <= 2 * NSLOT * kKBytes) {
+        // The accumulators hold, per lane, 16-byte pieces of a row that lie 32 bytes apart; written out as they
+        // are, one store instruction touches 32 rows with 32 bytes each.  Through the ring (free now: 16 KB per
+        // wave, 16-byte chunks XORed with the row so that neither side has bank conflicts) every store
+        // instruction writes two whole rows of 512 bytes.  Worth 0.6 % of the kernel on the memory-bound
+        // two-wave shape (many short pieces); nothing measurable with three waves and more, which keep the
+        // direct stores.
+        bare_barrier();                                  // every wave has read the last tiles
+        unsigned char* st = lds + wave * 16384;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
+                const int c = dt * 8 + i4 * 2 + lg;
+                *reinterpret_cast<f32x4*>(st + ln * 512 + ((c ^ ln) << 4)) = v;
+            }
+        const int first_row = rb * a.rows_per_block + wave * 32;
+#pragma unroll 2
+        for (int k = 0; k < 16; ++k) {                   // (not unrolled further: sixteen rows in flight spill registers)
+            const int rr = 2 * k + lg;                   // row of the wave; this lane moves chunk ln of it
+            const f32x4 v = *reinterpret_cast<const f32x4*>(st + rr * 512 + ((ln ^ rr) << 4));
+            const int r2 = first_row + rr;
+            if (r2 < R) {
+                const int t2 = r2 / a.G;
+                const int hq2 = kvh * a.G + (r2 - t2 * a.G);
+                const size_t prow = (static_cast<size_t>(item_idx) * a.T + t2) * a.Hq + hq2;
+                store_partial(a.part_acc + prow * kD + ln * 4, v);
+            }
         }
+    } else if (row_ok) {
+        const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
         float* __restrict__ po = a.part_acc + prow * kD;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
-                f32x4* dst = reinterpret_cast<f32x4*>(po + dt * 32 + i4 * 8 + lg * 4);
-                // (a compile-time choice: in two arms of a run-time branch the compiler folds the two stores of
-                // the same value into one plain store)
-                if constexpr (STREAM_PARTIALS) __builtin_nontemporal_store(v, dst);
-                else *dst = v;
+                store_partial(po + dt * 32 + i4 * 8 + lg * 4, v);
             }
     }
   }  // pieces of the stretch
