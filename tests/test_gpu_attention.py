@@ -66,6 +66,10 @@ CASES = {
     "mla_page32": (W.CONFIGS[4].scaled(B=2, Hq=16, page_size=32, ctx=("uniform", 100, 700)), {}),
     "mla_page128": (W.CONFIGS[4].scaled(B=2, Hq=16, page_size=128, ctx=("uniform", 100, 700)), {}),
     "mha_d64": (W.CONFIGS[1].scaled(Hq=4, Hkv=4, Dqk=64, Dv=64, page_size=8, ctx=("uniform", 50, 900)), {}),
+    # batches whose partial results exceed 64 MB: the kernel variants that write them with plain stores
+    # (two waves: through the LDS ring; four waves: directly)
+    "large_partials_two_waves": (W.CONFIGS[2].scaled(B=340, group_size=4, T=9, ctx=("uniform", 9, 120), shared_prefix=0), {}),
+    "large_partials_four_waves": (W.CONFIGS[2].scaled(B=72, group_size=4, T=32, ctx=("uniform", 32, 200), shared_prefix=0), {}),
     # the most verify slots a call takes (the mask word is full): every kernel, chain and tree
     "T64_chain_rows256": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=8, Hkv=2, T=64, ctx=("uniform", 64, 1200),
                                               shared_prefix=0), {}),
