@@ -3,12 +3,23 @@
 
 A step = one pass of the whole hot path over one batch of synthetic input that
 is already resident in HBM: seer_verify_attention (plan + partition kernel +
-combine) followed by seer_accept (vocabulary argmax + acceptance walk).
-Workload: the "8B-class grouped rollout" configuration (B=64 requests in 8
-prompt groups, Hq=32, Hkv=8, D=128, 16-token pages, lognormal contexts, k=8
-chain so T=9, V=152064).  Prints ONE JSON line.
+combine) followed by seer_accept (vocabulary argmax + acceptance walk), both
+through the product entry points.  Headline workload: the "8B-class grouped
+rollout" configuration (B=64 requests in 8 prompt groups, Hq=32, Hkv=8, D=128,
+16-token pages, lognormal contexts, k=8 chain so T=9, V=152064); the long-tail,
+shared-latent and multi-path configurations are measured the same way and
+reported under "per_config" of the same JSON line.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+Timing protocol.  The memory-side cache (256 MB) must not carry data from one
+step to the next: every timed step works on another of R = 3 copies of the KV
+pools, queries and logits at distinct addresses ("rotated"); the same loop on
+one set of buffers is reported beside it.  Per step, GPU time between events
+recorded on the stream: mean (the contract's ms_per_step comes from the wall
+clock around exactly K steps), median and minimum.  The partition kernel's
+duration comes from a second loop of K steps in which the library records two
+events around that kernel on the stream it launches on.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N | --configs 2,3,4,5] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -23,13 +34,17 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the partition kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled against
-# a 1 GiB copy (profiles/attn_gqa128_config2_hbm_traffic.md, attn_gqa128_config3_config5_hbm_traffic.md,
-# attn_mla_config4_kernel_trace_and_hbm_traffic.md); None where no counter run exists.
-MEASURED_TRAFFIC_BYTES = {2: 1.533e9, 3: 3.078e9, 4: 0.770e9, 5: 5.820e9}
+# HBM bytes per launch of the partition kernel as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, scaled
+# against a 1 GiB copy) in separate runs of this script; NOT measured by the run that prints them.
+PROFILED_TRAFFIC = {
+    2: (1.533e9, "profiles/attn_gqa128_config2_hbm_traffic.md"),
+    3: (3.078e9, "profiles/attn_gqa128_config3_config5_hbm_traffic.md"),
+    4: (0.770e9, "profiles/attn_mla_config4_kernel_trace_and_hbm_traffic.md"),
+    5: (5.820e9, "profiles/attn_gqa128_config3_config5_hbm_traffic.md"),
+}
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 METRIC = "verified tokens/s and verify-attention HBM GB/s (% of peak) on one MI355X"
 
 
@@ -199,7 +214,7 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
 def sweep_draft_acceptance(torch, binding, W) -> int:
     """Mean acceptance length (accepted draft tokens + the bonus token) of seer_draft's drafts against the tokens
     each request really produces next, by number of grouped references and by beam width: the measurement of the
-    paper's Table 1 on this build's synthetic group histories (groups of 16 like the table's n = 15; one live
+    paper's Table 2 on this build's synthetic group histories (groups of 16 like the table's n = 15; one live
     request per group; gamma_max = 8)."""
     cfg = W.CONFIGS[5].scaled(B=16 * 64, group_size=16)
     dev = "cuda"
@@ -231,142 +246,133 @@ def sweep_draft_acceptance(torch, binding, W) -> int:
     print(json.dumps({"what": "mean acceptance length incl. bonus token; rows = grouped references, columns = beam width "
                               "(k=1: linear); 64 groups of 16, one live request each, gamma_max 8, pattern 2..8",
                       "acceptance_length": table,
-                      "paper_table_1": {"n=0": [1.70, 1.77, 1.85], "n=1": [2.04, 2.14, 2.25], "n=5": [2.32, 2.44, 2.59],
+                      "paper_table_2": {"n=0": [1.70, 1.77, 1.85], "n=1": [2.04, 2.14, 2.25], "n=5": [2.32, 2.44, 2.59],
                                         "n=15": [2.53, 2.69, 2.85]}}))
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (2 = the headline configuration)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--attention-only", action="store_true", help="time only seer_verify_attention (profiling aid)")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="after the timed region, run three 1 GiB device-to-device tensor copies: a plain copy "
-                         "kernel of known size against which rocprofv3 FETCH_SIZE / WRITE_SIZE are scaled")
-    ap.add_argument("--ctx-scale", type=float, default=1.0,
-                    help="experiment aid: scale every context-length bound of the workload (not the headline run)")
-    ap.add_argument("--sweep-step-time", action="store_true",
-                    help="instead of the benchmark: measure the verify step (attention + accept) of the config-2 "
-                         "model shape over batch sizes and draft lengths, the T(B, gamma) table that the "
-                         "draft-length policy consumes, and print it with the policy's decisions as JSON")
-    ap.add_argument("--sweep-draft-acceptance", action="store_true",
-                    help="instead of the benchmark: mean acceptance length of seer_draft's drafts by number of grouped "
-                         "references and beam width (the measurement of the paper's Table 1, on synthetic histories)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange step; "
-              "no multi-GPU figure is produced). Re-run with --gpus 1.", file=sys.stderr)
-        return 2
+def _stats(ms) -> dict:
+    a = np.asarray(ms, dtype=np.float64)
+    return {"mean": float(a.mean()), "median": float(np.median(a)), "min": float(a.min()), "max": float(a.max())}
 
-    import torch
-    from paper_2511_14617_amd import binding, workloads as W
-    from gpu_util import accept_device_inputs, attention_device_inputs
 
-    binding.load_library()   # fails loudly if the HIP library is missing
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    if args.sweep_step_time:
-        return sweep_step_time(torch, binding, W, attention_device_inputs)
-    if args.sweep_draft_acceptance:
-        return sweep_draft_acceptance(torch, binding, W)
-    cfg = W.CONFIGS[args.config]
-    if args.ctx_scale != 1.0:
-        c = cfg.ctx
-        scaled = tuple(int(round(x * args.ctx_scale)) if (isinstance(x, (int, float)) and x > 1.5) else x for x in c[1:])
-        cfg = cfg.scaled(ctx=(c[0],) + scaled)
+def measure_config(torch, binding, W, cfg, args, steps: int, warmup: int, extras: bool) -> dict:
+    """One workload: the step (attention + accept) through the product entry points, rotated over R buffer
+    sets and on one set; the partition kernel's duration; the reproducible (fixed-split) mode beside the
+    default; the memory system's ceiling for the kernel's own load path."""
+    from paper_2511_14617_amd.device_inputs import accept_device_inputs, attention_device_inputs
     att = W.make_attention_inputs(cfg)
     acc = W.make_accept_inputs(cfg, tree_parent=att.tree_parent)
-    d = attention_device_inputs(att)
-    e = accept_device_inputs(acc)
-    dev = d["q"].device
-
-    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], att.scale, Dv=cfg.Dv)
+    dev = "cuda"
+    R = max(1, args.rotate)
+    # R sets of everything a step reads in bulk, at distinct addresses (block tables, lengths and masks are
+    # small and shared: the page ids are the same in every copy of the pools)
+    d0, e0 = attention_device_inputs(att), accept_device_inputs(acc)
+    sets = [(d0, e0)]
+    for _ in range(1, R):
+        d = dict(d0, q=d0["q"].clone(), k_pages=d0["k_pages"].clone(),
+                 v_pages=None if d0["v_pages"] is None else d0["v_pages"].clone())
+        sets.append((d, dict(e0, logits=e0["logits"].clone())))
+    p = binding.attn_params(d0["q"], d0["k_pages"], d0["v_pages"], d0["block_table"], att.scale, Dv=cfg.Dv)
     ws_att = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device=dev)
     ws_acc = torch.empty(max(16, binding.seer_accept_workspace(cfg.B, cfg.T, cfg.V)), dtype=torch.uint8, device=dev)
     out = torch.empty((cfg.B, cfg.T, cfg.Hq, cfg.Dv), dtype=torch.bfloat16, device=dev)
     acc_out = (torch.empty(cfg.B, dtype=torch.int32, device=dev), torch.empty((cfg.B, cfg.T), dtype=torch.int32, device=dev),
                torch.empty(cfg.B, dtype=torch.int32, device=dev), torch.empty((cfg.B, cfg.T), dtype=torch.int32, device=dev))
-    events = HipEvents(args.steps)
 
-    def step(ev=None):
+    def attention(slot, flags=0, ev=None):
+        d = sets[slot][0]
         binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
-                                      d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att, events=ev)
+                                      d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att, flags=flags,
+                                      events=ev)
+
+    def accept(slot):
+        e = sets[slot][1]
+        binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out)
+
+    def step(slot, flags=0, ev=None):
+        attention(slot, flags, ev)
         if not args.attention_only:
-            binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out)
+            accept(slot)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events.pairs[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # secondary figure: tokens a step emits = accepted draft tokens + the bonus token of every request
+    def timed_steps(n, rotate, flags=0):
+        """n steps through the product entry points: (wall-clock ms per step, per-step GPU ms)."""
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            marks[i].record()
+            step(i % R if rotate else 0, flags)
+        marks[n].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / n
+        return wall, [marks[i].elapsed_time(marks[i + 1]) for i in range(n)]
+
+    def kernel_times(n, rotate, flags=0):
+        """Partition-kernel durations of n steps (events recorded by the library around that kernel)."""
+        ev = HipEvents(n)
+        for i in range(n):
+            step(i % R if rotate else 0, flags, ev.pairs[i])
+        torch.cuda.synchronize()
+        ms = ev.elapsed_ms()
+        ev.close()
+        return ms
+
+    for i in range(warmup):
+        step(i % R)
+    # ---- the timed region: exactly `steps` steps, rotated buffers, product entry points
+    ms_per_step, step_gpu = timed_steps(steps, rotate=True)
     emitted = None if args.attention_only else int(acc_out[0].sum().item()) + cfg.B
-    kern_ms = events.elapsed_ms()
-    kern_avg_ms = float(np.mean(kern_ms))
-    events.close()
+    kern = kernel_times(steps, rotate=True)
+    # ---- the same on one set of buffers (what the memory-side cache carries from step to step shows here)
+    n_side = max(5, steps // 2)
+    same_wall, same_gpu = timed_steps(n_side, rotate=False)
+    same_kern = kernel_times(n_side, rotate=False)
+    # ---- the reproducible mode: equal stretches, output bits independent of earlier calls
+    fixed_wall, fixed_gpu = timed_steps(n_side, rotate=True, flags=binding.SEER_ATTN_FIXED_SPLIT)
+    fixed_kern = kernel_times(n_side, rotate=True, flags=binding.SEER_ATTN_FIXED_SPLIT)
+    for i in range(4):          # let the default mode's stretch lengths settle again
+        step(i % R)
 
-    # split of a step between the two calls (separate, untimed-for-`value` loop)
+    # ---- split of a step between the calls (GPU time; a queue of matrix products first, so that the host
+    # has enqueued the calls before the GPU reaches them)
     busy = torch.randn((4096, 4096), device=dev, dtype=torch.bfloat16)
     busy_out = torch.empty_like(busy)
 
-    def timed(fn, n=10, queue_first=False):
-        # matrix products first (queue_first of them): while the GPU works on them the host enqueues the calls,
-        # so that a short call is timed by the GPU's clock and not by the time Python needs to issue it
+    def timed(fn, n=10, queue_first=4):
         for _ in range(int(queue_first)):
             torch.mm(busy, busy, out=busy_out)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(n):
-            fn()
-        b.record()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        for i in range(n):
+            marks[i].record()
+            fn(i)
+        marks[n].record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b) / n
+        return float(np.median([marks[i].elapsed_time(marks[i + 1]) for i in range(n)]))
 
-    att_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
-                                                         d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
-                                                         workspace=ws_att))
-    # the call as the second and later layers of a step issue it: the plan of the first layer is reused
-    att_reuse_ms = timed(lambda: binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"],
-                                                               d["ctx_len"], d["tree_mask"], att.scale, Dv=cfg.Dv, out=out,
-                                                               workspace=ws_att, flags=binding.SEER_ATTN_REUSE_PLAN))
-    acc_ms = 0.0 if args.attention_only else timed(
-        lambda: binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out))
+    att_ms = timed(lambda i: attention(i % R))
+    att_reuse_ms = timed(lambda i: attention(0, binding.SEER_ATTN_REUSE_PLAN))   # layers 2.. of a step: same KV
+    acc_ms = 0.0 if args.attention_only else timed(lambda i: accept(i % R))
     # gather-read ceiling: the same call with the arithmetic left out of the tiled kernel (D = 128 shapes)
-    ceiling_ms = None
-    if not cfg.shared_latent and cfg.Dqk == 128 and cfg.page_size in (16, 32, 64, 128, 256, 512, 1024):
-        ev2 = HipEvents(10)
-        for i in range(10):
-            binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
-                                          d["tree_mask"], att.scale, Dv=cfg.Dv, out=out, workspace=ws_att,
-                                          flags=binding.SEER_ATTN_STREAM_ONLY, events=ev2.pairs[i])
-        torch.cuda.synchronize()
-        ceiling_ms = float(np.mean(ev2.elapsed_ms()[2:]))
-        ev2.close()
-    # the calls around the step (not part of `value`): acceptance under sampling, and the commit of the
-    # accepted path (on a copy of the lengths, so that every repetition moves the same rows)
-    sampled_ms = commit_ms = None
-    if not args.attention_only:
-        sampled_ms = timed(lambda: binding.seer_accept_sampled(e["logits"], e["draft_tokens"], e["tree_parent"], 0.8,
-                                                               20251114, workspace=ws_acc, out=acc_out))
-        binding.seer_accept(e["logits"], e["draft_tokens"], e["tree_parent"], workspace=ws_acc, out=acc_out)
+    kernel_name = binding.seer_verify_attention_kernel(p)
+    ceiling = None
+    if kernel_name.startswith("attn_gqa128"):
+        ceiling = _stats(kernel_times(10, rotate=True, flags=binding.SEER_ATTN_STREAM_ONLY)[2:])
+
+    result_extras = {}
+    if extras and not args.attention_only:
+        e = sets[0][1]
+        d = sets[0][0]
+        sampled_ms = timed(lambda i: binding.seer_accept_sampled(e["logits"], e["draft_tokens"], e["tree_parent"], 0.8,
+                                                                 20251114, workspace=ws_acc, out=acc_out))
+        accept(0)
         n_copy = d["ctx_len"].clone()
 
-        def commit():
+        def commit(i):
             n_copy.copy_(d["ctx_len"])
             binding.seer_kv_commit(d["k_pages"], d["v_pages"], d["block_table"], n_copy, acc_out[0], acc_out[1])
         commit_ms = timed(commit, queue_first=40)    # two short kernels: timed by the GPU's clock, not by Python's
-    # the step before verification (not part of `value` either): drafts from the groups' token histories
-    draft_info = None
-    if not args.attention_only:
+        # the step before verification: drafts from the groups' token histories
         top_k, gamma = cfg.tree if cfg.tree else (1, cfg.T - 1)
         dr = W.make_draft_inputs(cfg, gamma_max=gamma, top_k=top_k)
         t32 = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
@@ -379,19 +385,20 @@ def main() -> int:
                   torch.empty((cfg.B, dr.T), dtype=torch.int64, device=dev), torch.empty((cfg.B, dr.T), dtype=torch.int32, device=dev),
                   torch.empty(cfg.B, dtype=torch.int32, device=dev))
 
-        def draft():
+        def draft(i=0):
             binding.seer_draft(*dd, gamma_max=gamma, top_k=top_k, pattern_lookup_min=dr.p_min, vocab=cfg.V,
                                max_group_tokens=dr.max_group_tokens, workspace=ws_dr, out=dr_out)
         draft()
-        draft_ms = timed(draft, n=20, queue_first=True)
-        # algorithmic bytes of the match scan: the tokens of every group that has a live request, read once
+        draft_ms = timed(draft, n=20)
         live_groups = sorted(set(int(g) for g in dr.req_group))
         scanned = int(sum(int(dr.seq_len[dr.group_first[g]:dr.group_first[g + 1]].sum()) for g in live_groups))
-        draft_info = {"draft_ms": draft_ms, "top_k": top_k, "gamma_max": gamma, "pattern_lookup": [dr.p_min, dr.p_max],
-                      "history_tokens": scanned, "history_bytes": scanned * 4,
-                      "mean_match_len": float(dr_out[4].float().mean().item()),
-                      "max_match_places": int(dr_out[3][:, 0].max().item()),
-                      "mean_draft_nodes": float((dr_out[1][:, 1:] >= 0).sum(1).float().mean().item())}
+        result_extras = {"accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms,
+                         "draft": {"draft_ms": draft_ms, "top_k": top_k, "gamma_max": gamma,
+                                   "pattern_lookup": [dr.p_min, dr.p_max], "history_tokens": scanned,
+                                   "history_bytes": scanned * 4,
+                                   "mean_match_len": float(dr_out[4].float().mean().item()),
+                                   "max_match_places": int(dr_out[3][:, 0].max().item()),
+                                   "mean_draft_nodes": float((dr_out[1][:, 1:] >= 0).sum(1).float().mean().item())}}
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -402,41 +409,43 @@ def main() -> int:
     status = binding.seer_verify_attention_status(ws_att)
 
     ab = algorithmic_bytes(att)
-    achieved = ab["total"] / (kern_avg_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.config_id) if args.ctx_scale == 1.0 else None
-    tokens = cfg.B * cfg.T
-    kernel_name = ("attn_gqa128_kernel" if (cfg.Dqk == 128 and cfg.page_size in (16, 32, 64, 128, 256, 512, 1024) and not cfg.shared_latent) else
-                   "attn_mla_kernel" if (cfg.shared_latent and cfg.Dqk == 576 and cfg.page_size == 64) else
-                   "attn_general_kernel") + " (verify-attention partition kernel)"
+    k_rot, k_same, k_fixed = _stats(kern), _stats(same_kern), _stats(fixed_kern)
+    traffic = PROFILED_TRAFFIC.get(cfg.config_id) if args.ctx_scale == 1.0 else None
+    common = {"kernel": kernel_name + " (verify-attention partition kernel)",
+              "traffic": traffic[0] if traffic else None,
+              "traffic_source": (traffic[1] + " (rocprofv3 --pmc runs of this script; not measured by this run)") if traffic else None,
+              "algorithmic_bytes": ab,
+              "kernel_ms_avg": k_rot["mean"], "kernel_ms_median": k_rot["median"], "kernel_ms_min": k_rot["min"],
+              "buffers": "rotated over %d sets of KV pools, queries and logits" % R}
     if cfg.shared_latent:
         # the shared-latent shape is bound by the matrix cores: every KV token meets all Hq*T query rows
         flops = 2.0 * float(att.ctx_len.sum()) * cfg.T * cfg.Hq * (cfg.Dqk + cfg.Dv)
-        tflops = flops / (kern_avg_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": kernel_name, "achieved": tflops, "peak": 2500.0, "unit": "TFLOP/s",
-                    "frac": tflops / 2500.0, "traffic": traffic, "algorithmic_flops": flops,
-                    "algorithmic_bytes": ab, "kernel_ms_avg": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms))}
+        rate = lambda ms: flops / (ms * 1e-3) / 1e12
+        roofline = dict({"bound": "mfma", "achieved": rate(k_rot["mean"]), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": rate(k_rot["mean"]) / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops}, **common)
+        peak = MFMA_BF16_PEAK_TFLOPS
     else:
-        roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "algorithmic_bytes": ab,
-                    "kernel_ms_avg": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms))}
-        if ceiling_ms:
-            # what the memory system allows for this access pattern and launch shape (arithmetic left out)
-            ceil_gbps = ab["total"] / (ceiling_ms * 1e-3) / 1e9
-            roofline["gather_read_ceiling"] = {"GBps": ceil_gbps, "kernel_ms": ceiling_ms,
-                                               "achieved_over_ceiling": achieved / ceil_gbps}
-    line = {
-        "metric": METRIC,
-        "value": tokens / (ms_per_step * 1e-3),
-        "unit": "tokens/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16",
-        "data": "synthetic",
+        rate = lambda ms: ab["total"] / (ms * 1e-3) / 1e9
+        roofline = dict({"bound": "hbm", "achieved": rate(k_rot["mean"]), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": rate(k_rot["mean"]) / HBM_PEAK_GBPS}, **common)
+        peak = HBM_PEAK_GBPS
+        if ceiling:
+            roofline["gather_read_ceiling"] = {"GBps": rate(ceiling["median"]), "kernel_ms": ceiling["median"],
+                                               "achieved_over_ceiling": ceiling["median"] / k_rot["median"]}
+    roofline["frac_median"] = rate(k_rot["median"]) / peak
+    roofline["same_buffers"] = {"kernel_ms_avg": k_same["mean"], "kernel_ms_median": k_same["median"],
+                                "kernel_ms_min": k_same["min"], "frac": rate(k_same["mean"]) / peak}
+    roofline["fixed_split"] = {"kernel_ms_avg": k_fixed["mean"], "kernel_ms_median": k_fixed["median"],
+                               "kernel_ms_min": k_fixed["min"], "frac": rate(k_fixed["mean"]) / peak,
+                               "ms_per_step": fixed_wall, "step_gpu_ms_median": float(np.median(fixed_gpu))}
+    tokens = cfg.B * cfg.T
+    g = _stats(step_gpu)
+    leg = {
+        "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "step_gpu_ms_median": g["median"], "step_gpu_ms_min": g["min"],
+        "step_gpu_ms_mean": g["mean"],
+        "same_buffers": {"ms_per_step": same_wall, "step_gpu_ms_median": float(np.median(same_gpu)),
+                         "step_gpu_ms_min": float(np.min(same_gpu)), "steps": n_side},
         "config": {"workload": "config%d %s: B=%d (%d groups x %d), Hq=%d, Hkv=%d, Dqk=%d, Dv=%d, page=%d, T=%d, "
                                "V=%d, ctx %s, step = seer_verify_attention + seer_accept" % (
                                    cfg.config_id, cfg.name, cfg.B, cfg.B // cfg.group_size, cfg.group_size, cfg.Hq,
@@ -450,10 +459,94 @@ def main() -> int:
         "emitted_tokens_per_s": None if emitted is None else emitted / (ms_per_step * 1e-3),
         "mean_emitted_per_request": None if emitted is None else emitted / cfg.B,
         "attention_status_word": status,
-        "accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms, "draft": draft_info,
     }
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(att, acc)
+    leg.update(result_extras)
+    if not args.no_cpu_baseline and extras:
+        leg["cpu_baseline"] = cpu_baseline(att, acc)
+    del sets, d0, e0, out, ws_att, ws_acc, busy, busy_out
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    return leg
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--config", type=int, default=None, help="measure this workload (1..5) alone")
+    ap.add_argument("--configs", type=str, default="2,3,4,5",
+                    help="workloads to measure; the first is the headline of the JSON line, the others go under "
+                         "per_config (default: 2 = the headline configuration, then 3, 4, 5)")
+    ap.add_argument("--rotate", type=int, default=3, help="sets of KV pools / queries / logits the timed steps cycle through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attention-only", action="store_true", help="time only seer_verify_attention (profiling aid)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run three 1 GiB device-to-device tensor copies: a plain copy "
+                         "kernel of known size against which rocprofv3 FETCH_SIZE / WRITE_SIZE are scaled")
+    ap.add_argument("--ctx-scale", type=float, default=1.0,
+                    help="experiment aid: scale every context-length bound of the workload (not the headline run)")
+    ap.add_argument("--sweep-step-time", action="store_true",
+                    help="instead of the benchmark: measure the verify step (attention + accept) of the config-2 "
+                         "model shape over batch sizes and draft lengths, the T(B, gamma) table that the "
+                         "draft-length policy consumes, and print it with the policy's decisions as JSON")
+    ap.add_argument("--sweep-draft-acceptance", action="store_true",
+                    help="instead of the benchmark: mean acceptance length of seer_draft's drafts by number of grouped "
+                         "references and beam width (the measurement of the paper's Table 2, on synthetic histories)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange step; "
+              "no multi-GPU figure is produced). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2511_14617_amd import binding, workloads as W
+    from paper_2511_14617_amd.device_inputs import attention_device_inputs
+
+    binding.load_library()   # fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    if args.sweep_step_time:
+        return sweep_step_time(torch, binding, W, attention_device_inputs)
+    if args.sweep_draft_acceptance:
+        return sweep_draft_acceptance(torch, binding, W)
+    ids = [args.config] if args.config is not None else [int(x) for x in args.configs.split(",") if x.strip()]
+
+    def config_of(i):
+        cfg = W.CONFIGS[i]
+        if args.ctx_scale != 1.0:
+            c = cfg.ctx
+            scaled = tuple(int(round(x * args.ctx_scale)) if (isinstance(x, (int, float)) and x > 1.5) else x for x in c[1:])
+            cfg = cfg.scaled(ctx=(c[0],) + scaled)
+        return cfg
+
+    head = measure_config(torch, binding, W, config_of(ids[0]), args, args.steps, args.warmup, extras=True)
+    line = {
+        "metric": METRIC,
+        "value": head["value"],
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+    }
+    for k, v in head.items():
+        if k not in line:
+            line[k] = v
+    # the other named workloads, each measured the same way (fewer steps: the headline is the timed job)
+    per_config = {}
+    for i in ids[1:]:
+        per_config["config%d" % i] = measure_config(torch, binding, W, config_of(i), args, max(10, args.steps // 2),
+                                                    args.warmup, extras=False)
+    if per_config:
+        line["per_config"] = per_config
     print(json.dumps(line))
     return 0
 

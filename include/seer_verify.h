@@ -45,6 +45,9 @@
 extern "C" {
 #endif
 
+/* The library is built with hidden visibility; these are its only exported symbols. */
+#define SEER_API __attribute__((visibility("default")))
+
 #define SEER_OK 0
 #define SEER_EINVAL (-1)       /* null pointer, negative or zero size               */
 #define SEER_ESHAPE (-2)       /* T not in 1..64, Hq not a multiple of Hkv, ...     */
@@ -79,11 +82,7 @@ typedef struct seer_attn_params {
  * The result is the same up to the rounding order of the partial sums; with this flag the cut, and
  * therefore the result, does not depend on earlier calls. */
 #define SEER_ATTN_FIXED_SPLIT 2
-/* flags: measurement aid.  The tiled D = 128 kernel runs its whole load path (plan, page lookups,
- * loads into LDS, waits, partial-result writes) without the arithmetic; out is written as zeros.
- * The time of such a call is the gather-read ceiling of the memory system for this workload and
- * launch shape.  Ignored by the other kernels. */
-#define SEER_ATTN_STREAM_ONLY 4
+/* (bit 4 is a measurement aid, see seer_verify_diag.h) */
 /* flags: use the plan that the previous call on this workspace computed instead of planning again.  How the
  * KV stream is cut depends on the shape parameters and on ctx_len only, and a model calls this function
  * once per layer with the same ctx_len: the first layer plans, the others pass this flag (saves a ~10 us
@@ -94,17 +93,19 @@ typedef struct seer_attn_params {
 
 /* Supported shapes: (Dqk, Dv) in {(64,64), (128,128), (256,256), (192,128),
  * (576,512)} with any page_size >= 1.  Tiled matrix-core kernels exist for
- * Dqk = Dv = 128 with page_size 16 and G*T <= 256; every other combination
- * runs a slower general kernel. */
+ * Dqk = Dv = 128 with separate K and V pools and a power-of-two page_size of
+ * 16..1024 (any G*T: more than 256 query rows per KV head are cut into row
+ * blocks), and for the shared latent Dqk = 576, Dv = 512 with a power-of-two
+ * page_size of 32..1024; every other combination runs a slower general kernel. */
 
 /* Bytes of device scratch seer_verify_attention needs for these params; 0 on
  * invalid params.  Host-only arithmetic. */
-size_t seer_verify_attention_workspace(const seer_attn_params* p);
+SEER_API size_t seer_verify_attention_workspace(const seer_attn_params* p);
 
 /* Byte offset, inside the workspace, of a uint32 status word that the call
  * zeroes and its kernels OR into: bit 0 = some request had ctx_len < T or
  * beyond the block table; bit 1 = some page id was outside the pool. */
-size_t seer_verify_attention_status_offset(void);
+SEER_API size_t seer_verify_attention_status_offset(void);
 
 /*
  * Multi-token paged-KV attention for the verify pass.
@@ -128,27 +129,18 @@ size_t seer_verify_attention_status_offset(void);
  *  p           host
  *  workspace   device, >= seer_verify_attention_workspace(p) bytes, 256-byte aligned
  */
-int seer_verify_attention(void* out, const void* q, const void* k_pages, const void* v_pages,
+SEER_API int seer_verify_attention(void* out, const void* q, const void* k_pages, const void* v_pages,
                           const int32_t* block_table, const int32_t* ctx_len,
                           const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
 
-/*
- * Measurement aid: the same call, which also records two caller-created
- * hipEvent_t (passed as void*) on the stream immediately before and after the
- * partition kernel -- the kernel that streams the KV pages and dominates the
- * call -- so that its duration can be read with hipEventElapsedTime without a
- * profiler.  The plan kernel runs before event_begin, the combine after
- * event_end.  Results are identical to seer_verify_attention.
- */
-int seer_verify_attention_timed(void* out, const void* q, const void* k_pages, const void* v_pages,
-                                const int32_t* block_table, const int32_t* ctx_len,
-                                const uint64_t* tree_mask, const seer_attn_params* p, void* workspace,
-                                size_t workspace_bytes, void* hip_stream, void* event_begin,
-                                void* event_end);
+/* Name of the partition kernel (the kernel that streams the KV pages) a call with these params launches,
+ * e.g. "attn_gqa128_kernel<2,1>" (waves per workgroup, tiles in flight); NULL on invalid params.
+ * Static text, host-only. */
+SEER_API const char* seer_verify_attention_kernel(const seer_attn_params* p);
 
 /* Bytes of device scratch seer_accept needs; 0 on invalid sizes.  Host-only. */
-size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V);
+SEER_API size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V);
 
 /*
  * Acceptance from target logits.
@@ -171,7 +163,7 @@ size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V);
  *  target_argmax device [B,T] int32, written
  *  workspace     device, >= seer_accept_workspace(B,T,V) bytes, 16-byte aligned
  */
-int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+SEER_API int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
                 int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
                 int32_t* bonus_token, int32_t* target_argmax, void* workspace,
                 size_t workspace_bytes, void* hip_stream);
@@ -192,7 +184,7 @@ int seer_accept(const float* logits, const int32_t* draft_tokens, const int32_t*
  *  target_token device [B,T] int32, written: the drawn token of each slot
  * Everything else, the workspace size included, as for seer_accept.
  */
-int seer_accept_sampled(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+SEER_API int seer_accept_sampled(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
                         int32_t B, int32_t T, int32_t V, float temperature, uint64_t seed,
                         int32_t* accepted_len, int32_t* accepted_path, int32_t* bonus_token,
                         int32_t* target_token, void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -226,7 +218,7 @@ int seer_accept_sampled(const float* logits, const int32_t* draft_tokens, const 
  * Returns SEER_OK or a negative SEER_E* / positive hipError_t; asynchronous on
  * hip_stream.  Requests must not share the pages that hold their T verify slots.
  */
-int seer_kv_commit(const seer_attn_params* p, void* k_pages, void* v_pages, const int32_t* block_table,
+SEER_API int seer_kv_commit(const seer_attn_params* p, void* k_pages, void* v_pages, const int32_t* block_table,
                    int32_t* ctx_len, const int32_t* accepted_len, const int32_t* accepted_path,
                    const int32_t* draft_tokens, const int32_t* bonus_token, int32_t* emitted_tokens,
                    int32_t* n_emitted, int32_t* status, void* hip_stream);
@@ -247,7 +239,7 @@ int seer_kv_commit(const seer_attn_params* p, void* k_pages, void* v_pages, cons
  *              (1 - alpha^(gamma + 1)), alpha = mean of beta[0 .. gamma_max - 1]; ties -> smaller gamma
  * Returns SEER_OK or SEER_EINVAL / SEER_ESHAPE.
  */
-int seer_mba_draft_lengths(int32_t B_h, int32_t B_l, const double* beta, int32_t n_beta, int32_t gamma_max,
+SEER_API int seer_mba_draft_lengths(int32_t B_h, int32_t B_l, const double* beta, int32_t n_beta, int32_t gamma_max,
                            double lambda, const double* step_time, int32_t* gamma_h, int32_t* gamma_l,
                            int32_t* gamma_star);
 
@@ -300,7 +292,7 @@ typedef struct seer_draft_params {
 
 /* Bytes of device scratch seer_draft needs (two place lists of max_group_tokens entries per
  * request); 0 on invalid params.  Host-only. */
-size_t seer_draft_workspace(const seer_draft_params* p);
+SEER_API size_t seer_draft_workspace(const seer_draft_params* p);
 
 /*
  *  tokens, seq_start, seq_len, group_first   device int32, as above
@@ -314,7 +306,7 @@ size_t seer_draft_workspace(const seer_draft_params* p);
  *  workspace        device, >= seer_draft_workspace(p) bytes, 16-byte aligned
  * Asynchronous on hip_stream; returns SEER_OK, a negative SEER_E* or a positive hipError_t.
  */
-int seer_draft(const int32_t* tokens, const int32_t* seq_start, const int32_t* seq_len,
+SEER_API int seer_draft(const int32_t* tokens, const int32_t* seq_start, const int32_t* seq_len,
                const int32_t* group_first, const int32_t* req_group, const int32_t* pattern,
                const int32_t* pattern_len, const int32_t* max_spec_tokens, const seer_draft_params* p,
                int32_t* draft_tokens, int32_t* tree_parent, uint64_t* tree_mask, int32_t* node_count,
@@ -345,7 +337,7 @@ int seer_draft(const int32_t* tokens, const int32_t* seq_start, const int32_t* s
  *                 (nothing appended, pattern still refreshed).  The caller clears it.
  * Asynchronous on hip_stream; returns SEER_OK, a negative SEER_E* or a positive hipError_t.
  */
-int seer_history_append(int32_t* tokens, const int32_t* seq_start, int32_t* seq_len,
+SEER_API int seer_history_append(int32_t* tokens, const int32_t* seq_start, int32_t* seq_len,
                         const int32_t* seq_capacity, const int32_t* req_seq,
                         const int32_t* emitted_tokens, const int32_t* n_emitted, int32_t B, int32_t T,
                         int32_t n_seq, int64_t pool_tokens, int32_t pattern_lookup_max, int32_t* pattern,
@@ -353,7 +345,7 @@ int seer_history_append(int32_t* tokens, const int32_t* seq_start, int32_t* seq_
 
 /* Static text for a return code of either call (negative SEER_E*, or a
  * positive hipError_t). */
-const char* seer_strerror(int code);
+SEER_API const char* seer_strerror(int code);
 
 #ifdef __cplusplus
 }

@@ -36,7 +36,7 @@ no listing, so the definition below is this build's reading, written out as plai
                mask[t] = own bit | mask[parent].
 
 With top_k = 1 this is a single chain that follows the most frequent continuation, the
-single-path form the paper takes from SuffixDecoding; its Table 1 ("Linear" against
+single-path form the paper takes from SuffixDecoding; its Table 2 ("Linear" against
 "Multi-Path") is this call with top_k = 1, 2, 4.
 """
 from __future__ import annotations

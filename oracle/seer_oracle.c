@@ -21,8 +21,8 @@
  *
  *  - A step emits the accepted draft prefix plus one bonus token: with gamma
  *    drafts at most gamma + 1 tokens (Section 3.4.1, expected tokens per
- *    forward (1 - alpha^(gamma+1)) / (1 - alpha); Table "Mean acceptance
- *    length ... (including bonus token)").  With several candidate paths the
+ *    forward (1 - alpha^(gamma+1)) / (1 - alpha); Table 2 counts the bonus
+ *    token in its acceptance lengths).  With several candidate paths the
  *    longest accepted one is taken (Section 3.4.2: multi-path drafting is used
  *    to lengthen acceptance).
  *

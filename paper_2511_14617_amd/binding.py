@@ -1,4 +1,4 @@
-"""Thin Python binding of libseer_verify.so (include/seer_verify.h).
+"""Thin Python binding of libseer_verify.so (include/seer_verify.h, include/seer_verify_diag.h).
 
 Argument marshalling only: tensors are torch CUDA(HIP) tensors whose device
 pointers are handed to the C ABI; every step of the path runs in the library's
@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libseer_verify.so")
 SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALIGN = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
-           "seer_verify_attention_timed", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
+           "seer_verify_attention_timed", "seer_verify_attention_kernel", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
            "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_history_append",
            "seer_strerror")
 
@@ -70,6 +70,8 @@ def load_library() -> ctypes.CDLL:
         lib.seer_verify_attention.restype = ctypes.c_int
         lib.seer_verify_attention_timed.argtypes = lib.seer_verify_attention.argtypes + [vp, vp]
         lib.seer_verify_attention_timed.restype = ctypes.c_int
+        lib.seer_verify_attention_kernel.argtypes = [ctypes.POINTER(SeerAttnParams)]
+        lib.seer_verify_attention_kernel.restype = ctypes.c_char_p
         lib.seer_accept_workspace.argtypes = [i32, i32, i32]
         lib.seer_accept_workspace.restype = sz
         lib.seer_accept.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -131,6 +133,12 @@ def attn_params(q: torch.Tensor, k_pages: torch.Tensor, v_pages: Optional[torch.
 
 def seer_verify_attention_workspace(params: SeerAttnParams) -> int:
     return int(load_library().seer_verify_attention_workspace(ctypes.byref(params)))
+
+
+def seer_verify_attention_kernel(params: SeerAttnParams) -> Optional[str]:
+    """Name of the partition kernel a call with these params launches (None on invalid params)."""
+    name = load_library().seer_verify_attention_kernel(ctypes.byref(params))
+    return None if name is None else name.decode()
 
 
 def seer_verify_attention(q: torch.Tensor, k_pages: torch.Tensor, v_pages: Optional[torch.Tensor],

@@ -11,6 +11,8 @@ LIB = os.path.join(PKG, "libseer_verify.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
+    # only the C entry points declared in include/seer_verify.h are exported
+    "-fvisibility=hidden",
     # packed fp32 VALU forms are kept off on purpose on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
@@ -24,7 +26,8 @@ def sources():
 def build_library(verbose: bool = False, extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-o", tmp] + sources()
+    cmd = ([hipcc] + HIPCC_FLAGS + ["-Wl,--version-script=" + os.path.join(CSRC, "exports.map")] + list(extra_flags)
+           + ["-o", tmp] + sources())
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

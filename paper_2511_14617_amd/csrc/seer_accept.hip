@@ -2,8 +2,8 @@
 // accepted root path over the draft tree.
 //
 // The paper fixes what a verification step emits -- the accepted draft prefix
-// plus one bonus token (Section 3.4.1; Table "Mean acceptance length ...
-// including bonus token") -- and that with several candidate paths the longest
+// plus one bonus token (Section 3.4.1; Table 2, whose acceptance lengths count
+// the bonus token) -- and that with several candidate paths the longest
 // accepted one counts (Section 3.4.2).  The scan below is the HBM-bound part:
 // one pass over B*T*V fp32 logits.
 //

@@ -9,6 +9,9 @@
 // Section 3.4.2).  One read of a KV page must therefore serve all T slots and
 // all G query heads that share the KV head.
 #include "seer_attention.h"
+#include "../../include/seer_verify_diag.h"
+
+#include <stdio.h>
 
 #include "seer_device.h"
 
@@ -527,6 +530,32 @@ extern "C" size_t seer_verify_attention_workspace(const seer_attn_params* p) {
 }
 
 extern "C" size_t seer_verify_attention_status_offset(void) { return offsetof(seer::PlanHeader, status); }
+
+extern "C" const char* seer_verify_attention_kernel(const seer_attn_params* p) {
+    if (validate_params(p) != SEER_OK) return nullptr;
+    // the same tests, on the same fields, as the dispatch in run_verify_attention
+    seer::AttnArgs a{};
+    a.Dqk = p->Dqk, a.Dv = p->Dv, a.P = p->page_size, a.Hkv = p->Hkv;
+    a.v_pages = p->kv_shared_latent ? nullptr : static_cast<const void*>(p);   // only null / non-null is looked at
+    const bool tiled_ok = !(p->flags & SEER_ATTN_GENERAL_KERNEL);
+    if (tiled_ok && seer::gqa128_supports(a)) {
+        struct Names {
+            char text[9][40];
+            Names() {
+                for (int nw = 1; nw <= 8; ++nw)
+                    snprintf(text[nw], sizeof(text[nw]), "attn_gqa128_kernel<%d,%d>", nw, seer::gqa_pipe_depth(nw));
+            }
+        };
+        static const Names names;
+        return names.text[seer::gqa_rows_per_block((p->Hq / p->Hkv) * p->T) / 32];
+    }
+    if (tiled_ok && seer::mla_supports(a)) return "attn_mla_kernel";
+    if (p->Dqk == 64) return "attn_general_kernel<64,64>";
+    if (p->Dqk == 128) return "attn_general_kernel<128,128>";
+    if (p->Dqk == 256) return "attn_general_kernel<256,256>";
+    if (p->Dqk == 192) return "attn_general_kernel<192,128>";
+    return "attn_general_kernel<576,512>";
+}
 
 namespace {
 

@@ -56,8 +56,10 @@ __global__ __launch_bounds__(kCommitThreads) void kv_commit_kernel(CommitArgs a)
     if (len < 0 || len > T - 1) bad |= 4;
     if (!bad && tid <= len) {
         const int node = s_path[tid];
-        if (tid == 0 ? node != 0 : (node <= s_path[tid - 1] || node >= T)) atomicOr(&s_bad, 4);
-        if (tid >= 1) {
+        // a node is used as an index only once it is known to lie on an ascending path inside the T slots
+        const bool node_ok = tid == 0 ? node == 0 : (node > s_path[tid - 1] && node > 0 && node < T);
+        if (!node_ok) atomicOr(&s_bad, 4);
+        if (tid >= 1 && node_ok) {
             const int32_t* table = a.block_table + static_cast<size_t>(b) * a.max_pages;
             const int p_src = table[(n0 + node) / a.P], p_dst = table[(n0 + tid) / a.P];
             if (p_src < 0 || p_src >= a.num_pages || p_dst < 0 || p_dst >= a.num_pages) atomicOr(&s_bad, 2);

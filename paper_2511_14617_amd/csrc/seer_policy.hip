@@ -3,7 +3,8 @@
 //   expected time per generated token  T_SD(B, gamma) = (1 - alpha) (D + T)(B, gamma) / (1 - alpha^(gamma+1)),
 //   gamma* = argmin_gamma T_SD, total budget gamma* (B_h + B_l) draft tokens, handed out one token per
 //   request of a class at a time to the class with the larger marginal benefit (high priority weighted
-//   by lambda), each class capped at gamma_max.
+//   by lambda), each class capped at gamma_max.  The hand-out is written here as a merge of two
+//   precomputed lists of weighted marginal gains; its result is the algorithm's.
 // Host arithmetic only; the (D + T)(B, gamma) row comes from measured verify-step times.
 #include <stdint.h>
 
@@ -43,23 +44,35 @@ extern "C" int seer_mba_draft_lengths(int32_t B_h, int32_t B_l, const double* be
         *gamma_l = 0;
         return SEER_OK;
     }
-    auto b = [&](int k) { return k == 0 ? 1.0 : beta[k - 1]; };   // beta[0] = 1: the token already accepted
-    int gh = 1, gl = 0;
-    int64_t remaining = budget - B_h;
-    while (remaining > 0) {
-        const double benefit_h = B_h * (b(gh) - b(gh + 1));
-        const double benefit_l = B_l * (b(gl) - b(gl + 1));
-        if (benefit_h > lambda * benefit_l && gh < gamma_max && remaining >= B_h) {
-            ++gh;
-            remaining -= B_h;
-        } else if (B_l > 0 && gl < gamma_max && remaining >= B_l) {
-            ++gl;
-            remaining -= B_l;
-        } else {
-            break;
-        }
+    // The allocation is a merge of two descending-by-construction price lists.  Raising a class from level g to
+    // g + 1 costs one token per request of the class and buys size * (beta[g] - beta[g + 1]) expected tokens
+    // (beta[0] = 1: the token already accepted); the low class's prices carry the factor lambda, so that the
+    // high class wins a round only if its gain exceeds lambda times the other's.  Both lists are written out
+    // once, then rounds are dealt until neither class can take one.
+    struct Klass {
+        int64_t size;                      // requests: the cost of one more level
+        int level;                         // draft tokens per request so far
+        double price[SEER_MAX_T + 1];      // price[g]: weighted gain of level g -> g + 1
+        bool can_take(int64_t left, int cap) const { return size > 0 && level < cap && left >= size; }
+    };
+    Klass high{B_h, 1, {}}, low{B_l, 0, {}};                  // the budget check above paid the high class's first level
+    for (int g = 0; g <= gamma_max; ++g) {
+        const double drop = (g == 0 ? 1.0 : beta[g - 1]) - beta[g];
+        high.price[g] = static_cast<double>(B_h) * drop;
+        low.price[g] = lambda * (static_cast<double>(B_l) * drop);
     }
-    *gamma_h = gh;
-    *gamma_l = gl;
+    int64_t left = budget - B_h;
+    while (left > 0) {
+        // the high class takes the round if it bids more AND can pay; otherwise the round falls to the low
+        // class if that one can pay; otherwise the hand-out ends
+        Klass* taker = nullptr;
+        if (high.price[high.level] > low.price[low.level] && high.can_take(left, gamma_max)) taker = &high;
+        else if (low.can_take(left, gamma_max)) taker = &low;
+        if (!taker) break;
+        taker->level += 1;
+        left -= taker->size;
+    }
+    *gamma_h = high.level;
+    *gamma_l = low.level;
     return SEER_OK;
 }

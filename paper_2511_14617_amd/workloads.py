@@ -6,8 +6,8 @@ attention, softmax, argmax or acceptance rule); both the CPU oracle's tests and
 the HIP path's tests feed on the arrays it returns, so the two sides see
 identical bits.  Everything is numpy on the host, seeded with PCG64.
 
-Workload shapes follow the paper's evaluation setup (Table "Model
-configurations and RL workload characteristics": group size 8 or 16, generation
+Workload shapes follow the paper's evaluation setup (Table 3, the model
+configurations and workload characteristics: group size 8 or 16, generation
 lengths up to ~98k tokens; Section 3.4: batch sizes from a handful of
 stragglers to several hundred, draft length gamma_max = 8, a 16-token baseline,
 multi-path drafts with k = 4 in the long-tail stage).  The paper's own traces
@@ -653,7 +653,7 @@ def make_draft_inputs(cfg: VerifyConfig, seed: Optional[int] = None, *, gamma_ma
 
 def restrict_draft_inputs(d: DraftInputs, group_size: int, refs: int) -> DraftInputs:
     """The same pool seen by one live request per group (the group's first member) with `refs` of the other
-    members' sequences as references (0 = its own history only): the setting of the paper's Table 1, whose rows
+    members' sequences as references (0 = its own history only): the setting of the paper's Table 2, whose rows
     are the number of grouped references."""
     n_groups = len(d.group_first) - 1
     keep_seq, group_first, live = [], [0], []

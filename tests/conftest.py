@@ -27,3 +27,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    # how much of the attention tolerance each comparison used (tests/gpu_util.py), if a log file is named
+    try:
+        import gpu_util
+        gpu_util.dump_margins()
+    except Exception:
+        pass

@@ -26,13 +26,29 @@ def _params(**kw):
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "seer_verify.h")).read()
-    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(seer_[a-z_]+)\s*\(", body))
+    declared = set()
+    for name in ("seer_verify.h", "seer_verify_diag.h"):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(seer_[a-z_]+)\s*\(", body))
     from paper_2511_14617_amd import binding
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
+
+
+def test_nothing_but_the_declared_symbols_is_exported(lib):
+    """The library is built with hidden visibility: its dynamic symbol table defines the C entry points of
+    the header and nothing else (no C++ internals, no kernel stubs)."""
+    import subprocess
+    from paper_2511_14617_amd import binding
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], check=True, stdout=subprocess.PIPE,
+                         text=True).stdout
+    defined = {line.split()[-1] for line in out.splitlines() if line.strip()}
+    # what the toolchain itself adds to every shared object
+    defined -= {"_init", "_fini", "__bss_start", "_edata", "_end", "__hip_fatbin", "__hip_gpubin_handle"}
+    defined = {d for d in defined if not d.startswith("__hip_")}
+    assert defined == set(binding.EXPORTS), sorted(defined ^ set(binding.EXPORTS))
 
 
 def test_params_struct_matches_header():
@@ -236,3 +252,16 @@ def test_product_path_fails_loudly_without_the_library(tmp_path, monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libseer_verify.so"))
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+def test_kernel_name_follows_the_dispatch(lib):
+    from paper_2511_14617_amd import binding
+    name = binding.seer_verify_attention_kernel
+    assert name(_params(B=64, Hq=32, Hkv=8, T=9)) == "attn_gqa128_kernel<2,1>"          # 36 rows: two waves
+    assert name(_params(B=8, Hq=32, Hkv=8, T=17)) == "attn_gqa128_kernel<3,3>"          # 68 rows
+    assert name(_params(B=128, Hq=32, Hkv=8, T=33)) == "attn_gqa128_kernel<5,3>"        # 132 rows
+    assert name(_params(Hq=128, Hkv=1, Dqk=576, Dv=512, page_size=64, kv_shared_latent=1)) == "attn_mla_kernel"
+    assert name(_params(Hq=128, Hkv=1, Dqk=576, Dv=512, page_size=16, kv_shared_latent=1)) == "attn_general_kernel<576,512>"
+    assert name(_params(flags=binding.SEER_ATTN_GENERAL_KERNEL)) == "attn_general_kernel<128,128>"
+    assert name(_params(page_size=24)) == "attn_general_kernel<128,128>"
+    assert name(_params(T=65)) is None

@@ -18,7 +18,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 @pytest.mark.gpu
 def test_one_json_line_with_the_agreed_keys():
-    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--config", "1", "--steps", "3", "--warmup", "1"],
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--configs", "1,1", "--steps", "3", "--warmup", "1"],
                        capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
@@ -36,3 +36,11 @@ def test_one_json_line_with_the_agreed_keys():
         assert key in d["cpu_baseline"], key
     assert d["cpu_baseline"]["kind"] == "oracle"
     assert d["attention_status_word"] == 0
+    # median and minimum beside the mean, the same loop on one set of buffers, the reproducible mode
+    for key in ("step_gpu_ms_median", "step_gpu_ms_min", "same_buffers"):
+        assert key in d, key
+    for key in ("kernel_ms_avg", "kernel_ms_median", "kernel_ms_min", "same_buffers", "fixed_split", "kernel"):
+        assert key in d["roofline"], key
+    assert d["roofline"]["kernel"].startswith("attn_gqa128_kernel<1,1>")
+    # the other workloads ride in the same line, each with a roofline of its own
+    assert set(d["per_config"]) == {"config1"} and "roofline" in d["per_config"]["config1"]

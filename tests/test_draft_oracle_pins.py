@@ -246,7 +246,7 @@ def test_width_one_is_the_greedy_chain_and_wider_beams_contain_it():
 
 
 def test_more_references_and_more_paths_accept_more():
-    """The trend of the paper's Table 1 on the synthetic groups: drafts from the whole group's history are
+    """The trend of the paper's Table 2 on the synthetic groups: drafts from the whole group's history are
     accepted further than drafts from the request's own history, and a wider beam never accepts less."""
     cfg = W.CONFIGS[2]
 

@@ -271,3 +271,56 @@ def test_parity_random_shapes(seed):
     what = "random %d: G=%d Hkv=%d T=%d tree=%s P=%d B=%d ctx=%s" % (seed, cfg.G, cfg.Hkv, cfg.T, cfg.tree,
                                                                      cfg.page_size, cfg.B, inp.ctx_len.tolist())
     assert_attention_close(out, ref, what, hardened=True, ref_abs=_oracle_abs(inp))
+
+
+@pytest.mark.parametrize("case", ["chain_T9_multi_split", "tree_T33", "mla_latent", "rows528_G16_T33"])
+def test_page_permutation_is_bit_identical_with_the_fixed_split(case):
+    """Moving every page to another place of the pool, the block table following, changes nothing: the cut
+    of the KV stream is by logical position, so with SEER_ATTN_FIXED_SPLIT the output bits are the same."""
+    from paper_2511_14617_amd import binding
+    cfg, kw = CASES[case]
+    inp = W.make_attention_inputs(cfg, values="peaked", **kw)
+    a = _gpu(inp, flags=binding.SEER_ATTN_FIXED_SPLIT)
+    perm = np.random.default_rng(7).permutation(inp.num_pages)      # old page -> new page
+    k2 = np.empty_like(inp.k_pages)
+    k2[perm] = inp.k_pages
+    inp.k_pages = k2
+    if inp.v_pages is not None:
+        v2 = np.empty_like(inp.v_pages)
+        v2[perm] = inp.v_pages
+        inp.v_pages = v2
+    inp.block_table = perm[inp.block_table].astype(np.int32)
+    b = _gpu(inp, flags=binding.SEER_ATTN_FIXED_SPLIT)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert_attention_close(b, _oracle(inp), case + "/permuted pages", hardened=True, ref_abs=_oracle_abs(inp))
+
+
+def test_gqa_equals_mha_on_replicated_kv():
+    """Grouped-query heads against the same queries with every KV head stored G times (G = 1, Hkv = Hq):
+    another launch shape, another cut of the stream, the same attention."""
+    cfg, kw = CASES["chain_T9_multi_split"]
+    inp = W.make_attention_inputs(cfg, values="peaked", **kw)
+    ref, ref_abs = _oracle(inp), _oracle_abs(inp)
+    gqa = _gpu(inp)
+    inp.k_pages = np.repeat(inp.k_pages, cfg.G, axis=1)
+    inp.v_pages = np.repeat(inp.v_pages, cfg.G, axis=1)
+    mha = _gpu(inp)
+    assert_attention_close(gqa, ref, "gqa", hardened=True, ref_abs=ref_abs)
+    assert_attention_close(mha, ref, "mha on replicated kv", hardened=True, ref_abs=ref_abs)
+    assert float((gqa.float() - mha.float()).abs().max()) <= 0.05
+
+
+def test_shared_latent_equals_explicit_value_pool():
+    """V = the first Dv components of the latent, once implicit (the tiled shared-latent kernel) and once as
+    a value pool of its own (separate pools of these sizes take the general kernel)."""
+    cfg, kw = CASES["mla_latent"]
+    inp = W.make_attention_inputs(cfg, values="peaked", **kw)
+    assert inp.v_pages is None
+    ref = _oracle(inp)
+    ref_abs = _oracle_abs(inp)
+    shared = _gpu(inp)
+    inp.v_pages = np.ascontiguousarray(inp.k_pages[..., : cfg.Dv])
+    explicit = _gpu(inp)
+    assert_attention_close(shared, ref, "shared latent", hardened=True, ref_abs=ref_abs)
+    assert_attention_close(explicit, ref, "explicit value pool", hardened=True, ref_abs=ref_abs)
+    assert float((shared.float() - explicit.float()).abs().max()) <= 0.05

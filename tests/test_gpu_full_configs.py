@@ -3,7 +3,9 @@
 The oracle cannot run these whole in seconds, so attention is checked on sampled output rows
 (b, t, h) that the oracle computes one by one -- chosen to cover the longest and the shortest
 request, the first and last verify slot, every KV head -- plus properties that hold at any size
-(finite, and the status word clean).  Acceptance is compared in full, bit for bit."""
+(finite, and the status word clean).  Each workload runs with the stated value distribution
+("paper": N(0,1)/sqrt(D), outputs ~1e-3, where the stated tolerance is loose) and with the hardened
+one ("peaked": O(1) outputs, where it has teeth).  Acceptance is compared in full, bit for bit."""
 import gc
 
 import numpy as np
@@ -12,7 +14,7 @@ import torch
 
 import oracle
 from paper_2511_14617_amd import workloads as W
-from gpu_util import ATOL, RTOL, accept_device_inputs, attention_device_inputs
+from gpu_util import ATOL, RTOL, accept_device_inputs, attention_device_inputs, check_attention_values
 
 pytestmark = pytest.mark.gpu
 
@@ -33,11 +35,14 @@ def _sample_rows(inp, n_random=40, seed=0):
     return np.array(sorted(set(rows)), dtype=np.int32)
 
 
+@pytest.mark.parametrize("values", ["paper", "peaked"])
 @pytest.mark.parametrize("config_id", [1, 2, 3, 4, 5])
-def test_attention_full_size_sampled_rows(config_id):
+def test_attention_full_size_sampled_rows(config_id, values):
     from paper_2511_14617_amd import binding
     cfg = W.CONFIGS[config_id]
-    inp = W.make_attention_inputs(cfg)
+    inp = W.make_attention_inputs(cfg, values=values)
+    hard = values == "peaked"
+    what = "config %d full size/%s" % (config_id, values)
     d = attention_device_inputs(inp)
     p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], inp.scale, Dv=cfg.Dv)
     ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device="cuda")
@@ -53,14 +58,21 @@ def test_attention_full_size_sampled_rows(config_id):
     rows = _sample_rows(inp, seed=config_id)
     ref = oracle.verify_attention_rows(rows, inp.q, inp.k_pages, inp.v_pages, inp.block_table, inp.ctx_len,
                                        inp.tree_mask, inp.scale, Dv=cfg.Dv)
+    ref_abs = None
+    if hard:
+        # sum_j p_j |v_j| of the same rows (see check_attention_values): the oracle with the sign bit of V cleared
+        v = inp.v_pages if inp.v_pages is not None else np.ascontiguousarray(inp.k_pages[..., : cfg.Dv])
+        ref_abs = oracle.verify_attention_rows(rows, inp.q, inp.k_pages, v & np.uint16(0x7FFF), inp.block_table,
+                                               inp.ctx_len, inp.tree_mask, inp.scale)
+        del v
     got = got_all[rows[:, 0], rows[:, 1], rows[:, 2]].cpu().numpy().astype(np.float64)
+    check_attention_values(got, ref, what, hardened=hard, ref_abs=ref_abs)
     err = np.abs(got - ref)
-    bound = ATOL + RTOL * np.abs(ref)
-    assert (err <= bound).all(), "config %d: max err/bound %.3f" % (config_id, (err / bound).max())
-    # the stated tolerance is loose for these nearly uniform softmaxes: also require the error to be small
-    # against the signal, so that an all-zero or shifted output cannot pass
+    bound = ATOL + RTOL * np.abs(ref) + (0.0 if ref_abs is None else 2.0 ** -9 * ref_abs)
+    # the stated tolerance is loose for the nearly uniform softmaxes of the "paper" values: also require the
+    # error to be small against the signal, so that an all-zero or shifted output cannot pass
     nrms = np.sqrt((err ** 2).mean() / (ref ** 2).mean())
-    assert nrms < 2e-2, "config %d: normalised rms error %.3e" % (config_id, nrms)
+    assert nrms < 2e-2, "%s: normalised rms error %.3e" % (what, nrms)
     # Later calls on the same workspace cut the KV stream by the measured speed of each workgroup
     # slot: same result up to the rounding order of the partial sums, still inside the tolerance;
     # with SEER_ATTN_FIXED_SPLIT the cut, and the bits of the output, do not depend on earlier calls.
@@ -70,14 +82,15 @@ def test_attention_full_size_sampled_rows(config_id):
     torch.cuda.synchronize()
     assert binding.seer_verify_attention_status(ws) == 0
     got2 = out2.float()[rows[:, 0], rows[:, 1], rows[:, 2]].cpu().numpy().astype(np.float64)
-    assert (np.abs(got2 - ref) <= bound).all(), "config %d after adaptation" % config_id
-    assert float((out2.float() - got_all).abs().max()) <= 2 * ATOL
+    check_attention_values(got2, ref, what + "/after adaptation", hardened=hard, ref_abs=ref_abs)
+    assert float((out2.float() - got_all).abs().max()) <= (2 * ATOL if not hard else 0.05)
     fixed = [binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
                                            d["tree_mask"], inp.scale, Dv=cfg.Dv, workspace=ws,
                                            flags=binding.SEER_ATTN_FIXED_SPLIT).clone() for _ in range(2)]
     torch.cuda.synchronize()
     assert torch.equal(fixed[0], fixed[1])
-    assert (np.abs(fixed[0].float()[rows[:, 0], rows[:, 1], rows[:, 2]].cpu().numpy() - ref) <= bound).all()
+    check_attention_values(fixed[0].float()[rows[:, 0], rows[:, 1], rows[:, 2]].cpu().numpy().astype(np.float64), ref,
+                           what + "/fixed split", hardened=hard, ref_abs=ref_abs)
     del d, out, out2, fixed, ws, got_all
     gc.collect()
     torch.cuda.empty_cache()

@@ -169,12 +169,17 @@ def test_commit_reports_bad_requests_and_leaves_them():
     bad_len[2] = cfg.T                    # longer than the draft
     bad_ctx = inp.ctx_len.copy()
     bad_ctx[3] = cfg.T - 1                # shorter than the verify slots
+    # node ids far outside the T slots (garbage, huge, negative): reported, and never used as an index
+    bad_len[4] = max(int(bad_len[4]), 2)
+    bad_path[4, 1] = 0x3FFFFFF0
+    bad_len[5] = max(int(bad_len[5]), 2)
+    bad_path[5, 1], bad_path[5, 2] = 1, -0x40000000
     inp2 = inp.__class__(**{**inp.__dict__, "ctx_len": bad_ctx})
     rk, rv, rn = oracle.kv_commit(inp.k_pages, inp.v_pages, inp.block_table, inp.ctx_len, alen, path)
     k, v, n, status, _ = _run_commit(inp2, acc, bad_len, bad_path, bonus, with_tokens=False)
     assert int(status.item()) == (1 | 4)
     got_n = n.cpu().numpy()
-    for b in (1, 2, 3):
+    for b in (1, 2, 3, 4, 5):
         assert got_n[b] == bad_ctx[b]
-    ok = [b for b in range(cfg.B) if b not in (1, 2, 3)]
+    ok = [b for b in range(cfg.B) if b not in (1, 2, 3, 4, 5)]
     assert np.array_equal(got_n[ok], rn[ok])
