@@ -54,6 +54,7 @@ extern "C" {
 #define SEER_EUNSUPPORTED (-3) /* head dims / page size no kernel is built for      */
 #define SEER_EWORKSPACE (-4)   /* workspace NULL or smaller than *_workspace()      */
 #define SEER_EALIGN (-5)       /* a tensor pointer is not 16-byte aligned           */
+#define SEER_ELIMIT (-6)       /* problem larger than a fixed-size entry point holds */
 
 #define SEER_MAX_T 64          /* verify slots per request (width of the mask word) */
 
@@ -167,6 +168,29 @@ SEER_API int seer_accept(const float* logits, const int32_t* draft_tokens, const
                 int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
                 int32_t* bonus_token, int32_t* target_argmax, void* workspace,
                 size_t workspace_bytes, void* hip_stream);
+
+/*
+ * seer_accept for callers that cannot allocate or hand over scratch memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * seer_accept without the workspace: the per-chunk results of the vocabulary scan go to a fixed
+ * array of SEER_ACCEPT_STATIC_MAX_PAIRS * 8 bytes (1 MiB) that is part of the library's device
+ * image (every GPU the library runs on holds it until the process ends).  The call allocates
+ * nothing and frees nothing.
+ *
+ *  - Limit: B * T * ceil(V / 16384) <= SEER_ACCEPT_STATIC_MAX_PAIRS, else SEER_ELIMIT (checked on
+ *    the host before anything else; the multi-path configuration, 4224 rows of 152 064 logits,
+ *    needs 42 240 pairs).
+ *  - The first call on a device looks up that device's copy of the array (one
+ *    hipGetSymbolAddress, no allocation); a call with B = 0 does only that, so a caller can make
+ *    it before starting a graph capture.  The device of hip_stream must be the current device.
+ *  - All calls on one GPU share the array: calls that may overlap on one GPU (different streams,
+ *    different threads) race on it and must be ordered by the caller.  Nothing in it has to be
+ *    cleared between calls: every entry a call reads, it has written first.
+ */
+#define SEER_ACCEPT_STATIC_MAX_PAIRS 131072
+SEER_API int seer_accept_static(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+                                int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
+                                int32_t* bonus_token, int32_t* target_argmax, void* hip_stream);
 
 /*
  * Acceptance under sampling (Section 4.1 of the paper: its workloads sample at

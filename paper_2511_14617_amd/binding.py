@@ -16,10 +16,11 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libseer_verify.so")
 
-SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALIGN = 0, -1, -2, -3, -4, -5
+SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALIGN, SEER_ELIMIT = 0, -1, -2, -3, -4, -5, -6
+SEER_ACCEPT_STATIC_MAX_PAIRS = 131072
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
-           "seer_verify_attention_timed", "seer_verify_attention_kernel", "seer_accept_workspace", "seer_accept", "seer_accept_sampled",
+           "seer_verify_attention_timed", "seer_verify_attention_kernel", "seer_accept_workspace", "seer_accept", "seer_accept_static", "seer_accept_sampled",
            "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_history_append",
            "seer_strerror")
 
@@ -76,6 +77,8 @@ def load_library() -> ctypes.CDLL:
         lib.seer_accept_workspace.restype = sz
         lib.seer_accept.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.seer_accept.restype = ctypes.c_int
+        lib.seer_accept_static.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
+        lib.seer_accept_static.restype = ctypes.c_int
         lib.seer_accept_sampled.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_float, ctypes.c_uint64,
                                             vp, vp, vp, vp, vp, sz, vp]
         lib.seer_accept_sampled.restype = ctypes.c_int
@@ -226,6 +229,28 @@ def seer_accept(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: O
                                        _ptr(bonus), _ptr(tgt), _ptr(workspace), workspace.numel(),
                                        _stream_handle(stream)))
     return alen, path, bonus, tgt
+
+
+def seer_accept_static(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: Optional[torch.Tensor],
+                       out: Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor], *,
+                       stream: Optional[torch.cuda.Stream] = None):
+    """seer_accept without a workspace (the scan's scratch is a fixed array inside the library); the four
+    result tensors (accepted_len, accepted_path, bonus_token, target_argmax) must be passed: the call
+    allocates nothing."""
+    lib = load_library()
+    B, T, V = logits.shape
+    _want(logits, torch.float32, (B, T, V), "logits")
+    _want(draft_tokens, torch.int32, (B, T), "draft_tokens")
+    if tree_parent is not None:
+        _want(tree_parent, torch.int32, (B, T), "tree_parent")
+    alen, path, bonus, tgt = out
+    _want(alen, torch.int32, (B,), "accepted_len")
+    _want(path, torch.int32, (B, T), "accepted_path")
+    _want(bonus, torch.int32, (B,), "bonus_token")
+    _want(tgt, torch.int32, (B, T), "target_argmax")
+    _check(lib.seer_accept_static(_ptr(logits), _ptr(draft_tokens), _ptr(tree_parent), B, T, V, _ptr(alen), _ptr(path),
+                                  _ptr(bonus), _ptr(tgt), _stream_handle(stream)))
+    return out
 
 
 def seer_accept_sampled(logits: torch.Tensor, draft_tokens: torch.Tensor, tree_parent: Optional[torch.Tensor],

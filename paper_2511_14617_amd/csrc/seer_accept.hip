@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/seer_verify.h"
 #include "seer_device.h"
 #include "seer_sampling.h"
@@ -202,24 +204,26 @@ extern "C" size_t seer_accept_workspace(int32_t B, int32_t T, int32_t V) {
 
 namespace seer {
 
-static int run_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent, int32_t B,
-                      int32_t T, int32_t V, bool sampled, SampleArgs sa, int32_t* accepted_len,
-                      int32_t* accepted_path, int32_t* bonus_token, int32_t* target_token, void* workspace,
-                      size_t workspace_bytes, void* hip_stream) {
+// Argument checks that need no device: what both entry-point families share.
+static int check_accept_args(const float* logits, const int32_t* draft_tokens, int32_t B, int32_t T, int32_t V,
+                             const int32_t* accepted_len, const int32_t* accepted_path, const int32_t* target_token) {
     if (B < 0 || V < 1) return SEER_EINVAL;
     if (T < 1 || T > SEER_MAX_T) return SEER_ESHAPE;
     if (B == 0) return SEER_OK;
     if (!logits || !draft_tokens || !accepted_len || !accepted_path || !target_token) return SEER_EINVAL;
     if (static_cast<int64_t>(B) * T * accept_max_chunks(V) > 0x7fffffffLL) return SEER_ESHAPE;
-    const size_t need = seer_accept_workspace(B, T, V);
-    if (!workspace || workspace_bytes < need) return SEER_EWORKSPACE;
-    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return SEER_EALIGN;
     if (reinterpret_cast<uintptr_t>(logits) % 4 != 0) return SEER_EALIGN;
+    return SEER_OK;
+}
 
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+// The two launches.  scratch holds `capacity` (value, index) pairs: capacity floats, then capacity ints;
+// the caller has checked that B * T * n_chunks pairs fit.
+static int launch_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent, int32_t B,
+                         int32_t T, int32_t V, bool sampled, SampleArgs sa, int32_t* accepted_len,
+                         int32_t* accepted_path, int32_t* bonus_token, int32_t* target_token, void* scratch,
+                         size_t capacity, hipStream_t stream) {
     const int n_chunks = accept_num_chunks(V, sampled ? kChunkSampled : kChunkGreedy);
-    const size_t capacity = static_cast<size_t>(B) * T * accept_max_chunks(V);     // pairs the workspace holds
-    float* part_val = static_cast<float*>(workspace);
+    float* part_val = static_cast<float*>(scratch);
     int* part_idx = reinterpret_cast<int*>(part_val + capacity);
     const bool vec4 = (V % 4 == 0) && (reinterpret_cast<uintptr_t>(logits) % 16 == 0);
     const dim3 grid(static_cast<unsigned>(static_cast<size_t>(B) * T * n_chunks));
@@ -234,6 +238,20 @@ static int run_accept(const float* logits, const int32_t* draft_tokens, const in
                        tree_parent, T, accepted_len, accepted_path, bonus_token, target_token);
     err = hipGetLastError();
     return err == hipSuccess ? SEER_OK : static_cast<int>(err);
+}
+
+static int run_accept(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent, int32_t B,
+                      int32_t T, int32_t V, bool sampled, SampleArgs sa, int32_t* accepted_len,
+                      int32_t* accepted_path, int32_t* bonus_token, int32_t* target_token, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    const int rc = check_accept_args(logits, draft_tokens, B, T, V, accepted_len, accepted_path, target_token);
+    if (rc != SEER_OK || B == 0) return rc;
+    const size_t need = seer_accept_workspace(B, T, V);
+    if (!workspace || workspace_bytes < need) return SEER_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return SEER_EALIGN;
+    const size_t capacity = static_cast<size_t>(B) * T * accept_max_chunks(V);     // pairs the workspace holds
+    return launch_accept(logits, draft_tokens, tree_parent, B, T, V, sampled, sa, accepted_len, accepted_path,
+                         bonus_token, target_token, workspace, capacity, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // namespace seer
@@ -256,4 +274,54 @@ extern "C" int seer_accept_sampled(const float* logits, const int32_t* draft_tok
     const seer::SampleArgs sa{1.0f / temperature, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
     return seer::run_accept(logits, draft_tokens, tree_parent, B, T, V, true, sa, accepted_len, accepted_path,
                             bonus_token, target_token, workspace, workspace_bytes, hip_stream);
+}
+
+// ---------------------------------------------------------------------------
+// seer_accept_static: seer_accept for callers that cannot allocate.  The chunk results of the scan live in
+// a fixed array in the library's own device image instead of a caller workspace.
+// ---------------------------------------------------------------------------
+namespace seer {
+
+constexpr size_t kStaticPairs = size_t{SEER_ACCEPT_STATIC_MAX_PAIRS};      // (value, index) pairs
+static __device__ __align__(256) unsigned char scratch[kStaticPairs * (sizeof(float) + sizeof(int32_t))];
+
+// In host code `scratch` is only a stand-in for the symbol, not a device address; every GPU holds its own
+// copy of the array at its own address, looked up once per device and kept here.
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static void* g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(void** ptr) {
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return static_cast<int>(err);
+    if (dev < 0 || dev >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return static_cast<int>(err);
+        if (!p) return static_cast<int>(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return SEER_OK;
+}
+
+}  // namespace seer
+
+extern "C" int seer_accept_static(const float* logits, const int32_t* draft_tokens, const int32_t* tree_parent,
+                                  int32_t B, int32_t T, int32_t V, int32_t* accepted_len, int32_t* accepted_path,
+                                  int32_t* bonus_token, int32_t* target_argmax, void* hip_stream) {
+    const int rc = seer::check_accept_args(logits, draft_tokens, B, T, V, accepted_len, accepted_path, target_argmax);
+    if (rc != SEER_OK) return rc;
+    const size_t pairs = static_cast<size_t>(B) * T * seer::accept_num_chunks(V, seer::kChunkGreedy);
+    if (pairs > seer::kStaticPairs) return SEER_ELIMIT;
+    void* ptr = nullptr;
+    const int rs = seer::static_scratch(&ptr);      // also with B == 0: resolves the address, launches nothing
+    if (rs != SEER_OK || B == 0) return rs;
+    // Every pair the walk reads is written by this call's scan first, so nothing has to start at zero.
+    return seer::launch_accept(logits, draft_tokens, tree_parent, B, T, V, false, seer::SampleArgs{1.f, 0u, 0u},
+                               accepted_len, accepted_path, bonus_token, target_argmax, ptr, seer::kStaticPairs,
+                               static_cast<hipStream_t>(hip_stream));
 }

@@ -660,6 +660,7 @@ extern "C" const char* seer_strerror(int code) {
         case SEER_EUNSUPPORTED: return "no kernel for these head dimensions";
         case SEER_EWORKSPACE: return "workspace missing or too small";
         case SEER_EALIGN: return "pointer not aligned as required";
+        case SEER_ELIMIT: return "problem larger than this fixed-size entry point holds";
         default: break;
     }
     if (code > 0) return hipGetErrorString(static_cast<hipError_t>(code));

@@ -108,7 +108,7 @@ def test_attention_argument_errors_before_any_launch(lib):
     assert run(_params(), q=fake + 2) == b.SEER_EALIGN
     assert run(_params(), ws=0x10010) == b.SEER_EALIGN
     assert run(_params(B=0)) == b.SEER_OK                              # empty batch: nothing to do
-    for code in (0, -1, -2, -3, -4, -5, 1, -99):
+    for code in (0, -1, -2, -3, -4, -5, -6, 1, -99):
         assert isinstance(b.seer_strerror(code), str) and b.seer_strerror(code)
 
 
