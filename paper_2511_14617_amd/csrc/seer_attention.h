@@ -184,6 +184,7 @@ hipError_t launch_combine(const AttnArgs& a, hipStream_t stream);
 bool general_supports(int Dqk, int Dv);
 bool gqa128_supports(const AttnArgs& a);                            // D = 128, pages of 16..1024 tokens (power of two)
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream);
+bool gqa128_uses_helpers(int rows, int row_blocks);                 // 4 main + 4 helper waves instead of 5 waves
 bool mla_supports(const AttnArgs& a);                               // shared latent 576/512, pages of 32..1024 tokens
 hipError_t launch_mla(const AttnArgs& a, hipStream_t stream);
 

@@ -167,7 +167,7 @@ __device__ __forceinline__ void rescale_if_moved(f32x16 (&acc)[4], float alpha) 
 // V slot (row part of the lane's address included) the P.V product reads.  alpha is the
 // rescaling factor the previous step's softmax left for the output accumulators: it is applied
 // before this step's P.V, and replaced by this step's softmax.
-template <bool DO_QK, bool DO_SM, bool DO_PV>
+template <bool DO_QK, bool DO_SM, bool DO_PV, bool MASKED = true>
 __device__ __forceinline__ void pipe_step(const unsigned char* lds, int k_off, int v_off, const int (&k_rd)[8],
                                           const int (&v_rd)[4], const bf16x8 (&qreg)[8], f32x16& s_sm,
                                           f32x16& s_qk, const uint32_t (&pk_pv)[8], uint32_t (&pk_sm)[8],
@@ -221,7 +221,8 @@ __device__ __forceinline__ void pipe_step(const unsigned char* lds, int k_off, i
         float mx = kNegInf;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            if (!((vis >> ((i >> 2) * 8 + (i & 3))) & 1u)) s_sm[i] = kNegInf;
+            if constexpr (MASKED)
+                if (!((vis >> ((i >> 2) * 8 + (i & 3))) & 1u)) s_sm[i] = kNegInf;
             mx = fmaxf(mx, s_sm[i]);
         }
         const float m_use = move_reference(mx, scale_log2, m_run, alpha);
@@ -388,12 +389,23 @@ __device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, 
 // system allows for exactly this access pattern and launch shape: the ceiling the kernel's
 // bytes-per-second should be read against.  It writes "saw nothing" partials, so the output is zero.
 // STREAM_PARTIALS: the partial results leave with non-temporal stores (see kStreamPartialsBelow).
-template <int NW, int D, bool STREAM, bool STREAM_PARTIALS>
-__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == 1 ? 1 : 2, 2)))
+// NH: helper waves (0 or 4) behind the NW main waves.  A row count just above a multiple of 32 (the multi-path
+// tree on a group of four heads: 4 x 33 = 132 rows) would otherwise put a fifth wave with a handful of rows on the
+// SIMD of wave 0; that wave runs the whole per-tile instruction stream whatever its row count, and with in-order
+// issue it doubles the load of the one SIMD every step waits for.  Instead the NW = 4 main waves (one per SIMD)
+// are joined by four helper waves (again one per SIMD) that serve the leftover rows TOGETHER: helper h takes
+// the tiles u = h (mod 4) of a piece, each with a softmax state of its own, and the four states are merged
+// through LDS at the end of the piece (in a fixed order, so the result does not depend on timing).  A helper
+// scores and soft-maxes its tile at step u and multiplies by V at step u + 2, when that V tile has landed: a
+// quarter of a wave's work per step on every SIMD instead of a whole wave's on one.  All eight waves issue loads.
+template <int NW, int D, bool STREAM, bool STREAM_PARTIALS, int NH = 0>
+__global__ __launch_bounds__((NW + NH) * kWave) __attribute__((amdgpu_waves_per_eu(NW + NH == 1 ? 1 : 2, 2)))
 void attn_gqa128_kernel(AttnArgs a) {
-    constexpr int NT = NW * kWave;
+    static_assert(NH == 0 || (NH == 4 && D >= 2), "helpers: four of them, and V tiles that land two steps after K");
+    constexpr int NWT = NW + NH;                    // waves per workgroup
+    constexpr int NT = NWT * kWave;
     constexpr int NSLOT = D + 1;                    // slots in the K ring and in the V ring
-    constexpr int NL = Loaders<NW>::kCount;         // waves that issue loads (the others have nothing to wait for)
+    constexpr int NL = Loaders<NWT>::kCount;        // waves that issue loads (the others have nothing to wait for)
     constexpr int CEIL = (8 + NL - 1) / NL;         // half-tile blocks of the busiest loading waves
     constexpr int FLOOR = 8 / NL;
     constexpr int REM = 8 % NL;                     // loaders below this index load CEIL blocks, the others FLOOR
@@ -460,7 +472,8 @@ void attn_gqa128_kernel(AttnArgs a) {
     bare_barrier();                                // every wave is done with the previous piece's slots
 
     const int R = min(a.G * a.T, (rb + 1) * a.rows_per_block);     // rows of this row block end here
-    const int r = rb * a.rows_per_block + wave * 32 + ln;
+    const bool helper = NH > 0 && wave >= NW;                       // uniform for the wave
+    const int r = rb * a.rows_per_block + (helper ? NW : wave) * 32 + ln;
     const bool row_ok = r < R;
     const int t = row_ok ? r / a.G : 0;
     const int hq = kvh * a.G + (row_ok ? r - t * a.G : 0);
@@ -533,10 +546,10 @@ void attn_gqa128_kernel(AttnArgs a) {
     size_t pn0 = 0, pn1 = 0;
     auto issue_k_at = [&](int kt, int slot_bytes) __attribute__((always_inline)) {
         page_pair(tok_begin + kt * kTile, pn0, pn1);
-        issue_half_tile<NW>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
+        issue_half_tile<NWT>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
     };
     auto issue_v_at = [&](int slot_bytes) __attribute__((always_inline)) {
-        issue_half_tile<NW>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
+        issue_half_tile<NWT>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
     };
     auto shift_pages = [&]() __attribute__((always_inline)) { pr0 = pq0, pr1 = pq1, pq0 = pn0, pq1 = pn1; };
     auto issue_k = [&](int j) __attribute__((always_inline)) {
@@ -558,7 +571,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     auto wait_step = [&](int u) __attribute__((always_inline)) {
         const bool full = D > 1 && u >= 1 && u + D - 1 < n_tiles;
         if (full) {
-            if (REM == 0 || wave - Loaders<NW>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            if (REM == 0 || wave - Loaders<NWT>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
             else wait_vmcnt<(D - 1) * 2 * FLOOR>();
         } else {
             wait_vmcnt<0>();
@@ -587,6 +600,52 @@ void attn_gqa128_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) pk_a[i] = pk_b[i] = 0u;
 
+    // Ragged last tile of a request: slots past the end hold whatever the page holds (NaN included), and
+    // 0 * NaN must not reach the output: clear those V rows in LDS.  Every wave of the workgroup calls this at
+    // step n_tiles + 1, after that step's barrier and before its P.V product.
+    auto clear_ragged_tail = [&]() __attribute__((always_inline)) {
+        const int tb = tok_begin + (n_tiles - 1) * kTile;
+        if (tb + kTile > n) {
+            unsigned char* vl = lds + kVRing + ((n_tiles - 1) % NSLOT) * kKBytes;
+            const int first_bad = n - tb;
+            for (int c = tid; c < kTile * 16; c += NT)
+                if ((c >> 4) >= first_bad) *reinterpret_cast<u32x4*>(vl + c * 16) = u32x4{0u, 0u, 0u, 0u};
+            __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the clears are done
+            bare_barrier();
+        }
+    };
+
+  if (helper) {
+    // A helper wave: the same waits, barriers and loads as the main waves, step for step; of the arithmetic,
+    // the tiles u = h (mod NH) for the leftover rows, one phase per step so that no step is much longer than the
+    // others: scores at step u (K tile u is in its slot during that step only), softmax at step u + 1, P.V at
+    // step u + 2 (V tile u has landed by then and is overwritten after step u + 3's barrier).
+    if constexpr (NH > 0) {
+        const int h = wave - NW;
+        for (int u = 0; u <= n_tiles + 1; ++u) {
+            wait_step(u);
+            bare_barrier();
+            if (u == n_tiles + 1) clear_ragged_tail();
+            if (u <= n_tiles) issue_step(u);
+            if constexpr (!STREAM) {
+                if (u >= 2 && ((u - 2) & (NH - 1)) == h)
+                    pipe_step<false, false, true>(lds, 0, v_off(u - 2), k_rd, v_rd, qreg, s_b, s_b, pk_a, pk_b, acc, m_run, l_run,
+                                                  alpha, a.scale_log2, 0u);
+                if (u >= 1 && u <= n_tiles && ((u - 1) & (NH - 1)) == h) {
+                    if (tok_begin + u * kTile <= n0)          // a tile of prefix tokens only: nothing to mask
+                        pipe_step<false, true, false, false>(lds, 0, 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run,
+                                                             alpha, a.scale_log2, 0u);
+                    else
+                        pipe_step<false, true, false>(lds, 0, 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run, alpha,
+                                                      a.scale_log2, vis_of(u - 1));
+                }
+                if (u < n_tiles && (u & (NH - 1)) == h)
+                    pipe_step<true, false, false>(lds, k_off(u), 0, k_rd, v_rd, qreg, s_b, s_a, pk_b, pk_b, acc, m_run, l_run, alpha,
+                                                  a.scale_log2, 0u);
+            }
+        }
+    }
+  } else {
     // step 0: scores of tile 0 -> s_a
     wait_step(0);
     bare_barrier();
@@ -646,7 +705,7 @@ void attn_gqa128_kernel(AttnArgs a) {
             constexpr int I = decltype(ic)::value;
             constexpr int kReadSlot = (2 + I) % NSLOT, kVReadSlot = I % NSLOT;
             constexpr int kIssueSlot = (1 + I) % NSLOT, kVIssueSlot = (I + NSLOT - 1) % NSLOT;
-            if (REM == 0 || wave - Loaders<NW>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
+            if (REM == 0 || wave - Loaders<NWT>::kFirst < REM) wait_vmcnt<(D - 1) * 2 * CEIL>();
             else wait_vmcnt<(D - 1) * 2 * FLOOR>();
             bare_barrier();
             const int uu = u + I;
@@ -699,25 +758,78 @@ void attn_gqa128_kernel(AttnArgs a) {
         const int u = n_tiles + 1;
         wait_step(u);
         bare_barrier();
-        const int tb = tok_begin + (n_tiles - 1) * kTile;
-        if (tb + kTile > n) {
-            // Ragged last tile of a request: slots past the end hold whatever the page holds (NaN
-            // included), and 0 * NaN must not reach the output: clear those V rows in LDS.
-            unsigned char* vl = lds + kVRing + ((n_tiles - 1) % NSLOT) * kKBytes;
-            const int first_bad = n - tb;
-            for (int c = tid; c < kTile * 16; c += NT)
-                if ((c >> 4) >= first_bad) *reinterpret_cast<u32x4*>(vl + c * 16) = u32x4{0u, 0u, 0u, 0u};
-            __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the clears are done
-            bare_barrier();
-        }
+        clear_ragged_tail();
         if constexpr (!STREAM)
             pipe_step<false, false, true>(lds, 0, v_off(n_tiles - 1), k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run,
                                           l_run, alpha, a.scale_log2, 0u);
     }
+  }  // main waves
 
     // ---- partial result: (reference exponent, sum, unnormalised O) per row ------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    if (row_ok && lg == 0) {
+    float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    bool stores = row_ok;                           // this lane's row leaves from this wave
+    if constexpr (NH > 0) {
+        // The helpers' four states of the leftover rows become one.  Every wave takes part in the barriers.
+        // LDS (the ring is free once every wave has passed the first barrier): (m, l) of every helper lane,
+        // then the scaled accumulators of helpers 1..3, sixteen 16-byte chunks per lane, chunk-major so that
+        // a wave's access is one contiguous kilobyte.
+        float* xml = reinterpret_cast<float*>(lds);                                    // [NH][64][2]
+        unsigned char* xacc = lds + 4096;                                              // [NH - 1][16][64] x 16 bytes
+        const int h = wave - NW;
+        bare_barrier();                              // every wave has read the piece's last tiles
+        if (helper) {
+            xml[(h * kWave + lane) * 2] = m_run;
+            xml[(h * kWave + lane) * 2 + 1] = l_tot;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        bare_barrier();
+        if (helper) {
+            float mh[NH], lh[NH];
+#pragma unroll
+            for (int i = 0; i < NH; ++i) {
+                mh[i] = xml[(i * kWave + lane) * 2];
+                lh[i] = xml[(i * kWave + lane) * 2 + 1];
+            }
+            float M = mh[0];
+#pragma unroll
+            for (int i = 1; i < NH; ++i) M = fmaxf(M, mh[i]);
+            float L = 0.f;
+#pragma unroll
+            for (int i = 0; i < NH; ++i) L += (mh[i] == kNegInf) ? 0.f : lh[i] * fast_exp2(mh[i] - M);   // fixed order
+            const float f = (m_run == kNegInf) ? 0.f : fast_exp2(m_run - M);
+            m_run = M;
+            l_tot = L;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[dt][i] = (f == 0.f) ? 0.f : acc[dt][i] * f;
+            if (h > 0) {
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
+                        *reinterpret_cast<f32x4*>(xacc + (((h - 1) * 16 + dt * 4 + i4) * kWave + lane) * 16) = v;
+                    }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        bare_barrier();
+        if (helper && h == 0) {
+#pragma unroll
+            for (int o = 0; o < NH - 1; ++o)            // helper 1, then 2, then 3: a fixed order of additions
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const f32x4 v = *reinterpret_cast<const f32x4*>(xacc + ((o * 16 + dt * 4 + i4) * kWave + lane) * 16);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[dt][i4 * 4 + c] += v[c];
+                    }
+        }
+        stores = row_ok && (!helper || h == 0);
+    }
+    if (stores && lg == 0) {
         const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
         a.part_ml[2 * prow] = m_run;
         a.part_ml[2 * prow + 1] = l_tot;
@@ -758,7 +870,7 @@ void attn_gqa128_kernel(AttnArgs a) {
                 store_partial(a.part_acc + prow * kD + ln * 4, v);
             }
         }
-    } else if (row_ok) {
+    } else if (stores) {
         const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
         float* __restrict__ po = a.part_acc + prow * kD;
 #pragma unroll
@@ -784,10 +896,22 @@ bool gqa128_supports(const AttnArgs& a) {
            a.v_pages != nullptr && a.Hkv <= 65535;
 }
 
+// Four main waves and four helpers instead of five waves: 129 .. 144 query rows per KV head in one row block
+// (a fifth wave would hold at most half of its rows).
+bool gqa128_uses_helpers(int rows, int row_blocks) { return row_blocks == 1 && rows > 128 && rows <= 144; }
+
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int nw = a.rows_per_block / 32;
     const dim3 grid(static_cast<unsigned>((a.wgs_per_head + 7) / 8) * 8u * static_cast<unsigned>(a.Hkv) *
                     static_cast<unsigned>(a.row_blocks));
+    if (gqa128_uses_helpers(a.G * a.T, a.row_blocks)) {
+        const dim3 block(8 * kWave);
+        if (a.stream_only && a.stream_partials) hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, true, true, 4>), grid, block, 0, stream, a);
+        else if (a.stream_only) hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, true, false, 4>), grid, block, 0, stream, a);
+        else if (a.stream_partials) hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, false, true, 4>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, false, false, 4>), grid, block, 0, stream, a);
+        return hipGetLastError();
+    }
     switch (nw) {
 #define SEER_GQA_LAUNCH(NW_, STREAM_, PARTIALS_)                                                               \
     hipLaunchKernelGGL((attn_gqa128_kernel<NW_, gqa_pipe_depth(NW_), STREAM_, PARTIALS_>), grid, dim3(NW_ * kWave), 0, \

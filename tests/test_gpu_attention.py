@@ -50,6 +50,14 @@ CASES = {
     "rows168_G8_T21": (W.CONFIGS[2].scaled(B=3, group_size=3, Hq=16, Hkv=2, T=21, ctx=("uniform", 300, 1500)), {}),
     "rows224_G8_T28": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=16, Hkv=2, T=28, ctx=("uniform", 200, 1200)), {}),
     "rows256_G8_T32": (W.CONFIGS[2].scaled(B=2, group_size=2, Hq=8, Hkv=1, T=32, ctx=("uniform", 200, 1200)), {}),
+    # 129 .. 144 rows per KV head: four main waves plus four helper waves that share the leftover rows tile by tile
+    # (pieces shorter than four tiles leave some helpers without a tile; ragged tails; chain and tree masks)
+    "rows129_G3_T43": (W.CONFIGS[2].scaled(B=4, group_size=4, Hq=6, Hkv=2, T=43, ctx=("uniform", 43, 1500), shared_prefix=0), {}),
+    "rows144_G16_T9": (W.CONFIGS[2].scaled(B=5, group_size=5, Hq=32, Hkv=2, T=9, ctx=("uniform", 9, 2500), shared_prefix=64), {}),
+    "rows132_tree_short": (W.CONFIGS[5].scaled(B=9, group_size=3, ctx=("uniform", 33, 140), shared_prefix=0),
+                           {"dedup_fraction": 0.3}),
+    "rows132_tree_page64": (W.CONFIGS[5].scaled(B=4, group_size=4, page_size=64, ctx=("uniform", 500, 4000), shared_prefix=128),
+                            {"dedup_fraction": 0.3}),
     # one GPU's share of a 72B-class model under 8-way tensor parallelism (Section 4.1: 64 query / 8 KV
     # heads split over 8 GPUs -> Hq = 8, Hkv = 1, G = 8), groups of 16 requests, gamma = 8 and a 4 x 8 tree
     "tp8_share_72b_chain": (W.CONFIGS[2].scaled(B=16, group_size=16, Hq=8, Hkv=1, T=9, ctx=("uniform", 200, 2500),
@@ -273,7 +281,7 @@ def test_parity_random_shapes(seed):
     assert_attention_close(out, ref, what, hardened=True, ref_abs=_oracle_abs(inp))
 
 
-@pytest.mark.parametrize("case", ["chain_T9_multi_split", "tree_T33", "mla_latent", "rows528_G16_T33"])
+@pytest.mark.parametrize("case", ["chain_T9_multi_split", "tree_T33", "mla_latent", "rows528_G16_T33", "rows144_G16_T9"])
 def test_page_permutation_is_bit_identical_with_the_fixed_split(case):
     """Moving every page to another place of the pool, the block table following, changes nothing: the cut
     of the KV stream is by logical position, so with SEER_ATTN_FIXED_SPLIT the output bits are the same."""
