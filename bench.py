@@ -211,6 +211,61 @@ def sweep_step_time(torch, binding, W, attention_device_inputs) -> int:
     return 0
 
 
+def sweep_tp8_share(torch, binding, W, attention_device_inputs) -> int:
+    """The verify-attention call on one GPU's share of a 72B-class dense model under 8-way tensor parallelism
+    (the paper's second model: 64 query / 8 KV heads over 8 GPUs -> Hq = 8, Hkv = 1, G = 8 per GPU), prompt groups
+    of 16, lognormal contexts as config 2 / config 5: chains of gamma = 0 .. 8 draft tokens and the 4 x 8
+    multi-path tree, by batch size.  Per cell: GPU time of the call (planning included), of the call on the
+    first layer's plan, of the partition kernel alone, and that kernel's rate against both rooflines (unique KV
+    bytes over 8 TB/s; 4 * D * G * T flop per KV token over 2.5 PFLOP/s): with one KV head per GPU the same read
+    serves twice the rows of the 8B-class shape, so the wide shapes are bound by the matrix cores."""
+    dev = "cuda"
+    rows = []
+    shapes = [("chain", W.CONFIGS[2], (0, 2, 4, 8), (16, 64, 256)), ("tree 4x8", W.CONFIGS[5], (8,), (16, 64, 128))]
+    for kind, base, gammas, batches in shapes:
+        for B in batches:
+            for gamma in gammas:
+                T = 33 if kind != "chain" else gamma + 1
+                cfg = base.scaled(B=B, group_size=16, Hq=8, Hkv=1, T=T)
+                att = W.make_attention_inputs(cfg)
+                d = attention_device_inputs(att)
+                p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], att.scale)
+                ws = torch.empty(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device=dev)
+                out = torch.empty((cfg.B, cfg.T, cfg.Hq, cfg.Dv), dtype=torch.bfloat16, device=dev)
+
+                def call(flags=0, ev=None):
+                    binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"],
+                                                  d["tree_mask"], att.scale, out=out, workspace=ws, flags=flags, events=ev)
+                for _ in range(10):
+                    call()
+                ev = HipEvents(20)
+                marks = [torch.cuda.Event(enable_timing=True) for _ in range(41)]
+                for i in range(20):
+                    marks[i].record()
+                    call(0, ev.pairs[i])
+                for i in range(20, 40):
+                    marks[i].record()
+                    call(binding.SEER_ATTN_REUSE_PLAN)
+                marks[40].record()
+                torch.cuda.synchronize()
+                kern = float(np.median(ev.elapsed_ms()))
+                ev.close()
+                call_ms = float(np.median([marks[i].elapsed_time(marks[i + 1]) for i in range(20)]))
+                reuse_ms = float(np.median([marks[i].elapsed_time(marks[i + 1]) for i in range(20, 40)]))
+                ab = algorithmic_bytes(att)
+                flops = 4.0 * cfg.Dqk * cfg.G * cfg.T * float(att.ctx_len.sum()) * cfg.Hkv
+                rows.append({"draft": kind, "B": B, "gamma": gamma, "T": T, "rows_per_kv_head": cfg.G * cfg.T,
+                             "kernel": binding.seer_verify_attention_kernel(p), "kv_tokens": int(att.ctx_len.sum()),
+                             "call_ms": call_ms, "call_reuse_plan_ms": reuse_ms, "kernel_ms": kern,
+                             "hbm_GBps": ab["total"] / kern / 1e6, "hbm_frac": ab["total"] / kern / 1e6 / HBM_PEAK_GBPS,
+                             "TFLOPs": flops / kern / 1e9, "mfma_frac": flops / kern / 1e9 / MFMA_BF16_PEAK_TFLOPS})
+                del d, ws, out
+                torch.cuda.empty_cache()
+    print(json.dumps({"what": "seer_verify_attention on one GPU's share of a 72B-class model under TP8 (Hq=8, Hkv=1, G=8, "
+                              "D=128, page 16, groups of 16): medians of 20 calls, ms", "cells": rows}))
+    return 0
+
+
 def sweep_draft_acceptance(torch, binding, W) -> int:
     """Mean acceptance length (accepted draft tokens + the bonus token) of seer_draft's drafts against the tokens
     each request really produces next, by number of grouped references and by beam width: the measurement of the
@@ -491,6 +546,9 @@ def main() -> int:
                     help="instead of the benchmark: measure the verify step (attention + accept) of the config-2 "
                          "model shape over batch sizes and draft lengths, the T(B, gamma) table that the "
                          "draft-length policy consumes, and print it with the policy's decisions as JSON")
+    ap.add_argument("--sweep-tp8-share", action="store_true",
+                    help="instead of the benchmark: the attention call on the tensor-parallel share of a 72B-class "
+                         "model (Hq = 8, Hkv = 1, groups of 16), chains and the 4 x 8 tree, by batch size")
     ap.add_argument("--sweep-draft-acceptance", action="store_true",
                     help="instead of the benchmark: mean acceptance length of seer_draft's drafts by number of grouped "
                          "references and beam width (the measurement of the paper's Table 2, on synthetic histories)")
@@ -510,6 +568,8 @@ def main() -> int:
         return 2
     if args.sweep_step_time:
         return sweep_step_time(torch, binding, W, attention_device_inputs)
+    if args.sweep_tp8_share:
+        return sweep_tp8_share(torch, binding, W, attention_device_inputs)
     if args.sweep_draft_acceptance:
         return sweep_draft_acceptance(torch, binding, W)
     ids = [args.config] if args.config is not None else [int(x) for x in args.configs.split(",") if x.strip()]

@@ -16,7 +16,10 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "seer_oracle.c")
 _SRC_NEXT = os.path.join(_HERE, "seer_oracle_next.c")      # commit of the accepted path, sampled verification
-_LIB = os.path.join(_HERE, "libseer_oracle.so")
+# SEER_ORACLE_SANITIZE=1: the same sources under gcc's address and undefined-behaviour sanitizers (run the tests with
+# LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 so that the runtime comes first)
+_SANITIZE = os.environ.get("SEER_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "libseer_oracle_san.so" if _SANITIZE else "libseer_oracle.so")
 _lib = None
 
 _ERR = {-1: "bad shape or null pointer", -2: "ctx_len < T or more pages than the table holds",
@@ -29,6 +32,9 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + ".tmp%d" % os.getpid()
         common = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-Wall", "-Wextra"]
+        if _SANITIZE:
+            common = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-fPIC", "-Wall", "-Wextra", "-fno-omit-frame-pointer",
+                      "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
         objs = []
         # the second file decides an argmax in fp32: no contraction of a*b+c beyond the fmaf calls it writes
         for src, extra in ((_SRC, []), (_SRC_NEXT, ["-ffp-contract=off"])):

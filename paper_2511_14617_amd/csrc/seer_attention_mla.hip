@@ -7,7 +7,9 @@
 // data + expert parallelism, so each GPU sees all 128 attention heads of its own
 // requests): with T = gamma + 1 verify slots a request has 128*T query rows over
 // one latent stream, about 1200 flop per KV byte -- the kernel is bound by the
-// matrix cores (and, on this hardware, by LDS bandwidth feeding them), not HBM.
+// matrix cores and by the latency of the LDS reads that feed them (one wave per SIMD: nothing else
+// to issue while an operand is awaited), not by HBM and not by LDS bandwidth (counters: the LDS data
+// path is busy a third of the time, the matrix cores half of it).
 //
 // Work decomposition
 //   A workgroup = 4 waves = 128 query rows (wave i owns rows 32i..32i+31) of one request
@@ -20,7 +22,9 @@
 //   row XOR-swizzled by a 3-bit function of row bits 1..3 (bit 1 of the row moves the chunk by 64
 //   bytes), which spreads both read patterns below over all 64 LDS banks.
 //   S^T = K . Q^T : 36 steps of v_mfma_f32_32x32x16_bf16 (M = tokens, N = rows); K operand =
-//                   ds_read_b128, Q^T (32 rows x 576) lives in 144 VGPRs
+//                   ds_read_b128; Q^T (32 rows x 576 = 144 registers' worth per lane) is held in VGPRs for 24 of
+//                   the 36 steps, the other 12 are parked in LDS and re-read every tile (the 256 output
+//                   accumulators take the other half of the register file)
 //   softmax       : one query row per lane, as in the D = 128 kernel
 //   O^T += V^T.P^T: 16 d-tiles x 2 steps; V^T operand from the same LDS tile through the
 //                   transposing read ds_read_b64_tr_b16; O^T (32 rows x 512) = 256 accumulators
