@@ -459,11 +459,38 @@ void attn_gqa128_kernel(AttnArgs a) {
         v_rd[dt] = (lg * 4 + v_k) * kRowBytes + ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;   // token lg*4 + k
     }
 
+    // What a piece needs to know about its request comes from five small tables.  Read one after the other
+    // (each value steers the next address or a branch) that is five dependent round trips to the L2 per
+    // request boundary, several microseconds in which the workgroup has no tile in flight.  Instead one
+    // vector load fetches all five (lane i reads word i), and it is issued a whole piece ahead, together
+    // with the first 64 page ids of that next request: by the time a piece ends, the next one's plan words
+    // and page ids are in registers.
+    auto piece_words = [&](int bb) __attribute__((always_inline)) -> int {
+        const int bc = min(bb, a.B - 1);
+        const int32_t* ptr = a.tile_off + bc;
+        if (lane == 1) ptr = a.tile_off + bc + 1;
+        if (lane == 2) ptr = a.split_off + bc;
+        if (lane == 3) ptr = (L ? a.req_first : a.split_off) + bc;
+        if (lane == 4) ptr = a.ctx_len + bc;
+        return *ptr;
+    };
+    auto first_pages = [&](int bb) __attribute__((always_inline)) -> int {
+        return (a.block_table + static_cast<size_t>(min(bb, a.B - 1)) * a.max_pages)[min(lane, a.max_pages - 1)];
+    };
+    int pw = piece_words(b);
+    int pg_ahead = 0;                 // the first 64 page ids of request b, if have_ahead
+    bool have_ahead = false;
+
   for (; g < g_end; ++b) {
-    const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
+    const int t_lo = __builtin_amdgcn_readlane(pw, 0), t_hi = __builtin_amdgcn_readlane(pw, 1);
+    const int item_idx = __builtin_amdgcn_readlane(pw, 2) + (L ? wg - __builtin_amdgcn_readlane(pw, 3) : 0);
+    const int n = __builtin_amdgcn_readlane(pw, 4);
+    const int pg_first = pg_ahead;
+    const bool have_first = have_ahead;
+    pw = piece_words(b + 1);          // in flight while this piece is worked on
+    pg_ahead = first_pages(b + 1);
+    have_ahead = b + 1 < a.B;
     if (t_hi == t_lo) continue;
-    const int item_idx = uniform_load(a.split_off + b) + (L ? wg - uniform_load(a.req_first + b) : 0);
-    const int n = uniform_load(a.ctx_len + b);
     const int tok_begin = (g - t_lo) * kTile;
     const int tok_end = min(n, (min(g_end, t_hi) - t_lo) * kTile);
     g = t_hi;
@@ -481,29 +508,18 @@ void attn_gqa128_kernel(AttnArgs a) {
     if (row_ok) {
         word = a.tree_mask ? a.tree_mask[static_cast<size_t>(b) * a.T + t]
                            : (t >= 63 ? ~0ull : ((1ull << (t + 1)) - 1));
-        if (a.T < 64) word &= (1ull << a.T) - 1;
     }
+    // the query rows are requested here and awaited after the first tiles have been requested too
     bf16x8 qreg[8];
+    u32x4 qv[8];
     {
         const u32x4* qp = reinterpret_cast<const u32x4*>(
             static_cast<const uint16_t*>(a.q) + ((static_cast<size_t>(b) * a.T + t) * a.Hq + hq) * kD + lg * 8);
-        u32x4 qv[8];
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             qv[kk] = u32x4{0u, 0u, 0u, 0u};
             if (row_ok) qv[kk] = qp[kk * 2];
         }
-        // Pin the point where these loads must have returned to HERE, before the tile loop: left to
-        // itself the compiler waits for them at their first use inside the loop, with a wait that
-        // also drains the direct-to-LDS loads of the tiles in flight, on every iteration.
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            asm volatile("" : "+v"(qv[kk]));
-            qreg[kk] = as_bf16x8(qv[kk]);
-        }
-        uint32_t w_lo = static_cast<uint32_t>(word), w_hi = static_cast<uint32_t>(word >> 32);
-        asm volatile("" : "+v"(w_lo), "+v"(w_hi));
-        word = (static_cast<uint64_t>(w_hi) << 32) | w_lo;
     }
 
     f32x16 acc[4];
@@ -517,20 +533,24 @@ void attn_gqa128_kernel(AttnArgs a) {
     // With 16-token pages a tile is one even-numbered page and its successor, and windows start at even
     // pages, so one window test covers both; with larger pages a tile is 32 rows inside one page.
     const int32_t* __restrict__ table = a.block_table + static_cast<size_t>(b) * a.max_pages;
-    int cache_base = -0x40000000;
-    int pg_cache = 0;
     const int last_page = (n - 1) >> page_shift;
+    auto in_pool = [&](int pg, int idx) __attribute__((always_inline)) -> int {
+        if (pg < 0 || pg >= a.num_pages) {
+            if (idx <= last_page) bad_page = true;
+            pg = min(max(pg, 0), a.num_pages - 1);
+        }
+        return pg;
+    };
+    // a piece that starts at its request's first tile finds that window of page ids fetched ahead
+    const bool window_ahead = have_first && tok_begin == 0;
+    int cache_base = window_ahead ? 0 : -0x40000000;
+    int pg_cache = window_ahead ? in_pool(pg_first, lane) : 0;
     auto page_pair = [&](int tb, size_t& p0, size_t& p1) __attribute__((always_inline)) {
         const int lp = tb >> page_shift;
         if (lp < cache_base || lp >= cache_base + kWave) {   // uniform
             cache_base = lp;
             const int idx = cache_base + lane;
-            int pg = table[min(idx, a.max_pages - 1)];
-            if (pg < 0 || pg >= a.num_pages) {
-                if (idx <= last_page) bad_page = true;
-                pg = min(max(pg, 0), a.num_pages - 1);
-            }
-            pg_cache = pg;
+            pg_cache = in_pool(table[min(idx, a.max_pages - 1)], idx);
         }
         const int i0 = __builtin_amdgcn_readfirstlane(lp - cache_base);
         const int i1 = a.P == kMinPage ? i0 + 1 : i0;
@@ -592,6 +612,20 @@ void attn_gqa128_kernel(AttnArgs a) {
 
 #pragma unroll
     for (int j = -D; j < 0; ++j) issue_step(j);
+    {
+        // Pin the point where the query rows and the mask word must have returned to HERE, before the tile
+        // loop: left to itself the compiler waits for them at their first use inside the loop, with a wait
+        // that also drains the direct-to-LDS loads of the tiles in flight, on every iteration.
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            asm volatile("" : "+v"(qv[kk]));
+            qreg[kk] = as_bf16x8(qv[kk]);
+        }
+        uint32_t w_lo = static_cast<uint32_t>(word), w_hi = static_cast<uint32_t>(word >> 32);
+        asm volatile("" : "+v"(w_lo), "+v"(w_hi));
+        word = (static_cast<uint64_t>(w_hi) << 32) | w_lo;
+        if (a.T < 64) word &= (1ull << a.T) - 1;
+    }
 
     f32x16 s_a, s_b;
     uint32_t pk_a[8], pk_b[8];
@@ -608,7 +642,9 @@ void attn_gqa128_kernel(AttnArgs a) {
         if (tb + kTile > n) {
             unsigned char* vl = lds + kVRing + ((n_tiles - 1) % NSLOT) * kKBytes;
             const int first_bad = n - tb;
-            for (int c = tid; c < kTile * 16; c += NT)
+            int tid_here = tid;                    // (address computed here, not carried through the tile loop)
+            asm volatile("" : "+v"(tid_here));
+            for (int c = tid_here; c < kTile * 16; c += NT)
                 if ((c >> 4) >= first_bad) *reinterpret_cast<u32x4*>(vl + c * 16) = u32x4{0u, 0u, 0u, 0u};
             __builtin_amdgcn_s_waitcnt(0xc07f);    // lgkmcnt(0): the clears are done
             bare_barrier();
@@ -849,19 +885,23 @@ void attn_gqa128_kernel(AttnArgs a) {
         // direct stores.
         bare_barrier();                                  // every wave has read the last tiles
         unsigned char* st = lds + wave * 16384;
+        // (the addresses below are computed here, from a copy of the lane index the compiler cannot see through:
+        // hoisted out of the piece loop they would hold registers through the tile loop, which has none to spare)
+        int ln_here = ln;
+        asm volatile("" : "+v"(ln_here));
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
                 const int c = dt * 8 + i4 * 2 + lg;
-                *reinterpret_cast<f32x4*>(st + ln * 512 + ((c ^ ln) << 4)) = v;
+                *reinterpret_cast<f32x4*>(st + ln_here * 512 + ((c ^ ln_here) << 4)) = v;
             }
         const int first_row = rb * a.rows_per_block + wave * 32;
 #pragma unroll 2
         for (int k = 0; k < 16; ++k) {                   // (not unrolled further: sixteen rows in flight spill registers)
             const int rr = 2 * k + lg;                   // row of the wave; this lane moves chunk ln of it
-            const f32x4 v = *reinterpret_cast<const f32x4*>(st + rr * 512 + ((ln ^ rr) << 4));
+            const f32x4 v = *reinterpret_cast<const f32x4*>(st + rr * 512 + ((ln_here ^ rr) << 4));
             const int r2 = first_row + rr;
             if (r2 < R) {
                 const int t2 = r2 / a.G;
@@ -871,14 +911,16 @@ void attn_gqa128_kernel(AttnArgs a) {
             }
         }
     } else if (stores) {
+        int lg_here = lg;                                // (as above)
+        asm volatile("" : "+v"(lg_here));
         const size_t prow = (static_cast<size_t>(item_idx) * a.T + t) * a.Hq + hq;
-        float* __restrict__ po = a.part_acc + prow * kD;
+        float* __restrict__ po = a.part_acc + prow * kD + lg_here * 4;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const f32x4 v = {acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
-                store_partial(po + dt * 32 + i4 * 8 + lg * 4, v);
+                store_partial(po + dt * 32 + i4 * 8, v);
             }
     }
   }  // pieces of the stretch
