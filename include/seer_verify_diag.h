@@ -33,6 +33,15 @@ SEER_API int seer_verify_attention_timed(void* out, const void* q, const void* k
                                 size_t workspace_bytes, void* hip_stream, void* event_begin,
                                 void* event_end);
 
+/*
+ * Where in the workspace the plan of a call with these params leaves, per request, the number of leading
+ * 32-token tiles whose pages the request before or after it in the batch maps too (int32[B]; host-only
+ * arithmetic, 0 on invalid params).  The partition kernel of the D = 128 shapes reads those tiles with the
+ * cache policy that keeps them for the other requests of the prompt group; nothing that a call computes
+ * depends on it.  Tests read it back to check what the plan found.
+ */
+SEER_API size_t seer_verify_attention_shared_tiles_offset(const seer_attn_params* p);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,8 @@ SEER_OK, SEER_EINVAL, SEER_ESHAPE, SEER_EUNSUPPORTED, SEER_EWORKSPACE, SEER_EALI
 SEER_ACCEPT_STATIC_MAX_PAIRS = 131072
 
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
-           "seer_verify_attention_timed", "seer_verify_attention_kernel", "seer_accept_workspace", "seer_accept", "seer_accept_static", "seer_accept_sampled",
+           "seer_verify_attention_timed", "seer_verify_attention_kernel", "seer_verify_attention_shared_tiles_offset",
+           "seer_accept_workspace", "seer_accept", "seer_accept_static", "seer_accept_sampled",
            "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_history_append",
            "seer_strerror")
 
@@ -73,6 +74,8 @@ def load_library() -> ctypes.CDLL:
         lib.seer_verify_attention_timed.restype = ctypes.c_int
         lib.seer_verify_attention_kernel.argtypes = [ctypes.POINTER(SeerAttnParams)]
         lib.seer_verify_attention_kernel.restype = ctypes.c_char_p
+        lib.seer_verify_attention_shared_tiles_offset.argtypes = [ctypes.POINTER(SeerAttnParams)]
+        lib.seer_verify_attention_shared_tiles_offset.restype = sz
         lib.seer_accept_workspace.argtypes = [i32, i32, i32]
         lib.seer_accept_workspace.restype = sz
         lib.seer_accept.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -186,6 +189,13 @@ def seer_verify_attention_status(workspace: torch.Tensor) -> int:
     """The status word the last call on this workspace left (synchronises)."""
     off = int(load_library().seer_verify_attention_status_offset())
     return int(workspace[off:off + 4].view(torch.int32).item()) & 0xFFFFFFFF
+
+
+def seer_verify_attention_shared_tiles(workspace: torch.Tensor, params: SeerAttnParams) -> torch.Tensor:
+    """int32[B]: the leading tiles of each request that the last plan on this workspace found shared with a
+    neighbouring request (a diagnostic read-back; synchronises)."""
+    off = int(load_library().seer_verify_attention_shared_tiles_offset(ctypes.byref(params)))
+    return workspace[off:off + 4 * params.B].view(torch.int32).cpu()
 
 
 def seer_accept_workspace(B: int, T: int, V: int) -> int:

@@ -63,7 +63,7 @@ struct WorkspaceLayout {
     int max_items;
     int wgs_per_head;    // W (balanced mode) or B (one workgroup per request)
     int max_splits;
-    size_t off_header, off_split, off_tiles, off_first, off_start, off_reqfirst, off_fb, off_items, off_ml, off_acc, total;
+    size_t off_header, off_split, off_tiles, off_first, off_start, off_reqfirst, off_shared, off_fb, off_items, off_ml, off_acc, total;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -141,7 +141,8 @@ inline WorkspaceLayout workspace_layout(const seer_attn_params& p) {
     const size_t per_w = sizeof(int32_t) * (static_cast<size_t>(w.wgs_per_head) + 1);
     w.off_start = align_up(w.off_first + per_w, 256);
     w.off_reqfirst = align_up(w.off_start + per_w, 256);
-    w.off_fb = align_up(w.off_reqfirst + per_b, 256);             // time[W], tiles[W], smoothed speed[W]
+    w.off_shared = align_up(w.off_reqfirst + per_b, 256);
+    w.off_fb = align_up(w.off_shared + per_b, 256);               // time[W], tiles[W], smoothed speed[W]
     w.off_items = align_up(w.off_fb + 3 * per_w, 256);
     w.off_ml = align_up(w.off_items + sizeof(WorkItem) * static_cast<size_t>(w.max_items), 256);
     w.off_acc = align_up(w.off_ml + 2 * sizeof(float) * rows, 256);
@@ -164,6 +165,7 @@ struct AttnArgs {
     const int32_t* wg_first;    // [wgs_per_head] request in which each workgroup's stretch starts, -1 = idle
     const int32_t* wg_start;    // [wgs_per_head + 1] first tile of each stretch on the tile line (balanced mode)
     const int32_t* req_first;   // [B] first stretch that touches each request (balanced mode)
+    const int32_t* shared_tiles;  // [B] leading tiles of each request whose pages a neighbouring request maps too
     uint32_t* fb_time;          // [wgs_per_head] sum over KV heads of the workgroup's duration, 10 ns ticks
     uint32_t* fb_tiles;         // [wgs_per_head] sum over KV heads of the tiles it streamed
     float* fb_speed;            // [wgs_per_head] smoothed tiles per tick (owned by the plan kernel)

@@ -25,13 +25,15 @@ constexpr int kPlanThreads = 256;
 
 struct PlanArgs {
     const int32_t* ctx_len;
-    int B, T, max_ctx, wgs_per_head, max_splits, max_items, fixed_split;
+    const int32_t* block_table;
+    int B, T, max_ctx, wgs_per_head, max_splits, max_items, fixed_split, max_pages, page_size;
     PlanHeader* header;
     int32_t* split_off;
     int32_t* tile_off;
     int32_t* wg_first;
     int32_t* wg_start;
     int32_t* req_first;
+    int32_t* shared_tiles;
     uint32_t* fb_time;
     uint32_t* fb_tiles;
     float* fb_speed;
@@ -102,6 +104,62 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         if (n < p.T || n > p.max_ctx) return 0;   // flagged, gets a zero output
         return (n + kPlanTile - 1) / kPlanTile;
     };
+
+    // 0. Leading pages that a request has in common with the request before or after it (the prompt that the
+    // rollouts of a group share sits in the same physical pages).  The partition kernel loads such tiles with
+    // the cache policy that keeps them, so that the repeats are served by the memory-side cache; this is a
+    // hint only, results do not depend on it, so the length of the common run is found by probing instead of
+    // comparing every entry: sixteen entries at doubling distances, then sixteen evenly spaced ones between
+    // the last equal probe and the first unequal one (two dependent rounds of loads; exact up to 16 pages past
+    // a power of two, a lower bound otherwise if the tables are equal up to a point and differ behind it).
+    for (int b = b0; b < b1; ++b) {
+        const int n = p.ctx_len[b];
+        int best = 0;
+        if (n >= p.T && n <= p.max_ctx) {
+            const int32_t* mine = p.block_table + static_cast<size_t>(b) * p.max_pages;
+            const int pages = (n + p.page_size - 1) / p.page_size;
+            int m[2] = {0, 0};                 // entries that can be compared with the neighbour
+            const int32_t* other[2] = {mine, mine};
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int nb = s ? b + 1 : b - 1;
+                if (nb < 0 || nb >= p.B) continue;
+                const int nn = p.ctx_len[nb];
+                if (nn < p.T || nn > p.max_ctx) continue;
+                m[s] = min(pages, (nn + p.page_size - 1) / p.page_size);
+                other[s] = p.block_table + static_cast<size_t>(nb) * p.max_pages;
+            }
+            uint32_t eq[2] = {0u, 0u};        // bit k: probe k found equal entries
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const int i = (1 << k) - 1;
+                    const int ic = min(i, max(m[s] - 1, 0));
+                    eq[s] |= static_cast<uint32_t>((i < m[s]) & (mine[ic] == other[s][ic])) << k;
+                }
+            int lo[2], step[2], hi[2];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int k = __builtin_ctz(~eq[s]);          // first probe that differs or lies outside (<= 16)
+                lo[s] = k ? (1 << (k - 1)) : 0;               // number of leading entries taken as equal
+                hi[s] = k ? min((1 << k) - 1, m[s]) : 0;      // entry hi differs or does not exist
+                step[s] = max(1, (hi[s] - lo[s] + 15) / 16);
+                eq[s] = 0u;
+            }
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int i = lo[s] + (j + 1) * step[s] - 1;
+                    const int ic = min(i, max(m[s] - 1, 0));
+                    eq[s] |= static_cast<uint32_t>((i < hi[s]) & (mine[ic] == other[s][ic])) << j;
+                }
+#pragma unroll
+            for (int s = 0; s < 2; ++s) best = max(best, min(lo[s] + __builtin_ctz(~eq[s]) * step[s], hi[s]));
+        }
+        p.shared_tiles[b] = static_cast<int>(static_cast<long long>(best) * p.page_size / kPlanTile);
+    }
 
     // 1. tile line: exclusive prefix of tiles per request, and the longest request
     int cnt = 0, mx = 0, bad = 0;
@@ -263,6 +321,10 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
     const long long max_ctx_ll = static_cast<long long>(a.max_pages) * a.P;
     PlanArgs p;
     p.ctx_len = a.ctx_len;
+    p.block_table = a.block_table;
+    p.max_pages = a.max_pages;
+    p.page_size = a.P;
+    p.shared_tiles = const_cast<int32_t*>(a.shared_tiles);
     p.B = a.B;
     p.T = a.T;
     p.max_ctx = max_ctx_ll > 0x7fffffffLL - kPlanTile ? 0x7fffffff - kPlanTile : static_cast<int>(max_ctx_ll);
@@ -531,6 +593,11 @@ extern "C" size_t seer_verify_attention_workspace(const seer_attn_params* p) {
 
 extern "C" size_t seer_verify_attention_status_offset(void) { return offsetof(seer::PlanHeader, status); }
 
+extern "C" size_t seer_verify_attention_shared_tiles_offset(const seer_attn_params* p) {
+    if (validate_params(p) != SEER_OK || p->B == 0) return 0;
+    return seer::workspace_layout(*p).off_shared;
+}
+
 extern "C" const char* seer_verify_attention_kernel(const seer_attn_params* p) {
     if (validate_params(p) != SEER_OK) return nullptr;
     // the same tests, on the same fields, as the dispatch in run_verify_attention
@@ -593,6 +660,7 @@ int run_verify_attention(void* out, const void* q, const void* k_pages, const vo
     a.wg_first = reinterpret_cast<const int32_t*>(ws + w.off_first);
     a.wg_start = reinterpret_cast<const int32_t*>(ws + w.off_start);
     a.req_first = reinterpret_cast<const int32_t*>(ws + w.off_reqfirst);
+    a.shared_tiles = reinterpret_cast<const int32_t*>(ws + w.off_shared);
     a.fb_time = reinterpret_cast<uint32_t*>(ws + w.off_fb);
     a.fb_tiles = a.fb_time + (w.wgs_per_head + 1);
     a.fb_speed = reinterpret_cast<float*>(a.fb_tiles + (w.wgs_per_head + 1));

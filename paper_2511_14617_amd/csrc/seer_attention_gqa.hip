@@ -89,7 +89,7 @@ template <> struct Loaders<5> { static constexpr int kFirst = 1, kCount = 3; };
 constexpr int kTileLoadPolicy = 2;   // the "nt" bit of the instruction's cache-policy field
 
 // Loads of one half tile (K or V): its 8 one-KB blocks dealt round-robin to the loading waves.
-template <int NW>
+template <int NW, int POLICY = kTileLoadPolicy>
 __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, size_t p0, size_t p1,
                                                 const unsigned char* base, int goff, bool is_k) {
     constexpr int NL = Loaders<NW>::kCount;
@@ -102,7 +102,7 @@ __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, s
             const size_t pg = (j < 4) ? p0 : p1;
             const int lane_off = is_k ? goff ^ ((j & 3) << 6) : goff;   // K rows 4j + l16: f = 4(j & 3) + l16
             const unsigned char* src = base + pg + (j & 3) * (4 * kRowBytes) + lane_off;
-            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(slot + j * 1024), 16, 0, kTileLoadPolicy);
+            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src), (SEER_AS3 void*)(slot + j * 1024), 16, 0, POLICY);
         }
     }
 }
@@ -283,7 +283,7 @@ __device__ __forceinline__ void pipe_step(const unsigned char* lds, int k_off, i
 // issue_k / issue_v issue the step's HBM loads; they are called where their scalar address
 // arithmetic runs in the shadow of LDS reads already issued and of MFMAs already queued.
 //
-// The slots read are at byte offsets K_IMM + k_off (K ring) and V_IMM + v_off (V ring); in the
+// The slots read are at byte offsets K_IMM + k_off (K ring) and V_IMM + v_off (V ring, whose base is in v_rd); in the
 // unrolled steady state the runtime parts are zero and the slot is an instruction immediate.
 template <bool MASKED, int K_IMM, int V_IMM, typename IssueK, typename IssueV>
 __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_rd)[8], const int (&v_rd)[4],
@@ -456,7 +456,9 @@ void attn_gqa128_kernel(AttnArgs a) {
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
         const int chunk = dt * 4 + v_dhalf * 2 + (v_c4 >> 1);
-        v_rd[dt] = (lg * 4 + v_k) * kRowBytes + ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;   // token lg*4 + k
+        // token lg*4 + k; the V ring's place behind the K ring is part of the lane address, so that the slot
+        // offsets of both rings fit the 16-bit immediates of the LDS reads for rings of up to 8 slots
+        v_rd[dt] = kVRing + (lg * 4 + v_k) * kRowBytes + ((chunk ^ v_swz(v_k)) << 4) + (v_c4 & 1) * 8;
     }
 
     // What a piece needs to know about its request comes from five small tables.  Read one after the other
@@ -472,6 +474,7 @@ void attn_gqa128_kernel(AttnArgs a) {
         if (lane == 2) ptr = a.split_off + bc;
         if (lane == 3) ptr = (L ? a.req_first : a.split_off) + bc;
         if (lane == 4) ptr = a.ctx_len + bc;
+        if (lane == 5) ptr = a.shared_tiles + bc;
         return *ptr;
     };
     auto first_pages = [&](int bb) __attribute__((always_inline)) -> int {
@@ -485,6 +488,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     const int t_lo = __builtin_amdgcn_readlane(pw, 0), t_hi = __builtin_amdgcn_readlane(pw, 1);
     const int item_idx = __builtin_amdgcn_readlane(pw, 2) + (L ? wg - __builtin_amdgcn_readlane(pw, 3) : 0);
     const int n = __builtin_amdgcn_readlane(pw, 4);
+    const int shared_tiles = __builtin_amdgcn_readlane(pw, 5);
     const int pg_first = pg_ahead;
     const bool have_first = have_ahead;
     pw = piece_words(b + 1);          // in flight while this piece is worked on
@@ -564,21 +568,34 @@ void attn_gqa128_kernel(AttnArgs a) {
     // the same pages of its pool as the K tile issued two steps earlier, whose offsets are kept.
     size_t pq0 = 0, pq1 = 0, pr0 = 0, pr1 = 0;     // page offsets of the K tiles of steps j - 1 and j - 2
     size_t pn0 = 0, pn1 = 0;
-    auto issue_k_at = [&](int kt, int slot_bytes) __attribute__((always_inline)) {
+    // Tiles that a neighbouring request reads too (the plan's shared_tiles: a leading run of the request) are
+    // loaded with the default cache policy, which keeps them in the memory-side cache for the repeats; all
+    // other tiles are read once and stream past the caches.  The policy is an instruction immediate, so a
+    // load site either streams or decides per tile with a scalar branch.
+    const int keep_until = shared_tiles - tok_begin / kTile;   // tiles of this piece below this index are kept
+    using StreamLoads = std::false_type;
+    using CheckLoads = std::true_type;
+    auto issue_k_at = [&](int kt, int slot_bytes, auto mode) __attribute__((always_inline)) {
         page_pair(tok_begin + kt * kTile, pn0, pn1);
-        issue_half_tile<NWT>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
+        if (decltype(mode)::value && kt < keep_until)
+            issue_half_tile<NWT, 0>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
+        else
+            issue_half_tile<NWT>(lds + slot_bytes, wave, pn0, pn1, kbase, goff_k0, true);
     };
-    auto issue_v_at = [&](int slot_bytes) __attribute__((always_inline)) {
-        issue_half_tile<NWT>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
+    auto issue_v_at = [&](int vt, int slot_bytes, auto mode) __attribute__((always_inline)) {
+        if (decltype(mode)::value && vt < keep_until)
+            issue_half_tile<NWT, 0>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
+        else
+            issue_half_tile<NWT>(lds + kVRing + slot_bytes, wave, pr0, pr1, vbase, goff_v, false);
     };
     auto shift_pages = [&]() __attribute__((always_inline)) { pr0 = pq0, pr1 = pq1, pq0 = pn0, pq1 = pn1; };
     auto issue_k = [&](int j) __attribute__((always_inline)) {
         const int kt = j + D;
-        if (kt < n_tiles) issue_k_at(kt, (kt % NSLOT) * kKBytes);
+        if (kt < n_tiles) issue_k_at(kt, (kt % NSLOT) * kKBytes, CheckLoads{});
     };
     auto issue_v = [&](int j) __attribute__((always_inline)) {
         const int vt = j + D - 2;
-        if (vt >= 0 && vt < n_tiles) issue_v_at((vt % NSLOT) * kKBytes);
+        if (vt >= 0 && vt < n_tiles) issue_v_at(vt, (vt % NSLOT) * kKBytes, CheckLoads{});
         shift_pages();
     };
     auto issue_step = [&](int j) __attribute__((always_inline)) {
@@ -607,7 +624,7 @@ void attn_gqa128_kernel(AttnArgs a) {
     };
     auto k_off = [&](int j) __attribute__((always_inline)) -> int { return (j % NSLOT) * kKBytes; };
     auto v_off = [&](int j) __attribute__((always_inline)) -> int {
-        return kVRing + (j % NSLOT) * kKBytes;
+        return (j % NSLOT) * kKBytes;              // (v_rd holds the ring's base)
     };
 
 #pragma unroll
@@ -737,7 +754,7 @@ void attn_gqa128_kernel(AttnArgs a) {
         // the compile-time one, and (u = 2 mod NSLOT at the start of a group) every ring slot is
         // known at compile time.
         constexpr int P = NSLOT % 2 == 0 ? NSLOT : 2 * NSLOT;
-        auto steady_step = [&](auto ic) __attribute__((always_inline)) {
+        auto steady_step = [&](auto ic, auto mode) __attribute__((always_inline)) {
             constexpr int I = decltype(ic)::value;
             constexpr int kReadSlot = (2 + I) % NSLOT, kVReadSlot = I % NSLOT;
             constexpr int kIssueSlot = (1 + I) % NSLOT, kVIssueSlot = (I + NSLOT - 1) % NSLOT;
@@ -745,25 +762,32 @@ void attn_gqa128_kernel(AttnArgs a) {
             else wait_vmcnt<(D - 1) * 2 * FLOOR>();
             bare_barrier();
             const int uu = u + I;
-            auto ik = [&]() __attribute__((always_inline)) { issue_k_at(uu + D, kIssueSlot * kKBytes); };
+            auto ik = [&]() __attribute__((always_inline)) { issue_k_at(uu + D, kIssueSlot * kKBytes, mode); };
             auto iv = [&]() __attribute__((always_inline)) {
-                issue_v_at(kVIssueSlot * kKBytes);
+                issue_v_at(uu + D - 2, kVIssueSlot * kKBytes, mode);
                 shift_pages();
             };
             if constexpr (STREAM) {
                 ik();
                 iv();
             } else if constexpr (I % 2 == 0)
-                fused_step<false, kReadSlot * kKBytes, kVRing + kVReadSlot * kKBytes>(
+                fused_step<false, kReadSlot * kKBytes, kVReadSlot * kKBytes>(
                     0, 0, k_rd, v_rd, qreg, s_b, s_a, pk_a, pk_b, acc, m_run, l_run, alpha, a.scale_log2, 0u, ik, iv);
             else
-                fused_step<false, kReadSlot * kKBytes, kVRing + kVReadSlot * kKBytes>(
+                fused_step<false, kReadSlot * kKBytes, kVReadSlot * kKBytes>(
                     0, 0, k_rd, v_rd, qreg, s_a, s_b, pk_b, pk_a, acc, m_run, l_run, alpha, a.scale_log2, 0u, ik, iv);
         };
-        if constexpr (kVRing + NSLOT * kKBytes <= 65536) {
-            const int u_steady_end = min(u_split, n_tiles - D);
-            for (; u + P <= u_steady_end; u += P) for_each_index(steady_step, std::make_integer_sequence<int, P>{});
-        }
+        auto steady_checking = [&](auto ic) __attribute__((always_inline)) { steady_step(ic, CheckLoads{}); };
+        auto steady_streaming = [&](auto ic) __attribute__((always_inline)) { steady_step(ic, StreamLoads{}); };
+        constexpr bool kUnrolled = NSLOT * kKBytes <= 65536;
+        const int u_steady_end = min(u_split, n_tiles - D);
+        // groups that may still load a kept tile (the oldest tile a group loads is V tile u + D - 2) decide per
+        // tile; behind the kept run every load streams
+        if constexpr (kUnrolled)
+            for (; u + P <= u_steady_end && u + D - 2 < keep_until; u += P)
+                for_each_index(steady_checking, std::make_integer_sequence<int, P>{});
+        if constexpr (kUnrolled)
+            for (; u + P <= u_steady_end; u += P) for_each_index(steady_streaming, std::make_integer_sequence<int, P>{});
         for (; u + 1 < u_split; u += 2) {
             full_step(std::false_type{}, u, s_b, s_a, pk_a, pk_b);
             full_step(std::false_type{}, u + 1, s_a, s_b, pk_b, pk_a);
@@ -941,6 +965,10 @@ bool gqa128_supports(const AttnArgs& a) {
 // Four main waves and four helpers instead of five waves: 129 .. 144 query rows per KV head in one row block
 // (a fifth wave would hold at most half of its rows).
 bool gqa128_uses_helpers(int rows, int row_blocks) { return row_blocks == 1 && rows > 128 && rows <= 144; }
+#ifndef SEER_HELPER_DEPTH
+#define SEER_HELPER_DEPTH 3
+#endif
+constexpr int kHelperDepth = SEER_HELPER_DEPTH;
 
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int nw = a.rows_per_block / 32;
@@ -948,10 +976,10 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
                     static_cast<unsigned>(a.row_blocks));
     if (gqa128_uses_helpers(a.G * a.T, a.row_blocks)) {
         const dim3 block(8 * kWave);
-        if (a.stream_only && a.stream_partials) hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, true, true, 4>), grid, block, 0, stream, a);
-        else if (a.stream_only) hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, true, false, 4>), grid, block, 0, stream, a);
-        else if (a.stream_partials) hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, false, true, 4>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((attn_gqa128_kernel<4, 3, false, false, 4>), grid, block, 0, stream, a);
+        if (a.stream_only && a.stream_partials) hipLaunchKernelGGL((attn_gqa128_kernel<4, kHelperDepth, true, true, 4>), grid, block, 0, stream, a);
+        else if (a.stream_only) hipLaunchKernelGGL((attn_gqa128_kernel<4, kHelperDepth, true, false, 4>), grid, block, 0, stream, a);
+        else if (a.stream_partials) hipLaunchKernelGGL((attn_gqa128_kernel<4, kHelperDepth, false, true, 4>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((attn_gqa128_kernel<4, kHelperDepth, false, false, 4>), grid, block, 0, stream, a);
         return hipGetLastError();
     }
     switch (nw) {

@@ -67,6 +67,12 @@ CASES = {
     # more than 256 query rows per KV head: the tiled kernel cuts them into row blocks (528 rows -> 3 blocks)
     "rows528_G16_T33": (W.CONFIGS[5].scaled(B=3, group_size=3, Hq=32, Hkv=2, ctx=("uniform", 200, 1500),
                                             shared_prefix=0), {"dedup_fraction": 0.3}),
+    # prompt pages shared inside a group over more than one 64-page window of the block table, with stretch
+    # borders inside the shared run (tiles of the run are loaded under another cache policy than the rest)
+    "shared_prompt_1100": (W.CONFIGS[2].scaled(B=6, group_size=3, ctx=("uniform", 1200, 3000), shared_prefix=1100), {}),
+    "shared_prompt_rows100": (W.CONFIGS[2].scaled(B=4, group_size=2, T=25, ctx=("uniform", 800, 2000), shared_prefix=700), {}),
+    "shared_prompt_tree_helpers": (W.CONFIGS[5].scaled(B=4, group_size=4, ctx=("uniform", 1300, 2500), shared_prefix=1200),
+                                   {"dedup_fraction": 0.3}),
     # larger pages with the tiled D = 128 kernel (a 32-token tile lies inside one page)
     "d128_page64": (W.CONFIGS[2].scaled(B=5, group_size=5, page_size=64, ctx=("uniform", 9, 1500), shared_prefix=128), {}),
     "d128_page256_tree": (W.CONFIGS[5].scaled(B=4, group_size=4, page_size=256, ctx=("uniform", 33, 1200),
@@ -110,6 +116,54 @@ def test_parity_small_general_kernel(name):
     ref = _oracle(inp)
     out = _gpu(inp, flags=binding.SEER_ATTN_GENERAL_KERNEL)
     assert_attention_close(out, ref, name + "/general", hardened=True)
+
+
+@pytest.mark.parametrize("name", ["shared_prompt_1100", "shared_prompt_rows100", "shared_prompt_tree_helpers"])
+def test_shared_prompt_long_pieces(name):
+    """Few, long pieces (a cap of two pieces per request): the unrolled steady state of the tiled kernel runs through
+    the shared run of tiles and out of it."""
+    cfg, kw = CASES[name]
+    inp = W.make_attention_inputs(cfg, values="peaked", **kw)
+    ref = _oracle(inp)
+    out = _gpu(inp, max_splits=2)
+    assert_attention_close(out, ref, name + "/two pieces", hardened=True, ref_abs=_oracle_abs(inp))
+
+
+def _leading_common_pages(inp):
+    """Per request: the longest run of leading block-table entries equal to those of the request before or after it."""
+    P, n = inp.cfg.page_size, inp.ctx_len
+    pages = (n + P - 1) // P
+    best = np.zeros(len(n), dtype=np.int64)
+    for b in range(len(n)):
+        for nb in (b - 1, b + 1):
+            if 0 <= nb < len(n):
+                m = int(min(pages[b], pages[nb]))
+                same = inp.block_table[b, :m] == inp.block_table[nb, :m]
+                best[b] = max(best[b], m if same.all() else int(np.argmin(same)))
+    return best
+
+
+@pytest.mark.parametrize("prefix", [0, 16, 32, 48, 272, 512, 528, 1040, 4240, 16400])
+def test_plan_finds_the_pages_a_group_shares(prefix):
+    """The plan's count of leading tiles that a neighbouring request maps too (a cache-policy hint for the tiled
+    kernel) against a direct comparison of the block tables: exact for runs of up to 32 pages, else short by less
+    than a sixteenth of the run (it probes 16 + 16 entries), never long."""
+    from paper_2511_14617_amd import binding
+    cfg = W.CONFIGS[2].scaled(B=7, group_size=3, Hq=4, Hkv=1, ctx=("uniform", prefix + 9, prefix + 700), shared_prefix=prefix)
+    inp = W.make_attention_inputs(cfg)
+    d = attention_device_inputs(inp)
+    p = binding.attn_params(d["q"], d["k_pages"], d["v_pages"], d["block_table"], inp.scale, Dv=cfg.Dv)
+    ws = torch.zeros(binding.seer_verify_attention_workspace(p), dtype=torch.uint8, device="cuda")
+    binding.seer_verify_attention(d["q"], d["k_pages"], d["v_pages"], d["block_table"], d["ctx_len"], d["tree_mask"],
+                                  inp.scale, Dv=cfg.Dv, workspace=ws)
+    got = binding.seer_verify_attention_shared_tiles(ws, p).numpy().astype(np.int64)
+    true_pages = _leading_common_pages(inp)
+    if prefix >= cfg.page_size:
+        assert true_pages.max() >= prefix // cfg.page_size     # the generator did share the prompt's pages
+    per_tile = 32 // cfg.page_size
+    assert (got <= true_pages // per_tile).all(), (got, true_pages)
+    slack = np.where(true_pages <= 32, 0, (true_pages + 15) // 16)
+    assert (got >= (true_pages - slack) // per_tile).all(), (got, true_pages)
 
 
 def test_split_invariance_and_split_cap():
