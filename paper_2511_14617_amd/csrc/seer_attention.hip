@@ -19,7 +19,8 @@ namespace seer {
 
 // ---------------------------------------------------------------------------
 // Plan: one workgroup turns ctx_len[B] into the tile line, the stretch of every
-// partition workgroup, and the table of (request, stretch) pieces.
+// partition workgroup, and the table of (request, stretch) pieces; a second one,
+// beside it, compares neighbouring block-table rows (plan_shared_pages).
 // ---------------------------------------------------------------------------
 constexpr int kPlanThreads = 256;
 
@@ -89,30 +90,16 @@ __device__ __forceinline__ int plan_max(int v, int* s_tmp) {
     return m;
 }
 
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
-    __shared__ int s_tmp[2 * kPlanThreads / kWave];
-    __shared__ int s_start[kMaxWgsPerHead + 1];
-    const int tid = threadIdx.x;
-    const int W = p.wgs_per_head;
-    for (int w = tid; w < W; w += kPlanThreads) p.wg_first[w] = -1;
-
-    // thread `tid` owns a contiguous run of requests
-    const int per = (p.B + kPlanThreads - 1) / kPlanThreads;
-    const int b0 = min(p.B, tid * per), b1 = min(p.B, b0 + per);
-    auto tiles_of = [&](int b) -> int {
-        const int n = p.ctx_len[b];
-        if (n < p.T || n > p.max_ctx) return 0;   // flagged, gets a zero output
-        return (n + kPlanTile - 1) / kPlanTile;
-    };
-
-    // 0. Leading pages that a request has in common with the request before or after it (the prompt that the
-    // rollouts of a group share sits in the same physical pages).  The partition kernel loads such tiles with
-    // the cache policy that keeps them, so that the repeats are served by the memory-side cache; this is a
-    // hint only, results do not depend on it, so the length of the common run is found by probing instead of
-    // comparing every entry: sixteen entries at doubling distances, then sixteen evenly spaced ones between
-    // the last equal probe and the first unequal one (two dependent rounds of loads; exact up to 16 pages past
-    // a power of two, a lower bound otherwise if the tables are equal up to a point and differ behind it).
-    for (int b = b0; b < b1; ++b) {
+// The plan's second workgroup.  Leading pages that a request has in common with the request before or after it
+// (the prompt that the rollouts of a group share sits in the same physical pages): the partition kernel loads such
+// tiles with the cache policy that keeps them, so that the repeats are served by the memory-side cache.  This is a
+// hint only, results do not depend on it, so the length of the common run is found by probing instead of comparing
+// every entry: sixteen entries at doubling distances, then sixteen evenly spaced ones between the last equal probe
+// and the first unequal one (two dependent rounds of loads; exact for runs of up to 32 pages, else short by less
+// than a sixteenth of the run if the tables are equal up to a point and differ behind it).  It runs beside the
+// first workgroup, which needs about as long for the tile line and the stretches.
+__device__ __forceinline__ void plan_shared_pages(const PlanArgs& p) {
+    for (int b = threadIdx.x; b < p.B; b += kPlanThreads) {
         const int n = p.ctx_len[b];
         int best = 0;
         if (n >= p.T && n <= p.max_ctx) {
@@ -160,6 +147,27 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
         }
         p.shared_tiles[b] = static_cast<int>(static_cast<long long>(best) * p.page_size / kPlanTile);
     }
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs p) {
+    if (blockIdx.x == 1) {
+        plan_shared_pages(p);
+        return;
+    }
+    __shared__ int s_tmp[2 * kPlanThreads / kWave];
+    __shared__ int s_start[kMaxWgsPerHead + 1];
+    const int tid = threadIdx.x;
+    const int W = p.wgs_per_head;
+    for (int w = tid; w < W; w += kPlanThreads) p.wg_first[w] = -1;
+
+    // thread `tid` owns a contiguous run of requests
+    const int per = (p.B + kPlanThreads - 1) / kPlanThreads;
+    const int b0 = min(p.B, tid * per), b1 = min(p.B, b0 + per);
+    auto tiles_of = [&](int b) -> int {
+        const int n = p.ctx_len[b];
+        if (n < p.T || n > p.max_ctx) return 0;   // flagged, gets a zero output
+        return (n + kPlanTile - 1) / kPlanTile;
+    };
 
     // 1. tile line: exclusive prefix of tiles per request, and the longest request
     int cnt = 0, mx = 0, bad = 0;
@@ -342,7 +350,7 @@ hipError_t launch_plan(const AttnArgs& a, const WorkspaceLayout& w, hipStream_t 
     p.fb_speed = a.fb_speed;
     p.fixed_split = a.fixed_split;
     p.items = const_cast<WorkItem*>(a.items);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);
+    hipLaunchKernelGGL(plan_kernel, dim3(2), dim3(kPlanThreads), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -136,7 +136,9 @@ __device__ __forceinline__ void issue_half_tile(unsigned char* slot, int wave, s
 __device__ __forceinline__ float max_across_halves(float x) {
     float a = x, b = x;
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-    return fmaxf(a, b);
+    float m;
+    asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(a), "v"(b));   // (fmaxf would first quieten both operands: two more instructions)
+    return m;
 }
 
 // Softmax bookkeeping of one tile for this lane's row, from the row's raw score maximum mx_raw
@@ -231,8 +233,8 @@ __device__ __forceinline__ void pipe_step(const unsigned char* lds, int k_off, i
         for (int i = 0; i < 16; i += 2) {
             const float p0 = fast_exp2(fmaf(s_sm[i], scale_log2, -m_use));
             const float p1 = fast_exp2(fmaf(s_sm[i + 1], scale_log2, -m_use));
-            psum += p0 + p1;
             pk_sm[i >> 1] = cvt_pk_bf16(p0, p1);
+            psum = add_bf16_pair(pk_sm[i >> 1], psum);
         }
         l_run = l_run * alpha + psum;
     }
@@ -328,13 +330,19 @@ __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_r
     // ---- MFMAs 4..7: P.V on tokens 16..31 | exponent reference, first two pairs of probabilities
     const bf16x8 pb1 = as_bf16x8(u32x4{pk_pv[4], pk_pv[5], pk_pv[6], pk_pv[7]});
     float m_use = 0.f, psum = 0.f;
+    // One pair of probabilities: scaled differences, exponentials, then the sum of the PREVIOUS pair (an
+    // instruction that does not depend on the exponentials just issued, which need one more cycle before a
+    // plain vector instruction may read them), then the packing of this pair.
     auto pair = [&](int i) __attribute__((always_inline)) {
-        const float p0 = fast_exp2(fmaf(s_sm[2 * i], scale_log2, -m_use));
-        const float p1 = fast_exp2(fmaf(s_sm[2 * i + 1], scale_log2, -m_use));
-        psum += p0 + p1;
+        float p0 = fast_exp2(fmaf(s_sm[2 * i], scale_log2, -m_use));
+        float p1 = fast_exp2(fmaf(s_sm[2 * i + 1], scale_log2, -m_use));
+        asm volatile("" : "+v"(p0), "+v"(p1));
+        if (i > 0) {
+            psum = add_bf16_pair(pk_sm[i - 1], psum);
+            SEER_PIN(psum);
+        }
         pk_sm[i] = cvt_pk_bf16(p0, p1);
         SEER_PIN(pk_sm[i]);
-        SEER_PIN(psum);
     };
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
@@ -372,6 +380,7 @@ __device__ __forceinline__ void fused_step(int k_off, int v_off, const int (&k_r
         s_qk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kb[kk]), qreg[4 + kk], s_qk, 0, 0, 0);
         if (kk < 2) pair(6 + kk);
         if (kk == 2) {
+            psum = add_bf16_pair(pk_sm[7], psum);
             l_run = l_run * alpha + psum;
             SEER_PIN(l_run);
         }

@@ -190,15 +190,19 @@ __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 
         constexpr int i = decltype(ic)::value;
         if constexpr (DO_SM) {
             const float p = fast_exp2(fmaf(s_old[i], scale_log2, -m_use));
-            psum += p;
             if constexpr (i % 2 == 0) {
                 p_even = p;
                 SEER_MLA_PIN(p_even);
+                // the sum takes the probabilities as the P.V product will see them, a pair per instruction,
+                // one pair behind (not right after the packing that produces its operand)
+                if constexpr (i >= 2) {
+                    psum = add_bf16_pair(pk[(i >> 1) - 1], psum);
+                    SEER_MLA_PIN(psum);
+                }
             } else {
                 pk[i >> 1] = cvt_pk_bf16(p_even, p);
                 SEER_MLA_PIN(pk[i >> 1]);
             }
-            SEER_MLA_PIN(psum);
         }
     };
     SEER_MLA_FENCE();
@@ -221,6 +225,7 @@ __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 
         for_each_index(element, std::make_integer_sequence<int, 16>{});
     }
     if constexpr (DO_SM) {
+        psum = add_bf16_pair(pk[7], psum);
         l_run = l_run * alpha + psum;
         SEER_MLA_PIN(l_run);
     }

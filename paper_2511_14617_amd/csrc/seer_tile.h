@@ -24,6 +24,13 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// acc + lo + hi of a packed pair of bf16 values, in fp32 (v_dot2_f32_bf16 against the pair (1, 1)): the sum of
+// the probabilities exactly as the P.V matrix product will see them, in one instruction per pair.
+__device__ __forceinline__ float add_bf16_pair(uint32_t pair, float acc) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
+
 // s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
 // expcnt 6:4 and lgkmcnt 11:8 left at "do not wait").
 template <int N>
