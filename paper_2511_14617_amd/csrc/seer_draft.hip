@@ -847,6 +847,35 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
                 key[u] = ok[u] && !outside[u] ? (static_cast<uint32_t>(r) << 24) | static_cast<uint32_t>(t[u]) : kEmpty;
             }
         };
+        // A level of up to 8 places per thread is fetched once (two dependent round trips) and kept in registers
+        // for the three passes below (agreement, counting, reassignment); longer levels are fetched pass by pass.
+        constexpr int kHeld = 8;
+        const bool held = n_level <= kHeld * kThreads;
+        uint32_t hpl[kHeld], hkey[kHeld];
+        bool hout[kHeld];
+        if (held) {
+            keys_of(0, *reinterpret_cast<uint32_t(*)[4]>(&hpl[0]), *reinterpret_cast<uint32_t(*)[4]>(&hkey[0]),
+                    *reinterpret_cast<bool(*)[4]>(&hout[0]));
+            keys_of(4 * kThreads, *reinterpret_cast<uint32_t(*)[4]>(&hpl[4]), *reinterpret_cast<uint32_t(*)[4]>(&hkey[4]),
+                    *reinterpret_cast<bool(*)[4]>(&hout[4]));
+        }
+        // f(round, places, keys, outside) for every round of four places per thread
+        auto for_each_round = [&](auto&& f) {
+            if (held) {
+                f(0, *reinterpret_cast<uint32_t(*)[4]>(&hpl[0]), *reinterpret_cast<uint32_t(*)[4]>(&hkey[0]),
+                  *reinterpret_cast<bool(*)[4]>(&hout[0]));
+                if (n_level > 4 * kThreads)
+                    f(1, *reinterpret_cast<uint32_t(*)[4]>(&hpl[4]), *reinterpret_cast<uint32_t(*)[4]>(&hkey[4]),
+                      *reinterpret_cast<bool(*)[4]>(&hout[4]));
+            } else {
+                for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
+                    uint32_t pl[4], key[4];
+                    bool outside[4];
+                    keys_of(e0, pl, key, outside);
+                    f(e0 / (4 * kThreads), pl, key, outside);
+                }
+            }
+        };
         // A single member whose places all show the same token (inside a phrase that recurs): one pass finds
         // that out and counts them; the place list stays as it is (places whose sequence ended stay ended).
         if (nmem == 1) {
@@ -854,11 +883,8 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
             __syncthreads();
             bool agree = true;
             int wave_count = 0;
-            for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
-                uint32_t pl[4], key[4];
-                bool outside[4];
-                keys_of(e0, pl, key, outside);
-                if (e0 == 0) {                     // any token of the first round serves as the reference
+            for_each_round([&](int round, uint32_t (&pl)[4], uint32_t (&key)[4], bool (&outside)[4]) {
+                if (round == 0) {                  // any token of the first round serves as the reference
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
                         if (key[u] != kEmpty) x.ref[0] = static_cast<int>(key[u] & 0xffffffu);
@@ -871,7 +897,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
                     if (key[u] != kEmpty && static_cast<int>(key[u] & 0xffffffu) != ref) agree = false;
                     wave_count += __popcll(__ballot(key[u] != kEmpty));
                 }
-            }
+            });
             if (lane_id() == 0 && wave_count) atomicAdd(&x.ref_cnt[0], wave_count);
             if (__syncthreads_and(agree ? 1 : 0)) {
                 const int c = x.ref_cnt[0];
@@ -900,10 +926,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
             if (tid == 0) x.overflow = 0;
             __syncthreads();
             const int lo_tok = (pass - 1) * range;
-            for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
-                uint32_t pl[4], key[4];
-                bool outside[4];
-                keys_of(e0, pl, key, outside);
+            for_each_round([&](int, uint32_t (&pl)[4], uint32_t (&key)[4], bool (&outside)[4]) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (hashed) {
@@ -917,7 +940,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
                         }
                     }
                 }
-            }
+            });
             __syncthreads();
             const bool overflow = x.overflow != 0;
             if (!(hashed && overflow)) n_pick = pick_top(x, kTableSlots, threshold, a.top_k, n_pick);
@@ -930,10 +953,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
         if (tid == 0) emit_nodes(x, d, a.top_k, n_pick);
         __syncthreads();
         if (d < levels) {
-            for (int e0 = 0; e0 < n_level; e0 += 4 * kThreads) {
-                uint32_t pl[4], key[4];
-                bool outside[4];
-                keys_of(e0, pl, key, outside);
+            for_each_round([&](int, uint32_t (&pl)[4], uint32_t (&key)[4], bool (&outside)[4]) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     int child = -1;
@@ -947,7 +967,7 @@ __global__ __launch_bounds__(kThreads) void draft_expand_kernel(Args a) {
                         if (child == j) nxt[x.next[j].base + at] = pl[u];
                     }
                 }
-            }
+            });
         }
         __syncthreads();
         if (tid < n_pick) x.mem[tid] = x.next[tid];
