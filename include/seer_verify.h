@@ -23,7 +23,9 @@
  * Common rules
  *  - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
  *    NULL = the default stream): no device synchronisation, no allocation, no
- *    global state.  Scratch memory is sized by the *_workspace() functions
+ *    state inside the library (seer_verify_attention keeps a few hundred bytes
+ *    of call-to-call history in the caller's workspace, see
+ *    SEER_ATTN_FIXED_SPLIT).  Scratch memory is sized by the *_workspace() functions
  *    (host-only, no HIP call) and supplied by the caller; calls that share a
  *    workspace must be ordered on one stream.
  *  - Return value: 0 = launched; negative = SEER_E* argument error found on the
@@ -97,7 +99,13 @@ typedef struct seer_attn_params {
  * Dqk = Dv = 128 with separate K and V pools and a power-of-two page_size of
  * 16..1024 (any G*T: more than 256 query rows per KV head are cut into row
  * blocks), and for the shared latent Dqk = 576, Dv = 512 with a power-of-two
- * page_size of 32..1024; every other combination runs a slower general kernel. */
+ * page_size of 32..1024; every other combination runs a slower general kernel.
+ *
+ * Shared prompt pages (Section 2.3: the responses of a group are sampled for the same prompt): where a request's
+ * block_table row starts with the same page ids as the row before or after it, the D = 128 kernel reads
+ * those tiles with the cache policy that keeps them for the other requests and streams everything else,
+ * so only the first reader of a group pays DRAM for the shared pages.  Put the requests of a group in
+ * adjacent rows to benefit; results do not depend on it. */
 
 /* Bytes of device scratch seer_verify_attention needs for these params; 0 on
  * invalid params.  Host-only arithmetic. */
