@@ -427,6 +427,14 @@ def measure_config(torch, binding, W, cfg, args, steps: int, warmup: int, extras
             n_copy.copy_(d["ctx_len"])
             binding.seer_kv_commit(d["k_pages"], d["v_pages"], d["block_table"], n_copy, acc_out[0], acc_out[1])
         commit_ms = timed(commit, queue_first=40)    # two short kernels: timed by the GPU's clock, not by Python's
+        # the online acceptance statistics of the step (what the draft-length policy reads), and beta from them
+        counts = torch.zeros((3, cfg.T), dtype=torch.int64, device=dev)
+        stats_ms = timed(lambda i: binding.seer_acceptance_stats(acc_out[0], acc_out[1], e["tree_parent"], counts),
+                         queue_first=40)
+        counts.zero_()
+        binding.seer_acceptance_stats(acc_out[0], acc_out[1], e["tree_parent"], counts)
+        h_counts = counts.cpu().tolist()
+        beta = binding.seer_acceptance_beta(h_counts, False, 0.0)[:sum(1 for x in h_counts[0][1:] if x > 0)]
         # the step before verification: drafts from the groups' token histories
         top_k, gamma = cfg.tree if cfg.tree else (1, cfg.T - 1)
         dr = W.make_draft_inputs(cfg, gamma_max=gamma, top_k=top_k)
@@ -448,6 +456,7 @@ def measure_config(torch, binding, W, cfg, args, steps: int, warmup: int, extras
         live_groups = sorted(set(int(g) for g in dr.req_group))
         scanned = int(sum(int(dr.seq_len[dr.group_first[g]:dr.group_first[g + 1]].sum()) for g in live_groups))
         result_extras = {"accept_sampled_ms": sampled_ms, "kv_commit_ms": commit_ms,
+                         "acceptance_stats": {"ms": stats_ms, "beta_by_draft_position": [round(x, 4) for x in beta]},
                          "draft": {"draft_ms": draft_ms, "top_k": top_k, "gamma_max": gamma,
                                    "pattern_lookup": [dr.p_min, dr.p_max], "history_tokens": scanned,
                                    "history_bytes": scanned * 4,

@@ -276,6 +276,37 @@ SEER_API int seer_mba_draft_lengths(int32_t B_h, int32_t B_l, const double* beta
                            int32_t* gamma_star);
 
 /*
+ * Online acceptance statistics: what Algorithm 1 calls the per-position acceptance probabilities
+ * beta[1], beta[2], ... and Section 3.4.2 says are collected online.  Called after seer_accept (or
+ * seer_accept_sampled) of a step, it ADDS that step to three counters per draft position k = depth of
+ * a node under the root (k = 0 is the root):
+ *   offered[k]   the request's draft tree has a node of depth k
+ *   tried[k]     the accepted path reached depth k - 1 and its node there has a child, i.e. a draft
+ *                token of depth k was compared with the target's token
+ *   accepted[k]  accepted_len >= k
+ * A request whose accepted_len / accepted_path do not describe a root path of its tree is left out.
+ *
+ *  accepted_len, accepted_path  device, as written by seer_accept
+ *  tree_parent   device [B,T] int32 or NULL (= chain), as for seer_accept
+ *  counts        device [3][T] uint64 (offered, tried, accepted), 8-byte aligned; read-modify-write:
+ *                the caller zeroes it where a statistics window starts
+ * Asynchronous on hip_stream; no workspace.  Returns SEER_OK or SEER_EINVAL / SEER_ESHAPE / SEER_EALIGN
+ * or a positive hipError_t.
+ */
+SEER_API int seer_acceptance_stats(const int32_t* accepted_len, const int32_t* accepted_path, const int32_t* tree_parent,
+                          int32_t B, int32_t T, uint64_t* counts, void* hip_stream);
+
+/*
+ * beta[k - 1], k = 1 .. T - 1, from a HOST copy of those counts: accepted[k] / offered[k] (of the steps
+ * that drafted k or more tokens, the share in which the k-th was accepted: the sequence Algorithm 1
+ * differences, 1 at k = 0 and non-increasing for drafts of one depth), or, with conditional != 0,
+ * accepted[k] / tried[k] (how often a token that was compared was accepted: the per-token rate behind
+ * the expected-tokens law of Section 3.4.1).  Positions nothing was counted for get `prior` (in [0, 1]).
+ * Host arithmetic only.  Returns SEER_OK or SEER_EINVAL / SEER_ESHAPE.
+ */
+SEER_API int seer_acceptance_beta(const uint64_t* counts, int32_t T, int32_t conditional, double prior, double* beta);
+
+/*
  * Grouped n-gram drafting: the step right before verification (Section 2.3, pattern level: the
  * token histories of all requests of a prompt group serve as n-gram reference; Section 3.4.2 and
  * Appendix A.2, draft client call batch_speculate with SpeculationArgs max_spec_tokens,

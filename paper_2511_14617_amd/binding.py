@@ -22,7 +22,7 @@ SEER_ACCEPT_STATIC_MAX_PAIRS = 131072
 EXPORTS = ("seer_verify_attention_workspace", "seer_verify_attention_status_offset", "seer_verify_attention",
            "seer_verify_attention_timed", "seer_verify_attention_kernel", "seer_verify_attention_shared_tiles_offset",
            "seer_accept_workspace", "seer_accept", "seer_accept_static", "seer_accept_sampled",
-           "seer_kv_commit", "seer_mba_draft_lengths", "seer_draft_workspace", "seer_draft", "seer_history_append",
+           "seer_kv_commit", "seer_mba_draft_lengths", "seer_acceptance_stats", "seer_acceptance_beta", "seer_draft_workspace", "seer_draft", "seer_history_append",
            "seer_strerror")
 
 
@@ -89,6 +89,10 @@ def load_library() -> ctypes.CDLL:
         lib.seer_kv_commit.restype = ctypes.c_int
         lib.seer_mba_draft_lengths.argtypes = [i32, i32, vp, i32, i32, ctypes.c_double, vp, vp, vp, vp]
         lib.seer_mba_draft_lengths.restype = ctypes.c_int
+        lib.seer_acceptance_stats.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+        lib.seer_acceptance_stats.restype = ctypes.c_int
+        lib.seer_acceptance_beta.argtypes = [vp, i32, i32, ctypes.c_double, vp]
+        lib.seer_acceptance_beta.restype = ctypes.c_int
         lib.seer_draft_workspace.argtypes = [ctypes.POINTER(SeerDraftParams)]
         lib.seer_draft_workspace.restype = sz
         lib.seer_draft.argtypes = [vp] * 8 + [ctypes.POINTER(SeerDraftParams)] + [vp] * 7 + [sz, vp]
@@ -317,6 +321,29 @@ def seer_mba_draft_lengths(B_h: int, B_l: int, beta, gamma_max: int, lam: float,
     _check(lib.seer_mba_draft_lengths(B_h, B_l, bt, len(beta), gamma_max, float(lam), st, ctypes.byref(gh),
                                       ctypes.byref(gl), ctypes.byref(gs)))
     return gh.value, gl.value, gs.value
+
+
+def seer_acceptance_stats(accepted_len: torch.Tensor, accepted_path: torch.Tensor, tree_parent: Optional[torch.Tensor],
+                          counts: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Adds one verify step to counts [3,T] int64 on the device (offered, tried, accepted by draft position)."""
+    B, T = accepted_path.shape
+    _want(accepted_len, torch.int32, (B,), "accepted_len")
+    _want(accepted_path, torch.int32, (B, T), "accepted_path")
+    if tree_parent is not None:
+        _want(tree_parent, torch.int32, (B, T), "tree_parent")
+    _want(counts, torch.int64, (3, T), "counts")
+    _check(load_library().seer_acceptance_stats(_ptr(accepted_len), _ptr(accepted_path), _ptr(tree_parent), B, T,
+                                                _ptr(counts), _stream_handle(stream)))
+    return counts
+
+
+def seer_acceptance_beta(counts, conditional: bool = False, prior: float = 0.0):
+    """beta for draft positions 1 .. T-1 from a host copy of the counts ([3][T] integers)."""
+    T = len(counts[0])
+    flat = (ctypes.c_uint64 * (3 * T))(*[int(x) for row in counts for x in row])
+    beta = (ctypes.c_double * max(T - 1, 1))()
+    _check(load_library().seer_acceptance_beta(flat, T, 1 if conditional else 0, float(prior), beta))
+    return [beta[i] for i in range(T - 1)]
 
 
 def seer_draft_workspace(params: SeerDraftParams) -> int:

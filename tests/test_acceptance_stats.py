@@ -159,3 +159,94 @@ def test_prior_where_nothing_was_counted():
     c = so.acceptance_counts([1], [[0, 1, -1, -1]], [[0, 0, -2, -2]], 4)
     assert so.beta_from_counts(c, 4, prior=0.25) == [1.0, 0.25, 0.25]
     assert so.beta_from_counts(c, 4, conditional=True, prior=0.5) == [1.0, 0.5, 0.5]
+
+
+# ---- the library's host function (no GPU needed) and its argument checks ---------------------------------------
+
+def test_library_beta_matches_the_oracle():
+    from paper_2511_14617_amd import binding
+    rng = np.random.default_rng(21)
+    for T, top_k in ((9, 1), (33, 4), (64, 2), (1, 1)):
+        a, path, parent = _random_step(rng, 100, T, top_k)
+        c = so.acceptance_counts(a, path, parent, T)
+        for conditional in (False, True):
+            for prior in (0.0, 0.3, 1.0):
+                assert binding.seer_acceptance_beta(c, conditional, prior) == so.beta_from_counts(c, T, conditional, prior)
+
+
+def test_host_side_argument_checks():
+    import ctypes
+    from paper_2511_14617_amd import binding
+    lib = binding.load_library()
+    counts = (ctypes.c_uint64 * 12)(*([4] * 12))
+    beta = (ctypes.c_double * 3)()
+    assert lib.seer_acceptance_beta(None, 4, 0, 0.0, beta) == binding.SEER_EINVAL
+    assert lib.seer_acceptance_beta(counts, 4, 0, 0.0, None) == binding.SEER_EINVAL
+    assert lib.seer_acceptance_beta(counts, 0, 0, 0.0, beta) == binding.SEER_ESHAPE
+    assert lib.seer_acceptance_beta(counts, 65, 0, 0.0, beta) == binding.SEER_ESHAPE
+    assert lib.seer_acceptance_beta(counts, 4, 0, 1.5, beta) == binding.SEER_EINVAL
+    bad = (ctypes.c_uint64 * 12)(*([1] * 8 + [2] * 4))          # accepted > offered: not counts of the library
+    assert lib.seer_acceptance_beta(bad, 4, 0, 0.0, beta) == binding.SEER_EINVAL
+    assert lib.seer_acceptance_beta(counts, 4, 0, 0.0, beta) == binding.SEER_OK and list(beta) == [1.0, 1.0, 1.0]
+    # the device call: shape, null and alignment errors are found before anything is launched
+    fake = ctypes.c_void_p(1 << 20)
+    assert lib.seer_acceptance_stats(fake, fake, None, -1, 4, fake, None) == binding.SEER_ESHAPE
+    assert lib.seer_acceptance_stats(fake, fake, None, 1, 0, fake, None) == binding.SEER_ESHAPE
+    assert lib.seer_acceptance_stats(fake, fake, None, 1, 65, fake, None) == binding.SEER_ESHAPE
+    assert lib.seer_acceptance_stats(None, None, None, 0, 4, None, None) == binding.SEER_OK          # nothing to do
+    assert lib.seer_acceptance_stats(None, fake, None, 1, 4, fake, None) == binding.SEER_EINVAL
+    assert lib.seer_acceptance_stats(fake, fake, None, 1, 4, None, None) == binding.SEER_EINVAL
+    assert lib.seer_acceptance_stats(fake, fake, None, 1, 4, ctypes.c_void_p((1 << 20) + 4), None) == binding.SEER_EALIGN
+
+
+# ---- GPU parity: counts bit for bit ----------------------------------------------------------------------------
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed,B,T,top_k", [(1, 1, 9, 1), (2, 300, 9, 1), (3, 128, 33, 4), (4, 77, 64, 3), (5, 1000, 17, 2), (6, 5, 1, 1)])
+def test_gpu_counts_match_the_oracle(seed, B, T, top_k):
+    import torch
+    from paper_2511_14617_amd import binding
+    rng = np.random.default_rng(seed)
+    a, path, parent = _random_step(rng, B, T, top_k)
+    # malformed requests (left out by both sides): a path through a padded slot, a length out of range, a wrong root
+    if B >= 5:
+        if T > 1:
+            path[1, 1] = T - 1 if parent[1, T - 1] < 0 else path[1, 1]
+            a[1] = max(a[1], 1)
+        a[2] = T
+        path[3, 0] = 1
+        a[4] = -1
+    want = so.acceptance_counts(a, path, parent, T)
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).cuda()
+    counts = torch.zeros((3, T), dtype=torch.int64, device="cuda")
+    binding.seer_acceptance_stats(dev(a), dev(path), dev(parent), counts)
+    assert counts.cpu().tolist() == want
+    # a second step accumulates; a chain given without a parent array
+    chain_a = rng.integers(0, T, size=B)
+    chain_path = np.full((B, T), -1, dtype=np.int64)
+    for b in range(B):
+        chain_path[b, : chain_a[b] + 1] = np.arange(chain_a[b] + 1)
+    so.acceptance_counts(chain_a, chain_path, None, T, want)
+    binding.seer_acceptance_stats(dev(chain_a), dev(chain_path), None, counts)
+    assert counts.cpu().tolist() == want
+    assert binding.seer_acceptance_beta(want, False, 0.5) == so.beta_from_counts(want, T, False, 0.5)
+
+
+@pytest.mark.gpu
+def test_gpu_counts_after_accept_on_planted_trees():
+    """draft trees with planted acceptance -> seer_accept -> seer_acceptance_stats, against the oracles of both."""
+    import torch
+    import oracle
+    from paper_2511_14617_amd import binding, workloads as W
+    from gpu_util import accept_device_inputs
+    cfg = W.CONFIGS[5].scaled(B=24, V=1000)
+    parent = W.multipath_parent(cfg.B, 4, 8, np.random.default_rng(4), dedup_fraction=0.4)
+    acc = W.make_accept_inputs(cfg, tree_parent=parent)
+    d = accept_device_inputs(acc)
+    alen, apath, bonus, tgt = binding.seer_accept(d["logits"], d["draft_tokens"], d["tree_parent"])
+    counts = torch.zeros((3, cfg.T), dtype=torch.int64, device="cuda")
+    binding.seer_acceptance_stats(alen, apath, d["tree_parent"], counts)
+    o_len, o_path, _, _ = oracle.verify_accept(acc.logits, acc.draft_tokens, acc.tree_parent)
+    want = so.acceptance_counts(o_len, o_path, acc.tree_parent, cfg.T)
+    assert counts.cpu().tolist() == want
+    assert want[so.ACCEPTED][1] > 0

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle import draft_oracle as D
+from oracle import mba_oracle, stats_oracle
 import oracle
 from paper_2511_14617_amd import workloads as W
 
@@ -310,6 +311,8 @@ def test_decode_loop_emits_exactly_the_true_sequence(top_k, gamma_max):
     rng = np.random.default_rng(8)
     total_accepted = 0
     max_group = int(d.max_group_tokens + cfg.group_size * steps * (gamma_max + 1))
+    counts = torch.zeros((3, T), dtype=torch.int64, device="cuda")     # acceptance statistics over the six steps
+    h_counts = None
     for step in range(steps):
         tok, par, msk, cnt, mlen = binding.seer_draft(tokens, seq_start, seq_len, group_first, req_group, pattern,
                                                        pattern_len, max_spec, gamma_max=gamma_max, top_k=top_k,
@@ -335,6 +338,8 @@ def test_decode_loop_emits_exactly_the_true_sequence(top_k, gamma_max):
         alen, path, bonus, tgt = binding.seer_accept(torch.from_numpy(logits).to("cuda"), tok, par)
         torch.cuda.synchronize()
         a_, p_, bo = alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy()
+        binding.seer_acceptance_stats(alen, path, par, counts)
+        h_counts = stats_oracle.acceptance_counts(a_, p_, h_par, T, h_counts)
         emitted = np.full((cfg.B, T), -1, np.int32)
         for b in range(cfg.B):
             for i in range(a_[b]):
@@ -358,6 +363,15 @@ def test_decode_loop_emits_exactly_the_true_sequence(top_k, gamma_max):
         assert h_len[q] == old + done[b]
         assert np.array_equal(h_tokens[start + old:start + h_len[q]], d.future[b, :done[b]])
     assert total_accepted > cfg.B                         # the drafts did shorten the loop
+    # the statistics of the six steps, and the draft lengths the policy takes from them (Algorithm 1)
+    assert counts.cpu().tolist() == h_counts
+    assert sum(h_counts[2][1:]) == total_accepted
+    beta = binding.seer_acceptance_beta(h_counts, prior=0.0)
+    assert beta == stats_oracle.beta_from_counts(h_counts, T) and beta[0] > 0.0
+    beta = (beta + [0.0] * (gamma_max + 1))[:gamma_max + 1]
+    step_time = [1.0 + 0.05 * g for g in range(gamma_max + 1)]
+    assert binding.seer_mba_draft_lengths(4, 12, beta, gamma_max, 2.0, step_time) == \
+        mba_oracle.mba(4, 12, beta, gamma_max, 2.0, step_time)
 
 
 @pytest.mark.parametrize("seed", range(64))
