@@ -129,6 +129,18 @@ def test_shared_prompt_long_pieces(name):
     assert_attention_close(out, ref, name + "/two pieces", hardened=True, ref_abs=_oracle_abs(inp))
 
 
+def test_requests_that_map_the_same_pages_throughout():
+    """Two requests with one and the same block-table row and length (every tile, the draft slots' included, counts as
+    shared: the whole request is read under the keeping cache policy), next to requests that share nothing."""
+    cfg = W.CONFIGS[2].scaled(B=4, group_size=1, ctx=("uniform", 700, 1500), shared_prefix=0)
+    inp = W.make_attention_inputs(cfg, values="peaked")
+    inp.block_table[2] = inp.block_table[1]
+    inp.ctx_len[2] = inp.ctx_len[1]
+    ref = _oracle(inp)
+    out = _gpu(inp)
+    assert_attention_close(out, ref, "identical block-table rows", hardened=True, ref_abs=_oracle_abs(inp))
+
+
 def _leading_common_pages(inp):
     """Per request: the longest run of leading block-table entries equal to those of the request before or after it."""
     P, n = inp.cfg.page_size, inp.ctx_len
