@@ -87,17 +87,22 @@ constexpr size_t kStreamPartialsBelow = size_t{64} << 20;
 // the first find the tiles in that XCD's L2).
 inline bool gqa_page_size_ok(int P) { return P >= 16 && P <= 1024 && (P & (P - 1)) == 0; }
 inline int gqa_row_blocks(int rows) { return (rows + 255) / 256; }
+// A row block of 129 .. 144 rows is served by four main waves plus four helper waves that share the leftover rows
+// (see the kernel) instead of by a fifth wave; such a block keeps its exact row count.
+inline bool gqa_block_uses_helpers(int rows_per_block) { return rows_per_block > 128 && rows_per_block <= 144; }
 inline int gqa_rows_per_block(int rows) {
     const int nb = gqa_row_blocks(rows);
-    return ((rows + nb - 1) / nb + 31) / 32 * 32;
+    const int per = (rows + nb - 1) / nb;
+    return gqa_block_uses_helpers(per) ? per : (per + 31) / 32 * 32;
 }
+inline int gqa_waves_per_block(int rows_per_block) { return gqa_block_uses_helpers(rows_per_block) ? 8 : rows_per_block / 32; }
 
 // Workgroups of the partition kernel that one CU holds at once, by kernel shape.
 inline int resident_wgs_per_cu(const seer_attn_params& p) {
     const bool tiled = p.Dqk == 128 && p.Dv == 128 && gqa_page_size_ok(p.page_size) && !p.kv_shared_latent &&
                        !(p.flags & SEER_ATTN_GENERAL_KERNEL);
     if (!tiled) return 4;
-    const int waves = gqa_rows_per_block((p.Hq / p.Hkv) * p.T) / 32;   // one wave per 32 query rows
+    const int waves = gqa_waves_per_block(gqa_rows_per_block((p.Hq / p.Hkv) * p.T));   // one wave per 32 query rows
     const int by_waves = 8 / waves;                       // 2 waves per SIMD, 4 SIMDs
     const int depth = gqa_pipe_depth(waves);
     // 160 KB of LDS per CU, 16 KB per ring slot pair; five 32 KB workgroups would need all of it and
@@ -186,7 +191,6 @@ hipError_t launch_combine(const AttnArgs& a, hipStream_t stream);
 bool general_supports(int Dqk, int Dv);
 bool gqa128_supports(const AttnArgs& a);                            // D = 128, pages of 16..1024 tokens (power of two)
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream);
-bool gqa128_uses_helpers(int rows, int row_blocks);                 // 4 main + 4 helper waves instead of 5 waves
 bool mla_supports(const AttnArgs& a);                               // shared latent 576/512, pages of 32..1024 tokens
 hipError_t launch_mla(const AttnArgs& a, hipStream_t stream);
 

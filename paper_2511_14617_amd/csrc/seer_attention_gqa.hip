@@ -971,9 +971,6 @@ bool gqa128_supports(const AttnArgs& a) {
            a.v_pages != nullptr && a.Hkv <= 65535;
 }
 
-// Four main waves and four helpers instead of five waves: 129 .. 144 query rows per KV head in one row block
-// (a fifth wave would hold at most half of its rows).
-bool gqa128_uses_helpers(int rows, int row_blocks) { return row_blocks == 1 && rows > 128 && rows <= 144; }
 #ifndef SEER_HELPER_DEPTH
 #define SEER_HELPER_DEPTH 3
 #endif
@@ -983,7 +980,9 @@ hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int nw = a.rows_per_block / 32;
     const dim3 grid(static_cast<unsigned>((a.wgs_per_head + 7) / 8) * 8u * static_cast<unsigned>(a.Hkv) *
                     static_cast<unsigned>(a.row_blocks));
-    if (gqa128_uses_helpers(a.G * a.T, a.row_blocks)) {
+    // four main waves and four helpers instead of five waves: 129 .. 144 query rows in a row block (a fifth wave
+    // would hold at most half of its rows)
+    if (gqa_block_uses_helpers(a.rows_per_block)) {
         const dim3 block(8 * kWave);
         if (a.stream_only && a.stream_partials) hipLaunchKernelGGL((attn_gqa128_kernel<4, kHelperDepth, true, true, 4>), grid, block, 0, stream, a);
         else if (a.stream_only) hipLaunchKernelGGL((attn_gqa128_kernel<4, kHelperDepth, true, false, 4>), grid, block, 0, stream, a);

@@ -64,6 +64,9 @@ CASES = {
                                                shared_prefix=256), {}),
     "tp8_share_72b_tree": (W.CONFIGS[5].scaled(B=16, group_size=16, Hq=8, Hkv=1, ctx=("uniform", 100, 1500),
                                               shared_prefix=256), {"dedup_fraction": 0.3}),
+    # 265 rows per KV head: two row blocks of 133 and 132 rows, each four main waves plus four helper waves
+    "rows265_two_helper_blocks": (W.CONFIGS[2].scaled(B=3, group_size=3, Hq=5, Hkv=1, T=53, ctx=("uniform", 53, 1500),
+                                                     shared_prefix=64), {}),
     # more than 256 query rows per KV head: the tiled kernel cuts them into row blocks (528 rows -> 3 blocks)
     "rows528_G16_T33": (W.CONFIGS[5].scaled(B=3, group_size=3, Hq=32, Hkv=2, ctx=("uniform", 200, 1500),
                                             shared_prefix=0), {"dedup_fraction": 0.3}),
