@@ -623,7 +623,7 @@ extern "C" const char* seer_verify_attention_kernel(const seer_attn_params* p) {
         };
         static const Names names;
         const int rows = (p->Hq / p->Hkv) * p->T;
-        if (seer::gqa_block_uses_helpers(seer::gqa_rows_per_block(rows))) return "attn_gqa128_kernel<4,3,helpers=4>";
+        if (seer::gqa_block_uses_helpers(seer::gqa_rows_per_block(rows))) return "attn_gqa128_kernel<4,2,helpers=4>";
         return names.text[seer::gqa_rows_per_block(rows) / 32];
     }
     if (tiled_ok && seer::mla_supports(a)) return "attn_mla_kernel";

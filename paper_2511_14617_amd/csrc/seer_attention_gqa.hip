@@ -420,7 +420,10 @@ void attn_gqa128_kernel(AttnArgs a) {
     constexpr int REM = 8 % NL;                     // loaders below this index load CEIL blocks, the others FLOOR
     static_assert(D >= 1 && (D - 1) * 2 * CEIL < 64, "vmcnt range");
 
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * NSLOT * kKBytes];   // K ring, then V ring
+    // K ring, then V ring; at the end of a piece the helpers' states pass through the same memory
+    constexpr int kMergeBytes = NH > 0 ? 4096 + (NH - 1) * 16 * kWave * 16 : 0;
+    constexpr int kLdsBytes = 2 * NSLOT * kKBytes > kMergeBytes ? 2 * NSLOT * kKBytes : kMergeBytes;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsBytes];
     constexpr int kVRing = NSLOT * kKBytes;
 
     // Workgroup ids are dealt round-robin to the 8 XCDs and dispatched in id order.  The grid is laid
@@ -844,6 +847,7 @@ void attn_gqa128_kernel(AttnArgs a) {
         // a wave's access is one contiguous kilobyte.
         float* xml = reinterpret_cast<float*>(lds);                                    // [NH][64][2]
         unsigned char* xacc = lds + 4096;                                              // [NH - 1][16][64] x 16 bytes
+        static_assert(NH * kWave * 2 * 4 <= 4096 && kMergeBytes <= kLdsBytes, "the merge area fits the ring's memory");
         const int h = wave - NW;
         bare_barrier();                              // every wave has read the piece's last tiles
         if (helper) {
@@ -971,10 +975,10 @@ bool gqa128_supports(const AttnArgs& a) {
            a.v_pages != nullptr && a.Hkv <= 65535;
 }
 
-#ifndef SEER_HELPER_DEPTH
-#define SEER_HELPER_DEPTH 3
-#endif
-constexpr int kHelperDepth = SEER_HELPER_DEPTH;
+// Ring depth of the helper shape: two tiles in flight.  Its eight waves spend their time on operand reads and on
+// each other, not on waiting for tiles (measured per wave on the multi-path batch: 50 of a step's 2000 clocks), and
+// with three tiles in flight instead of two the kernel is 4 % slower (1.28 vs 1.23 ms; rings of 5 and 7: as 3).
+constexpr int kHelperDepth = 2;
 
 hipError_t launch_gqa128(const AttnArgs& a, hipStream_t stream) {
     const int nw = a.rows_per_block / 32;

@@ -259,7 +259,7 @@ def test_kernel_name_follows_the_dispatch(lib):
     name = binding.seer_verify_attention_kernel
     assert name(_params(B=64, Hq=32, Hkv=8, T=9)) == "attn_gqa128_kernel<2,1>"          # 36 rows: two waves
     assert name(_params(B=8, Hq=32, Hkv=8, T=17)) == "attn_gqa128_kernel<3,3>"          # 68 rows
-    assert name(_params(B=128, Hq=32, Hkv=8, T=33)) == "attn_gqa128_kernel<4,3,helpers=4>"   # 132 rows: 128 + 4
+    assert name(_params(B=128, Hq=32, Hkv=8, T=33)) == "attn_gqa128_kernel<4,2,helpers=4>"   # 132 rows: 128 + 4
     assert name(_params(B=8, Hq=20, Hkv=4, T=30)) == "attn_gqa128_kernel<5,3>"          # 150 rows
     assert name(_params(Hq=128, Hkv=1, Dqk=576, Dv=512, page_size=64, kv_shared_latent=1)) == "attn_mla_kernel"
     assert name(_params(Hq=128, Hkv=1, Dqk=576, Dv=512, page_size=16, kv_shared_latent=1)) == "attn_general_kernel<576,512>"
