@@ -39,10 +39,10 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the partition kernel as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, scaled
 # against a 1 GiB copy) in separate runs of this script; NOT measured by the run that prints them.
 PROFILED_TRAFFIC = {
-    2: (1.522e9, "profiles/attn_gqa128_config2_counters.md"),
+    2: (1.521e9, "profiles/attn_gqa128_config2_counters.md"),
     3: (3.082e9, "profiles/attn_gqa128_config3_counters.md"),
     4: (0.769e9, "profiles/attn_mla_config4_counters.md"),
-    5: (5.799e9, "profiles/attn_gqa128_config5_counters.md"),
+    5: (5.818e9, "profiles/attn_gqa128_config5_counters.md"),
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 METRIC = "verified tokens/s and verify-attention HBM GB/s (% of peak) on one MI355X"
