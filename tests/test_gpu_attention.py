@@ -350,6 +350,32 @@ def test_parity_random_shapes(seed):
     assert_attention_close(out, ref, what, hardened=True, ref_abs=_oracle_abs(inp))
 
 
+@pytest.mark.parametrize("seed", range(32))
+def test_parity_random_shapes_with_shared_prompts(seed):
+    """Random shapes again, now with prompt groups of random size that share 0 .. 2100 leading tokens and with a random
+    cap on the pieces per request (long pieces run the unrolled steady state through the shared run and out of it)."""
+    rng = np.random.default_rng(5000 + seed)
+    G, Hkv = int(rng.choice([1, 2, 4, 5, 8, 16])), int(rng.choice([1, 2, 4]))
+    if rng.random() < 0.5:
+        n_paths, path_len = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        T, tree = 1 + n_paths * path_len, (n_paths, path_len)
+    else:
+        T, tree = int(rng.integers(1, 40)), None
+    P, B = int(rng.choice([16, 16, 32, 64, 128])), int(rng.integers(2, 8))
+    group = int(rng.integers(1, B + 1))
+    hi = int(rng.choice([300, 700, 2500, 4000]))
+    lo = int(rng.integers(max(T, hi // 4), max(T + 1, hi // 2)))
+    shared = min(int(rng.choice([0, 16, 48, 200, 600, 1100, 2100])), max(lo - T - 1, 0))
+    cfg = W.CONFIGS[2].scaled(B=B, group_size=group, Hq=G * Hkv, Hkv=Hkv, T=T, tree=tree, page_size=P,
+                              ctx=("uniform", lo, max(lo, hi)), shared_prefix=shared)
+    max_splits = int(rng.choice([0, 0, 2, 3]))
+    inp = W.make_attention_inputs(cfg, seed=cfg.seed + seed, values="peaked",
+                                  **({"dedup_fraction": 0.3} if cfg.tree else {}))
+    what = "shared %d: G=%d Hkv=%d T=%d tree=%s P=%d B=%d group=%d shared=%d splits=%d" % (
+        seed, G, Hkv, T, tree, P, B, group, shared, max_splits)
+    assert_attention_close(_gpu(inp, max_splits=max_splits), _oracle(inp), what, hardened=True, ref_abs=_oracle_abs(inp))
+
+
 @pytest.mark.parametrize("case", ["chain_T9_multi_split", "tree_T33", "mla_latent", "rows528_G16_T33", "rows144_G16_T9"])
 def test_page_permutation_is_bit_identical_with_the_fixed_split(case):
     """Moving every page to another place of the pool, the block table following, changes nothing: the cut
