@@ -134,31 +134,50 @@ __device__ __forceinline__ float max_across_halves(float x) {
 constexpr int kKAhead = 8;    // the K operand of score step kk is read kKAhead MFMAs before it is used
 constexpr int kQAhead = 4;    // ... the parked Q^T operands kQAhead MFMAs before
 constexpr int kVAhead = 6;    // the V^T operand of a P.V MFMA (two transposing reads) kVAhead MFMAs before
+constexpr int kLoadFirst = 1, kLoadEvery = 4;   // load i of the next tile goes behind score MFMA kLoadFirst + i kLoadEvery
+static_assert(kLoadFirst + (kLoadsPerWave - 1) * kLoadEvery < kKSteps, "all loads of a tile fit in one score phase");
 
 // LDS reads outstanding behind the operand(s) of score step kk at the point where that step waits,
 // from the order in which phase_a issues them
-constexpr int qk_wait_count(int kk) {
+// (with V_AHEAD, the last kVAhead score steps are each followed by the two transposing reads of one of the first
+// kVAhead P.V MFMAs of the phase that comes next)
+constexpr int kVFirst = kKSteps - kVAhead;
+constexpr int qk_wait_count(int kk, bool v_ahead) {
     int seq = 0, pos_k[kKSteps] = {}, pos_q[kKSteps] = {}, before[kKSteps] = {};
     for (int i = 0; i < kKAhead; ++i) pos_k[i] = seq++;
     for (int m = 0; m < kKSteps; ++m) {
         before[m] = seq;
         if (m + kKAhead < kKSteps) pos_k[m + kKAhead] = seq++;
         if (m + kQAhead >= kQRegSteps && m + kQAhead < kKSteps) pos_q[m + kQAhead] = seq++;
+        if (v_ahead && m >= kVFirst) seq += 2;
     }
     int need = pos_k[kk];
     if (kk >= kQRegSteps && pos_q[kk] > need) need = pos_q[kk];
     return before[kk] - 1 - need;
 }
-static_assert(kQRegSteps >= kQAhead && qk_wait_count(0) == kKAhead - 1 && qk_wait_count(kKSteps - 1) == 0, "");
+static_assert(kQRegSteps >= kQAhead && qk_wait_count(0, false) == kKAhead - 1 && qk_wait_count(kKSteps - 1, false) == 0, "");
+static_assert(qk_wait_count(kKSteps - 1, true) < 16, "lgkmcnt is a 4-bit counter");
+
+// The V^T operand of P.V MFMA m (see phase_b) : two transposing reads into ring slot m % kVAhead.
+template <int m>
+__device__ __forceinline__ void v_read(u32x2 (&vr)[kVAhead][2], int a_even, int a_even8, int a_odd, int a_odd8) {
+    constexpr int G2 = m >> 2, w = m & 3;
+    constexpr int off_lo = G2 * 128 + (w >= 2 ? 16 : 0) * kRowBytes, off_hi = off_lo + 8 * kRowBytes;
+    if constexpr (w & 1) SEER_MLA_READ_TR2(vr[m % kVAhead], a_odd, a_odd8, off_lo, off_hi);
+    else SEER_MLA_READ_TR2(vr[m % kVAhead], a_even, a_even8, off_lo, off_hi);
+}
 
 // Phase A of a pipeline step: the scores of tile u (36 MFMAs into s_new) with, in their shadow, the
-// softmax of tile u-1 (s_old -> pk, m_run, l_run, alpha).  ka: LDS addresses of this lane's K
+// probabilities of tile u-1 (s_old -> pk, l_run; the exponent reference m_use and the factor alpha of that
+// tile were set during the phase B before).  ka: LDS addresses of this lane's K
 // operand chunks for contraction steps 0..3 of the tile (steps 4g + j are 128 g bytes further);
 // qt: LDS address of this lane's parked Q^T operands.  s_old must already carry -inf in masked slots.
-template <bool DO_QK, bool DO_SM>
+// With DO_SM, the V^T operands of the first kVAhead P.V MFMAs of tile u-1 (addresses va) are requested behind the
+// last score MFMAs, so that phase B starts without waiting for LDS.
+template <bool DO_QK, bool DO_SM, typename LOAD>
 __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 (&qreg)[kQRegSteps], f32x16& s_new,
-                                        f32x16& s_old, uint32_t (&pk)[8], float& m_run, float& l_run, float& alpha,
-                                        float scale_log2) {
+                                        f32x16& s_old, uint32_t (&pk)[8], float m_use, float& l_run, float alpha,
+                                        float scale_log2, const int (&va)[4], u32x2 (&vr)[kVAhead][2], LOAD&& load) {
     u32x4 kr[kKAhead], qr[kQAhead];
     if constexpr (DO_QK) {
         for_each_index([&](auto ic) __attribute__((always_inline)) {
@@ -167,23 +186,12 @@ __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 
             SEER_MLA_READ128(kr[I], ka[I & 3], (I >> 2) * 128);
         }, std::make_integer_sequence<int, kKAhead>{});
     }
-    float m_use = 0.f, psum = 0.f, p_even = 0.f;
-    if constexpr (DO_SM) {
-        // register i of s_old holds token (i/4)*8 + lg*4 + i%4 of the tile, for this lane's row
-        float mx = kNegInf;
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(mx, s_old[i]), s_old[i + 1]);
-        // Lazy reference: m_run is the exponent reference of (l, acc), not necessarily the true
-        // maximum; it moves only when the tile maximum exceeds it by more than 8 (log2 units), so p
-        // stays below 2^8 (bf16 and fp32 have the range) and the 256-register rescale is rare.
-        mx = max_across_halves(mx) * scale_log2;
-        const float m_new = (mx > m_run + 8.f) ? mx : m_run;
-        m_use = (m_new == kNegInf) ? 0.f : m_new;
-        alpha = fast_exp2(m_run - m_use);
-        m_run = m_new;
-        SEER_MLA_PIN(m_use);
-        SEER_MLA_PIN(alpha);
-        SEER_MLA_PIN(m_run);
+    float psum = 0.f, p_even = 0.f;
+    if constexpr (!DO_QK && DO_SM) {
+        for_each_index([&](auto ic) __attribute__((always_inline)) {
+            (void)&vr, (void)&va;
+            v_read<decltype(ic)::value>(vr, va[0], va[1], va[2], va[3]);
+        }, std::make_integer_sequence<int, kVAhead>{});
     }
     // probability of slot i; two of them make one packed register
     auto element = [&](auto ic) __attribute__((always_inline)) {
@@ -210,15 +218,22 @@ __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 
         for_each_index([&](auto ic) __attribute__((always_inline)) {
             constexpr int kk = decltype(ic)::value;
             (void)&kr, (void)&qr, (void)&ka, (void)&qt;   // (asm operands alone do not capture)
-            wait_lgkm<qk_wait_count(kk)>();
+            wait_lgkm<qk_wait_count(kk, DO_SM)>();
             const u32x4 qv = kk < kQRegSteps ? qreg[kk < kQRegSteps ? kk : 0] : qr[kk % kQAhead];
             if constexpr (kk == 0) mfma_vgpr_first(s_new, kr[0], qv); else mfma_vgpr(s_new, kr[kk % kKAhead], qv);
             if constexpr (kk + kKAhead < kKSteps)
                 SEER_MLA_READ128(kr[kk % kKAhead], ka[(kk + kKAhead) & 3], ((kk + kKAhead) >> 2) * 128);
             if constexpr (kk + kQAhead >= kQRegSteps && kk + kQAhead < kKSteps)
                 SEER_MLA_READ128(qr[kk % kQAhead], qt, (kk + kQAhead - kQRegSteps) * 1024);
+            if constexpr (DO_SM && kk >= kVFirst) {
+                (void)&vr, (void)&va;
+                v_read<kk - kVFirst>(vr, va[0], va[1], va[2], va[3]);
+            }
             // one probability in the shadow of every second MFMA
             if constexpr (kk >= 2 && kk % 2 == 0 && (kk - 2) / 2 < 16) element(std::integral_constant<int, (kk - 2) / 2>{});
+            // ... and one of this wave's loads of the next tile behind every kLoadEvery-th
+            if constexpr (kk >= kLoadFirst && (kk - kLoadFirst) % kLoadEvery == 0 && (kk - kLoadFirst) / kLoadEvery < kLoadsPerWave)
+                load(std::integral_constant<int, (kk - kLoadFirst) / kLoadEvery>{});
             SEER_MLA_FENCE();
         }, std::make_integer_sequence<int, kKSteps>{});
     } else {
@@ -234,29 +249,25 @@ __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 
 // Phase B: O^T[d][row] += sum_token V[token][d] * P[row][token] for one tile (32 MFMAs), V = first 512
 // dims of the latent through the transposing read.  MFMA m = 4 G2 + w works on the pair of d-tiles G2:
 // w = 0, 1: even, odd d-tile, tokens 0..15;  w = 2, 3: even, odd d-tile, tokens 16..31.
-// a_even / a_odd: lane address for even / odd d-tiles; the token rows +8 and +24 differ from +0 and
-// +16 in row bit 3, which the swizzle uses: they go through addresses of their own (a_even8 / a_odd8).
-__device__ __forceinline__ void phase_b(int a_even, int a_even8, int a_odd, int a_odd8, const uint32_t (&pk)[8],
-                                        f32x16 (&acc)[kDTiles]) {
+// va = {a_even, a_even8, a_odd, a_odd8}: lane address for even / odd d-tiles; the token rows +8 and +24 differ
+// from +0 and +16 in row bit 3, which the swizzle uses: they go through addresses of their own.
+// The operands of MFMAs 0..kVAhead-1 are already on their way into vr (requested by phase A); shadow(m) is vector
+// arithmetic to issue behind MFMA m (it must not touch LDS).
+template <typename SHADOW>
+__device__ __forceinline__ void phase_b(const int (&va)[4], u32x2 (&vr)[kVAhead][2], const uint32_t (&pk)[8],
+                                        f32x16 (&acc)[kDTiles], SHADOW&& shadow) {
     const u32x4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
     const u32x4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
-    u32x2 vr[kVAhead][2];   // [ring slot][tokens +0..3 | +8..11 of the MFMA's 16]
-    auto read_for = [&](auto ic) __attribute__((always_inline)) {
-        constexpr int m = decltype(ic)::value;
-        constexpr int G2 = m >> 2, w = m & 3;
-        constexpr int off_lo = G2 * 128 + (w >= 2 ? 16 : 0) * kRowBytes, off_hi = off_lo + 8 * kRowBytes;
-        (void)&vr, (void)&a_even, (void)&a_even8, (void)&a_odd, (void)&a_odd8;   // (asm operands alone do not capture)
-        if constexpr (w & 1) SEER_MLA_READ_TR2(vr[m % kVAhead], a_odd, a_odd8, off_lo, off_hi);
-        else SEER_MLA_READ_TR2(vr[m % kVAhead], a_even, a_even8, off_lo, off_hi);
-    };
-    for_each_index(read_for, std::make_integer_sequence<int, kVAhead>{});
     for_each_index([&](auto ic) __attribute__((always_inline)) {
         constexpr int m = decltype(ic)::value;
         constexpr int left = kDTiles * 2 - 1 - m;                       // MFMAs after this one
+        (void)&vr, (void)&va;                                           // (asm operands alone do not capture)
         wait_lgkm<2 * (left < kVAhead - 1 ? left : kVAhead - 1)>();
         const u32x4 v = {vr[m % kVAhead][0][0], vr[m % kVAhead][0][1], vr[m % kVAhead][1][0], vr[m % kVAhead][1][1]};
         mfma_acc(acc[(m >> 2) * 2 + (m & 1)], v, (m & 2) ? pb1 : pb0);
-        if constexpr (m + kVAhead < kDTiles * 2) read_for(std::integral_constant<int, m + kVAhead>{});
+        if constexpr (m + kVAhead < kDTiles * 2) v_read<m + kVAhead>(vr, va[0], va[1], va[2], va[3]);
+        shadow(ic);
+        SEER_MLA_FENCE();
     }, std::make_integer_sequence<int, kDTiles * 2>{});
 }
 
@@ -313,6 +324,14 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     const int v_odd = v_row0 + (((4 + v_dhalf * 2 + (v_c4 >> 1)) ^ v_swz) << 4) + (v_c4 & 1) * 8;
     const int v_even8 = v_row0 + (((v_dhalf * 2 + (v_c4 >> 1)) ^ v_swz ^ 1) << 4) + (v_c4 & 1) * 8;
     const int v_odd8 = v_row0 + (((4 + v_dhalf * 2 + (v_c4 >> 1)) ^ v_swz ^ 1) << 4) + (v_c4 & 1) * 8;
+    // tile loads: byte offset in the tile (global side) of what LDS slot c of the first 18 blocks receives
+    int pat[5];
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        const unsigned c = static_cast<unsigned>((j < 4 ? wave + 4 * j : 16 + (wave & 1)) * 64 + lane);
+        const unsigned row = c / kChunksPerRow, pos = c - row * kChunksPerRow;
+        pat[j] = static_cast<int>(row * kRowBytes + ((pos ^ static_cast<unsigned>(swz(static_cast<int>(row)))) << 4));
+    }
 
   for (; g < g_end; ++b) {
     const int t_lo = uniform_load(a.tile_off + b), t_hi = uniform_load(a.tile_off + b + 1);
@@ -390,20 +409,28 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
         const int pg = __builtin_amdgcn_readlane(pg_cache, __builtin_amdgcn_readfirstlane(logical_page - cache_base));
         return static_cast<size_t>(pg) * page_bytes + head_off;
     };
-    auto issue_tile = [&](int tile) __attribute__((always_inline)) {
+    // Tile loads go through a buffer descriptor of the tile (base = the tile's first row, 36 KB long): a
+    // 32-bit lane offset and a scalar offset per load instead of 64-bit address arithmetic.  LDS slot
+    // c = block * 64 + lane holds chunk (c % 72) ^ swz(row) of row c / 72; blocks k and k + 18 lie 16 rows
+    // apart (same swizzle), so 18 lane patterns serve the 36 blocks.  Wave w takes the blocks w + 4j and
+    // w + 4j + 18 (j = 0..3) and one of 16, 17, 34, 35: five pattern registers.
+    auto tile_rsrc = [&](int tile) __attribute__((always_inline)) {
         const int tb = tok_begin + tile * kTile;
         const unsigned char* src = kbase + page_offset(tb >> page_shift) + static_cast<size_t>(tb & (a.P - 1)) * kRowBytes;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(src), 0, kStageBytes, 0x00020000);
+    };
+    auto issue_load = [&](auto ic, __amdgpu_buffer_rsrc_t rsrc, int tile) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        const int half = i < 8 ? (i & 1) : (wave >> 1);
+        const int block = (i < 8 ? wave + 4 * (i >> 1) : 16 + (wave & 1)) + 18 * half;
         unsigned char* stage = lds + (tile % kStages) * kStageBytes;
-#pragma unroll
-        for (int i = 0; i < kLoadsPerWave; ++i) {
-            // LDS slot c = block*64 + lane holds chunk (c % 72) ^ swz(row) of row c / 72 (recomputed per
-            // load: nine more live registers per lane would not fit beside Q^T and the accumulators)
-            const unsigned c = static_cast<unsigned>((wave + i * kWaves) * 64 + lane);
-            const unsigned row = c / kChunksPerRow, pos = c - row * kChunksPerRow;
-            const int goff = static_cast<int>(row * kRowBytes + ((pos ^ static_cast<unsigned>(swz(static_cast<int>(row)))) << 4));
-            __builtin_amdgcn_global_load_lds((const SEER_AS1 void*)(src + goff),
-                                             (SEER_AS3 void*)(stage + (wave + i * kWaves) * 1024), 16, 0, 0);
-        }
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SEER_AS3 void*)(stage + block * 1024), 16, pat[i < 8 ? (i >> 1) : 4],
+                                                 half * (16 * kRowBytes), 0, 0);
+    };
+    auto issue_tile = [&](int tile) __attribute__((always_inline)) {
+        const __amdgpu_buffer_rsrc_t rsrc = tile_rsrc(tile);
+        for_each_index([&](auto ic) __attribute__((always_inline)) { issue_load(ic, rsrc, tile); },
+                       std::make_integer_sequence<int, kLoadsPerWave>{});
     };
 
     // ---- the pipeline: step u = scores of tile u | softmax of tile u-1, then P.V of tile u-1 ------
@@ -416,7 +443,6 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     auto step_top = [&](int u) __attribute__((always_inline)) {
         if (kStages > 3 && u + 1 < n_tiles) wait_vmcnt<(kStages > 3 ? kLoadsPerWave : 0)>(); else wait_vmcnt<0>();
         bare_barrier();
-        if (u + kStages - 2 < n_tiles) issue_tile(u + kStages - 2);
         if (u == n_tiles - 1 && tok_begin + (u + 1) * kTile > n) {
             // ragged last tile: clear the rows past the end (0 * NaN must not reach the output)
             unsigned char* kl = lds + (u % kStages) * kStageBytes;
@@ -443,7 +469,58 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) ka[j] = st + k_rd[j];
     };
-    auto pv = [&](int j) __attribute__((always_inline)) {
+    // V^T operand addresses of tile j
+    auto v_addrs = [&](int j, int (&va)[4]) __attribute__((always_inline)) {
+        const int st = lds_base + (j % kStages) * kStageBytes;
+        va[0] = st + v_even, va[1] = st + v_even8, va[2] = st + v_odd, va[3] = st + v_odd8;
+    };
+    // The exponent reference for the scores sc of one tile, in four slices (issued in the shadow of P.V MFMAs, or in
+    // one go).  Lazy reference: m_run is the exponent reference of (l, acc), not necessarily the true maximum; it
+    // moves only when the tile maximum exceeds it by more than 8 (log2 units), so p stays below 2^8 (bf16 and fp32
+    // have the range) and the 256-register rescale is rare.  Sets m_use and alpha for the tile, and m_run.
+    // Register i of sc holds token (i/4)*8 + lg*4 + i%4 of the tile, for this lane's row.
+    float m_use = 0.f, mx_part = 0.f;
+    auto reference = [&](auto ic, const f32x16& sc) __attribute__((always_inline)) {
+        constexpr int part = decltype(ic)::value;
+        if constexpr (part == 0) {
+            mx_part = fmaxf(fmaxf(sc[0], sc[1]), sc[2]);
+#pragma unroll
+            for (int i = 3; i < 9; i += 2) mx_part = fmaxf(fmaxf(mx_part, sc[i]), sc[i + 1]);
+            SEER_MLA_PIN(mx_part);
+        } else if constexpr (part == 1) {
+#pragma unroll
+            for (int i = 9; i < 15; i += 2) mx_part = fmaxf(fmaxf(mx_part, sc[i]), sc[i + 1]);
+            mx_part = fmaxf(mx_part, sc[15]);
+            SEER_MLA_PIN(mx_part);
+        } else if constexpr (part == 2) {
+            mx_part = max_across_halves(mx_part) * a.scale_log2;
+            SEER_MLA_PIN(mx_part);
+        } else {
+            const float m_new = (mx_part > m_run + 8.f) ? mx_part : m_run;
+            m_use = (m_new == kNegInf) ? 0.f : m_new;
+            alpha = fast_exp2(m_run - m_use);
+            m_run = m_new;
+            SEER_MLA_PIN(m_use);
+            SEER_MLA_PIN(alpha);
+            SEER_MLA_PIN(m_run);
+        }
+    };
+    // P.V of tile j (probabilities pk, first operands already requested into vr) with, in its shadow, the exponent
+    // reference of the scores of tile j + 1 (sc_next; NEXT = false: there is none).  The accumulators are rescaled
+    // first if any row of the wave moved its reference for tile j.
+    u32x2 vr[kVAhead][2];   // [ring slot][tokens +0..3 | +8..11 of the MFMA's 16]
+    int va[4];
+    auto pv = [&](int j, auto next, f32x16& sc_next) __attribute__((always_inline)) {
+        constexpr bool NEXT = decltype(next)::value;
+        if constexpr (NEXT) {
+            // -inf into the slots of tile j + 1 that this lane's row does not see (only the tiles that reach the draft
+            // slots have any); the scores were written by MFMAs the compiler knows nothing of: idle past them first
+            const int rel = tok_begin + (j + 1) * kTile - n0;
+            if (rel > -kTile) {
+                mfma_drain();
+                apply_mask(j + 1, sc_next);
+            }
+        }
         if (__any(alpha != 1.f)) {
             mfma_drain();
             // one d-tile at a time through VGPRs (the empty asm statements keep the compiler from
@@ -459,46 +536,76 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
             }
             asm volatile("s_nop 7");
         }
-        const int st = lds_base + (j % kStages) * kStageBytes;
-        phase_b(st + v_even, st + v_even8, st + v_odd, st + v_odd8, pk, acc);
+        // the score MFMAs of sc_next were issued before the phase began; its first use here sits behind P.V MFMA
+        // kRefFirst, more than an MFMA's depth later
+        constexpr int kRefFirst = 4;
+        phase_b(va, vr, pk, acc, [&](auto ic) __attribute__((always_inline)) {
+            constexpr int m = decltype(ic)::value;
+            if constexpr (NEXT && m >= kRefFirst && (m - kRefFirst) % 2 == 0 && (m - kRefFirst) / 2 < 4)
+                reference(std::integral_constant<int, (m - kRefFirst) / 2>{}, sc_next);
+        });
     };
+    using yes = std::true_type;
+    using no = std::false_type;
 
 #pragma unroll
     for (int t2 = 0; t2 < kStages - 2; ++t2)
         if (t2 < n_tiles) issue_tile(t2);
 
     int ka[4];
+    // the loads of tile u + 1, requested inside step u's score phase (its stage held tile u - 2, which every
+    // wave left before the barrier at the top of step u)
+    __amdgpu_buffer_rsrc_t next_rsrc = tile_rsrc(0);
+    bool next_ok = false;
+    int next_tile = 0;
+    auto next_setup = [&](int u) __attribute__((always_inline)) {
+        next_tile = u + kStages - 2;
+        next_ok = next_tile < n_tiles;
+        if (next_ok) next_rsrc = tile_rsrc(next_tile);
+    };
+    auto next_load = [&](auto ic) __attribute__((always_inline)) {
+        if (next_ok) issue_load(ic, next_rsrc, next_tile);
+    };
+    auto no_load = [](auto) {};
     step_top(0);
     k_addrs(0, ka);
-    phase_a<true, false>(ka, qt, qreg, s_a, s_b, pk, m_run, l_run, alpha, a.scale_log2);
+    next_setup(0);
+    phase_a<true, false>(ka, qt, qreg, s_a, s_b, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
+    // the first tile's exponent reference, with nothing to hide behind
+    mfma_drain();
+    apply_mask(0, s_a);
+    for_each_index([&](auto ic) __attribute__((always_inline)) { reference(ic, s_a); }, std::make_integer_sequence<int, 4>{});
     // steps 1 .. n_tiles - 1, two per iteration so that s_a and s_b swap roles without register moves
     int u = 1;
     for (; u + 1 < n_tiles; u += 2) {
         step_top(u);
         k_addrs(u, ka);
-        apply_mask(u - 1, s_a);
-        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_run, l_run, alpha, a.scale_log2);
-        pv(u - 1);
+        v_addrs(u - 1, va);
+        next_setup(u);
+        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
+        pv(u - 1, yes{}, s_b);
         step_top(u + 1);
         k_addrs(u + 1, ka);
-        apply_mask(u, s_b);
-        phase_a<true, true>(ka, qt, qreg, s_a, s_b, pk, m_run, l_run, alpha, a.scale_log2);
-        pv(u);
+        v_addrs(u, va);
+        next_setup(u + 1);
+        phase_a<true, true>(ka, qt, qreg, s_a, s_b, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
+        pv(u, yes{}, s_a);
     }
     if (u < n_tiles) {
         step_top(u);
         k_addrs(u, ka);
-        apply_mask(u - 1, s_a);
-        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_run, l_run, alpha, a.scale_log2);
-        pv(u - 1);
+        v_addrs(u - 1, va);
+        next_setup(u);
+        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
+        pv(u - 1, yes{}, s_b);
         asm volatile("" : "+v"(s_b));       // the copy below reads s_b after the P.V MFMAs, not right behind the score MFMAs
 #pragma unroll
         for (int i = 0; i < 16; ++i) s_a[i] = s_b[i];
     }
-    // the last tile's scores are in s_a
-    apply_mask(n_tiles - 1, s_a);
-    phase_a<false, true>(ka, qt, qreg, s_b, s_a, pk, m_run, l_run, alpha, a.scale_log2);
-    pv(n_tiles - 1);
+    // the last tile's scores are in s_a, masked, and its reference is set
+    v_addrs(n_tiles - 1, va);
+    phase_a<false, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, no_load);
+    pv(n_tiles - 1, no{}, s_a);
 
     // ---- partial result ------------------------------------------------------------------------
     mfma_drain();
