@@ -7,9 +7,9 @@
 // data + expert parallelism, so each GPU sees all 128 attention heads of its own
 // requests): with T = gamma + 1 verify slots a request has 128*T query rows over
 // one latent stream, about 1200 flop per KV byte -- the kernel is bound by the
-// matrix cores and by the latency of the LDS reads that feed them (one wave per SIMD: nothing else
-// to issue while an operand is awaited), not by HBM and not by LDS bandwidth (counters: the LDS data
-// path is busy a third of the time, the matrix cores half of it).
+// matrix cores and by what the one wave per SIMD issues between its MFMAs (nothing else feeds the
+// SIMD's matrix core while that wave requests a tile load or awaits an operand), not by HBM and not by
+// LDS bandwidth (counters: the LDS data path is busy a third of the time, the matrix cores 57 % of it).
 //
 // Work decomposition
 //   A workgroup = 4 waves = 128 query rows (wave i owns rows 32i..32i+31) of one request
@@ -18,7 +18,7 @@
 //   (workgroup ids are dealt round-robin to the 8 XCDs), so that one of them pulls a latent
 //   tile from HBM and the others find it in that XCD's L2.
 // Data flow per 32-token tile (36 KB: 32 rows of 1152 B)
-//   HBM/L2 -> LDS directly (global_load_lds_dwordx4), ring of 3 stages; 16-byte chunks of a
+//   HBM/L2 -> LDS directly (buffer_load_dwordx4 ... lds, requested inside the score phase), ring of 3 stages; 16-byte chunks of a
 //   row XOR-swizzled by a 3-bit function of row bits 1..3 (bit 1 of the row moves the chunk by 64
 //   bytes), which spreads both read patterns below over all 64 LDS banks.
 //   S^T = K . Q^T : 36 steps of v_mfma_f32_32x32x16_bf16 (M = tokens, N = rows); K operand =
