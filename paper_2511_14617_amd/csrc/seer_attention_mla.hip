@@ -174,10 +174,13 @@ __device__ __forceinline__ void v_read(u32x2 (&vr)[kVAhead][2], int a_even, int 
 // qt: LDS address of this lane's parked Q^T operands.  s_old must already carry -inf in masked slots.
 // With DO_SM, the V^T operands of the first kVAhead P.V MFMAs of tile u-1 (addresses va) are requested behind the
 // last score MFMAs, so that phase B starts without waiting for LDS.
-template <bool DO_QK, bool DO_SM, typename LOAD>
+// load(i): request load i of the next tile; extra(kk): other arithmetic for the shadow of score MFMA kk (no LDS traffic;
+// it may write va before step kVFirst).
+template <bool DO_QK, bool DO_SM, typename LOAD, typename EXTRA>
 __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 (&qreg)[kQRegSteps], f32x16& s_new,
                                         f32x16& s_old, uint32_t (&pk)[8], float m_use, float& l_run, float alpha,
-                                        float scale_log2, const int (&va)[4], u32x2 (&vr)[kVAhead][2], LOAD&& load) {
+                                        float scale_log2, int (&va)[4], u32x2 (&vr)[kVAhead][2], LOAD&& load,
+                                        EXTRA&& extra) {
     u32x4 kr[kKAhead], qr[kQAhead];
     if constexpr (DO_QK) {
         for_each_index([&](auto ic) __attribute__((always_inline)) {
@@ -234,6 +237,7 @@ __device__ __forceinline__ void phase_a(const int (&ka)[4], int qt, const u32x4 
             // ... and one of this wave's loads of the next tile behind every kLoadEvery-th
             if constexpr (kk >= kLoadFirst && (kk - kLoadFirst) % kLoadEvery == 0 && (kk - kLoadFirst) / kLoadEvery < kLoadsPerWave)
                 load(std::integral_constant<int, (kk - kLoadFirst) / kLoadEvery>{});
+            extra(ic);
             SEER_MLA_FENCE();
         }, std::make_integer_sequence<int, kKSteps>{});
     } else {
@@ -419,22 +423,25 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
         const unsigned char* src = kbase + page_offset(tb >> page_shift) + static_cast<size_t>(tb & (a.P - 1)) * kRowBytes;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(src), 0, kStageBytes, 0x00020000);
     };
-    auto issue_load = [&](auto ic, __amdgpu_buffer_rsrc_t rsrc, int tile) __attribute__((always_inline)) {
+    auto issue_load = [&](auto ic, __amdgpu_buffer_rsrc_t rsrc, int stage_off) __attribute__((always_inline)) {
         constexpr int i = decltype(ic)::value;
         const int half = i < 8 ? (i & 1) : (wave >> 1);
         const int block = (i < 8 ? wave + 4 * (i >> 1) : 16 + (wave & 1)) + 18 * half;
-        unsigned char* stage = lds + (tile % kStages) * kStageBytes;
+        unsigned char* stage = lds + stage_off;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (SEER_AS3 void*)(stage + block * 1024), 16, pat[i < 8 ? (i >> 1) : 4],
                                                  half * (16 * kRowBytes), 0, 0);
     };
-    auto issue_tile = [&](int tile) __attribute__((always_inline)) {
+    auto issue_tile = [&](int tile, int stage_off) __attribute__((always_inline)) {
         const __amdgpu_buffer_rsrc_t rsrc = tile_rsrc(tile);
-        for_each_index([&](auto ic) __attribute__((always_inline)) { issue_load(ic, rsrc, tile); },
+        for_each_index([&](auto ic) __attribute__((always_inline)) { issue_load(ic, rsrc, stage_off); },
                        std::make_integer_sequence<int, kLoadsPerWave>{});
     };
 
     // ---- the pipeline: step u = scores of tile u | softmax of tile u-1, then P.V of tile u-1 ------
-    // Tile u + kStages - 2 is requested at step u, into the stage that tile u-2 left at the end of step u-1.
+    // Tile u + 1 is requested at step u, into the stage that tile u-2 left at the end of step u-1.
+    // Byte offsets of the stages that hold tiles u-1, u and u+1 at step u: they rotate, no arithmetic.
+    static_assert(kStages == 3, "the three stage offsets below rotate");
+    int st_prev = 2 * kStageBytes, st_cur = 0, st_next = kStageBytes;
     const int lds_base = lds_addr(lds);
     const int qt = lds_addr(&q_tail[wave][0][lane]);
     f32x16 s_a, s_b;
@@ -445,7 +452,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
         bare_barrier();
         if (u == n_tiles - 1 && tok_begin + (u + 1) * kTile > n) {
             // ragged last tile: clear the rows past the end (0 * NaN must not reach the output)
-            unsigned char* kl = lds + (u % kStages) * kStageBytes;
+            unsigned char* kl = lds + st_cur;
             const int first_bad = n - (tok_begin + u * kTile);
             for (int c = tid; c < kTile * kChunksPerRow; c += NT)
                 if (c / kChunksPerRow >= first_bad) *reinterpret_cast<u32x4*>(kl + c * 16) = u32x4{0u, 0u, 0u, 0u};
@@ -464,14 +471,15 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
         for (int i = 0; i < 16; ++i)
             if (!((vis >> ((i >> 2) * 8 + (i & 3))) & 1u)) sc[i] = kNegInf;
     };
-    auto k_addrs = [&](int u, int (&ka)[4]) __attribute__((always_inline)) {
-        const int st = lds_base + (u % kStages) * kStageBytes;
+    // K operand addresses of the tile in the stage at byte offset stage_off
+    auto k_addrs = [&](int stage_off, int (&ka)[4]) __attribute__((always_inline)) {
+        const int st = lds_base + stage_off;
 #pragma unroll
         for (int j = 0; j < 4; ++j) ka[j] = st + k_rd[j];
     };
-    // V^T operand addresses of tile j
-    auto v_addrs = [&](int j, int (&va)[4]) __attribute__((always_inline)) {
-        const int st = lds_base + (j % kStages) * kStageBytes;
+    // V^T operand addresses
+    auto v_addrs = [&](int stage_off, int (&va)[4]) __attribute__((always_inline)) {
+        const int st = lds_base + stage_off;
         va[0] = st + v_even, va[1] = st + v_even8, va[2] = st + v_odd, va[3] = st + v_odd8;
     };
     // The exponent reference for the scores sc of one tile, in four slices (issued in the shadow of P.V MFMAs, or in
@@ -510,7 +518,7 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
     // first if any row of the wave moved its reference for tile j.
     u32x2 vr[kVAhead][2];   // [ring slot][tokens +0..3 | +8..11 of the MFMA's 16]
     int va[4];
-    auto pv = [&](int j, auto next, f32x16& sc_next) __attribute__((always_inline)) {
+    auto pv = [&](int j, auto next, f32x16& sc_next, auto&& prepare) __attribute__((always_inline)) {
         constexpr bool NEXT = decltype(next)::value;
         if constexpr (NEXT) {
             // -inf into the slots of tile j + 1 that this lane's row does not see (only the tiles that reach the draft
@@ -543,69 +551,77 @@ void attn_mla_kernel(AttnArgs a, int row_blocks) {
             constexpr int m = decltype(ic)::value;
             if constexpr (NEXT && m >= kRefFirst && (m - kRefFirst) % 2 == 0 && (m - kRefFirst) / 2 < 4)
                 reference(std::integral_constant<int, (m - kRefFirst) / 2>{}, sc_next);
+            prepare(ic);
         });
     };
     using yes = std::true_type;
     using no = std::false_type;
 
-#pragma unroll
-    for (int t2 = 0; t2 < kStages - 2; ++t2)
-        if (t2 < n_tiles) issue_tile(t2);
+    issue_tile(0, st_cur);
 
     int ka[4];
     // the loads of tile u + 1, requested inside step u's score phase (its stage held tile u - 2, which every
     // wave left before the barrier at the top of step u)
     __amdgpu_buffer_rsrc_t next_rsrc = tile_rsrc(0);
     bool next_ok = false;
-    int next_tile = 0;
     auto next_setup = [&](int u) __attribute__((always_inline)) {
-        next_tile = u + kStages - 2;
-        next_ok = next_tile < n_tiles;
-        if (next_ok) next_rsrc = tile_rsrc(next_tile);
+        next_ok = u + 1 < n_tiles;
+        if (next_ok) next_rsrc = tile_rsrc(u + 1);
     };
     auto next_load = [&](auto ic) __attribute__((always_inline)) {
-        if (next_ok) issue_load(ic, next_rsrc, next_tile);
+        if (next_ok) issue_load(ic, next_rsrc, st_next);
     };
-    auto no_load = [](auto) {};
-    step_top(0);
-    k_addrs(0, ka);
+    auto nothing = [](auto) {};
+    // What step u + 1 needs before its first LDS read, done in the shadow of step u's P.V MFMAs instead of behind the
+    // barrier: the stage offsets move on, the K operand addresses, the descriptor of the tile after.
+    int u = 0;
+    auto prepare_next = [&](auto ic) __attribute__((always_inline)) {
+        constexpr int m = decltype(ic)::value;
+        if constexpr (m == 14) {
+            const int t = st_prev;
+            st_prev = st_cur, st_cur = st_next, st_next = t;
+            k_addrs(st_cur, ka);
+        } else if constexpr (m == 18) {
+            next_setup(u + 1);
+        }
+    };
+    // the V^T operand addresses of tile u - 1, early in step u's score phase (first used behind score MFMA kVFirst)
+    auto v_addrs_early = [&](auto ic) __attribute__((always_inline)) {
+        if constexpr (decltype(ic)::value == 2) v_addrs(st_prev, va);
+    };
+    k_addrs(st_cur, ka);
     next_setup(0);
-    phase_a<true, false>(ka, qt, qreg, s_a, s_b, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
+    step_top(0);
+    phase_a<true, false>(ka, qt, qreg, s_a, s_b, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load, nothing);
     // the first tile's exponent reference, with nothing to hide behind
     mfma_drain();
     apply_mask(0, s_a);
     for_each_index([&](auto ic) __attribute__((always_inline)) { reference(ic, s_a); }, std::make_integer_sequence<int, 4>{});
+    prepare_next(std::integral_constant<int, 14>{});
+    prepare_next(std::integral_constant<int, 18>{});
     // steps 1 .. n_tiles - 1, two per iteration so that s_a and s_b swap roles without register moves
-    int u = 1;
-    for (; u + 1 < n_tiles; u += 2) {
+    for (u = 1; u + 1 < n_tiles;) {
         step_top(u);
-        k_addrs(u, ka);
-        v_addrs(u - 1, va);
-        next_setup(u);
-        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
-        pv(u - 1, yes{}, s_b);
-        step_top(u + 1);
-        k_addrs(u + 1, ka);
-        v_addrs(u, va);
-        next_setup(u + 1);
-        phase_a<true, true>(ka, qt, qreg, s_a, s_b, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
-        pv(u, yes{}, s_a);
+        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load, v_addrs_early);
+        pv(u - 1, yes{}, s_b, prepare_next);
+        ++u;
+        step_top(u);
+        phase_a<true, true>(ka, qt, qreg, s_a, s_b, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load, v_addrs_early);
+        pv(u - 1, yes{}, s_a, prepare_next);
+        ++u;
     }
     if (u < n_tiles) {
         step_top(u);
-        k_addrs(u, ka);
-        v_addrs(u - 1, va);
-        next_setup(u);
-        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load);
-        pv(u - 1, yes{}, s_b);
+        phase_a<true, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, next_load, v_addrs_early);
+        pv(u - 1, yes{}, s_b, prepare_next);
         asm volatile("" : "+v"(s_b));       // the copy below reads s_b after the P.V MFMAs, not right behind the score MFMAs
 #pragma unroll
         for (int i = 0; i < 16; ++i) s_a[i] = s_b[i];
     }
-    // the last tile's scores are in s_a, masked, and its reference is set
-    v_addrs(n_tiles - 1, va);
-    phase_a<false, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, no_load);
-    pv(n_tiles - 1, no{}, s_a);
+    // the last tile's scores are in s_a, masked, and its reference is set; its stage is the one before the current
+    v_addrs(st_prev, va);
+    phase_a<false, true>(ka, qt, qreg, s_b, s_a, pk, m_use, l_run, alpha, a.scale_log2, va, vr, nothing, nothing);
+    pv(n_tiles - 1, no{}, s_a, nothing);
 
     // ---- partial result ------------------------------------------------------------------------
     mfma_drain();
