@@ -86,7 +86,9 @@ __device__ __forceinline__ int lds_addr(T* p) {
 template <int N>
 __device__ __forceinline__ void wait_lgkm() {
     static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
-    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+    // (through the builtin: an instruction the compiler knows between two asm MFMAs on one accumulator keeps it from
+    // padding them with a wait state of its own; vmcnt and expcnt fields at their maxima = no wait on those)
+    __builtin_amdgcn_s_waitcnt(0xc07f | (N << 8));
 }
 #define SEER_MLA_FENCE() __builtin_amdgcn_sched_barrier(0)
 // Keeps the computation of x at the place where it is written (see the D = 128 kernel).
