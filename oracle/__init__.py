@@ -8,6 +8,7 @@ from .seer_oracle import (  # noqa: F401
     build,
     emitted_tokens,
     gumbel,
+    gumbel_of_words,
     kv_commit,
     log2_det,
     num_threads,

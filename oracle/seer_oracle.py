@@ -69,6 +69,8 @@ def _load():
         _lib.oracle_log2_det.restype = ctypes.c_float
         _lib.oracle_gumbel.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32]
         _lib.oracle_gumbel.restype = ctypes.c_float
+        _lib.oracle_gumbel_of_words.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        _lib.oracle_gumbel_of_words.restype = None
         _lib.oracle_argmax_sampled.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float,
                                                ctypes.c_uint64, ctypes.c_void_p]
     return _lib
@@ -212,6 +214,14 @@ def log2_det(x: float) -> float:
 
 def gumbel(seed: int, row: int, v: int) -> float:
     return float(_load().oracle_gumbel(seed, row, v))
+
+
+def gumbel_of_words(words) -> np.ndarray:
+    """The Gumbel deviates that the given 32-bit generator words turn into (same arithmetic as `gumbel`)."""
+    w = _c(words, np.uint32)
+    out = np.empty(w.shape, dtype=np.float32)
+    _load().oracle_gumbel_of_words(_p(w), w.size, _p(out))
+    return out
 
 
 def argmax_sampled(logits, temperature: float, seed: int) -> np.ndarray:

@@ -149,13 +149,24 @@ float oracle_log2_det(float x) {
     return fmaf(f, p, (float)e);
 }
 
+/* standard Gumbel deviate from one 32-bit word of the generator (its upper 23 bits) */
+static float gumbel_of_word(uint32_t word) {
+    const float u = ((float)(word >> 9) + 0.5f) * 1.1920928955078125e-07f;   /* 2^-23 */
+    const float e = -oracle_log2_det(u) * 0.693147182f;
+    return -(oracle_log2_det(e) * 0.693147182f);
+}
+
 float oracle_gumbel(uint64_t seed, uint32_t row, uint32_t v) {
     const uint32_t ctr[4] = {v >> 2, row, 0u, 0u}, key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
     uint32_t w[4];
     oracle_philox4x32_10(ctr, key, w);
-    const float u = ((float)(w[v & 3u] >> 9) + 0.5f) * 1.1920928955078125e-07f;   /* 2^-23 */
-    const float e = -oracle_log2_det(u) * 0.693147182f;
-    return -(oracle_log2_det(e) * 0.693147182f);
+    return gumbel_of_word(w[v & 3u]);
+}
+
+/* the same deviates for given generator words (tests sweep all 2^23 distinct inputs) */
+void oracle_gumbel_of_words(const uint32_t *words, int64_t n, float *out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) out[i] = gumbel_of_word(words[i]);
 }
 
 int oracle_argmax_sampled(const float *logits, int64_t n_rows, int V, float temperature, uint64_t seed,

@@ -47,6 +47,40 @@ def test_gumbel_noise_moments():
     assert np.isfinite(g).all() and g.min() > -3.0 and g.max() < 17.0   # u in [2^-24, 1 - 2^-24]
 
 
+def test_gumbel_of_words_is_the_noise_of_the_draws_and_has_the_closed_form():
+    """The vectorised form takes the generator's word where `gumbel` takes (seed, row, v); both give the same
+    deviate, and it is -ln(-ln u) of u = (word's upper 23 bits + 1/2) 2^-23 to the accuracy of the fixed logarithm."""
+    seed, row = 0x1234567890ABCDEF, 17
+    for v in (0, 1, 2, 3, 4, 1001, 151935):
+        words = oracle.philox4x32_10([v >> 2, row, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        assert oracle.gumbel_of_words(words[v & 3: (v & 3) + 1])[0] == np.float32(oracle.gumbel(seed, row, v))
+    rng = np.random.default_rng(5)
+    w = rng.integers(0, 1 << 32, size=200000, dtype=np.uint64).astype(np.uint32)
+    u = ((w >> 9).astype(np.float64) + 0.5) * 2.0 ** -23
+    want = -np.log(-np.log(u))
+    assert np.max(np.abs(oracle.gumbel_of_words(w) - want)) < 2e-5
+
+
+def test_every_word_stays_below_the_bound_by_leading_ones():
+    """What lets the sampled scan skip the logarithms of most logits: with z leading one bits in the word's upper
+    23 bits, 1 - u > 2^-(z+1) and so G < (z + 1) ln 2.  Checked for all 2^23 inputs of the fixed-polynomial
+    arithmetic, with the slack the kernel's constant (ln 2 + 0.05) leaves for fp32 roundings: G + 0.04 <= bound."""
+    hi = np.arange(1 << 23, dtype=np.uint32)
+    g = oracle.gumbel_of_words(hi << np.uint32(9)).astype(np.float64)
+    assert np.array_equal(g, oracle.gumbel_of_words((hi << np.uint32(9)) | np.uint32(0x1ff)))   # the low 9 bits play no part
+    inv = (~hi) & np.uint32((1 << 23) - 1)
+    # leading ones of a 23-bit field = 23 - bit length of its complement
+    bitlen = np.zeros(hi.shape, dtype=np.int64)
+    nz = inv > 0
+    bitlen[nz] = np.floor(np.log2(inv[nz].astype(np.float64))).astype(np.int64) + 1
+    z = 23 - bitlen
+    assert z.min() == 0 and z.max() == 23 and np.count_nonzero(z == 23) == 1
+    bound = z.astype(np.float64) * float(np.float32(0.693147182)) + float(np.float32(np.float32(0.693147182) + np.float32(0.05)))
+    assert np.all(g + 0.04 <= bound)
+    assert np.all(np.diff(g) >= 0)                       # and the noise grows with the word, as -ln(-ln u) does
+    assert (bound - g)[z >= 8].max() < 0.75                      # no looser than a factor of two in 1 - u, plus the slack
+
+
 @pytest.mark.parametrize("tau", [1.0, 0.8])
 def test_draws_follow_softmax_of_logits_over_temperature(tau):
     """The token drawn at a verify position must be a sample of softmax(logits / tau): chi-square of
