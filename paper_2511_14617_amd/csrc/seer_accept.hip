@@ -32,7 +32,7 @@ namespace seer {
 constexpr int kArgmaxThreads = 256;
 // Floats per workgroup: 16 x 16-byte loads per lane for the greedy scan, 8 for the sampled one (measured on
 // V = 152 064: 16 384 instead of 8192 floats takes the greedy scan from 54 to 52 us for 576 rows and from 374 to
-// 364 us for 4224 rows; the sampled scan, bound by its arithmetic, is 5 % slower with the larger chunk).
+// 364 us for 4224 rows; the sampled scan, bound by its arithmetic, takes the same time with either).
 constexpr int kChunkGreedy = 16384;
 constexpr int kChunkSampled = 8192;
 
@@ -54,6 +54,19 @@ struct SampleArgs {
     uint32_t seed_lo, seed_hi;
 };
 
+// Upper bound of logits[v] / tau + G_v without the two logarithms: with z = the number of leading one bits of the
+// generator's word (of its upper 23 bits, which are all that G uses), 1 - u > 2^-(z+1), so G < (z + 1) ln 2.
+// kGumbelBoundC = ln 2 plus 0.05 for the error of the fixed-polynomial logarithms and for the roundings of the
+// three fused multiply-adds involved (checked for every one of the 2^23 words on the host; the roundings stay
+// below the slack while |logit / tau| < 2^17, beyond which the caller takes the exact path).
+constexpr float kLn2 = 0.693147182f;
+constexpr float kGumbelBoundC = 0.693147182f + 0.05f;
+constexpr float kGumbelBoundMaxLogit = 131072.f;
+__device__ __forceinline__ float perturb_upper_bound(float logit, float inv_tau, uint32_t w) {
+    const int z = __builtin_clz(~w | 0x1ffu);          // 0 .. 23
+    return __builtin_fmaf(static_cast<float>(z), kLn2, __builtin_fmaf(logit, inv_tau, kGumbelBoundC));
+}
+
 template <bool kVec4, bool kSampled>
 __global__ __launch_bounds__(kArgmaxThreads) void argmax_chunks(const float* __restrict__ logits, int V,
                                                                 int n_chunks, float* __restrict__ part_val,
@@ -67,7 +80,63 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_chunks(const float* __r
 
     float best = kNegInf;
     int best_i = begin;  // a row of -inf (or an all -inf chunk) resolves to its first index
-    if constexpr (kVec4) {
+    if constexpr (kVec4 && kSampled) {
+        // The sampled scan is bound by its arithmetic (ten generator rounds and two polynomial logarithms per
+        // logit), and almost all of the logarithms are spent on elements that cannot win: an element whose upper
+        // bound lies strictly below a perturbed value that the workgroup has already seen is neither the maximum
+        // nor tied with it.  Per 16-byte load a wave evaluates the generator and the bound; only if some lane's
+        // bound reaches the best value seen so far does the wave compute the four exact values of every lane.
+        // The result is that of the plain scan, bit for bit: only provable losers are skipped.
+        constexpr int kIter = kChunk / (kArgmaxThreads * 4);
+        constexpr int kWaves = kArgmaxThreads / kWave;
+        __shared__ volatile float s_seen[kWaves];        // per wave: a perturbed value it has met (its maximum so far)
+        if (threadIdx.x < kWaves) s_seen[threadIdx.x] = kNegInf;
+        __syncthreads();
+        const int wv = threadIdx.x / kWave;
+        float seen = kNegInf;                            // wave-uniform
+        f32x4 x[kIter];
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int i = begin + (it * kArgmaxThreads + threadIdx.x) * 4;
+            x[it] = (i < end) ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(base + i))
+                              : f32x4{kNegInf, kNegInf, kNegInf, kNegInf};
+        }
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int i = begin + (it * kArgmaxThreads + threadIdx.x) * 4;
+            const Philox4 r = philox4x32_10(static_cast<uint32_t>(i) >> 2, static_cast<uint32_t>(row), 0u, 0u,
+                                            sa.seed_lo, sa.seed_hi);
+            // what the other waves of the workgroup have met (a stale value is still a value that was met)
+            float floor_v = seen;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) floor_v = fmaxf(floor_v, s_seen[w]);
+            const float u0 = perturb_upper_bound(x[it].x, sa.inv_tau, r.w[0]);
+            const float u1 = perturb_upper_bound(x[it].y, sa.inv_tau, r.w[1]);
+            const float u2 = perturb_upper_bound(x[it].z, sa.inv_tau, r.w[2]);
+            const float u3 = perturb_upper_bound(x[it].w, sa.inv_tau, r.w[3]);
+            const float ub = fmaxf(fmaxf(u0, u1), fmaxf(u2, u3));
+            const float mag = fmaxf(fmaxf(fabsf(x[it].x), fabsf(x[it].y)), fmaxf(fabsf(x[it].z), fabsf(x[it].w)));
+            // (written so that a NaN anywhere, an infinity or a huge logit takes the exact path)
+            const bool provably_below = i >= end || (ub < floor_v && mag * fabsf(sa.inv_tau) < kGumbelBoundMaxLogit);
+            if (__any(!provably_below)) {
+                if (i < end) {  // indices ascend within a lane: strict '>' keeps the lowest
+                    const float y0 = perturb(x[it].x, sa.inv_tau, r.w[0]);
+                    const float y1 = perturb(x[it].y, sa.inv_tau, r.w[1]);
+                    const float y2 = perturb(x[it].z, sa.inv_tau, r.w[2]);
+                    const float y3 = perturb(x[it].w, sa.inv_tau, r.w[3]);
+                    if (y0 > best) { best = y0; best_i = i; }
+                    if (y1 > best) { best = y1; best_i = i + 1; }
+                    if (y2 > best) { best = y2; best_i = i + 2; }
+                    if (y3 > best) { best = y3; best_i = i + 3; }
+                }
+                float m = best;
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, kWave));
+                seen = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(m)));
+                if ((threadIdx.x & (kWave - 1)) == 0) s_seen[wv] = seen;
+            }
+        }
+    } else if constexpr (kVec4) {
         // V % 4 == 0 and a 16-byte aligned base: every row starts aligned.
         constexpr int kIter = kChunk / (kArgmaxThreads * 4);
         f32x4 x[kIter];

@@ -43,6 +43,45 @@ def test_sampled_tokens_bit_exact(V, tau):
         assert drawn[0, 0] == 0 and (drawn.reshape(-1)[1:] >= V // 50).all()
 
 
+@pytest.mark.parametrize("case", ["peaked", "wide", "equal", "huge", "huge_tau", "nan_inf", "near_ties", "late_winner"])
+def test_sampled_tokens_bit_exact_where_the_scan_skips_or_must_not(case):
+    """The sampled scan skips the logarithms of elements whose upper bound lies below a value already met.  Shapes
+    of logits that exercise it: a peaked row (nearly everything is skipped), a wide one (little is), equal logits
+    (the noise alone decides; ties in the perturbed values resolve to the lowest index as in the oracle), magnitudes
+    beyond the range in which the bound's roundings are covered (exact path), NaN and infinities, values within
+    the bound's slack of one another, and a winner that sits at the very end of the row."""
+    rng = np.random.default_rng(hash(case) % 1000)
+    B, T, V = 3, 4, 40000
+    tau = 0.8
+    logits = rng.standard_normal((B, T, V)).astype(np.float32)
+    if case == "peaked":
+        logits *= 0.1
+        logits[..., 777] = 30.0
+    elif case == "wide":
+        logits *= 12.0
+    elif case == "equal":
+        logits[:] = 1.25
+    elif case == "huge":
+        logits *= 3.0e5
+        logits[1] = np.float32(2.0e5) + rng.standard_normal((T, V)).astype(np.float32) * 4.0
+    elif case == "huge_tau":
+        tau = 1.0e-5
+    elif case == "nan_inf":
+        logits[0, 0, 1::7] = np.nan                   # (not slot 0: a NaN there is the oracle's starting value)
+        logits[0, 1, ::5] = -np.inf
+        logits[0, 2, 123] = np.inf
+        logits[1, 0, :] = np.nan
+        logits[2, 3, 5:] = -np.inf
+    elif case == "near_ties":
+        logits[:] = (rng.integers(0, 3, size=(B, T, V)) * 0.02).astype(np.float32)
+    elif case == "late_winner":
+        logits *= 0.5
+        logits[..., V - 1] = 25.0
+    draft = rng.integers(0, V, size=(B, T)).astype(np.int32)
+    for seed in (1, 0xFEDCBA9876543210):
+        _check_sampled(logits, draft, None, tau, seed)
+
+
 def test_sampled_acceptance_with_drafts_planted_on_the_draws():
     """Drafts that follow the drawn tokens down to a planted depth are accepted to exactly that depth,
     on a multi-path tree with a flat distribution (temperature matters: most draws are not the argmax)."""
