@@ -687,6 +687,9 @@ void attn_gqa128_kernel(AttnArgs a) {
     // step u + 2 (V tile u has landed by then and is overwritten after step u + 3's barrier).
     if constexpr (NH > 0) {
         const int h = wave - NW;
+        // (the helpers' phases are dependent chains that otherwise wait behind the main wave of their SIMD, which the
+        // issue arbiter prefers as the older wave, and every wave then waits for them at the barrier)
+        __builtin_amdgcn_s_setprio(3);
         for (int u = 0; u <= n_tiles + 1; ++u) {
             wait_step(u);
             bare_barrier();
