@@ -376,6 +376,30 @@ def test_parity_random_shapes_with_shared_prompts(seed):
     assert_attention_close(_gpu(inp, max_splits=max_splits), _oracle(inp), what, hardened=True, ref_abs=_oracle_abs(inp))
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_parity_random_shapes_shared_latent(seed):
+    """Random shapes of the shared-latent form (576/512, one KV head): head counts that fill one row block or
+    several, chains and trees, pages of 32 .. 256 tokens, contexts from a single tile (less than one, even) to a few
+    dozen, odd and even tile counts, ragged last tiles, draft slots that straddle tiles, several pieces per request."""
+    rng = np.random.default_rng(9000 + seed)
+    Hq = int(rng.choice([8, 16, 16, 32, 64, 128]))
+    if rng.random() < 0.4:
+        n_paths, path_len = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        T, tree = 1 + n_paths * path_len, (n_paths, path_len)
+    else:
+        T, tree = int(rng.integers(1, 40 if Hq <= 32 else 12)), None
+    P, B = int(rng.choice([32, 64, 64, 128, 256])), int(rng.integers(1, 6))
+    hi = int(rng.choice([40, 100, 300, 900, 1500]))
+    lo = int(rng.integers(T, max(T + 1, hi // 2)))
+    cfg = W.CONFIGS[4].scaled(B=B, Hq=Hq, T=T, tree=tree, page_size=P, ctx=("uniform", lo, max(lo, hi)))
+    max_splits = int(rng.choice([0, 0, 2, 3]))
+    inp = W.make_attention_inputs(cfg, seed=cfg.seed + seed, values="peaked",
+                                  **({"dedup_fraction": 0.3} if cfg.tree else {}))
+    what = "latent %d: Hq=%d T=%d tree=%s P=%d B=%d ctx=%s splits=%d" % (seed, Hq, T, tree, P, B, inp.ctx_len.tolist(),
+                                                                        max_splits)
+    assert_attention_close(_gpu(inp, max_splits=max_splits), _oracle(inp), what, hardened=True, ref_abs=_oracle_abs(inp))
+
+
 @pytest.mark.parametrize("case", ["chain_T9_multi_split", "tree_T33", "mla_latent", "rows528_G16_T33", "rows144_G16_T9"])
 def test_page_permutation_is_bit_identical_with_the_fixed_split(case):
     """Moving every page to another place of the pool, the block table following, changes nothing: the cut
