@@ -525,6 +525,40 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnArgs a, lo
     const size_t acc_stride = static_cast<size_t>(per_b) * a.Dv;
     float M = kNegInf;
     int s = 0;
+    if (ns >= 1 && ns <= 4) {
+        // The common case, a request cut into a handful of pieces: everything is requested at once (the pieces past
+        // ns re-read the last one and count as having seen nothing), one round trip instead of one per piece and
+        // pass.  Same operations in the same order as the general path below.
+        float2 msl[4];
+        f32x4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int su = min(u, ns - 1);
+            msl[u] = ml[static_cast<size_t>(su) * per_b];
+            p[u] = *reinterpret_cast<const f32x4*>(acc + su * acc_stride);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u >= ns) msl[u].x = kNegInf;
+            M = fmaxf(M, msl[u].x);
+        }
+        float L = 0.f;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool live = msl[u].x != kNegInf;
+            const float w = live ? fast_exp2(msl[u].x - M) : 0.f;
+            L += live ? msl[u].y * w : 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] += live ? p[u][c] * w : 0.f;
+        }
+        const float inv = (L > 0.f) ? 1.f / L : 0.f;
+        u32x2 o;
+        o[0] = pack_bf16x2(v[0] * inv, v[1] * inv);
+        o[1] = pack_bf16x2(v[2] * inv, v[3] * inv);
+        *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.out) + row * a.Dv + d) = o;
+        return;
+    }
     for (; s + 4 <= ns; s += 4) {
         float m4[4];
 #pragma unroll
